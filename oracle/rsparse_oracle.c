@@ -1,0 +1,246 @@
+/*
+ * rsparse_oracle.c -- TEST INFRASTRUCTURE, not part of the product.
+ *
+ * Plain, slow, fp64 CPU implementation of the R-Sparse linear layer
+ * (R-Sparse, Sec. 3.4) used to check the HIP library.  Only the test-suite,
+ * the smoke check and the benchmark's "cpu_baseline" leg may call it.  It
+ * shares no code with the HIP path and takes the algorithm's steps in the
+ * paper's order and notation:
+ *
+ *   1. sparsification function  sigma_t(X)_j = X_j if |X_j| >= t else 0   (Sec. 3.4, "Sparsifying Input Activation")
+ *   2. sparse part              Y_s = sigma_t(X) W^T, only the columns of W whose channel survived
+ *   3. low-rank part            Y_r = (X - sigma_t(X)) (A_r B_r)^T       (Sec. 3.4, "R-Sparse Inference")
+ *   4. sum                      Y   = Y_s + Y_r
+ *
+ * with A_r B_r stored as the two factors U_r [d_out][r] and S_r V_r^T [r][d_in]
+ * (same product as the paper's U_r S^1/2 and S^1/2 V_r^T).  Operands are the
+ * *stored* values (fp16 / bf16 bit patterns, widened exactly to double, or
+ * doubles); nothing is rounded on the way and the result stays in double.
+ *
+ * Pins (tests/test_oracle_pins.py): tau = -inf or r = rank(W) gives the dense
+ * product; r = 0 and tau = +inf give the "Sparse" and "Low-Rank" ablations of
+ * Sec. 4.4; the (singular component, channel) double sum of Sec. 3.3 restricted
+ * to the kept block, brute-forced over all masks of 8x8 layers; closed-form
+ * factors; the Eckart-Young bound; numpy's matvec.  No function here is
+ * "parity unpinned".
+ *
+ * W is [d_out][d_in] row-major (nn.Linear orientation, Y = X W^T); "columns of
+ * W" are input channels.  X is [B][d_in], Y is [B][d_out].
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORC_F16 = 0, ORC_BF16 = 1, ORC_F64 = 2 };
+
+/* ---- exact widening of the 16-bit storage formats ---------------------- */
+
+double orc_half_to_double(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int expo = (h >> 10) & 0x1F;
+    int frac = h & 0x3FF;
+    double v;
+    if (expo == 0)
+        v = ldexp((double)frac, -24);                 /* zero and subnormals: frac * 2^-10 * 2^-14 */
+    else if (expo == 31)
+        v = frac ? NAN : INFINITY;
+    else
+        v = ldexp(1.0 + (double)frac / 1024.0, expo - 15);
+    return sign ? -v : v;
+}
+
+double orc_bf16_to_double(uint16_t h)
+{
+    /* bf16 is the upper half of an IEEE binary32 */
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+static inline double ld(const void *p, size_t i, int kind)
+{
+    switch (kind) {
+    case ORC_F16:  return orc_half_to_double(((const uint16_t *)p)[i]);
+    case ORC_BF16: return orc_bf16_to_double(((const uint16_t *)p)[i]);
+    default:       return ((const double *)p)[i];
+    }
+}
+
+void orc_decode16(const uint16_t *in, size_t n, int dtype, double *out)
+{
+    for (size_t i = 0; i < n; ++i) out[i] = ld(in, i, dtype);
+}
+
+/* ---- step 1: the sparsification mask ----------------------------------- */
+
+/* Keep-predicate of sigma_t: |x| >= t (the paper's definition, cmp_mode 0) or the
+ * strict variant |x| > t (cmp_mode 1).  A NaN compares false: it is not kept. */
+static inline int keep(double x, float tau, int cmp_mode)
+{
+    double a = fabs(x);
+    return cmp_mode == 0 ? (a >= (double)tau) : (a > (double)tau);
+}
+
+/* mask[c] = 1 if channel c of token x is kept.  Returns the number kept. */
+int orc_mask(const void *x, int x_kind, int d_in, float tau, int cmp_mode, uint8_t *mask)
+{
+    int k = 0;
+    for (int c = 0; c < d_in; ++c) {
+        mask[c] = (uint8_t)keep(ld(x, (size_t)c, x_kind), tau, cmp_mode);
+        k += mask[c];
+    }
+    return k;
+}
+
+/* ascending list of the channels with mask[c] == want */
+static int list_of(const uint8_t *mask, int d_in, int want, int32_t *out)
+{
+    int n = 0;
+    for (int c = 0; c < d_in; ++c)
+        if (mask[c] == want) out[n++] = c;
+    return n;
+}
+
+/* ---- the R-Sparse linear layer ------------------------------------------ */
+
+/*
+ * kind_w / kind_x: ORC_F16, ORC_BF16 (W, U, SV, X are uint16 bit patterns) or ORC_F64.
+ * batch_mask_mode 0: every token uses its own mask (the paper's elementwise sigma_t).
+ * batch_mask_mode 1: every token uses the union of the batch's masks.
+ * Optional outputs (may be NULL): act [B][d_in] ascending kept channels per token (first
+ * cnt[b] entries valid), cnt [B], uni [d_in] ascending union of kept channels, ucnt [1].
+ * Returns 0, or -1 on allocation failure / bad arguments.
+ */
+int orc_rsparse_linear(const void *W, const void *U, const void *SV, int kind_w,
+                       const void *X, int kind_x,
+                       int B, int d_in, int d_out, int r,
+                       float tau, int cmp_mode, int batch_mask_mode,
+                       double *Y, int32_t *act, int32_t *cnt, int32_t *uni, int32_t *ucnt,
+                       int nthreads)
+{
+    if (B < 1 || d_in < 1 || d_out < 1 || r < 0 || tau != tau) return -1;
+    if (nthreads < 1) nthreads = 1;
+    size_t esz = (kind_x == ORC_F64) ? 8 : 2;
+    uint8_t *mask = malloc((size_t)B * d_in);
+    uint8_t *umask = calloc((size_t)d_in, 1);
+    int32_t *a_list = malloc(sizeof(int32_t) * (size_t)d_in);
+    int32_t *i_list = malloc(sizeof(int32_t) * (size_t)d_in);
+    double *xs = malloc(sizeof(double) * (size_t)d_in);
+    double *t = malloc(sizeof(double) * (size_t)(r > 0 ? r : 1));
+    if (!mask || !umask || !a_list || !i_list || !xs || !t) {
+        free(mask); free(umask); free(a_list); free(i_list); free(xs); free(t);
+        return -1;
+    }
+
+    /* step 1 for every token, and the union over the batch */
+    for (int b = 0; b < B; ++b) {
+        const void *xb = (const char *)X + (size_t)b * d_in * esz;
+        orc_mask(xb, kind_x, d_in, tau, cmp_mode, mask + (size_t)b * d_in);
+        for (int c = 0; c < d_in; ++c) umask[c] |= mask[(size_t)b * d_in + c];
+    }
+    if (uni && ucnt) *ucnt = list_of(umask, d_in, 1, uni);
+
+    for (int b = 0; b < B; ++b) {
+        const uint8_t *mb = batch_mask_mode == 1 ? umask : mask + (size_t)b * d_in;
+        int k = list_of(mb, d_in, 1, a_list);         /* kept channels:  sigma_t(X) != 0      */
+        int z = list_of(mb, d_in, 0, i_list);         /* the rest:       X - sigma_t(X) != 0  */
+        if (act) memcpy(act + (size_t)b * d_in, a_list, sizeof(int32_t) * (size_t)k);
+        if (cnt) cnt[b] = k;
+        for (int c = 0; c < d_in; ++c) xs[c] = ld(X, (size_t)b * d_in + c, kind_x);
+
+        /* step 3a: t = (S_r V_r^T) (x - sigma_t(x)), only the channels that were zeroed */
+#pragma omp parallel for num_threads(nthreads) schedule(static)
+        for (int i = 0; i < r; ++i) {
+            double s = 0.0;
+            for (int j = 0; j < z; ++j) {
+                int c = i_list[j];
+                s += ld(SV, (size_t)i * d_in + c, kind_w) * xs[c];
+            }
+            t[i] = s;
+        }
+
+#pragma omp parallel for num_threads(nthreads) schedule(static)
+        for (int o = 0; o < d_out; ++o) {
+            /* step 2: sparse part, skipping the columns of W whose channel is zero */
+            double ys = 0.0;
+            for (int j = 0; j < k; ++j) {
+                int c = a_list[j];
+                ys += ld(W, (size_t)o * d_in + c, kind_w) * xs[c];
+            }
+            /* step 3b: y_r = U_r t */
+            double yr = 0.0;
+            for (int i = 0; i < r; ++i)
+                yr += ld(U, (size_t)o * r + i, kind_w) * t[i];
+            /* step 4 */
+            Y[(size_t)b * d_out + o] = ys + yr;
+        }
+    }
+    free(mask); free(umask); free(a_list); free(i_list); free(xs); free(t);
+    return 0;
+}
+
+/* The full linear layer Y = X W^T (Sec. 3.1), the thing R-Sparse approximates. */
+int orc_dense_linear(const void *W, int kind_w, const void *X, int kind_x,
+                     int B, int d_in, int d_out, double *Y, int nthreads)
+{
+    if (B < 1 || d_in < 1 || d_out < 1) return -1;
+    if (nthreads < 1) nthreads = 1;
+    double *xs = malloc(sizeof(double) * (size_t)d_in);
+    if (!xs) return -1;
+    for (int b = 0; b < B; ++b) {
+        for (int c = 0; c < d_in; ++c) xs[c] = ld(X, (size_t)b * d_in + c, kind_x);
+#pragma omp parallel for num_threads(nthreads) schedule(static)
+        for (int o = 0; o < d_out; ++o) {
+            double s = 0.0;
+            for (int c = 0; c < d_in; ++c)
+                s += ld(W, (size_t)o * d_in + c, kind_w) * xs[c];
+            Y[(size_t)b * d_out + o] = s;
+        }
+    }
+    free(xs);
+    return 0;
+}
+
+/* ---- threshold estimation ----------------------------------------------- */
+
+static int cmp_double(const void *a, const void *b)
+{
+    double x = *(const double *)a, y = *(const double *)b;
+    return (x > y) - (x < y);
+}
+
+/*
+ * t(s): the s-quantile of |X| over the pooled calibration activations
+ * (Sec. 3.4: P(|X| < t(s)) = s), taken as the order statistic a_(floor(s N)) of the
+ * ascending magnitudes (0-based, clamped to N-1, no interpolation), so that
+ * #{|x| < t} <= floor(s N) <= #{|x| <= t}.  `x` holds n values of kind x_kind.
+ * Returns NaN on failure.
+ */
+double orc_quantile_tau(const void *x, int x_kind, size_t n, double s)
+{
+    if (n == 0 || !(s >= 0.0) || s > 1.0) return NAN;
+    double *a = malloc(sizeof(double) * n);
+    if (!a) return NAN;
+    for (size_t i = 0; i < n; ++i) a[i] = fabs(ld(x, i, x_kind));
+    qsort(a, n, sizeof(double), cmp_double);
+    size_t idx = (size_t)floor(s * (double)n);
+    if (idx > n - 1) idx = n - 1;
+    double tau = a[idx];
+    free(a);
+    return tau;
+}
+
+int orc_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

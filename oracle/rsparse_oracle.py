@@ -1,0 +1,120 @@
+"""ctypes binding of oracle/rsparse_oracle.c (argument marshalling only).
+
+TEST INFRASTRUCTURE: see the header of rsparse_oracle.c."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+F16, BF16, F64 = 0, 1, 2
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        lib = C.CDLL(path)
+        lib.orc_rsparse_linear.restype = C.c_int
+        lib.orc_rsparse_linear.argtypes = [
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int,
+            C.c_int, C.c_int, C.c_int, C.c_int, C.c_float, C.c_int, C.c_int,
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]
+        lib.orc_dense_linear.restype = C.c_int
+        lib.orc_dense_linear.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int,
+                                         C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int]
+        lib.orc_quantile_tau.restype = C.c_double
+        lib.orc_quantile_tau.argtypes = [C.c_void_p, C.c_int, C.c_size_t, C.c_double]
+        lib.orc_mask.restype = C.c_int
+        lib.orc_mask.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_float, C.c_int, C.c_void_p]
+        lib.orc_decode16.restype = None
+        lib.orc_decode16.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_void_p]
+        lib.orc_max_threads.restype = C.c_int
+        _lib = lib
+    return _lib
+
+
+def _arr(a, kind):
+    want = np.float64 if kind == F64 else np.uint16
+    a = np.ascontiguousarray(a, dtype=want)
+    return a
+
+
+def _ptr(a):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def max_threads() -> int:
+    return int(_load().orc_max_threads())
+
+
+def decode16(bits, dtype) -> np.ndarray:
+    bits = _arr(bits, dtype)
+    out = np.empty(bits.shape, dtype=np.float64)
+    _load().orc_decode16(_ptr(bits), bits.size, dtype, _ptr(out))
+    return out
+
+
+def mask(x, x_kind, tau, cmp_mode=0) -> np.ndarray:
+    x = _arr(x, x_kind).reshape(-1)
+    m = np.empty(x.size, dtype=np.uint8)
+    _load().orc_mask(_ptr(x), x_kind, x.size, float(np.float32(tau)), cmp_mode, _ptr(m))
+    return m
+
+
+def rsparse_linear(W, U, SV, X, kind_w, kind_x, tau, *, cmp_mode=0, batch_mask_mode=0,
+                   nthreads=1):
+    """Returns dict(Y [B,d_out] float64, act: list of ascending int32 arrays per token,
+    union: ascending int32 array)."""
+    W = _arr(W, kind_w)
+    d_out, d_in = W.shape
+    X = _arr(X, kind_x)
+    if X.ndim == 1:
+        X = X[None, :]
+    B = X.shape[0]
+    assert X.shape[1] == d_in
+    if U is None:
+        r = 0
+        U = np.zeros((d_out, 0), dtype=W.dtype)
+        SV = np.zeros((0, d_in), dtype=W.dtype)
+    U = _arr(U, kind_w)
+    SV = _arr(SV, kind_w)
+    r = U.shape[1] if U.ndim == 2 else 0
+    assert U.shape == (d_out, r) and SV.shape == (r, d_in)
+    Y = np.empty((B, d_out), dtype=np.float64)
+    act = np.full((B, d_in), -1, dtype=np.int32)
+    cnt = np.zeros(B, dtype=np.int32)
+    uni = np.full(d_in, -1, dtype=np.int32)
+    ucnt = np.zeros(1, dtype=np.int32)
+    rc = _load().orc_rsparse_linear(_ptr(W), _ptr(U), _ptr(SV), kind_w, _ptr(X), kind_x,
+                                    B, d_in, d_out, r, float(np.float32(tau)), cmp_mode,
+                                    batch_mask_mode, _ptr(Y), _ptr(act), _ptr(cnt), _ptr(uni),
+                                    _ptr(ucnt), nthreads)
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments")
+    return {"Y": Y, "act": [act[b, :cnt[b]].copy() for b in range(B)],
+            "union": uni[:ucnt[0]].copy()}
+
+
+def dense_linear(W, X, kind_w, kind_x, nthreads=1) -> np.ndarray:
+    W = _arr(W, kind_w)
+    d_out, d_in = W.shape
+    X = _arr(X, kind_x)
+    if X.ndim == 1:
+        X = X[None, :]
+    Y = np.empty((X.shape[0], d_out), dtype=np.float64)
+    rc = _load().orc_dense_linear(_ptr(W), kind_w, _ptr(X), kind_x, X.shape[0], d_in, d_out,
+                                  _ptr(Y), nthreads)
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments")
+    return Y
+
+
+def quantile_tau(x, x_kind, s) -> float:
+    x = _arr(x, x_kind).reshape(-1)
+    return float(_load().orc_quantile_tau(_ptr(x), x_kind, x.size, float(s)))
