@@ -1,0 +1,161 @@
+/*
+ * rsparse.h -- C ABI of the MI355X (gfx950) R-Sparse linear layer.
+ *
+ * The library implements one operation, the rank-aware sparse linear layer of
+ * R-Sparse (Sec. 3.4, "R-Sparse Inference") for small-batch decode:
+ *
+ *     Y = sigma_t(X) W^T  +  (X - sigma_t(X)) (U_r S_r V_r^T)^T
+ *
+ * where sigma_t keeps the input channels with |x| >= t (Sec. 3.4, "Sparsifying Input
+ * Activation"), the first term only touches the columns of W whose channel was
+ * kept (W is held column-major, as Sec. 3.4 asks, so each kept channel is one
+ * contiguous run), and the second term sends the remaining channels through the
+ * rank-r factors of W's top singular components.
+ *
+ * Conventions
+ *   - W is [d_out][d_in] row-major on the host (nn.Linear orientation, Y = X W^T,
+ *     Sec. 3.1); "columns" of W are input channels.
+ *   - X is [batch][d_in], Y is [batch][d_out], row-major, on the DEVICE.
+ *   - 16-bit values are raw IEEE fp16 or bfloat16 bit patterns (uint16_t).
+ *   - Every function returns an rsparse_status; nothing throws or aborts across
+ *     the ABI.  rsparse_last_error() gives a thread-local message for the last failure.
+ *   - "host" / "device" is stated for every pointer.  The caller owns everything it
+ *     passes in; the handle owns its packed weights and scratch (all allocated at
+ *     prepare time -- the hot calls never allocate and never synchronise).
+ *   - A handle must not be used by two calls at once (its scratch is shared); calls
+ *     on one stream are ordered by the stream.
+ */
+#ifndef RSPARSE_H
+#define RSPARSE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rsparse_layer rsparse_layer; /* opaque; owns device memory */
+
+typedef enum {
+    RSPARSE_F16 = 0,
+    RSPARSE_BF16 = 1,
+    RSPARSE_F32 = 2 /* legal for out_dtype only: unrounded accumulators, for tight parity checks */
+} rsparse_dtype;
+
+typedef enum {
+    RSPARSE_OK = 0,
+    RSPARSE_EINVAL = 1,  /* bad argument (null, range, NaN tau, unsupported shape) */
+    RSPARSE_ENOMEM = 2,  /* host or device allocation failed */
+    RSPARSE_EHIP = 3,    /* a HIP call failed; message holds the HIP error string */
+    RSPARSE_EBATCH = 4,  /* batch outside [1, max_batch] */
+    RSPARSE_EALIGN = 5,  /* X or Y not 16-byte aligned */
+    RSPARSE_ESVD = 6     /* the host SVD did not converge */
+} rsparse_status;
+
+#define RSPARSE_MAX_BATCH 32
+
+typedef struct {
+    int32_t d_in;            /* input channels; multiple of 8 */
+    int32_t d_out;           /* output features; multiple of 8 */
+    int32_t rank;            /* r in [0, min(d_in, d_out)]; 0 = sparse part only */
+    int32_t max_batch;       /* 1..RSPARSE_MAX_BATCH; scratch is sized for it */
+    float   tau;             /* threshold t(s) (Sec. 3.4); fp32 so that the compare is exact.
+                                -INFINITY keeps every channel, +INFINITY none; NaN is rejected */
+    int32_t dtype;           /* of W, X and the factors: RSPARSE_F16 or RSPARSE_BF16 */
+    int32_t out_dtype;       /* of Y: equal to dtype, or RSPARSE_F32 */
+    int32_t cmp_mode;        /* 0: keep |x| >= tau (the paper's definition)   1: keep |x| > tau */
+    int32_t batch_mask_mode; /* 0: every token uses its own mask (sigma_t is elementwise)
+                                1: every token uses the union of the batch's masks */
+    int32_t dense_rowmajor;  /* 1: also keep W row-major on the device so that rsparse_dense_ref
+                                can use its row-dot kernel (doubles the weight footprint) */
+} rsparse_config;
+
+/* Launch-shape overrides for measurements; 0 = library default. */
+typedef struct {
+    int32_t splits;          /* channel splits per column tile of the gather / dense-axpy kernels */
+    int32_t waves;           /* waves (of 64 lanes) per workgroup in those kernels: 1, 2, 4 or 8 */
+    int32_t lowrank_rows;    /* rows of S_r V_r^T per workgroup in the stage-1 kernel */
+    int32_t dense_kernel;    /* rsparse_dense_ref: 0 auto, 1 axpy over column-major W, 2 row-dot */
+    int32_t nontemporal;     /* 1: stream weights with non-temporal loads */
+    int32_t reserved[3];
+} rsparse_tuning;
+
+/*
+ * Offline preparation (Sec. 3.4: "computed offline through a single SVD").
+ * W_host: host, [d_out][d_in] 16-bit of cfg->dtype.  The library computes the top-`rank`
+ * singular triplets on the host, forms U_r and S_r V_r^T, rounds each once to cfg->dtype,
+ * packs W column-major and uploads everything.  *out receives a new handle.
+ */
+rsparse_status rsparse_prepare(const rsparse_config *cfg, const void *W_host, rsparse_layer **out);
+
+/*
+ * The host SVD step of rsparse_prepare on its own (no device needed): top-`rank` singular
+ * triplets of W_host, written as the stored factors U16_host [d_out][rank] and SV16_host
+ * [rank][d_in] (host, 16-bit of cfg->dtype) and, if sigma_host != NULL, the singular values
+ * [rank] in fp64.  Lets callers cache factors and feed rsparse_prepare_factors.
+ */
+rsparse_status rsparse_compute_factors(const rsparse_config *cfg, const void *W_host, void *U16_host,
+                                       void *SV16_host, double *sigma_host);
+
+/*
+ * Same as rsparse_prepare, with the factors supplied by the caller (closed form or an external SVD):
+ * U16_host [d_out][rank] and SV16_host [rank][d_in] (= S_r V_r^T), host, 16-bit of cfg->dtype.
+ * Both may be NULL when rank == 0.  The product U_r (S_r V_r^T) equals the paper's A_r B_r.
+ */
+rsparse_status rsparse_prepare_factors(const rsparse_config *cfg, const void *W_host,
+                                       const void *U16_host, const void *SV16_host,
+                                       rsparse_layer **out);
+
+/*
+ * The hot path (Sec. 3.4): threshold X, build the kept-channel lists, gather-multiply the
+ * kept columns of W, run the other channels through the rank-r factors, sum, round once.
+ * X_dev: device, [batch][d_in] 16-bit, 16-byte aligned.  Y_dev: device, [batch][d_out] of
+ * out_dtype, 16-byte aligned.  stream: a hipStream_t (NULL = default stream).  Asynchronous:
+ * returns after enqueueing; no allocation, no synchronisation.
+ */
+rsparse_status rsparse_linear(rsparse_layer *layer, const void *X_dev, int32_t batch,
+                              void *Y_dev, void *stream);
+
+/* The full layer Y = X W^T (Sec. 3.1) with the hand-written dense GEMV; same argument rules. */
+rsparse_status rsparse_dense_ref(rsparse_layer *layer, const void *X_dev, int32_t batch,
+                                 void *Y_dev, void *stream);
+
+/*
+ * Kept-channel index set of the last rsparse_linear call on this handle (synchronises that
+ * call's stream).  token in [0, batch): that token's ascending list; token == -1: the ascending
+ * union over the batch.  idx_host: host, room for d_in int32; *count receives the length.
+ */
+rsparse_status rsparse_last_active(rsparse_layer *layer, int32_t token, int32_t *idx_host,
+                                   int32_t *count);
+
+/* Stored 16-bit factors, host buffers U16 [d_out][rank] and SV16 [rank][d_in] (either may be NULL). */
+rsparse_status rsparse_get_factors(const rsparse_layer *layer, void *U16_host, void *SV16_host);
+
+rsparse_status rsparse_set_tau(rsparse_layer *layer, float tau);
+rsparse_status rsparse_set_tuning(rsparse_layer *layer, const rsparse_tuning *tuning);
+rsparse_status rsparse_get_config(const rsparse_layer *layer, rsparse_config *cfg_out);
+
+/*
+ * Threshold estimation (Sec. 3.4: P(|X| < t(s)) = s).  X_host: host, n 16-bit activations of
+ * `dtype` pooled over the calibration tokens; s in [0,1].  *tau_out = the order statistic
+ * a_(floor(s n)) of the ascending magnitudes (0-based, clamped, no interpolation).  Host code.
+ */
+rsparse_status rsparse_calibrate_tau(const void *X_host, int32_t dtype, size_t n, double s,
+                                     float *tau_out);
+
+/*
+ * Bytes the method must move for one call (Sec. 3.4's I/O model, in bytes): the k_union kept
+ * columns of W, both factors, X and Y.  rsparse_dense_bytes: all of W, X and Y.
+ */
+size_t rsparse_required_bytes(const rsparse_layer *layer, int32_t batch, int32_t k_union);
+size_t rsparse_dense_bytes(const rsparse_layer *layer, int32_t batch);
+
+void rsparse_destroy(rsparse_layer *layer);
+
+const char *rsparse_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RSPARSE_H */

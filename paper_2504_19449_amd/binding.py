@@ -1,0 +1,220 @@
+"""ctypes binding of include/rsparse.h -- argument marshalling only; every step of the path runs
+in the library's kernels.  There is no CPU fallback: a missing library is an error."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+F16, BF16, F32 = 0, 1, 2
+OK, EINVAL, ENOMEM, EHIP, EBATCH, EALIGN, ESVD = range(7)
+_STATUS = {1: "EINVAL", 2: "ENOMEM", 3: "EHIP", 4: "EBATCH", 5: "EALIGN", 6: "ESVD"}
+
+EXPORTED_SYMBOLS = [
+    "rsparse_prepare", "rsparse_compute_factors", "rsparse_prepare_factors", "rsparse_linear",
+    "rsparse_dense_ref", "rsparse_last_active", "rsparse_get_factors", "rsparse_set_tau", "rsparse_set_tuning",
+    "rsparse_get_config", "rsparse_calibrate_tau", "rsparse_required_bytes", "rsparse_dense_bytes",
+    "rsparse_destroy", "rsparse_last_error",
+]
+
+
+class Config(C.Structure):
+    _fields_ = [("d_in", C.c_int32), ("d_out", C.c_int32), ("rank", C.c_int32), ("max_batch", C.c_int32),
+                ("tau", C.c_float), ("dtype", C.c_int32), ("out_dtype", C.c_int32), ("cmp_mode", C.c_int32),
+                ("batch_mask_mode", C.c_int32), ("dense_rowmajor", C.c_int32)]
+
+
+class Tuning(C.Structure):
+    _fields_ = [("splits", C.c_int32), ("waves", C.c_int32), ("lowrank_rows", C.c_int32),
+                ("dense_kernel", C.c_int32), ("nontemporal", C.c_int32), ("reserved", C.c_int32 * 3)]
+
+
+class RSparseError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"rsparse status {status} ({_STATUS.get(status, '?')}): {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "librsparse.so")
+
+
+def load_library():
+    """Load librsparse.so (built in-tree by paper_2504_19449_amd/build.py).  Raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it with `python -m paper_2504_19449_amd.build` "
+                           "(there is no CPU fallback)")
+    lib = C.CDLL(path)
+    vp, i32 = C.c_void_p, C.c_int32
+    lib.rsparse_prepare.argtypes = [C.POINTER(Config), vp, C.POINTER(vp)]
+    lib.rsparse_compute_factors.argtypes = [C.POINTER(Config), vp, vp, vp, vp]
+    lib.rsparse_prepare_factors.argtypes = [C.POINTER(Config), vp, vp, vp, C.POINTER(vp)]
+    lib.rsparse_linear.argtypes = [vp, vp, i32, vp, vp]
+    lib.rsparse_dense_ref.argtypes = [vp, vp, i32, vp, vp]
+    lib.rsparse_last_active.argtypes = [vp, i32, vp, C.POINTER(i32)]
+    lib.rsparse_get_factors.argtypes = [vp, vp, vp]
+    lib.rsparse_set_tau.argtypes = [vp, C.c_float]
+    lib.rsparse_set_tuning.argtypes = [vp, C.POINTER(Tuning)]
+    lib.rsparse_get_config.argtypes = [vp, C.POINTER(Config)]
+    lib.rsparse_calibrate_tau.argtypes = [vp, i32, C.c_size_t, C.c_double, C.POINTER(C.c_float)]
+    lib.rsparse_required_bytes.argtypes = [vp, i32, i32]
+    lib.rsparse_required_bytes.restype = C.c_size_t
+    lib.rsparse_dense_bytes.argtypes = [vp, i32]
+    lib.rsparse_dense_bytes.restype = C.c_size_t
+    lib.rsparse_destroy.argtypes = [vp]
+    lib.rsparse_destroy.restype = None
+    lib.rsparse_last_error.restype = C.c_char_p
+    for name in ("rsparse_prepare", "rsparse_compute_factors", "rsparse_prepare_factors", "rsparse_linear", "rsparse_dense_ref",
+                 "rsparse_last_active", "rsparse_get_factors", "rsparse_set_tau", "rsparse_set_tuning",
+                 "rsparse_get_config", "rsparse_calibrate_tau"):
+        getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def rsparse_last_error() -> str:
+    return load_library().rsparse_last_error().decode()
+
+
+def _check(st: int):
+    if st != OK:
+        raise RSparseError(st, rsparse_last_error())
+
+
+def _host16(a, name):
+    if a is None:
+        return None
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.uint16:
+        raise TypeError(f"{name} must be uint16 bit patterns")
+    return a
+
+
+def _hp(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+class Layer:
+    """Owner of an rsparse_layer handle."""
+
+    def __init__(self, handle, cfg: Config):
+        self.handle, self.cfg = handle, cfg
+
+    def __del__(self):
+        self.destroy()
+
+    def destroy(self):
+        if getattr(self, "handle", None):
+            rsparse_destroy(self)
+            self.handle = None
+
+
+def _make_config(d_in, d_out, rank, tau, dtype, max_batch=1, out_dtype=None, cmp_mode=0,
+                 batch_mask_mode=0, dense_rowmajor=0) -> Config:
+    return Config(d_in, d_out, rank, max_batch, float(tau), dtype, dtype if out_dtype is None else out_dtype,
+                  cmp_mode, batch_mask_mode, dense_rowmajor)
+
+
+def rsparse_prepare(cfg: Config, W16) -> Layer:
+    W16 = _host16(W16, "W")
+    if W16.shape != (cfg.d_out, cfg.d_in):
+        raise ValueError("W must be [d_out, d_in]")
+    h = C.c_void_p()
+    _check(load_library().rsparse_prepare(C.byref(cfg), _hp(W16), C.byref(h)))
+    return Layer(h, cfg)
+
+
+def rsparse_compute_factors(cfg: Config, W16):
+    """Host SVD only: returns (U16 [d_out, rank], SV16 [rank, d_in], sigma [rank] float64)."""
+    W16 = _host16(W16, "W")
+    if W16.shape != (cfg.d_out, cfg.d_in):
+        raise ValueError("W must be [d_out, d_in]")
+    U = np.zeros((cfg.d_out, cfg.rank), dtype=np.uint16)
+    SV = np.zeros((cfg.rank, cfg.d_in), dtype=np.uint16)
+    sig = np.zeros(cfg.rank, dtype=np.float64)
+    _check(load_library().rsparse_compute_factors(C.byref(cfg), _hp(W16), _hp(U), _hp(SV),
+                                                  sig.ctypes.data_as(C.c_void_p)))
+    return U, SV, sig
+
+
+def rsparse_prepare_factors(cfg: Config, W16, U16, SV16) -> Layer:
+    W16, U16, SV16 = _host16(W16, "W"), _host16(U16, "U"), _host16(SV16, "SV")
+    if W16.shape != (cfg.d_out, cfg.d_in):
+        raise ValueError("W must be [d_out, d_in]")
+    if cfg.rank > 0 and (U16 is None or SV16 is None or U16.shape != (cfg.d_out, cfg.rank)
+                         or SV16.shape != (cfg.rank, cfg.d_in)):
+        raise ValueError("U must be [d_out, rank] and SV [rank, d_in]")
+    h = C.c_void_p()
+    _check(load_library().rsparse_prepare_factors(C.byref(cfg), _hp(W16), _hp(U16), _hp(SV16), C.byref(h)))
+    return Layer(h, cfg)
+
+
+def rsparse_linear(layer: Layer, X_dev: int, batch: int, Y_dev: int, stream: int = 0):
+    """X_dev / Y_dev / stream are raw device pointers / a hipStream_t as integers."""
+    _check(load_library().rsparse_linear(layer.handle, X_dev, batch, Y_dev, stream))
+
+
+def rsparse_dense_ref(layer: Layer, X_dev: int, batch: int, Y_dev: int, stream: int = 0):
+    _check(load_library().rsparse_dense_ref(layer.handle, X_dev, batch, Y_dev, stream))
+
+
+def rsparse_last_active(layer: Layer, token: int) -> np.ndarray:
+    idx = np.empty(layer.cfg.d_in, dtype=np.int32)
+    n = C.c_int32(0)
+    _check(load_library().rsparse_last_active(layer.handle, token, _hp(idx), C.byref(n)))
+    return idx[: n.value].copy()
+
+
+def rsparse_get_factors(layer: Layer):
+    U = np.empty((layer.cfg.d_out, layer.cfg.rank), dtype=np.uint16)
+    SV = np.empty((layer.cfg.rank, layer.cfg.d_in), dtype=np.uint16)
+    _check(load_library().rsparse_get_factors(layer.handle, _hp(U), _hp(SV)))
+    return U, SV
+
+
+def rsparse_set_tau(layer: Layer, tau: float):
+    _check(load_library().rsparse_set_tau(layer.handle, float(tau)))
+    layer.cfg.tau = float(tau)
+
+
+def rsparse_set_tuning(layer: Layer, **kw):
+    t = Tuning()
+    for k, v in kw.items():
+        setattr(t, k, int(v))
+    _check(load_library().rsparse_set_tuning(layer.handle, C.byref(t)))
+
+
+def rsparse_get_config(layer: Layer) -> Config:
+    c = Config()
+    _check(load_library().rsparse_get_config(layer.handle, C.byref(c)))
+    return c
+
+
+def rsparse_calibrate_tau(X16, dtype: int, s: float) -> float:
+    X16 = _host16(X16, "X").reshape(-1)
+    tau = C.c_float(0)
+    _check(load_library().rsparse_calibrate_tau(_hp(X16), dtype, X16.size, float(s), C.byref(tau)))
+    return float(tau.value)
+
+
+def rsparse_required_bytes(layer: Layer, batch: int, k_union: int) -> int:
+    return int(load_library().rsparse_required_bytes(layer.handle, batch, k_union))
+
+
+def rsparse_dense_bytes(layer: Layer, batch: int) -> int:
+    return int(load_library().rsparse_dense_bytes(layer.handle, batch))
+
+
+def rsparse_destroy(layer: Layer):
+    load_library().rsparse_destroy(layer.handle)
+
+
+make_config = _make_config

@@ -1,0 +1,497 @@
+// Host side of the C ABI declared in include/rsparse.h: argument checks, offline packing
+// (column-major W, U_r^T appended as extra rows, S_r V_r^T), uploads, launch-shape choice,
+// read-back decoding.  No arithmetic of the hot path runs here.
+#include "../../include/rsparse.h"
+#include "kernels.h"
+#include "svd_host.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <limits>
+#include <new>
+#include <thread>
+#include <vector>
+
+using namespace rsparse;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+rsparse_status fail(rsparse_status st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+#define RS_HIP(call)                                                                             \
+    do {                                                                                         \
+        hipError_t e_ = (call);                                                                  \
+        if (e_ != hipSuccess)                                                                    \
+            return fail(e_ == hipErrorOutOfMemory ? RSPARSE_ENOMEM : RSPARSE_EHIP, "%s: %s", #call, \
+                        hipGetErrorString(e_));                                                  \
+    } while (0)
+
+// Exact widening of the 16-bit storage formats on the host (used by the SVD intake and the
+// threshold calibration only).
+float half_bits_to_float(uint16_t h)
+{
+    const uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+    const uint32_t em = h & 0x7fffu;
+    uint32_t out;
+    if (em >= 0x7c00u) out = sign | 0x7f800000u | ((em & 0x3ffu) << 13);           // inf / nan
+    else if (em >= 0x0400u) out = sign | ((em + (112u << 10)) << 13);              // normal
+    else if (em == 0) out = sign;
+    else {                                                                          // subnormal
+        float f = (float)em * (1.0f / 16777216.0f);                                 // em * 2^-24
+        uint32_t u;
+        memcpy(&u, &f, 4);
+        out = sign | u;
+    }
+    float f;
+    memcpy(&f, &out, 4);
+    return f;
+}
+float bf16_bits_to_float(uint16_t h)
+{
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+float widen16(uint16_t h, int dtype) { return dtype == RSPARSE_F16 ? half_bits_to_float(h) : bf16_bits_to_float(h); }
+
+uint16_t double_to_bf16(double d)
+{
+    float f = (float)d;   // double -> float -> bf16; the first step is exact enough for factor storage
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+uint16_t double_to_f16(double d)
+{
+    _Float16 h = (_Float16)d;
+    uint16_t u;
+    memcpy(&u, &h, 2);
+    return u;
+}
+
+template <typename F>
+void parallel_for(size_t n, F &&f)
+{
+    unsigned nt = std::thread::hardware_concurrency();
+    if (nt == 0) nt = 1;
+    if (nt > 16) nt = 16;
+    if (n < 2 * nt) nt = 1;
+    std::vector<std::thread> th;
+    for (unsigned t = 0; t < nt; ++t)
+        th.emplace_back([&, t]() {
+            const size_t lo = n * t / nt, hi = n * (t + 1) / nt;
+            for (size_t i = lo; i < hi; ++i) f(i);
+        });
+    for (auto &x : th) x.join();
+}
+
+// dst[cols][rows] = transpose of src[rows][cols], 16-bit elements, 64x64 blocks.
+void transpose16(const uint16_t *src, size_t rows, size_t cols, uint16_t *dst)
+{
+    constexpr size_t B = 64;
+    const size_t rb = (rows + B - 1) / B;
+    parallel_for(rb, [&](size_t bi) {
+        const size_t r0 = bi * B, r1 = std::min(rows, r0 + B);
+        for (size_t c0 = 0; c0 < cols; c0 += B) {
+            const size_t c1 = std::min(cols, c0 + B);
+            for (size_t r = r0; r < r1; ++r)
+                for (size_t c = c0; c < c1; ++c) dst[c * rows + r] = src[r * cols + c];
+        }
+    });
+}
+
+}  // namespace
+
+struct rsparse_layer {
+    rsparse_config cfg{};
+    rsparse_tuning tuning{};
+    int device = 0;
+    int cus = 256;
+    uint16_t *M = nullptr, *SVt = nullptr, *Wrow = nullptr;
+    float *t = nullptr, *yacc = nullptr;
+    uint32_t *tile_done = nullptr, *act_bits = nullptr;
+    int32_t *act_list = nullptr, *act_count = nullptr;
+    int tiles = 0, nz_max = 1;
+    std::vector<uint16_t> U16, SV16;       // host copies of the stored factors
+    hipStream_t last_stream = nullptr;
+    int last_batch = 0;
+
+    LayerView view() const
+    {
+        LayerView v{};
+        v.M = M; v.SVt = SVt; v.Wrow = Wrow; v.t = t; v.yacc = yacc; v.tile_done = tile_done;
+        v.act_list = act_list; v.act_bits = act_bits; v.act_count = act_count;
+        v.d_in = cfg.d_in; v.d_out = cfg.d_out; v.rank = cfg.rank;
+        v.dtype = cfg.dtype; v.out_dtype = cfg.out_dtype; v.cmp_mode = cfg.cmp_mode;
+        v.batch_mask_mode = cfg.batch_mask_mode; v.tau = cfg.tau;
+        return v;
+    }
+};
+
+namespace {
+
+int batch_tile_of(int batch) { return batch <= 1 ? 1 : batch <= 2 ? 2 : batch <= 4 ? 4 : 8; }
+
+rsparse_status check_config(const rsparse_config *c)
+{
+    if (!c) return fail(RSPARSE_EINVAL, "config is NULL");
+    if (c->d_in < 8 || c->d_out < 8 || (c->d_in % 8) || (c->d_out % 8))
+        return fail(RSPARSE_EINVAL, "d_in and d_out must be positive multiples of 8 (got %d, %d)", c->d_in, c->d_out);
+    if (c->d_in > (1 << 20) || c->d_out > (1 << 20)) return fail(RSPARSE_EINVAL, "dimension too large");
+    if (c->rank < 0 || c->rank > std::min(c->d_in, c->d_out))
+        return fail(RSPARSE_EINVAL, "rank %d outside [0, min(d_in, d_out)]", c->rank);
+    if (c->max_batch < 1 || c->max_batch > RSPARSE_MAX_BATCH)
+        return fail(RSPARSE_EINVAL, "max_batch %d outside [1, %d]", c->max_batch, RSPARSE_MAX_BATCH);
+    if (std::isnan(c->tau)) return fail(RSPARSE_EINVAL, "tau is NaN");
+    if (c->dtype != RSPARSE_F16 && c->dtype != RSPARSE_BF16) return fail(RSPARSE_EINVAL, "dtype must be F16 or BF16");
+    if (c->out_dtype != c->dtype && c->out_dtype != RSPARSE_F32)
+        return fail(RSPARSE_EINVAL, "out_dtype must equal dtype or be F32");
+    if (c->cmp_mode != 0 && c->cmp_mode != 1) return fail(RSPARSE_EINVAL, "cmp_mode must be 0 or 1");
+    if (c->batch_mask_mode != 0 && c->batch_mask_mode != 1) return fail(RSPARSE_EINVAL, "batch_mask_mode must be 0 or 1");
+    if (c->dense_rowmajor != 0 && c->dense_rowmajor != 1) return fail(RSPARSE_EINVAL, "dense_rowmajor must be 0 or 1");
+    return RSPARSE_OK;
+}
+
+// Launch shape: column tiles x channel splits ~ a few workgroups per compute unit, each with
+// enough rows to amortise its scan, and the staged share small enough for 64 KiB of LDS.
+Launch resolve_launch(const rsparse_layer *L, int batch, bool dense)
+{
+    Launch c{};
+    const rsparse_tuning &t = L->tuning;
+    const int bt = batch_tile_of(batch);
+    c.waves = (t.waves == 1 || t.waves == 2 || t.waves == 4 || t.waves == 8) ? t.waves : 4;
+    c.nontemporal = t.nontemporal ? 1 : 0;
+    const int rows = dense ? L->cfg.d_in : L->cfg.d_in / 2 + L->cfg.rank;   // expected rows to stream
+    int splits = t.splits;
+    if (splits <= 0) {
+        const int target_wgs = 2 * L->cus;
+        splits = (target_wgs + L->tiles - 1) / L->tiles;
+        const int max_by_rows = std::max(1, rows / (c.waves * 4));          // >= 4 rows per wave
+        splits = std::max(1, std::min(splits, max_by_rows));
+    }
+    splits = std::min(splits, 4096);
+    const int rank = dense ? 0 : L->cfg.rank;
+    (void)rank;
+    while (gather_lds_bytes(L->cfg.d_in, L->cfg.rank, splits, c.waves, bt) > 60 * 1024) splits *= 2;
+    c.splits = splits;
+    int lr = t.lowrank_rows;
+    if (lr != 1 && lr != 2 && lr != 4) lr = (L->cfg.rank > 4 * L->cus) ? 4 : (L->cfg.rank > 2 * L->cus ? 2 : 1);
+    c.lowrank_rows = lr;
+    return c;
+}
+
+rsparse_status check_call(rsparse_layer *L, const void *X, int32_t batch, void *Y)
+{
+    if (!L) return fail(RSPARSE_EINVAL, "layer is NULL");
+    if (!X || !Y) return fail(RSPARSE_EINVAL, "X and Y must be non-NULL device pointers");
+    if (batch < 1 || batch > L->cfg.max_batch)
+        return fail(RSPARSE_EBATCH, "batch %d outside [1, max_batch=%d]", batch, L->cfg.max_batch);
+    if (((uintptr_t)X & 15u) || ((uintptr_t)Y & 15u)) return fail(RSPARSE_EALIGN, "X and Y must be 16-byte aligned");
+    return RSPARSE_OK;
+}
+
+void free_layer(rsparse_layer *L)
+{
+    if (!L) return;
+    (void)hipFree(L->M); (void)hipFree(L->SVt); (void)hipFree(L->Wrow); (void)hipFree(L->t);
+    (void)hipFree(L->yacc); (void)hipFree(L->tile_done); (void)hipFree(L->act_bits);
+    (void)hipFree(L->act_list); (void)hipFree(L->act_count);
+    delete L;
+}
+
+rsparse_status build_layer(const rsparse_config *cfg, const uint16_t *W, const uint16_t *U16, const uint16_t *SV16,
+                           rsparse_layer **out)
+{
+    rsparse_layer *L = new (std::nothrow) rsparse_layer();
+    if (!L) return fail(RSPARSE_ENOMEM, "host allocation failed");
+    L->cfg = *cfg;
+    const size_t d_in = cfg->d_in, d_out = cfg->d_out, r = cfg->rank;
+    L->tiles = (int)((d_out + kTile - 1) / kTile);
+    L->nz_max = std::max(1, (cfg->max_batch + kMaxBT - 1) / kMaxBT);
+
+    rsparse_status st = RSPARSE_OK;
+    auto body = [&]() -> rsparse_status {
+        RS_HIP(hipGetDevice(&L->device));
+        hipDeviceProp_t prop;
+        RS_HIP(hipGetDeviceProperties(&prop, L->device));
+        L->cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+
+        // pack: rows 0..d_in-1 = W^T (column-major W), rows d_in.. = U_r^T
+        std::vector<uint16_t> host;
+        try {
+            host.resize((d_in + r) * d_out);
+            if (r) { L->U16.assign(U16, U16 + d_out * r); L->SV16.assign(SV16, SV16 + r * d_in); }
+        } catch (const std::bad_alloc &) { return fail(RSPARSE_ENOMEM, "host allocation failed"); }
+        transpose16(W, d_out, d_in, host.data());
+        if (r) transpose16(U16, d_out, r, host.data() + d_in * d_out);
+
+        RS_HIP(hipMalloc((void **)&L->M, host.size() * 2));
+        RS_HIP(hipMemcpy(L->M, host.data(), host.size() * 2, hipMemcpyHostToDevice));
+        if (r) {
+            RS_HIP(hipMalloc((void **)&L->SVt, r * d_in * 2));
+            RS_HIP(hipMemcpy(L->SVt, SV16, r * d_in * 2, hipMemcpyHostToDevice));
+        }
+        if (cfg->dense_rowmajor) {
+            RS_HIP(hipMalloc((void **)&L->Wrow, d_in * d_out * 2));
+            RS_HIP(hipMemcpy(L->Wrow, W, d_in * d_out * 2, hipMemcpyHostToDevice));
+        }
+        const size_t bpad = (size_t)L->nz_max * kMaxBT;
+        const size_t n_t = std::max<size_t>(1, r * bpad);
+        const size_t n_y = (size_t)cfg->max_batch * d_out;
+        const size_t n_done = (size_t)L->nz_max * L->tiles;
+        const size_t n_list = (size_t)L->nz_max * d_in;
+        RS_HIP(hipMalloc((void **)&L->t, n_t * 4));
+        RS_HIP(hipMalloc((void **)&L->yacc, n_y * 4));
+        RS_HIP(hipMalloc((void **)&L->tile_done, n_done * 4));
+        RS_HIP(hipMalloc((void **)&L->act_list, n_list * 4));
+        RS_HIP(hipMalloc((void **)&L->act_bits, n_list * 4));
+        RS_HIP(hipMalloc((void **)&L->act_count, (size_t)L->nz_max * 4));
+        RS_HIP(hipMemset(L->t, 0, n_t * 4));
+        RS_HIP(hipMemset(L->yacc, 0, n_y * 4));
+        RS_HIP(hipMemset(L->tile_done, 0, n_done * 4));
+        RS_HIP(hipMemset(L->act_list, 0, n_list * 4));
+        RS_HIP(hipMemset(L->act_bits, 0, n_list * 4));
+        RS_HIP(hipMemset(L->act_count, 0, (size_t)L->nz_max * 4));
+        RS_HIP(hipDeviceSynchronize());
+        return RSPARSE_OK;
+    };
+    st = body();
+    if (st != RSPARSE_OK) { free_layer(L); return st; }
+    *out = L;
+    return RSPARSE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *rsparse_last_error(void) { return g_err; }
+
+rsparse_status rsparse_prepare_factors(const rsparse_config *cfg, const void *W_host, const void *U16_host,
+                                       const void *SV16_host, rsparse_layer **out)
+{
+    if (!out) return fail(RSPARSE_EINVAL, "out is NULL");
+    *out = nullptr;
+    rsparse_status st = check_config(cfg);
+    if (st != RSPARSE_OK) return st;
+    if (!W_host) return fail(RSPARSE_EINVAL, "W_host is NULL");
+    if (cfg->rank > 0 && (!U16_host || !SV16_host)) return fail(RSPARSE_EINVAL, "factors are NULL but rank > 0");
+    return build_layer(cfg, (const uint16_t *)W_host, (const uint16_t *)U16_host, (const uint16_t *)SV16_host, out);
+}
+
+rsparse_status rsparse_compute_factors(const rsparse_config *cfg, const void *W_host, void *U16_host,
+                                       void *SV16_host, double *sigma_host)
+{
+    rsparse_status st = check_config(cfg);
+    if (st != RSPARSE_OK) return st;
+    if (!W_host) return fail(RSPARSE_EINVAL, "W_host is NULL");
+    const size_t d_in = cfg->d_in, d_out = cfg->d_out, r = cfg->rank;
+    if (r == 0) return RSPARSE_OK;
+    if (!U16_host || !SV16_host) return fail(RSPARSE_EINVAL, "factor buffers are NULL but rank > 0");
+    std::vector<double> W, U, S, V;
+    try {
+        W.resize(d_in * d_out);
+        U.resize(d_out * r); S.resize(r); V.resize(d_in * r);
+    } catch (const std::bad_alloc &) { return fail(RSPARSE_ENOMEM, "host allocation failed"); }
+    const uint16_t *w16 = (const uint16_t *)W_host;
+    const int dt = cfg->dtype;
+    parallel_for(d_out, [&](size_t o) {
+        for (size_t c = 0; c < d_in; ++c) W[o * d_in + c] = (double)widen16(w16[o * d_in + c], dt);
+    });
+    char msg[256] = "";
+    if (svd_top_r(W.data(), (int)d_out, (int)d_in, (int)r, U.data(), S.data(), V.data(), msg, sizeof msg) != 0)
+        return fail(RSPARSE_ESVD, "host SVD failed: %s", msg);
+    // U_r [d_out][r];  S_r V_r^T [r][d_in]; each rounded once to the storage type
+    uint16_t *U16 = (uint16_t *)U16_host, *SV16 = (uint16_t *)SV16_host;
+    for (size_t o = 0; o < d_out; ++o)
+        for (size_t i = 0; i < r; ++i)
+            U16[o * r + i] = dt == RSPARSE_F16 ? double_to_f16(U[o * r + i]) : double_to_bf16(U[o * r + i]);
+    for (size_t i = 0; i < r; ++i)
+        for (size_t c = 0; c < d_in; ++c) {
+            const double v = S[i] * V[c * r + i];
+            SV16[i * d_in + c] = dt == RSPARSE_F16 ? double_to_f16(v) : double_to_bf16(v);
+        }
+    if (sigma_host) memcpy(sigma_host, S.data(), r * sizeof(double));
+    return RSPARSE_OK;
+}
+
+rsparse_status rsparse_prepare(const rsparse_config *cfg, const void *W_host, rsparse_layer **out)
+{
+    if (!out) return fail(RSPARSE_EINVAL, "out is NULL");
+    *out = nullptr;
+    rsparse_status st = check_config(cfg);
+    if (st != RSPARSE_OK) return st;
+    if (!W_host) return fail(RSPARSE_EINVAL, "W_host is NULL");
+    std::vector<uint16_t> U16, SV16;
+    try {
+        U16.resize((size_t)cfg->d_out * cfg->rank);
+        SV16.resize((size_t)cfg->rank * cfg->d_in);
+    } catch (const std::bad_alloc &) { return fail(RSPARSE_ENOMEM, "host allocation failed"); }
+    st = rsparse_compute_factors(cfg, W_host, U16.data(), SV16.data(), nullptr);
+    if (st != RSPARSE_OK) return st;
+    return build_layer(cfg, (const uint16_t *)W_host, U16.data(), SV16.data(), out);
+}
+
+rsparse_status rsparse_linear(rsparse_layer *L, const void *X_dev, int32_t batch, void *Y_dev, void *stream)
+{
+    rsparse_status st = check_call(L, X_dev, batch, Y_dev);
+    if (st != RSPARSE_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    const Launch lc = resolve_launch(L, batch, false);
+    const LayerView v = L->view();
+    RS_HIP(launch_lowrank_t(v, lc, X_dev, batch, s));
+    RS_HIP(launch_gather(v, lc, X_dev, batch, Y_dev, s));
+    L->last_stream = s;
+    L->last_batch = batch;
+    return RSPARSE_OK;
+}
+
+rsparse_status rsparse_dense_ref(rsparse_layer *L, const void *X_dev, int32_t batch, void *Y_dev, void *stream)
+{
+    rsparse_status st = check_call(L, X_dev, batch, Y_dev);
+    if (st != RSPARSE_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    const Launch lc = resolve_launch(L, batch, true);
+    const LayerView v = L->view();
+    int kernel = L->tuning.dense_kernel;
+    const bool can_rowdot = L->Wrow != nullptr && rowdot_supported(L->cfg.d_in, batch);
+    if (kernel == 2 && !can_rowdot)
+        return fail(RSPARSE_EINVAL, "row-dot dense kernel needs dense_rowmajor=1 and batch_tile*d_in*2 <= 64 KiB");
+    if (kernel == 0) kernel = can_rowdot ? 2 : 1;
+    if (kernel == 2) RS_HIP(launch_dense_rowdot(v, lc, X_dev, batch, Y_dev, s));
+    else RS_HIP(launch_dense_axpy(v, lc, X_dev, batch, Y_dev, s));
+    return RSPARSE_OK;
+}
+
+rsparse_status rsparse_last_active(rsparse_layer *L, int32_t token, int32_t *idx_host, int32_t *count)
+{
+    if (!L || !idx_host || !count) return fail(RSPARSE_EINVAL, "NULL argument");
+    if (L->last_batch == 0) return fail(RSPARSE_EINVAL, "no rsparse_linear call has been made on this layer");
+    if (token < -1 || token >= L->last_batch) return fail(RSPARSE_EINVAL, "token %d outside [-1, %d)", token, L->last_batch);
+    RS_HIP(hipStreamSynchronize(L->last_stream));
+    const int bt = batch_tile_of(L->last_batch);
+    const int nz = (L->last_batch + bt - 1) / bt;
+    const size_t d_in = L->cfg.d_in;
+    std::vector<int32_t> cnt(nz), list;
+    std::vector<uint32_t> bits;
+    RS_HIP(hipMemcpy(cnt.data(), L->act_count, nz * 4, hipMemcpyDeviceToHost));
+    auto fetch = [&](int z) -> rsparse_status {
+        if (cnt[z] < 0 || (size_t)cnt[z] > d_in) return fail(RSPARSE_EHIP, "corrupt list count %d", cnt[z]);
+        list.resize(cnt[z]); bits.resize(cnt[z]);
+        if (cnt[z]) {
+            RS_HIP(hipMemcpy(list.data(), L->act_list + z * d_in, (size_t)cnt[z] * 4, hipMemcpyDeviceToHost));
+            RS_HIP(hipMemcpy(bits.data(), L->act_bits + z * d_in, (size_t)cnt[z] * 4, hipMemcpyDeviceToHost));
+        }
+        return RSPARSE_OK;
+    };
+    if (token >= 0) {
+        const int z = token / bt, b = token % bt;
+        rsparse_status st = fetch(z);
+        if (st != RSPARSE_OK) return st;
+        int32_t n = 0;
+        for (size_t j = 0; j < list.size(); ++j)
+            if ((bits[j] >> b) & 1u) idx_host[n++] = list[j];
+        *count = n;
+        return RSPARSE_OK;
+    }
+    // union over the batch: merge the batch tiles' ascending lists
+    std::vector<uint8_t> seen(d_in, 0);
+    for (int z = 0; z < nz; ++z) {
+        rsparse_status st = fetch(z);
+        if (st != RSPARSE_OK) return st;
+        for (int32_t c : list)
+            if (c >= 0 && (size_t)c < d_in) seen[c] = 1;
+    }
+    int32_t n = 0;
+    for (size_t c = 0; c < d_in; ++c)
+        if (seen[c]) idx_host[n++] = (int32_t)c;
+    *count = n;
+    return RSPARSE_OK;
+}
+
+rsparse_status rsparse_get_factors(const rsparse_layer *L, void *U16_host, void *SV16_host)
+{
+    if (!L) return fail(RSPARSE_EINVAL, "layer is NULL");
+    if (U16_host && !L->U16.empty()) memcpy(U16_host, L->U16.data(), L->U16.size() * 2);
+    if (SV16_host && !L->SV16.empty()) memcpy(SV16_host, L->SV16.data(), L->SV16.size() * 2);
+    return RSPARSE_OK;
+}
+
+rsparse_status rsparse_set_tau(rsparse_layer *L, float tau)
+{
+    if (!L) return fail(RSPARSE_EINVAL, "layer is NULL");
+    if (std::isnan(tau)) return fail(RSPARSE_EINVAL, "tau is NaN");
+    L->cfg.tau = tau;
+    return RSPARSE_OK;
+}
+
+rsparse_status rsparse_set_tuning(rsparse_layer *L, const rsparse_tuning *t)
+{
+    if (!L || !t) return fail(RSPARSE_EINVAL, "NULL argument");
+    if (t->splits < 0 || t->waves < 0 || t->lowrank_rows < 0 || t->dense_kernel < 0 || t->dense_kernel > 2)
+        return fail(RSPARSE_EINVAL, "negative or unknown tuning value");
+    if (t->waves != 0 && t->waves != 1 && t->waves != 2 && t->waves != 4 && t->waves != 8)
+        return fail(RSPARSE_EINVAL, "waves must be 0, 1, 2, 4 or 8");
+    L->tuning = *t;
+    return RSPARSE_OK;
+}
+
+rsparse_status rsparse_get_config(const rsparse_layer *L, rsparse_config *out)
+{
+    if (!L || !out) return fail(RSPARSE_EINVAL, "NULL argument");
+    *out = L->cfg;
+    return RSPARSE_OK;
+}
+
+rsparse_status rsparse_calibrate_tau(const void *X_host, int32_t dtype, size_t n, double s, float *tau_out)
+{
+    if (!X_host || !tau_out) return fail(RSPARSE_EINVAL, "NULL argument");
+    if (dtype != RSPARSE_F16 && dtype != RSPARSE_BF16) return fail(RSPARSE_EINVAL, "dtype must be F16 or BF16");
+    if (n == 0) return fail(RSPARSE_EINVAL, "no calibration activations");
+    if (!(s >= 0.0) || s > 1.0) return fail(RSPARSE_EINVAL, "s must be in [0, 1]");
+    std::vector<float> a;
+    try { a.resize(n); } catch (const std::bad_alloc &) { return fail(RSPARSE_ENOMEM, "host allocation failed"); }
+    const uint16_t *x = (const uint16_t *)X_host;
+    for (size_t i = 0; i < n; ++i) a[i] = std::fabs(widen16(x[i], dtype));   // exact: 16-bit values fit fp32
+    size_t idx = (size_t)std::floor(s * (double)n);
+    if (idx > n - 1) idx = n - 1;
+    std::nth_element(a.begin(), a.begin() + idx, a.end());
+    *tau_out = a[idx];
+    return RSPARSE_OK;
+}
+
+size_t rsparse_required_bytes(const rsparse_layer *L, int32_t batch, int32_t k_union)
+{
+    if (!L || batch < 1 || k_union < 0) return 0;
+    const size_t e = 2, d_in = L->cfg.d_in, d_out = L->cfg.d_out, r = L->cfg.rank, B = batch, k = k_union;
+    const size_t eo = L->cfg.out_dtype == RSPARSE_F32 ? 4 : 2;
+    return e * (k * d_out + r * d_out + r * d_in + B * d_in) + eo * B * d_out;
+}
+
+size_t rsparse_dense_bytes(const rsparse_layer *L, int32_t batch)
+{
+    if (!L || batch < 1) return 0;
+    const size_t e = 2, d_in = L->cfg.d_in, d_out = L->cfg.d_out, B = batch;
+    const size_t eo = L->cfg.out_dtype == RSPARSE_F32 ? 4 : 2;
+    return e * (d_in * d_out + B * d_in) + eo * B * d_out;
+}
+
+void rsparse_destroy(rsparse_layer *L) { free_layer(L); }
+
+}  // extern "C"

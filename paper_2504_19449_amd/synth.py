@@ -164,3 +164,24 @@ class DownInput:
         g = rng.standard_normal((n, self.d))
         u = rng.standard_normal((n, self.d))
         return g / (1.0 + np.exp(-g)) * u
+
+
+def random_layer(d_in: int, d_out: int, rank: int, dtype: int, seed: int) -> Layer:
+    """Cheap stand-in for very large shapes where the QR construction is too slow for a test:
+    i.i.d. Gaussian W and factors with the same entry scales as make_layer's (W rms
+    ~ sqrt(sum sigma^2 / (d_in d_out)), U entries ~ 1/sqrt(d_out), S V^T entries ~ sigma_i/sqrt(d_in)).
+    The factors are NOT the SVD of W -- parity of the kernels against the oracle does not need
+    them to be; accuracy statements do, and never use this generator."""
+    g = _rng(seed)
+    p = min(d_in, d_out)
+    sig = spectrum(p)
+    out = object.__new__(Layer)
+    out.d_in, out.d_out, out.rank, out.dtype = d_in, d_out, rank, dtype
+    out.U = out.V = None
+    out.sigma = sig
+    w_rms = np.sqrt(np.sum(sig ** 2) / (d_in * d_out))
+    out.W16 = encode16(g.standard_normal((d_out, d_in), dtype=np.float32) * np.float32(w_rms), dtype)
+    out.U16 = encode16(g.standard_normal((d_out, rank), dtype=np.float32) / np.float32(np.sqrt(d_out)), dtype)
+    sv = g.standard_normal((rank, d_in), dtype=np.float32) * (sig[:rank, None] / np.sqrt(d_in)).astype(np.float32)
+    out.SV16 = encode16(sv, dtype)
+    return out

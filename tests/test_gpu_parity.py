@@ -1,0 +1,217 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle on the same
+seeded inputs.  Kept-channel lists must be equal; outputs within the stated tolerances."""
+import numpy as np
+import pytest
+
+import paper_2504_19449_amd as rs
+from paper_2504_19449_amd import synth
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+INF = float("inf")
+
+
+@pytest.fixture(scope="module")
+def ragged():
+    """Several column tiles with a ragged tail (1096 = 2*512 + 72), d_in not a multiple of 256."""
+    return {dt: synth.make_layer(1032, 1096, 40, dt, config=81, linear=dt) for dt in (synth.F16, synth.BF16)}
+
+
+@pytest.fixture(scope="module")
+def config0():
+    return synth.make_layer(4096, 4096, 256, synth.F16, config=0, linear=0)
+
+
+def _parity(L, X16, tau, out_dtype=None, max_batch=None, tuning=None, **cfg_kw):
+    X16 = np.atleast_2d(X16)
+    layer = gu.prepare(L, tau, max_batch=max_batch or X16.shape[0], out_dtype=out_dtype, **cfg_kw)
+    if tuning:
+        rs.rsparse_set_tuning(layer, **tuning)
+    got = gu.run_linear(layer, X16)
+    want = gu.oracle_linear(L, X16, tau, cmp_mode=cfg_kw.get("cmp_mode", 0),
+                            batch_mask_mode=cfg_kw.get("batch_mask_mode", 0))
+    gu.check_lists(got, want)
+    gu.check_outputs(got["Y"], want["Y"], layer.cfg.out_dtype)
+    layer.destroy()
+    return got, want
+
+
+@pytest.mark.parametrize("dt", [synth.F16, synth.BF16])
+@pytest.mark.parametrize("out", [None, rs.F32])
+def test_ragged_batch1(ragged, dt, out):
+    L = ragged[dt]
+    X16, src = gu.tokens_for(L, 3, linear=dt)
+    tau = gu.calibrated_tau(L, src, 0.5)
+    for b in range(3):
+        got, _ = _parity(L, X16[b], tau, out_dtype=out)
+        assert 0.3 * L.d_in < len(got["act"][0]) < 0.7 * L.d_in
+
+
+@pytest.mark.parametrize("out", [None, rs.F32])
+def test_config0_full_size(config0, out):
+    """configs[0]: 4096x4096 fp16, r = 256, tau = 50% quantile of 64 calibration tokens."""
+    L = config0
+    src = synth.DModelInput(L.d_in, config=0, linear=0)
+    tau = gu.calibrated_tau(L, src, 0.5)
+    X16 = synth.encode16(src.tokens(4), L.dtype)
+    for b in range(4):
+        got, _ = _parity(L, X16[b], tau, out_dtype=out)
+        assert abs(len(got["act"][0]) - 2048) < 200
+
+
+def test_edge_thresholds(ragged):
+    L = ragged[synth.F16]
+    X16, _ = gu.tokens_for(L, 1)
+    for tau in (-INF, 0.0, INF, 1e30):
+        for mode in (0, 1):
+            _parity(L, X16, tau, out_dtype=rs.F32, cmp_mode=mode)
+
+
+def test_all_ties_token(ragged):
+    L = ragged[synth.BF16]
+    x = np.where(np.arange(L.d_in) % 3 == 0, -0.75, 0.75)
+    X16 = synth.encode16(x, L.dtype)
+    got0, _ = _parity(L, X16, 0.75, cmp_mode=0)
+    got1, _ = _parity(L, X16, 0.75, cmp_mode=1)
+    assert len(got0["act"][0]) == L.d_in and len(got1["act"][0]) == 0
+
+
+def test_rank_zero_and_full_rank():
+    L0 = synth.make_layer(520, 264, 0, synth.F16, config=82, linear=0)
+    X16, src = gu.tokens_for(L0, 2)
+    tau = gu.calibrated_tau(L0, src, 0.6)
+    _parity(L0, X16[0], tau, out_dtype=rs.F32)
+    Lf = synth.make_layer(520, 264, 264, synth.F16, config=82, linear=0)
+    got, _ = _parity(Lf, X16[1], tau, out_dtype=rs.F32)
+    # full rank: the layer is (up to factor rounding) the dense product
+    dense = synth.decode16(X16[1], Lf.dtype) @ synth.decode16(Lf.W16, Lf.dtype).T
+    assert np.linalg.norm(got["Y"][0] - dense) <= 5e-3 * np.linalg.norm(dense)
+
+
+def test_nan_inf_inputs(ragged):
+    L = ragged[synth.F16]
+    X16, src = gu.tokens_for(L, 1)
+    tau = gu.calibrated_tau(L, src, 0.5)
+    X = X16[0].copy()
+    X[5] = 0x7C00          # +inf: kept
+    X[77] = 0xFC00         # -inf: kept
+    X[8] = 0x8000          # -0
+    got, want = _parity(L, X, tau, out_dtype=rs.F32)
+    assert 5 in got["act"][0] and 77 in got["act"][0] and 8 not in got["act"][0]
+    X[9] = 0x7E00          # NaN: never kept, goes through the low-rank path and poisons the output
+    got, want = _parity(L, X, tau, out_dtype=rs.F32)
+    assert 9 not in got["act"][0]
+    assert np.all(np.isnan(got["Y"]))
+
+
+def test_fp16_subnormal_weights_are_not_flushed():
+    L = synth.make_layer(264, 520, 8, synth.F16, config=83, linear=0)
+    W = synth.decode16(L.W16, L.dtype)
+    scale = 3e-5 / np.max(np.abs(W))           # push every weight into fp16's subnormal range
+    L.W16 = synth.encode16(W * scale, L.dtype)
+    assert np.all((L.W16 & 0x7C00) == 0) and np.count_nonzero(L.W16 & 0x3FF) > 0.9 * L.W16.size
+    L.rank, L.U16, L.SV16 = 0, L.U16[:, :0], L.SV16[:0]
+    X16, _ = gu.tokens_for(L, 1)
+    got, want = _parity(L, X16, 0.5, out_dtype=rs.F32)
+    assert np.linalg.norm(want["Y"]) > 0
+
+
+@pytest.mark.parametrize("B", [2, 3, 4, 5, 8, 9, 16, 32])
+@pytest.mark.parametrize("mask_mode", [0, 1])
+def test_batches(ragged, B, mask_mode):
+    L = ragged[synth.BF16]
+    X16, src = gu.tokens_for(L, B, linear=B)
+    tau = gu.calibrated_tau(L, src, 0.5)
+    _parity(L, X16, tau, out_dtype=rs.F32, batch_mask_mode=mask_mode)
+    _parity(L, X16, tau, batch_mask_mode=mask_mode)
+
+
+def test_batch_smaller_than_max_batch_and_reuse(ragged):
+    L = ragged[synth.F16]
+    X16, src = gu.tokens_for(L, 8)
+    tau = gu.calibrated_tau(L, src, 0.5)
+    layer = gu.prepare(L, tau, max_batch=8, out_dtype=rs.F32)
+    for B in (8, 1, 3, 8, 2):
+        got = gu.run_linear(layer, X16[:B])
+        want = gu.oracle_linear(L, X16[:B], tau)
+        gu.check_lists(got, want)
+        gu.check_outputs(got["Y"], want["Y"], rs.F32)
+    # tau sweep without re-packing
+    for s in (0.4, 0.7):
+        t2 = gu.calibrated_tau(L, src, s)
+        rs.rsparse_set_tau(layer, t2)
+        got = gu.run_linear(layer, X16[:2])
+        want = gu.oracle_linear(L, X16[:2], t2)
+        gu.check_lists(got, want)
+        gu.check_outputs(got["Y"], want["Y"], rs.F32)
+        assert abs(len(got["act"][0]) / L.d_in - (1 - s)) < 0.1
+
+
+@pytest.mark.parametrize("tuning", [
+    dict(splits=1), dict(splits=3, waves=1), dict(splits=7, waves=2), dict(splits=64, waves=8),
+    dict(splits=500, waves=4), dict(lowrank_rows=2), dict(lowrank_rows=4, nontemporal=1),
+])
+def test_launch_shapes(ragged, tuning):
+    L = ragged[synth.F16]
+    X16, src = gu.tokens_for(L, 4)
+    tau = gu.calibrated_tau(L, src, 0.5)
+    _parity(L, X16[0], tau, out_dtype=rs.F32, tuning=tuning)
+    _parity(L, X16, tau, out_dtype=rs.F32, tuning=tuning)
+
+
+@pytest.mark.parametrize("dt", [synth.F16, synth.BF16])
+def test_dense_ref_both_kernels(ragged, dt):
+    import oracle
+    L = ragged[dt]
+    X16, _ = gu.tokens_for(L, 5)
+    want = oracle.dense_linear(L.W16, X16, L.dtype, L.dtype, nthreads=8)
+    for out in (None, rs.F32):
+        layer = gu.prepare(L, 0.5, max_batch=8, out_dtype=out, dense_rowmajor=1)
+        for kernel in (1, 2, 0):
+            rs.rsparse_set_tuning(layer, dense_kernel=kernel)
+            for B in (1, 5):
+                got = gu.run_dense(layer, X16[:B])
+                gu.check_outputs(got, want[:B], layer.cfg.out_dtype)
+        layer.destroy()
+
+
+def test_determinism_of_lists_and_bounded_output_jitter(config0):
+    L = config0
+    src = synth.DModelInput(L.d_in, config=0, linear=0)
+    tau = gu.calibrated_tau(L, src, 0.5)
+    X16 = synth.encode16(src.tokens(1, offset=3), L.dtype)
+    layer = gu.prepare(L, tau, out_dtype=rs.F32)
+    first = gu.run_linear(layer, X16)
+    for _ in range(20):
+        again = gu.run_linear(layer, X16)
+        assert np.array_equal(again["act"][0], first["act"][0])
+        # fp32 atomics: summation order may differ between runs, within accumulation rounding
+        assert np.linalg.norm(again["Y"] - first["Y"]) <= 1e-5 * np.linalg.norm(first["Y"])
+
+
+@pytest.mark.parametrize("shape", [(4096, 11008, 512, "dmodel"), (11008, 4096, 512, "down")])
+def test_config1_shapes_sparsity_sweep(shape):
+    """configs[1]: Llama-2-7B MLP shapes, bf16, r = 512, tau at 40 / 50 / 70 % sparsity."""
+    d_in, d_out, r, kind = shape
+    L = synth.make_layer(d_in, d_out, r, synth.BF16, config=1, linear=0 if kind == "dmodel" else 2)
+    X16, src = gu.tokens_for(L, 2, kind=kind, config=1, linear=0 if kind == "dmodel" else 2)
+    for s in (0.4, 0.5, 0.7):
+        tau = gu.calibrated_tau(L, src, s)
+        got, _ = _parity(L, X16[0], tau)
+        assert abs(len(got["act"][0]) / d_in - (1 - s)) < 0.05
+    tau = gu.calibrated_tau(L, src, 0.5)
+    _parity(L, X16[1], tau, out_dtype=rs.F32)
+
+
+def test_largest_shape_sampled():
+    """Llama-3-70B gate/up shape (8192 -> 28672, r = 1024), cheap random operands; the oracle checks
+    every output of one token (about a second of CPU)."""
+    L = synth.random_layer(8192, 28672, 1024, synth.BF16, seed=4001)
+    X16, src = gu.tokens_for(L, 1, config=4)
+    tau = gu.calibrated_tau(L, src, 0.5)
+    _parity(L, X16, tau)
+    L2 = synth.random_layer(28672, 8192, 1024, synth.BF16, seed=4002)
+    X16, src = gu.tokens_for(L2, 2, kind="down", config=4)
+    tau = gu.calibrated_tau(L2, src, 0.5)
+    _parity(L2, X16, tau, out_dtype=rs.F32)

@@ -1,0 +1,113 @@
+"""CPU-only checks of the product's host code: the C ABI loads and exports every declared symbol,
+argument validation, threshold calibration against the oracle, the byte model, the host SVD."""
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2504_19449_amd as rs
+from paper_2504_19449_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "rsparse.h")).read()
+    declared = sorted(set(re.findall(r"\b(rsparse_[a-z_]+)\s*\(", header)))
+    lib = rs.load_library()
+    assert declared, "no declarations found"
+    for name in declared:
+        assert hasattr(lib, name), f"{name} is declared in rsparse.h but not exported"
+    assert sorted(rs.EXPORTED_SYMBOLS) == declared
+
+
+def test_product_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2504_19449_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".cpp", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                for pat in (r"^\s*(import|from)\s+oracle", r"librsparse_oracle", r"\borc_[a-z]", r"rsparse_oracle"):
+                    assert not re.search(pat, text, re.M), f"{f} reaches into the oracle ({pat})"
+
+
+@pytest.mark.parametrize("bad", [
+    dict(d_in=12), dict(d_out=0), dict(rank=-1), dict(rank=65), dict(max_batch=0), dict(max_batch=33),
+    dict(tau=float("nan")), dict(dtype=2), dict(out_dtype=0, dtype=1), dict(cmp_mode=2), dict(batch_mask_mode=-1),
+])
+def test_config_validation(bad):
+    kw = dict(d_in=64, d_out=64, rank=8, tau=0.5, dtype=rs.F16, max_batch=1)
+    kw.update(bad)
+    cfg = rs.make_config(kw["d_in"], kw["d_out"], kw["rank"], kw["tau"], kw["dtype"], max_batch=kw["max_batch"],
+                         out_dtype=kw.get("out_dtype"), cmp_mode=kw.get("cmp_mode", 0),
+                         batch_mask_mode=kw.get("batch_mask_mode", 0))
+    W = np.zeros((max(kw["d_out"], 1), max(kw["d_in"], 1)), dtype=np.uint16)
+    lib = rs.load_library()
+    import ctypes as C
+    h = C.c_void_p()
+    st = lib.rsparse_prepare_factors(C.byref(cfg), W.ctypes.data_as(C.c_void_p), None, None, C.byref(h))
+    assert st == 1 and h.value is None
+    assert rs.rsparse_last_error()
+
+
+def test_null_arguments_are_rejected():
+    import ctypes as C
+    lib = rs.load_library()
+    assert lib.rsparse_linear(None, None, 1, None, None) == 1
+    assert lib.rsparse_dense_ref(None, None, 1, None, None) == 1
+    assert lib.rsparse_last_active(None, 0, None, None) == 1
+    assert lib.rsparse_set_tau(None, 0.5) == 1
+    assert lib.rsparse_calibrate_tau(None, 0, 10, 0.5, None) == 1
+    assert lib.rsparse_required_bytes(None, 1, 1) == 0
+    lib.rsparse_destroy(None)
+
+
+@pytest.mark.parametrize("dt", [synth.F16, synth.BF16])
+@pytest.mark.parametrize("s", [0.0, 0.4, 0.5, 0.7, 1.0])
+def test_calibrate_tau_matches_the_oracle_bit_for_bit(dt, s):
+    src = synth.DModelInput(512, config=70, linear=dt)
+    X16 = synth.encode16(src.tokens(64, stream=synth.STREAM_CALIB), dt)
+    got = rs.rsparse_calibrate_tau(X16, dt, s)
+    want = oracle.quantile_tau(X16, dt, s)
+    assert got == want
+
+
+def test_compute_factors_weyl_and_eckart_young():
+    """Host SVD on W = U diag(sigma) V^T (rounded to 16 bit): singular values within ||E||_2 of the
+    closed form (Weyl), and the rank-r product attains the Eckart-Young error sum_{i>r} sigma_i^2.
+    A spectrum with a gap after r makes the truncation well conditioned."""
+    d_in, d_out, r = 192, 128, 24
+    p = min(d_in, d_out)
+    sigma = np.concatenate([np.linspace(2.0, 1.0, r), 0.3 * np.arange(1, p - r + 1) ** -0.6])
+    L = synth.make_layer(d_in, d_out, r, synth.BF16, config=71, linear=0, sigma=sigma)
+    cfg = rs.make_config(d_in, d_out, r, 0.5, synth.BF16)
+    U16, SV16, sig = rs.rsparse_compute_factors(cfg, L.W16)
+    Wd = synth.decode16(L.W16, L.dtype)
+    E = Wd - (L.U * L.sigma) @ L.V.T
+    assert np.max(np.abs(sig - sigma[:r])) <= np.linalg.norm(E, 2) * 1.01
+    s_true = np.linalg.svd(Wd, compute_uv=False)
+    assert np.allclose(sig, s_true[:r], rtol=1e-8)
+    approx = synth.decode16(U16, L.dtype) @ synth.decode16(SV16, L.dtype)
+    tail = np.sum(s_true[r:] ** 2)
+    err = np.linalg.norm(Wd - approx) ** 2
+    # the stored factors are rounded to bf16 (relative 2^-9 each): allow that on top of the optimum
+    slack = (2 * 2.0 ** -9) ** 2 * np.sum(s_true[:r] ** 2)
+    assert tail * (1 - 1e-9) <= err <= tail + 4 * slack
+    # U_r has orthonormal columns up to storage rounding
+    Ud = synth.decode16(U16, L.dtype)
+    assert np.max(np.abs(Ud.T @ Ud - np.eye(r))) < 0.02
+
+
+def test_compute_factors_power_law_spectrum_fp16():
+    L = synth.make_layer(160, 224, 20, synth.F16, config=71, linear=1)
+    cfg = rs.make_config(160, 224, 20, 0.5, synth.F16)
+    U16, SV16, sig = rs.rsparse_compute_factors(cfg, L.W16)
+    Wd = synth.decode16(L.W16, L.dtype)
+    s_true = np.linalg.svd(Wd, compute_uv=False)
+    assert np.allclose(sig, s_true[:20], rtol=1e-7)
+    approx = synth.decode16(U16, L.dtype) @ synth.decode16(SV16, L.dtype)
+    tail = np.sum(s_true[20:] ** 2)
+    assert np.linalg.norm(Wd - approx) ** 2 <= tail * 1.01 + 1e-6
