@@ -52,6 +52,13 @@ def load_library():
     if not os.path.exists(path):
         raise RuntimeError(f"{path} is missing: build it with `python -m paper_2504_19449_amd.build` "
                            "(there is no CPU fallback)")
+    try:
+        # One HIP runtime per process: PyTorch-ROCm bundles its own libamdhip64 (same SONAME as
+        # the one this library links).  Loading torch first makes both share torch's copy, so
+        # device pointers and streams made by torch are valid here.
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(path)
     vp, i32 = C.c_void_p, C.c_int32
     lib.rsparse_prepare.argtypes = [C.POINTER(Config), vp, C.POINTER(vp)]

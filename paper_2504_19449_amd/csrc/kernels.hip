@@ -40,7 +40,8 @@ __device__ __forceinline__ void unpack8(const u32x4 v, float (&f)[8])
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         if (DT == F16) {
-            h2 p = __builtin_bit_cast(h2, v[i]);
+            const uint32_t word = v[i];      // bit_cast needs a scalar copy, not a vector-element lvalue
+            h2 p = __builtin_bit_cast(h2, word);
             f[2 * i] = (float)p[0];          // v_cvt_f32_f16 keeps fp16 subnormals
             f[2 * i + 1] = (float)p[1];
         } else {
