@@ -1,0 +1,246 @@
+#!/usr/bin/env python3
+"""Benchmark of the R-Sparse linear layer on one MI355X.
+
+Workload (benchmark configs[1]): Llama-2-7B MLP shapes at batch 1, bf16, rank 512,
+50 % channel sparsity: gate and up (4096 -> 11008, heavy-tailed d_model input) and down
+(11008 -> 4096, SiLU(g)*u input).  One "step" = the three linears of one MLP block, each
+a full pass of the hot path (threshold, compaction, gather-GEMV, both low-rank products,
+sum, store).  Steps walk a ring of distinct prepared layers (> 1 GiB of weights) so that
+every weight byte comes from HBM, not from L2 / Infinity Cache, and are replayed from a
+captured HIP graph so that host launch overhead is not what is timed.  Inputs are resident
+in HBM before the timed region.
+
+Prints ONE JSON line.  `value` = microseconds per R-Sparse linear (whole-call, both
+launches).  `roofline` is for the dominant kernel (k_gather) timed alone with events;
+`cpu_baseline` is the fp64 CPU oracle timed on the host cores on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+RING_BLOCKS = 4            # MLP blocks in the ring: 12 layers, ~1.2 GiB of column-major weights
+RANK = 512
+D_MODEL, D_FF = 4096, 11008
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--sparsity", type=float, default=0.5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the sparsity sweep and per-kernel legs")
+    ap.add_argument("--eager", action="store_true", help="time eager launches instead of graph replay")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU by design (one MI355X); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2504_19449_amd as rs
+    from paper_2504_19449_amd import build as lib_build
+    from paper_2504_19449_amd import synth
+
+    if not os.path.exists(rs.library_path()):
+        lib_build.build(force=True)
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dt = synth.BF16
+
+    # ------------------------------------------------------------------ layers, tokens, thresholds
+    t0 = time.time()
+    specs = [("gate", D_MODEL, D_FF, 0, "dmodel"), ("up", D_MODEL, D_FF, 1, "dmodel"), ("down", D_FF, D_MODEL, 2, "down")]
+    base, sources, taus = {}, {}, {}
+    for name, d_in, d_out, lin, kind in specs:
+        base[name] = synth.make_layer(d_in, d_out, RANK, dt, config=1, linear=lin)
+        src = (synth.DModelInput if kind == "dmodel" else synth.DownInput)(d_in, config=1, linear=lin)
+        sources[name] = src
+        calib = synth.encode16(src.tokens(64, stream=synth.STREAM_CALIB), dt)
+        taus[name] = {s: rs.rsparse_calibrate_tau(calib, dt, s) for s in (0.4, 0.5, 0.7, args.sparsity)}
+        log(f"built {name} {d_in}->{d_out} ({time.time() - t0:.1f}s)")
+
+    ring = []       # (name, Layer handle, X device tensor, Y device tensor, synth layer)
+    perm_rng = np.random.Generator(np.random.PCG64(1999))
+    for blk in range(RING_BLOCKS):
+        for name, d_in, d_out, lin, kind in specs:
+            L = base[name] if blk == 0 else base[name].permuted_channels(perm_rng.permutation(d_in))
+            cfg = rs.make_config(d_in, d_out, RANK, taus[name][args.sparsity], dt, max_batch=1, dense_rowmajor=1)
+            layer = rs.rsparse_prepare_factors(cfg, L.W16, L.U16, L.SV16)
+            x = synth.encode16(sources[name].tokens(1, offset=1 + blk), dt)
+            xd = torch.from_numpy(x.view(np.int16)).cuda()
+            yd = torch.zeros((1, d_out), dtype=torch.int16, device="cuda")
+            ring.append((name, layer, xd, yd, L if blk == 0 else None, x))
+    torch.cuda.synchronize()
+    log(f"ring of {len(ring)} layers resident ({time.time() - t0:.1f}s)")
+    steps_per_pass = RING_BLOCKS
+    stream = torch.cuda.current_stream()
+
+    def set_all(**kw):
+        for _, layer, *_ in ring:
+            rs.rsparse_set_tuning(layer, **kw)
+
+    def pass_rsparse(sptr):
+        for _, layer, xd, yd, *_ in ring:
+            rs.rsparse_linear(layer, xd.data_ptr(), 1, yd.data_ptr(), sptr)
+
+    def pass_dense(sptr):
+        for _, layer, xd, yd, *_ in ring:
+            rs.rsparse_dense_ref(layer, xd.data_ptr(), 1, yd.data_ptr(), sptr)
+
+    def timed(pass_fn, steps, warmup, eager=False):
+        """ms per step over exactly `steps` steps (ring passes replayed from a HIP graph)."""
+        graph = None
+        if not eager:
+            pass_fn(stream.cuda_stream)                 # make sure everything is loaded before capture
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                pass_fn(torch.cuda.current_stream().cuda_stream)
+
+        def run(n_steps):
+            full, rem = divmod(n_steps, steps_per_pass)
+            for _ in range(full):
+                graph.replay() if graph is not None else pass_fn(stream.cuda_stream)
+            for i in range(rem * 3):                    # leftover steps: eager, first layers of the ring
+                _, layer, xd, yd, *_ = ring[i]
+                (rs.rsparse_linear if pass_fn is pass_rsparse else rs.rsparse_dense_ref)(
+                    layer, xd.data_ptr(), 1, yd.data_ptr(), stream.cuda_stream)
+
+        run(warmup)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        run(steps)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    # ------------------------------------------------------------------ parity sanity on the timed configuration
+    import oracle
+    pass_rsparse(stream.cuda_stream)
+    torch.cuda.synchronize()
+    k_of = []
+    for name, layer, xd, yd, L, x in ring:
+        k_of.append(len(rs.rsparse_last_active(layer, -1)))
+        if L is not None:
+            want = oracle.rsparse_linear(L.W16, L.U16, L.SV16, x, dt, dt, taus[name][args.sparsity], nthreads=16)
+            got = synth.decode16(yd.cpu().numpy().view(np.uint16), dt)
+            rel = np.linalg.norm(got - want["Y"]) / np.linalg.norm(want["Y"])
+            assert np.array_equal(rs.rsparse_last_active(layer, 0), want["act"][0]), f"{name}: kept list differs"
+            assert rel <= 2e-3, f"{name}: rel L2 {rel}"
+    log(f"parity ok on the timed configuration; kept channels per layer: {k_of}")
+
+    req_bytes = [rs.rsparse_required_bytes(layer, 1, k) for (_, layer, *_), k in zip(ring, k_of)]
+    dense_bytes = [rs.rsparse_dense_bytes(layer, 1) for _, layer, *_ in ring]
+    n_lin = len(ring)
+
+    # ------------------------------------------------------------------ the timed legs
+    ms_step = timed(pass_rsparse, args.steps, args.warmup, eager=args.eager)
+    us_linear = ms_step * 1000.0 / 3.0
+    gbs_required = (sum(req_bytes) / n_lin) / (us_linear * 1e-6) / 1e9
+    log(f"rsparse: {us_linear:.2f} us/linear, {gbs_required:.0f} GB/s on required bytes")
+
+    extras = {}
+    # dominant kernel alone (k_sparse_and_t, the first launch): algorithmic bytes = kept W columns
+    # + S_r V_r^T + X; the second launch (k_finish) moves U_r + Y.
+    set_all(stages=1)
+    ms_g = timed(pass_rsparse, args.steps, args.warmup)
+    set_all(stages=2)
+    ms_t = timed(pass_rsparse, args.steps, args.warmup)
+    set_all(stages=0)
+    us_gather = ms_g * 1000.0 / 3.0
+    gather_bytes = []
+    for (_, layer, *_), k in zip(ring, k_of):
+        c = layer.cfg
+        gather_bytes.append(2 * (k * c.d_out + c.rank * c.d_in + c.d_in))
+    achieved = (sum(gather_bytes) / n_lin) / (us_gather * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "kernel": "k_sparse_and_t", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "us_per_launch": round(us_gather, 3), "bytes_per_launch": int(sum(gather_bytes) / n_lin)}
+    extras["us_k_finish_alone"] = round(ms_t * 1000.0 / 3.0, 3)
+
+    # dense GEMV baseline, both hand-written kernels; best one is the baseline
+    dense_us = {}
+    for label, kern in (("rowdot", 2), ("axpy", 1)):
+        set_all(dense_kernel=kern)
+        dense_us[label] = timed(pass_dense, args.steps, args.warmup) * 1000.0 / 3.0
+    set_all(dense_kernel=0)
+    best_dense = min(dense_us.values())
+    dense_gbs = (sum(dense_bytes) / n_lin) / (best_dense * 1e-6) / 1e9
+    log(f"dense: {dense_us}, {dense_gbs:.0f} GB/s; speed-up {best_dense / us_linear:.2f}x")
+
+    if not args.no_extras:
+        sweep = {}
+        for s in (0.4, 0.7):
+            for name, layer, *_ in ring:
+                rs.rsparse_set_tau(layer, taus[name][s])
+            pass_rsparse(stream.cuda_stream)
+            torch.cuda.synchronize()
+            ks = [len(rs.rsparse_last_active(layer, -1)) for _, layer, *_ in ring]
+            rb = [rs.rsparse_required_bytes(layer, 1, k) for (_, layer, *_), k in zip(ring, ks)]
+            us = timed(pass_rsparse, args.steps, args.warmup) * 1000.0 / 3.0
+            sweep[f"{int(s * 100)}%"] = {"us_per_linear": round(us, 3),
+                                         "gbs_required": round((sum(rb) / n_lin) / (us * 1e-6) / 1e9, 1),
+                                         "speedup_vs_dense": round(best_dense / us, 3)}
+        for name, layer, *_ in ring:
+            rs.rsparse_set_tau(layer, taus[name][args.sparsity])
+        extras["sparsity_sweep"] = sweep
+        extras["us_per_linear_eager_launches"] = round(timed(pass_rsparse, args.steps, args.warmup, eager=True) * 1000 / 3, 3)
+
+    # ------------------------------------------------------------------ CPU oracle baseline (bounded sample)
+    cpu = None
+    if not args.no_cpu_baseline:
+        threads = min(oracle.max_threads(), os.cpu_count() or 1, 16)
+        t_cpu, n_calls = 0.0, 0
+        t_begin = time.time()
+        while time.time() - t_begin < 12.0 and n_calls < 30:
+            for name, layer, xd, yd, L, x in ring[:3]:
+                t1 = time.time()
+                oracle.rsparse_linear(L.W16, L.U16, L.SV16, x, dt, dt, taus[name][args.sparsity], nthreads=threads)
+                t_cpu += time.time() - t1
+                n_calls += 1
+        cpu = {"value": round(t_cpu / n_calls * 1e6, 1), "unit": "us", "cores": threads, "kind": "oracle",
+               "sample": f"{n_calls} R-Sparse linear calls (gate, up, down of one block, batch 1, same tokens and "
+                         f"thresholds as the GPU run), fp64 C oracle with OpenMP over outputs"}
+
+    out = {
+        "metric": "us_per_rsparse_linear_batch1", "value": round(us_linear, 3), "unit": "us",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 5),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[1]: Llama-2-7B MLP gate/up (4096->11008) + down (11008->4096), bf16, "
+                               "batch 1, rank 512, channel sparsity %.0f%%; step = the 3 linears of one block; "
+                               "ring of %d distinct layers; %s" % (args.sparsity * 100, n_lin,
+                                                                 "eager launches" if args.eager else "HIP-graph replay"),
+                   "batch": 1, "rank": RANK, "sparsity": args.sparsity,
+                   "kept_channels_mean": round(float(np.mean(k_of)), 1)},
+        "hbm_gbs_on_required_bytes": round(gbs_required, 1),
+        "hbm_frac_on_required_bytes": round(gbs_required / HBM_PEAK_GBS, 4),
+        "required_bytes_per_linear": int(sum(req_bytes) / n_lin),
+        "dense_gemv_us": {k: round(v, 3) for k, v in dense_us.items()},
+        "dense_gemv_gbs": round(dense_gbs, 1),
+        "speedup_vs_dense_gemv": round(best_dense / us_linear, 3),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    out.update(extras)
+    print(json.dumps(out), flush=True)
+    for _, layer, *_ in ring:
+        layer.destroy()
+
+
+if __name__ == "__main__":
+    main()

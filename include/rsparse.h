@@ -58,7 +58,7 @@ typedef enum {
 typedef struct {
     int32_t d_in;            /* input channels; multiple of 8 */
     int32_t d_out;           /* output features; multiple of 8 */
-    int32_t rank;            /* r in [0, min(d_in, d_out)]; 0 = sparse part only */
+    int32_t rank;            /* r in [0, min(d_in, d_out)], multiple of 8; 0 = sparse part only */
     int32_t max_batch;       /* 1..RSPARSE_MAX_BATCH; scratch is sized for it */
     float   tau;             /* threshold t(s) (Sec. 3.4); fp32 so that the compare is exact.
                                 -INFINITY keeps every channel, +INFINITY none; NaN is rejected */
@@ -75,10 +75,12 @@ typedef struct {
 typedef struct {
     int32_t splits;          /* channel splits per column tile of the gather / dense-axpy kernels */
     int32_t waves;           /* waves (of 64 lanes) per workgroup in those kernels: 1, 2, 4 or 8 */
-    int32_t lowrank_rows;    /* rows of S_r V_r^T per workgroup in the stage-1 kernel */
+    int32_t lowrank_rows;    /* rows of S_r V_r^T per stage-1 workgroup */
     int32_t dense_kernel;    /* rsparse_dense_ref: 0 auto, 1 axpy over column-major W, 2 row-dot */
     int32_t nontemporal;     /* 1: stream weights with non-temporal loads */
-    int32_t reserved[3];
+    int32_t stages;          /* rsparse_linear: 0 both launches, 1 first launch only, 2 second only -- for
+                                timing one kernel in isolation; results are only valid with 0 */
+    int32_t reserved[2];
 } rsparse_tuning;
 
 /*

@@ -27,7 +27,8 @@ class Config(C.Structure):
 
 class Tuning(C.Structure):
     _fields_ = [("splits", C.c_int32), ("waves", C.c_int32), ("lowrank_rows", C.c_int32),
-                ("dense_kernel", C.c_int32), ("nontemporal", C.c_int32), ("reserved", C.c_int32 * 3)]
+                ("dense_kernel", C.c_int32), ("nontemporal", C.c_int32), ("stages", C.c_int32),
+                ("reserved", C.c_int32 * 2)]
 
 
 class RSparseError(RuntimeError):

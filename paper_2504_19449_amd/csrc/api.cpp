@@ -123,9 +123,9 @@ struct rsparse_layer {
     rsparse_tuning tuning{};
     int device = 0;
     int cus = 256;
-    uint16_t *M = nullptr, *SVt = nullptr, *Wrow = nullptr;
+    uint16_t *M = nullptr, *SVt = nullptr, *U = nullptr, *Wrow = nullptr;
     float *t = nullptr, *yacc = nullptr;
-    uint32_t *tile_done = nullptr, *act_bits = nullptr;
+    uint32_t *act_bits = nullptr;
     int32_t *act_list = nullptr, *act_count = nullptr;
     int tiles = 0, nz_max = 1;
     std::vector<uint16_t> U16, SV16;       // host copies of the stored factors
@@ -135,7 +135,7 @@ struct rsparse_layer {
     LayerView view() const
     {
         LayerView v{};
-        v.M = M; v.SVt = SVt; v.Wrow = Wrow; v.t = t; v.yacc = yacc; v.tile_done = tile_done;
+        v.M = M; v.SVt = SVt; v.U = U; v.Wrow = Wrow; v.t = t; v.yacc = yacc;
         v.act_list = act_list; v.act_bits = act_bits; v.act_count = act_count;
         v.d_in = cfg.d_in; v.d_out = cfg.d_out; v.rank = cfg.rank;
         v.dtype = cfg.dtype; v.out_dtype = cfg.out_dtype; v.cmp_mode = cfg.cmp_mode;
@@ -154,8 +154,8 @@ rsparse_status check_config(const rsparse_config *c)
     if (c->d_in < 8 || c->d_out < 8 || (c->d_in % 8) || (c->d_out % 8))
         return fail(RSPARSE_EINVAL, "d_in and d_out must be positive multiples of 8 (got %d, %d)", c->d_in, c->d_out);
     if (c->d_in > (1 << 20) || c->d_out > (1 << 20)) return fail(RSPARSE_EINVAL, "dimension too large");
-    if (c->rank < 0 || c->rank > std::min(c->d_in, c->d_out))
-        return fail(RSPARSE_EINVAL, "rank %d outside [0, min(d_in, d_out)]", c->rank);
+    if (c->rank < 0 || c->rank > std::min(c->d_in, c->d_out) || (c->rank % 8))
+        return fail(RSPARSE_EINVAL, "rank %d must be a multiple of 8 in [0, min(d_in, d_out)]", c->rank);
     if (c->max_batch < 1 || c->max_batch > RSPARSE_MAX_BATCH)
         return fail(RSPARSE_EINVAL, "max_batch %d outside [1, %d]", c->max_batch, RSPARSE_MAX_BATCH);
     if (std::isnan(c->tau)) return fail(RSPARSE_EINVAL, "tau is NaN");
@@ -170,6 +170,7 @@ rsparse_status check_config(const rsparse_config *c)
 
 // Launch shape: column tiles x channel splits ~ a few workgroups per compute unit, each with
 // enough rows to amortise its scan, and the staged share small enough for 64 KiB of LDS.
+// Stage-1 workgroups get about as many bytes of S_r V_r^T as a gather workgroup gets of W.
 Launch resolve_launch(const rsparse_layer *L, int batch, bool dense)
 {
     Launch c{};
@@ -177,21 +178,23 @@ Launch resolve_launch(const rsparse_layer *L, int batch, bool dense)
     const int bt = batch_tile_of(batch);
     c.waves = (t.waves == 1 || t.waves == 2 || t.waves == 4 || t.waves == 8) ? t.waves : 4;
     c.nontemporal = t.nontemporal ? 1 : 0;
-    const int rows = dense ? L->cfg.d_in : L->cfg.d_in / 2 + L->cfg.rank;   // expected rows to stream
+    const int rows = dense ? L->cfg.d_in : std::max(8, L->cfg.d_in / 2);     // expected rows to stream
     int splits = t.splits;
     if (splits <= 0) {
-        const int target_wgs = 2 * L->cus;
+        const int target_wgs = 4 * L->cus;
         splits = (target_wgs + L->tiles - 1) / L->tiles;
         const int max_by_rows = std::max(1, rows / (c.waves * 4));          // >= 4 rows per wave
         splits = std::max(1, std::min(splits, max_by_rows));
     }
     splits = std::min(splits, 4096);
-    const int rank = dense ? 0 : L->cfg.rank;
-    (void)rank;
-    while (gather_lds_bytes(L->cfg.d_in, L->cfg.rank, splits, c.waves, bt) > 60 * 1024) splits *= 2;
+    while (gather_lds_bytes(L->cfg.d_in, splits, c.waves, bt) > 60 * 1024) splits *= 2;
     c.splits = splits;
     int lr = t.lowrank_rows;
-    if (lr != 1 && lr != 2 && lr != 4) lr = (L->cfg.rank > 4 * L->cus) ? 4 : (L->cfg.rank > 2 * L->cus ? 2 : 1);
+    if (lr <= 0) {
+        const double wg_bytes = (double)rows / splits * kTile * 2.0;          // W bytes of one gather workgroup
+        lr = (int)(wg_bytes / (2.0 * L->cfg.d_in) + 0.5);
+        lr = std::max(1, std::min(lr, 64));
+    }
     c.lowrank_rows = lr;
     return c;
 }
@@ -209,8 +212,8 @@ rsparse_status check_call(rsparse_layer *L, const void *X, int32_t batch, void *
 void free_layer(rsparse_layer *L)
 {
     if (!L) return;
-    (void)hipFree(L->M); (void)hipFree(L->SVt); (void)hipFree(L->Wrow); (void)hipFree(L->t);
-    (void)hipFree(L->yacc); (void)hipFree(L->tile_done); (void)hipFree(L->act_bits);
+    (void)hipFree(L->M); (void)hipFree(L->SVt); (void)hipFree(L->U); (void)hipFree(L->Wrow); (void)hipFree(L->t);
+    (void)hipFree(L->yacc); (void)hipFree(L->act_bits);
     (void)hipFree(L->act_list); (void)hipFree(L->act_count);
     delete L;
 }
@@ -232,20 +235,21 @@ rsparse_status build_layer(const rsparse_config *cfg, const uint16_t *W, const u
         RS_HIP(hipGetDeviceProperties(&prop, L->device));
         L->cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
 
-        // pack: rows 0..d_in-1 = W^T (column-major W), rows d_in.. = U_r^T
+        // pack W column-major: row c of M = W[:, c]
         std::vector<uint16_t> host;
         try {
-            host.resize((d_in + r) * d_out);
+            host.resize(d_in * d_out);
             if (r) { L->U16.assign(U16, U16 + d_out * r); L->SV16.assign(SV16, SV16 + r * d_in); }
         } catch (const std::bad_alloc &) { return fail(RSPARSE_ENOMEM, "host allocation failed"); }
         transpose16(W, d_out, d_in, host.data());
-        if (r) transpose16(U16, d_out, r, host.data() + d_in * d_out);
 
         RS_HIP(hipMalloc((void **)&L->M, host.size() * 2));
         RS_HIP(hipMemcpy(L->M, host.data(), host.size() * 2, hipMemcpyHostToDevice));
         if (r) {
             RS_HIP(hipMalloc((void **)&L->SVt, r * d_in * 2));
             RS_HIP(hipMemcpy(L->SVt, SV16, r * d_in * 2, hipMemcpyHostToDevice));
+            RS_HIP(hipMalloc((void **)&L->U, d_out * r * 2));
+            RS_HIP(hipMemcpy(L->U, U16, d_out * r * 2, hipMemcpyHostToDevice));
         }
         if (cfg->dense_rowmajor) {
             RS_HIP(hipMalloc((void **)&L->Wrow, d_in * d_out * 2));
@@ -254,17 +258,14 @@ rsparse_status build_layer(const rsparse_config *cfg, const uint16_t *W, const u
         const size_t bpad = (size_t)L->nz_max * kMaxBT;
         const size_t n_t = std::max<size_t>(1, r * bpad);
         const size_t n_y = (size_t)cfg->max_batch * d_out;
-        const size_t n_done = (size_t)L->nz_max * L->tiles;
         const size_t n_list = (size_t)L->nz_max * d_in;
         RS_HIP(hipMalloc((void **)&L->t, n_t * 4));
         RS_HIP(hipMalloc((void **)&L->yacc, n_y * 4));
-        RS_HIP(hipMalloc((void **)&L->tile_done, n_done * 4));
         RS_HIP(hipMalloc((void **)&L->act_list, n_list * 4));
         RS_HIP(hipMalloc((void **)&L->act_bits, n_list * 4));
         RS_HIP(hipMalloc((void **)&L->act_count, (size_t)L->nz_max * 4));
         RS_HIP(hipMemset(L->t, 0, n_t * 4));
         RS_HIP(hipMemset(L->yacc, 0, n_y * 4));
-        RS_HIP(hipMemset(L->tile_done, 0, n_done * 4));
         RS_HIP(hipMemset(L->act_list, 0, n_list * 4));
         RS_HIP(hipMemset(L->act_bits, 0, n_list * 4));
         RS_HIP(hipMemset(L->act_count, 0, (size_t)L->nz_max * 4));
@@ -355,8 +356,8 @@ rsparse_status rsparse_linear(rsparse_layer *L, const void *X_dev, int32_t batch
     hipStream_t s = (hipStream_t)stream;
     const Launch lc = resolve_launch(L, batch, false);
     const LayerView v = L->view();
-    RS_HIP(launch_lowrank_t(v, lc, X_dev, batch, s));
-    RS_HIP(launch_gather(v, lc, X_dev, batch, Y_dev, s));
+    if (L->tuning.stages != 2) RS_HIP(launch_sparse_and_t(v, lc, X_dev, batch, true, true, s));
+    if (L->tuning.stages != 1) RS_HIP(launch_finish(v, batch, Y_dev, true, s));
     L->last_stream = s;
     L->last_batch = batch;
     return RSPARSE_OK;
@@ -446,6 +447,7 @@ rsparse_status rsparse_set_tuning(rsparse_layer *L, const rsparse_tuning *t)
     if (!L || !t) return fail(RSPARSE_EINVAL, "NULL argument");
     if (t->splits < 0 || t->waves < 0 || t->lowrank_rows < 0 || t->dense_kernel < 0 || t->dense_kernel > 2)
         return fail(RSPARSE_EINVAL, "negative or unknown tuning value");
+    if (t->stages < 0 || t->stages > 2) return fail(RSPARSE_EINVAL, "stages must be 0, 1 or 2");
     if (t->waves != 0 && t->waves != 1 && t->waves != 2 && t->waves != 4 && t->waves != 8)
         return fail(RSPARSE_EINVAL, "waves must be 0, 1, 2, 4 or 8");
     L->tuning = *t;

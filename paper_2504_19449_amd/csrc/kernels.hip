@@ -3,22 +3,22 @@
 // Everything here is bound by HBM bandwidth at decode batch sizes (2*B flops per 2-byte
 // weight), so the kernels are organised around the weight stream: 16-byte loads, one
 // 1 KiB row segment per 64-lane wave, many rows in flight, fp32 accumulation on the
-// vector ALU.  Three storage layouts make all three products the same primitive
-// "out[0:N] += coef_j * row_j[0:N]" or a plain row dot:
+// vector ALU.  Storage:
 //
-//   M    [d_in + r][d_out]   rows 0..d_in-1: W column-major (row c = all outputs of input
-//                            channel c; Sec. 3.4 asks for this layout so a kept channel is one
-//                            contiguous run); rows d_in..: U_r^T.  One row index space for both.
-//   SVt  [r][d_in]           S_r V_r^T, one singular component per row.
+//   M    [d_in][d_out]   W column-major (row c = all outputs of input channel c; Sec. 3.4 asks
+//                        for this layout so that a kept channel is one contiguous run)
+//   SVt  [r][d_in]       S_r V_r^T, one singular component per row
+//   U    [d_out][r]      U_r row-major
 //
-//   stage 1 (k_lowrank_t)  t_i = SVt[i,:] . (x - sigma_t(x))           one workgroup per few rows
-//   stage 2 (k_gather)     y   = sum_{c kept} x_c M[c,:] + sum_i t_i M[d_in+i,:]
+// One call is two launches, ordered by the stream (no intra-kernel cross-workgroup waits):
 //
-// k_gather thresholds and compacts x itself (every workgroup scans the whole token -- 2*d_in
-// bytes from L2 -- and keeps only its balanced share of the ascending kept list), so there
-// is no separate compaction launch and no cross-workgroup dependency before the stream starts.
-// Column tiles x channel splits fill the chip; partial sums meet in fp32 atomics, and the
-// last workgroup to arrive at a column tile rounds it once and stores Y.
+//   k_sparse_and_t   workgroups [0, lr_wgs):  t_i = SVt[i,:] . (x - sigma_t(x))      (row dots)
+//                    the others:              yacc += sum_{c kept} x_c M[c,:]         (gather-axpy)
+//                    Each gather workgroup thresholds and compacts x itself (it scans the whole
+//                    token -- 2*d_in bytes from L2 -- and keeps its balanced share of the ascending
+//                    kept list), so there is no compaction launch.  Column tiles x channel splits
+//                    fill the chip; partial sums meet in fp32 atomics.
+//   k_finish         Y = round(yacc + U t)   (row dots over U, no reduction), yacc re-zeroed.
 #include "kernels.h"
 
 namespace rsparse {
@@ -213,19 +213,19 @@ __device__ __forceinline__ void stream_rows(const uint16_t *__restrict__ M, size
     }
 }
 
-// Cross-wave reduction of a column tile through LDS, fp32 atomics into yacc, and -- for the last
-// workgroup to arrive at this (batch tile, column tile) -- one rounding and the store of Y.
-// yacc and the arrival counter are left zero for the next call.
+// Cross-wave reduction of a column tile through LDS, then fp32 atomics into yacc.  No fences and no
+// arrival counters: the kernel boundary before k_finish orders the atomics (an agent-scope fence
+// per workgroup costs an L2 write-back + invalidate on this chip and dominated the run time).
 template <int BT>
-__device__ __forceinline__ void reduce_and_finish(float (&acc)[BT][8], float *s_red, int *s_flag,
-                                                  float *yacc, uint32_t *done_ctr, void *Y, int out_dtype,
-                                                  int b0, int nb, int d_out, int tile, int splits)
+__device__ __forceinline__ void reduce_to_yacc(float (&acc)[BT][8], float *s_red, float *yacc, int b0, int nb,
+                                               int d_out, int tile)
 {
     const int tid = threadIdx.x, nthr = blockDim.x, lane = tid & 63, w = tid >> 6, nw = nthr >> 6;
     const int colbase = tile * kTile;
     for (int b = 0; b < nb; ++b) {
         float *yrow = yacc + (size_t)(b0 + b) * d_out;
         if (nw > 1) {
+            if (b > 0) __syncthreads();
             float4 *dst = reinterpret_cast<float4 *>(s_red + w * kTile + lane * 8);
             dst[0] = float4{acc[b][0], acc[b][1], acc[b][2], acc[b][3]};
             dst[1] = float4{acc[b][4], acc[b][5], acc[b][6], acc[b][7]};
@@ -236,7 +236,6 @@ __device__ __forceinline__ void reduce_and_finish(float (&acc)[BT][8], float *s_
                 if (colbase + col < d_out)
                     __hip_atomic_fetch_add(yrow + colbase + col, s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-            __syncthreads();
         } else {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -247,39 +246,16 @@ __device__ __forceinline__ void reduce_and_finish(float (&acc)[BT][8], float *s_
             }
         }
     }
-    // Arrival: make this workgroup's atomics visible, then count in.
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        uint32_t old = __hip_atomic_fetch_add(done_ctr, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        *s_flag = (old == (uint32_t)(splits - 1));
-    }
-    __syncthreads();
-    if (*s_flag) {
-        __threadfence();
-        for (int b = 0; b < nb; ++b) {
-            float *yrow = yacc + (size_t)(b0 + b) * d_out;
-            for (int col = tid; col < kTile; col += nthr) {
-                const int gc = colbase + col;
-                if (gc < d_out) {
-                    float v = __hip_atomic_load(yrow + gc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    store_out(Y, (size_t)(b0 + b) * d_out + gc, v, out_dtype);
-                    __hip_atomic_store(yrow + gc, 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
-            }
-        }
-        if (tid == 0) __hip_atomic_store(done_ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
 }
 
 struct GatherArgs {
     LayerView L;
     const uint16_t *X;
-    void *Y;
     int batch, splits, tiles, cap;
+    int lr_wgs, lr_rows, lr_chunk;     // stage-1 workgroups at the front of the grid, rows each, LDS chunk
 };
 
-// LDS carve-up shared by k_gather and k_dense_axpy.
+// LDS carve-up of the gather part.
 struct GatherLds {
     int *idx;
     float *coef;
@@ -297,20 +273,114 @@ __device__ __forceinline__ GatherLds carve(unsigned char *smem, int cap, int bt,
 }
 
 // ---------------------------------------------------------------------------------------------
-// Steps 1-2 and 4-5 of the layer in one launch: sparsification mask and ascending kept-channel
-// list (Sec. 3.4, sigma_t), the sparse part over the kept columns of W, the second low-rank
-// product U_r t, their sum and the single rounding.
-// grid.x = tiles * splits, grid.z = batch tiles of BT tokens, block = 64 * waves.
+// Stage 1 of the low-rank part (Sec. 3.4): t_i = sum_c (S_r V_r^T)[i, c] * (x - sigma_t(x))_c.
+// A workgroup stages the masked token(s) in LDS (kept channels zeroed) and dots its rows of
+// S_r V_r^T against them, RU rows at a time; a row is complete inside one workgroup, so t needs
+// no cross-workgroup sum and no zeroing.  t is stored [batch tile][token][rank].
+// ---------------------------------------------------------------------------------------------
+template <int DT, int BT>
+__device__ __forceinline__ void lowrank_rows(const GatherArgs &a, unsigned char *smem, int wg, int z)
+{
+    constexpr int RU = 4;
+    const int tid = threadIdx.x, nthr = blockDim.x, lane = tid & 63, w = tid >> 6, nw = nthr >> 6;
+    const LayerView &L = a.L;
+    const int d_in = L.d_in, r = L.rank;
+    const int b0 = z * BT;
+    const int nb = min(BT, a.batch - b0);
+    const bool union_all = L.batch_mask_mode == 1;
+    uint16_t *s_xm = reinterpret_cast<uint16_t *>(smem);                           // [BT][chunk]
+    float *s_part = reinterpret_cast<float *>(smem + (size_t)BT * a.lr_chunk * 2); // [8 waves][RU*BT]
+    const int row_lo = wg * a.lr_rows, row_hi = min(r, row_lo + a.lr_rows);
+    const bool single_chunk = a.lr_chunk >= d_in;
+
+    for (int i0 = row_lo; i0 < row_hi; i0 += RU) {
+        float part[RU][BT];
+#pragma unroll
+        for (int ru = 0; ru < RU; ++ru)
+#pragma unroll
+            for (int b = 0; b < BT; ++b) part[ru][b] = 0.f;
+
+        for (int c0 = 0; c0 < d_in; c0 += a.lr_chunk) {
+            const int len = min(a.lr_chunk, d_in - c0);
+            if (!(single_chunk && i0 > row_lo)) {          // the masked token stays staged across row groups
+                __syncthreads();
+                for (int q = tid; q < len / 8; q += nthr) {
+                    u32x4 raw[BT]; float xv[BT][8]; uint32_t m[BT];
+                    load_tokens8<DT, BT>(a.X, a.batch, b0, nb, d_in, c0 + q * 8, L.tau, L.cmp_mode, union_all, raw, xv, m);
+#pragma unroll
+                    for (int b = 0; b < BT; ++b) {
+                        u32x4 o = raw[b];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if ((m[b] >> e) & 1u) o[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;   // kept -> 0
+                        *reinterpret_cast<u32x4 *>(s_xm + (size_t)b * a.lr_chunk + q * 8) = o;
+                    }
+                }
+                __syncthreads();
+            }
+            for (int q = tid; q < len / 8; q += nthr) {
+                u32x4 v[RU];
+#pragma unroll
+                for (int ru = 0; ru < RU; ++ru)
+                    v[ru] = (i0 + ru < row_hi) ? ldg16<false>(L.SVt + (size_t)(i0 + ru) * d_in + c0 + q * 8)
+                                               : u32x4{0, 0, 0, 0};
+                float xf[BT][8];
+#pragma unroll
+                for (int b = 0; b < BT; ++b)
+                    unpack8<DT>(*reinterpret_cast<const u32x4 *>(s_xm + (size_t)b * a.lr_chunk + q * 8), xf[b]);
+#pragma unroll
+                for (int ru = 0; ru < RU; ++ru) {
+                    float f[8];
+                    unpack8<DT>(v[ru], f);
+#pragma unroll
+                    for (int b = 0; b < BT; ++b)
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) part[ru][b] = __builtin_fmaf(f[e], xf[b][e], part[ru][b]);
+                }
+            }
+        }
+        __syncthreads();                                    // s_part is free again
+#pragma unroll
+        for (int ru = 0; ru < RU; ++ru)
+#pragma unroll
+            for (int b = 0; b < BT; ++b) {
+                float v = wave_sum(part[ru][b]);
+                if (lane == 0) s_part[w * (RU * BT) + ru * BT + b] = v;
+            }
+        __syncthreads();
+        if (tid < RU * BT) {
+            const int ru = tid / BT, b = tid % BT;
+            if (i0 + ru < row_hi) {
+                float v = 0.f;
+                for (int i = 0; i < nw; ++i) v += s_part[i * (RU * BT) + tid];
+                L.t[((size_t)z * BT + b) * r + i0 + ru] = v;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// First launch of the layer.  Workgroups [0, lr_wgs) compute stage 1 of the low-rank part; the
+// others do steps 1-2 of the sparse part: sparsification mask and ascending kept-channel list
+// (Sec. 3.4, sigma_t) -- every workgroup scans the whole token and keeps its balanced share --
+// then the gather-GEMV over the kept columns of W, accumulated into yacc with fp32 atomics.
+// The two groups are independent, so they share one launch.
+// grid.x = lr_wgs + tiles * splits, grid.z = batch tiles of BT tokens, block = 64 * waves.
 // ---------------------------------------------------------------------------------------------
 template <int DT, int BT, bool NT>
-__global__ __launch_bounds__(512) void k_gather(const GatherArgs a)
+__global__ __launch_bounds__(512) void k_sparse_and_t(const GatherArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    const int tid = threadIdx.x, nthr = blockDim.x, lane = tid & 63, w = tid >> 6, nw = nthr >> 6;
     const int z = blockIdx.z;
-    const int tile = blockIdx.x % a.tiles, split = blockIdx.x / a.tiles;
+    if ((int)blockIdx.x < a.lr_wgs) {
+        lowrank_rows<DT, BT>(a, smem, blockIdx.x, z);
+        return;
+    }
+    const int tid = threadIdx.x, nthr = blockDim.x, lane = tid & 63, w = tid >> 6, nw = nthr >> 6;
+    const int g = blockIdx.x - a.lr_wgs;
+    const int tile = g % a.tiles, split = g / a.tiles;
     const LayerView &L = a.L;
-    const int d_in = L.d_in, d_out = L.d_out, r = L.rank;
+    const int d_in = L.d_in, d_out = L.d_out;
     const int b0 = z * BT;
     const int nb = min(BT, a.batch - b0);
     const bool union_all = L.batch_mask_mode == 1;
@@ -328,12 +398,10 @@ __global__ __launch_bounds__(512) void k_gather(const GatherArgs a)
     int k;
     int pos = block_exclusive_scan(cnt, s.misc, k);
 
-    // ---- my balanced share of the kept list and of the U_r^T rows
+    // ---- my balanced share of the kept list
     const int lo = (int)(((long long)split * k) / a.splits);
     const int hi = (int)(((long long)(split + 1) * k) / a.splits);
-    const int ulo = (int)(((long long)split * r) / a.splits);
-    const int uhi = (int)(((long long)(split + 1) * r) / a.splits);
-    const int nW = hi - lo, nU = uhi - ulo, n = nW + nU;
+    const int n = hi - lo;
 
     if (cnt > 0 && pos < hi && pos + cnt > lo) {
         for (int c = c_begin; c < c_end; c += 8) {
@@ -362,12 +430,6 @@ __global__ __launch_bounds__(512) void k_gather(const GatherArgs a)
             }
         }
     }
-    for (int j = tid; j < nU; j += nthr) {
-        s.idx[nW + j] = d_in + ulo + j;
-#pragma unroll
-        for (int b = 0; b < BT; ++b)
-            s.coef[(nW + j) * BT + b] = L.t[((size_t)z * r + ulo + j) * BT + b];
-    }
     if (tile == 0 && split == 0 && tid == 0) L.act_count[z] = k;
     __syncthreads();
 
@@ -380,13 +442,12 @@ __global__ __launch_bounds__(512) void k_gather(const GatherArgs a)
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[b][e] = 0.f;
     stream_rows<DT, BT, NT>(L.M, (size_t)d_out, col, colok, s.idx, s.coef, n, w, nw, acc);
-
-    reduce_and_finish<BT>(acc, s.red, s.misc + 15, L.yacc, L.tile_done + (size_t)z * a.tiles + tile, a.Y,
-                          L.out_dtype, b0, nb, d_out, tile, a.splits);
+    reduce_to_yacc<BT>(acc, s.red, L.yacc, b0, nb, d_out, tile);
 }
 
 // ---------------------------------------------------------------------------------------------
 // Dense baseline, axpy form over the same column-major W: every channel, no mask, no low rank.
+// Followed by k_finish with rank 0.
 // ---------------------------------------------------------------------------------------------
 template <int DT, int BT, bool NT>
 __global__ __launch_bounds__(512) void k_dense_axpy(const GatherArgs a)
@@ -426,94 +487,73 @@ __global__ __launch_bounds__(512) void k_dense_axpy(const GatherArgs a)
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[b][e] = 0.f;
     stream_rows<DT, BT, NT>(L.M, (size_t)d_out, col, colok, s.idx, s.coef, n, w, nw, acc);
-
-    reduce_and_finish<BT>(acc, s.red, s.misc + 15, L.yacc, L.tile_done + (size_t)z * a.tiles + tile, a.Y,
-                          L.out_dtype, b0, nb, d_out, tile, a.splits);
+    reduce_to_yacc<BT>(acc, s.red, L.yacc, b0, nb, d_out, tile);
 }
 
 // ---------------------------------------------------------------------------------------------
-// Stage 1 of the low-rank part (Sec. 3.4): t_i = sum_c (S_r V_r^T)[i, c] * (x - sigma_t(x))_c.
-// Each workgroup stages the masked token(s) in LDS (kept channels zeroed) and dots RU rows of
-// S_r V_r^T against it; a row is complete inside one workgroup, so t needs no cross-workgroup sum.
-// grid.x = ceil(r / RU), grid.z = batch tiles, block = 256.
+// Second launch: steps 3b-4 of the layer.  Y[b, o] = round(yacc[b, o] + U_r[o, :] . t[b, :]), a row
+// dot over U_r [d_out][rank] row-major (no cross-workgroup reduction), then yacc is re-zeroed for
+// the next call.  LPR = lanes that cover one row of U_r (power of two, 16 bytes per lane and pass);
+// a wave handles 64/LPR rows per pass.  rank == 0 just rounds yacc.
+// grid.x workgroups of 4 waves over row groups, grid.z batch tiles.
 // ---------------------------------------------------------------------------------------------
-struct LowrankArgs {
+struct FinishArgs {
     LayerView L;
-    const uint16_t *X;
-    int batch, chunk;
+    void *Y;
+    int batch, lpr, passes, use_rank;
 };
 
-template <int DT, int BT, int RU>
-__global__ __launch_bounds__(256) void k_lowrank_t(const LowrankArgs a)
+template <int DT, int BT>
+__global__ __launch_bounds__(256) void k_finish(const FinishArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int z = blockIdx.z;
     const LayerView &L = a.L;
-    const int d_in = L.d_in, r = L.rank;
+    const int d_out = L.d_out, r = a.use_rank;
     const int b0 = z * BT;
     const int nb = min(BT, a.batch - b0);
-    const bool union_all = L.batch_mask_mode == 1;
-    const int i0 = blockIdx.x * RU;
-    uint16_t *s_xm = reinterpret_cast<uint16_t *>(smem);                        // [BT][chunk]
-    float *s_part = reinterpret_cast<float *>(smem + (size_t)BT * a.chunk * 2); // [4][RU*BT]
-
-    float part[RU][BT];
-#pragma unroll
-    for (int ru = 0; ru < RU; ++ru)
-#pragma unroll
-        for (int b = 0; b < BT; ++b) part[ru][b] = 0.f;
-
-    for (int c0 = 0; c0 < d_in; c0 += a.chunk) {
-        const int len = min(a.chunk, d_in - c0);
-        if (c0 > 0) __syncthreads();
-        for (int q = tid; q < len / 8; q += 256) {
-            u32x4 raw[BT]; float xv[BT][8]; uint32_t m[BT];
-            load_tokens8<DT, BT>(a.X, a.batch, b0, nb, d_in, c0 + q * 8, L.tau, L.cmp_mode, union_all, raw, xv, m);
-#pragma unroll
-            for (int b = 0; b < BT; ++b) {
-                u32x4 o = raw[b];
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if ((m[b] >> e) & 1u) o[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;   // kept -> 0
-                *reinterpret_cast<u32x4 *>(s_xm + (size_t)b * a.chunk + q * 8) = o;
-            }
-        }
-        __syncthreads();
-        for (int q = tid; q < len / 8; q += 256) {
-            float xf[BT][8];
-#pragma unroll
-            for (int b = 0; b < BT; ++b)
-                unpack8<DT>(*reinterpret_cast<const u32x4 *>(s_xm + (size_t)b * a.chunk + q * 8), xf[b]);
-            u32x4 v[RU];
-#pragma unroll
-            for (int ru = 0; ru < RU; ++ru)
-                v[ru] = (i0 + ru < r) ? ldg16<false>(L.SVt + (size_t)(i0 + ru) * d_in + c0 + q * 8)
-                                      : u32x4{0, 0, 0, 0};
-#pragma unroll
-            for (int ru = 0; ru < RU; ++ru) {
-                float f[8];
-                unpack8<DT>(v[ru], f);
-#pragma unroll
-                for (int b = 0; b < BT; ++b)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) part[ru][b] = __builtin_fmaf(f[e], xf[b][e], part[ru][b]);
-            }
-        }
+    float *s_t = reinterpret_cast<float *>(smem);             // [BT][r]
+    for (int i = tid; i < BT * r; i += 256) {
+        const int b = i / r;
+        s_t[i] = (b < nb) ? L.t[((size_t)z * BT) * r + i] : 0.f;
     }
+    __syncthreads();
+    const int lpr = a.lpr, rpi = 64 / lpr;                    // lanes per row, rows per wave pass
+    const int sub = lane % lpr, rsel = lane / lpr;
+    const int rows_per_wg = 4 * rpi;
+    for (int o0 = blockIdx.x * rows_per_wg; o0 < d_out; o0 += gridDim.x * rows_per_wg) {
+        const int o = o0 + w * rpi + rsel;
+        float acc[BT];
 #pragma unroll
-    for (int ru = 0; ru < RU; ++ru)
+        for (int b = 0; b < BT; ++b) acc[b] = 0.f;
+        if (o < d_out) {
+            for (int p = 0; p < a.passes; ++p) {
+                const int i = (p * lpr + sub) * 8;
+                if (i < r) {
+                    float f[8];
+                    unpack8<DT>(ldg16<false>(L.U + (size_t)o * r + i), f);
+#pragma unroll
+                    for (int b = 0; b < BT; ++b) {
+                        const float4 t0 = *reinterpret_cast<const float4 *>(s_t + b * r + i);
+                        const float4 t1 = *reinterpret_cast<const float4 *>(s_t + b * r + i + 4);
+                        acc[b] = __builtin_fmaf(f[0], t0.x, acc[b]); acc[b] = __builtin_fmaf(f[1], t0.y, acc[b]);
+                        acc[b] = __builtin_fmaf(f[2], t0.z, acc[b]); acc[b] = __builtin_fmaf(f[3], t0.w, acc[b]);
+                        acc[b] = __builtin_fmaf(f[4], t1.x, acc[b]); acc[b] = __builtin_fmaf(f[5], t1.y, acc[b]);
+                        acc[b] = __builtin_fmaf(f[6], t1.z, acc[b]); acc[b] = __builtin_fmaf(f[7], t1.w, acc[b]);
+                    }
+                }
+            }
+        }
 #pragma unroll
         for (int b = 0; b < BT; ++b) {
-            float v = wave_sum(part[ru][b]);
-            if (lane == 0) s_part[w * (RU * BT) + ru * BT + b] = v;
-        }
-    __syncthreads();
-    if (tid < RU * BT) {
-        const int ru = tid / BT, b = tid % BT;
-        if (i0 + ru < r) {
-            float v = s_part[tid] + s_part[RU * BT + tid] + s_part[2 * RU * BT + tid] + s_part[3 * RU * BT + tid];
-            L.t[((size_t)z * r + i0 + ru) * BT + b] = v;
+            float v = acc[b];
+            for (int d = lpr >> 1; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+            if (sub == 0 && o < d_out && b < nb) {
+                float *ya = L.yacc + (size_t)(b0 + b) * d_out + o;
+                store_out(a.Y, (size_t)(b0 + b) * d_out + o, *ya + v, L.out_dtype);
+                *ya = 0.f;
+            }
         }
     }
 }
@@ -589,28 +629,25 @@ int batch_tile(int batch)
     return 8;
 }
 
-int gather_cap(int d_in, int rank, int splits)
-{
-    return (d_in + splits - 1) / splits + (rank + splits - 1) / splits + 2;
-}
+int gather_cap(int d_in, int splits) { return (d_in + splits - 1) / splits + 2; }
 
-}  // namespace
-
-size_t gather_lds_bytes(int d_in, int rank, int splits, int waves, int bt)
-{
-    const size_t cap = gather_cap(d_in, rank, splits);
-    return (waves > 1 ? (size_t)waves * kTile * 4 : 0) + cap * bt * 4 + cap * 4 + 16 * 4;
-}
-
-static int lowrank_chunk(int d_in, int bt)
+int lowrank_chunk(int d_in, int bt)
 {
     int chunk = (24576 / bt) & ~7;
     return d_in < chunk ? d_in : chunk;
 }
 
+}  // namespace
+
+size_t gather_lds_bytes(int d_in, int splits, int waves, int bt)
+{
+    const size_t cap = gather_cap(d_in, splits);
+    return (waves > 1 ? (size_t)waves * kTile * 4 : 0) + cap * bt * 4 + cap * 4 + 16 * 4;
+}
+
 size_t lowrank_lds_bytes(int d_in, int bt)
 {
-    return (size_t)bt * lowrank_chunk(d_in, bt) * 2 + 4 * 4 * kMaxBT * 4;
+    return (size_t)bt * lowrank_chunk(d_in, bt) * 2 + 8 * 4 * kMaxBT * 4;
 }
 
 bool rowdot_supported(int d_in, int batch)
@@ -626,42 +663,53 @@ bool rowdot_supported(int d_in, int batch)
     default: { constexpr int BT = 8; __VA_ARGS__; } break; \
     }
 
-hipError_t launch_lowrank_t(const LayerView &L, const Launch &cfg, const void *X, int batch, hipStream_t stream)
-{
-    if (L.rank == 0) return hipSuccess;
-    const int bt = batch_tile(batch);
-    const int nz = (batch + bt - 1) / bt;
-    LowrankArgs a{L, (const uint16_t *)X, batch, lowrank_chunk(L.d_in, bt)};
-    const size_t lds = lowrank_lds_bytes(L.d_in, bt);
-    const int ru = cfg.lowrank_rows;
-    dim3 grid((L.rank + ru - 1) / ru, 1, nz), block(256);
-#define RS_LR(DT)                                                                                       \
-    RS_DISPATCH_BT(bt, {                                                                                \
-        if (ru == 1) hipLaunchKernelGGL((k_lowrank_t<DT, BT, 1>), grid, block, lds, stream, a);         \
-        else if (ru == 2) hipLaunchKernelGGL((k_lowrank_t<DT, BT, 2>), grid, block, lds, stream, a);    \
-        else hipLaunchKernelGGL((k_lowrank_t<DT, BT, 4>), grid, block, lds, stream, a);                 \
-    })
-    if (L.dtype == F16) { RS_LR(F16) } else { RS_LR(BF16) }
-#undef RS_LR
-    return hipGetLastError();
-}
-
-hipError_t launch_gather(const LayerView &L, const Launch &cfg, const void *X, int batch, void *Y,
-                         hipStream_t stream)
+hipError_t launch_sparse_and_t(const LayerView &L, const Launch &cfg, const void *X, int batch, bool with_t,
+                               bool with_gather, hipStream_t stream)
 {
     const int bt = batch_tile(batch);
     const int nz = (batch + bt - 1) / bt;
     const int tiles = (L.d_out + kTile - 1) / kTile;
-    GatherArgs a{L, (const uint16_t *)X, Y, batch, cfg.splits, tiles, gather_cap(L.d_in, L.rank, cfg.splits)};
-    const size_t lds = gather_lds_bytes(L.d_in, L.rank, cfg.splits, cfg.waves, bt);
-    dim3 grid(tiles * cfg.splits, 1, nz), block(kWave * cfg.waves);
-#define RS_G(DT)                                                                                         \
-    RS_DISPATCH_BT(bt, {                                                                                 \
-        if (cfg.nontemporal) hipLaunchKernelGGL((k_gather<DT, BT, true>), grid, block, lds, stream, a);  \
-        else hipLaunchKernelGGL((k_gather<DT, BT, false>), grid, block, lds, stream, a);                 \
+    GatherArgs a{};
+    a.L = L; a.X = (const uint16_t *)X; a.batch = batch; a.splits = cfg.splits; a.tiles = tiles;
+    a.cap = gather_cap(L.d_in, cfg.splits);
+    a.lr_rows = cfg.lowrank_rows;
+    a.lr_wgs = (with_t && L.rank > 0) ? (L.rank + cfg.lowrank_rows - 1) / cfg.lowrank_rows : 0;
+    a.lr_chunk = lowrank_chunk(L.d_in, bt);
+    const int gather_wgs = with_gather ? tiles * cfg.splits : 0;
+    if (a.lr_wgs + gather_wgs == 0) return hipSuccess;
+    size_t lds = gather_lds_bytes(L.d_in, cfg.splits, cfg.waves, bt);
+    if (a.lr_wgs > 0 && lowrank_lds_bytes(L.d_in, bt) > lds) lds = lowrank_lds_bytes(L.d_in, bt);
+    dim3 grid(a.lr_wgs + gather_wgs, 1, nz), block(kWave * cfg.waves);
+#define RS_G(DT)                                                                                               \
+    RS_DISPATCH_BT(bt, {                                                                                       \
+        if (cfg.nontemporal) hipLaunchKernelGGL((k_sparse_and_t<DT, BT, true>), grid, block, lds, stream, a);  \
+        else hipLaunchKernelGGL((k_sparse_and_t<DT, BT, false>), grid, block, lds, stream, a);                 \
     })
     if (L.dtype == F16) { RS_G(F16) } else { RS_G(BF16) }
 #undef RS_G
+    return hipGetLastError();
+}
+
+hipError_t launch_finish(const LayerView &L, int batch, void *Y, bool use_rank, hipStream_t stream)
+{
+    const int bt = batch_tile(batch);
+    const int nz = (batch + bt - 1) / bt;
+    FinishArgs a{};
+    a.L = L; a.Y = Y; a.batch = batch;
+    a.use_rank = use_rank ? L.rank : 0;
+    const int chunks = (a.use_rank + 7) / 8;          // 16-byte pieces per row of U_r
+    int lpr = 1;
+    while (lpr < chunks && lpr < 64) lpr <<= 1;
+    a.lpr = lpr;
+    a.passes = chunks == 0 ? 0 : (chunks + lpr - 1) / lpr;
+    const int rows_per_wg = 4 * (64 / lpr);
+    int wgs = (L.d_out + rows_per_wg - 1) / rows_per_wg;
+    if (wgs > 2048) wgs = 2048;
+    const size_t lds = (size_t)bt * a.use_rank * 4 + 16;
+    dim3 grid(wgs, 1, nz), block(256);
+#define RS_F(DT) RS_DISPATCH_BT(bt, { hipLaunchKernelGGL((k_finish<DT, BT>), grid, block, lds, stream, a); })
+    if (L.dtype == F16) { RS_F(F16) } else { RS_F(BF16) }
+#undef RS_F
     return hipGetLastError();
 }
 
@@ -671,8 +719,10 @@ hipError_t launch_dense_axpy(const LayerView &L, const Launch &cfg, const void *
     const int bt = batch_tile(batch);
     const int nz = (batch + bt - 1) / bt;
     const int tiles = (L.d_out + kTile - 1) / kTile;
-    GatherArgs a{L, (const uint16_t *)X, Y, batch, cfg.splits, tiles, gather_cap(L.d_in, L.rank, cfg.splits)};
-    const size_t lds = gather_lds_bytes(L.d_in, L.rank, cfg.splits, cfg.waves, bt);
+    GatherArgs a{};
+    a.L = L; a.X = (const uint16_t *)X; a.batch = batch; a.splits = cfg.splits; a.tiles = tiles;
+    a.cap = gather_cap(L.d_in, cfg.splits);
+    const size_t lds = gather_lds_bytes(L.d_in, cfg.splits, cfg.waves, bt);
     dim3 grid(tiles * cfg.splits, 1, nz), block(kWave * cfg.waves);
 #define RS_D(DT)                                                                                             \
     RS_DISPATCH_BT(bt, {                                                                                     \
@@ -681,7 +731,9 @@ hipError_t launch_dense_axpy(const LayerView &L, const Launch &cfg, const void *
     })
     if (L.dtype == F16) { RS_D(F16) } else { RS_D(BF16) }
 #undef RS_D
-    return hipGetLastError();
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_finish(L, batch, Y, false, stream);
 }
 
 hipError_t launch_dense_rowdot(const LayerView &L, const Launch &cfg, const void *X, int batch, void *Y,
