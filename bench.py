@@ -43,6 +43,11 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the sparsity sweep and per-kernel legs")
     ap.add_argument("--eager", action="store_true", help="time eager launches instead of graph replay")
+    ap.add_argument("--fast-layers", action="store_true",
+                    help="fill the layers with cheap i.i.d. values instead of the U diag(s) V^T construction "
+                         "(for profiling passes: traffic and time do not depend on the values)")
+    ap.add_argument("--pmc-pass", action="store_true",
+                    help="for rocprofv3 --pmc: one 256 MiB device copy of known size, then 3 eager ring passes; no timing")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (one MI355X); run with --gpus 1", file=sys.stderr)
@@ -66,7 +71,8 @@ def main():
     specs = [("gate", D_MODEL, D_FF, 0, "dmodel"), ("up", D_MODEL, D_FF, 1, "dmodel"), ("down", D_FF, D_MODEL, 2, "down")]
     base, sources, taus = {}, {}, {}
     for name, d_in, d_out, lin, kind in specs:
-        base[name] = synth.make_layer(d_in, d_out, RANK, dt, config=1, linear=lin)
+        base[name] = (synth.random_layer(d_in, d_out, RANK, dt, seed=1000 + lin) if args.fast_layers
+                      else synth.make_layer(d_in, d_out, RANK, dt, config=1, linear=lin))
         src = (synth.DModelInput if kind == "dmodel" else synth.DownInput)(d_in, config=1, linear=lin)
         sources[name] = src
         calib = synth.encode16(src.tokens(64, stream=synth.STREAM_CALIB), dt)
@@ -128,6 +134,21 @@ def main():
         e1.record(stream)
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / steps
+
+    if args.pmc_pass:
+        a = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")     # 256 MiB
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        b.copy_(a)                                  # calibration: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        for _ in range(3):
+            pass_rsparse(stream.cuda_stream)
+            torch.cuda.synchronize()
+        for _ in range(3):
+            pass_dense(stream.cuda_stream)
+            torch.cuda.synchronize()
+        print(json.dumps({"pmc_pass": True, "copy_bytes": int(a.numel() * 4)}), flush=True)
+        return
 
     # ------------------------------------------------------------------ parity sanity on the timed configuration
     import oracle

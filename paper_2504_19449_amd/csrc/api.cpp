@@ -176,12 +176,15 @@ Launch resolve_launch(const rsparse_layer *L, int batch, bool dense)
     Launch c{};
     const rsparse_tuning &t = L->tuning;
     const int bt = batch_tile_of(batch);
-    c.waves = (t.waves == 1 || t.waves == 2 || t.waves == 4 || t.waves == 8) ? t.waves : 4;
+    // 8 waves per workgroup and ~1.5 workgroups per compute unit measured best on MI355X: enough
+    // loads in flight, while each output column only receives `splits` atomic adds (same-address
+    // device-scope atomics serialise at ~0.1 us each, which sets the kernel's tail).
+    c.waves = (t.waves == 1 || t.waves == 2 || t.waves == 4 || t.waves == 8) ? t.waves : (bt >= 8 ? 4 : 8);
     c.nontemporal = t.nontemporal ? 1 : 0;
     const int rows = dense ? L->cfg.d_in : std::max(8, L->cfg.d_in / 2);     // expected rows to stream
     int splits = t.splits;
     if (splits <= 0) {
-        const int target_wgs = 4 * L->cus;
+        const int target_wgs = (3 * L->cus) / 2 * (8 / c.waves);
         splits = (target_wgs + L->tiles - 1) / L->tiles;
         const int max_by_rows = std::max(1, rows / (c.waves * 4));          // >= 4 rows per wave
         splits = std::max(1, std::min(splits, max_by_rows));
@@ -193,9 +196,8 @@ Launch resolve_launch(const rsparse_layer *L, int batch, bool dense)
     if (lr <= 0) {
         const double wg_bytes = (double)rows / splits * kTile * 2.0;          // W bytes of one gather workgroup
         lr = (int)(wg_bytes / (2.0 * L->cfg.d_in) + 0.5);
-        lr = std::max(1, std::min(lr, 64));
     }
-    c.lowrank_rows = lr;
+    c.lowrank_rows = std::max(1, std::min(lr, 4 * c.waves));                  // at most 4 rows per wave
     return c;
 }
 

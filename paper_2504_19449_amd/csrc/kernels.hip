@@ -160,56 +160,66 @@ __device__ __forceinline__ uint32_t load_tokens8(const uint16_t *X, int batch, i
 
 // ---------------------------------------------------------------------------------------------
 // Streaming primitive: acc[b][0:8] += sum_j coef[j][b] * M[idx[j], col:col+8] over the n staged rows.
-// Wave w of nw takes kUnroll consecutive rows at a time; all of a group's loads are issued
-// before the first FMA.  idx / coef live in LDS and are wave-uniform (scalar registers).
+// Wave w of nw takes kUnroll consecutive rows per batch; a batch's loads are all issued before its
+// first FMA, and the next batch is issued before the current one is consumed (two batches of
+// 16-byte loads in flight per lane).  idx / coef live in LDS and are wave-uniform (scalar registers).
 // ---------------------------------------------------------------------------------------------
-template <int DT, int BT, bool NT>
-__device__ __forceinline__ void stream_rows(const uint16_t *__restrict__ M, size_t ld, int col, bool colok,
-                                            const int *s_idx, const float *s_coef, int n, int w, int nw,
-                                            float (&acc)[BT][8])
+template <bool NT>
+__device__ __forceinline__ void load_batch(const uint16_t *__restrict__ M, size_t ld, int col, bool colok,
+                                           const int *s_idx, int n, int j0, u32x4 (&v)[kUnroll])
 {
-    for (int j0 = w * kUnroll; j0 < n; j0 += nw * kUnroll) {
-        u32x4 v[kUnroll];
-        if (j0 + kUnroll <= n) {
+    if (j0 + kUnroll <= n) {
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
+        for (int u = 0; u < kUnroll; ++u) {
+            const int idx = uniform(s_idx[j0 + u]);
+            v[u] = colok ? ldg16<NT>(M + (size_t)idx * ld + col) : u32x4{0, 0, 0, 0};
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            v[u] = u32x4{0, 0, 0, 0};
+            if (j0 + u < n) {
                 const int idx = uniform(s_idx[j0 + u]);
-                v[u] = colok ? ldg16<NT>(M + (size_t)idx * ld + col) : u32x4{0, 0, 0, 0};
-            }
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                float f[8];
-                unpack8<DT>(v[u], f);
-#pragma unroll
-                for (int b = 0; b < BT; ++b) {
-                    const float cf = uniform(s_coef[(j0 + u) * BT + b]);
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[b][e] = __builtin_fmaf(cf, f[e], acc[b][e]);
-                }
-            }
-        } else {
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                v[u] = u32x4{0, 0, 0, 0};
-                if (j0 + u < n) {
-                    const int idx = uniform(s_idx[j0 + u]);
-                    if (colok) v[u] = ldg16<NT>(M + (size_t)idx * ld + col);
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                if (j0 + u < n) {
-                    float f[8];
-                    unpack8<DT>(v[u], f);
-#pragma unroll
-                    for (int b = 0; b < BT; ++b) {
-                        const float cf = uniform(s_coef[(j0 + u) * BT + b]);
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) acc[b][e] = __builtin_fmaf(cf, f[e], acc[b][e]);
-                    }
-                }
+                if (colok) v[u] = ldg16<NT>(M + (size_t)idx * ld + col);
             }
         }
+    }
+}
+
+template <int DT, int BT>
+__device__ __forceinline__ void fma_batch(const u32x4 (&v)[kUnroll], const float *s_coef, int n, int j0,
+                                          float (&acc)[BT][8])
+{
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        if (j0 + u < n) {
+            float f[8];
+            unpack8<DT>(v[u], f);
+#pragma unroll
+            for (int b = 0; b < BT; ++b) {
+                const float cf = uniform(s_coef[(j0 + u) * BT + b]);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[b][e] = __builtin_fmaf(cf, f[e], acc[b][e]);
+            }
+        }
+    }
+}
+
+// Consume the already-issued batch `va` (rows j0..) and stream the rest of the wave's rows.
+template <int DT, int BT, bool NT>
+__device__ __forceinline__ void stream_rest(const uint16_t *__restrict__ M, size_t ld, int col, bool colok,
+                                            const int *s_idx, const float *s_coef, int n, int j0, int step,
+                                            u32x4 (&va)[kUnroll], float (&acc)[BT][8])
+{
+    u32x4 vb[kUnroll];
+    while (j0 < n) {
+        load_batch<NT>(M, ld, col, colok, s_idx, n, j0 + step, vb);
+        fma_batch<DT, BT>(va, s_coef, n, j0, acc);
+        j0 += step;
+        if (j0 >= n) break;
+        load_batch<NT>(M, ld, col, colok, s_idx, n, j0 + step, va);
+        fma_batch<DT, BT>(vb, s_coef, n, j0, acc);
+        j0 += step;
     }
 }
 
@@ -274,14 +284,17 @@ __device__ __forceinline__ GatherLds carve(unsigned char *smem, int cap, int bt,
 
 // ---------------------------------------------------------------------------------------------
 // Stage 1 of the low-rank part (Sec. 3.4): t_i = sum_c (S_r V_r^T)[i, c] * (x - sigma_t(x))_c.
-// A workgroup stages the masked token(s) in LDS (kept channels zeroed) and dots its rows of
-// S_r V_r^T against them, RU rows at a time; a row is complete inside one workgroup, so t needs
-// no cross-workgroup sum and no zeroing.  t is stored [batch tile][token][rank].
+// A workgroup stages the masked token(s) in LDS (kept channels zeroed); each of its waves then dots
+// whole rows of S_r V_r^T against them, eight 16-byte loads in flight per lane.  A row is complete
+// inside one wave, so t needs no cross-workgroup sum, no atomics and no zeroing.
+// t is stored [batch tile][token][rank].  At most kRowsPerWave rows per wave (host-enforced).
 // ---------------------------------------------------------------------------------------------
+constexpr int kRowsPerWave = 4;
+
 template <int DT, int BT>
 __device__ __forceinline__ void lowrank_rows(const GatherArgs &a, unsigned char *smem, int wg, int z)
 {
-    constexpr int RU = 4;
+    constexpr int LU = 8;
     const int tid = threadIdx.x, nthr = blockDim.x, lane = tid & 63, w = tid >> 6, nw = nthr >> 6;
     const LayerView &L = a.L;
     const int d_in = L.d_in, r = L.rank;
@@ -289,72 +302,69 @@ __device__ __forceinline__ void lowrank_rows(const GatherArgs &a, unsigned char 
     const int nb = min(BT, a.batch - b0);
     const bool union_all = L.batch_mask_mode == 1;
     uint16_t *s_xm = reinterpret_cast<uint16_t *>(smem);                           // [BT][chunk]
-    float *s_part = reinterpret_cast<float *>(smem + (size_t)BT * a.lr_chunk * 2); // [8 waves][RU*BT]
     const int row_lo = wg * a.lr_rows, row_hi = min(r, row_lo + a.lr_rows);
-    const bool single_chunk = a.lr_chunk >= d_in;
 
-    for (int i0 = row_lo; i0 < row_hi; i0 += RU) {
-        float part[RU][BT];
+    float part[kRowsPerWave][BT];
 #pragma unroll
-        for (int ru = 0; ru < RU; ++ru)
+    for (int sl = 0; sl < kRowsPerWave; ++sl)
 #pragma unroll
-            for (int b = 0; b < BT; ++b) part[ru][b] = 0.f;
+        for (int b = 0; b < BT; ++b) part[sl][b] = 0.f;
 
-        for (int c0 = 0; c0 < d_in; c0 += a.lr_chunk) {
-            const int len = min(a.lr_chunk, d_in - c0);
-            if (!(single_chunk && i0 > row_lo)) {          // the masked token stays staged across row groups
-                __syncthreads();
-                for (int q = tid; q < len / 8; q += nthr) {
-                    u32x4 raw[BT]; float xv[BT][8]; uint32_t m[BT];
-                    load_tokens8<DT, BT>(a.X, a.batch, b0, nb, d_in, c0 + q * 8, L.tau, L.cmp_mode, union_all, raw, xv, m);
+    for (int c0 = 0; c0 < d_in; c0 += a.lr_chunk) {
+        const int len = min(a.lr_chunk, d_in - c0);
+        const int nq = len / 8;
+        if (c0 > 0) __syncthreads();
+        for (int q = tid; q < nq; q += nthr) {
+            u32x4 raw[BT]; float xv[BT][8]; uint32_t m[BT];
+            load_tokens8<DT, BT>(a.X, a.batch, b0, nb, d_in, c0 + q * 8, L.tau, L.cmp_mode, union_all, raw, xv, m);
 #pragma unroll
-                    for (int b = 0; b < BT; ++b) {
-                        u32x4 o = raw[b];
+            for (int b = 0; b < BT; ++b) {
+                u32x4 o = raw[b];
 #pragma unroll
-                        for (int e = 0; e < 8; ++e)
-                            if ((m[b] >> e) & 1u) o[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;   // kept -> 0
-                        *reinterpret_cast<u32x4 *>(s_xm + (size_t)b * a.lr_chunk + q * 8) = o;
-                    }
-                }
-                __syncthreads();
+                for (int e = 0; e < 8; ++e)
+                    if ((m[b] >> e) & 1u) o[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;   // kept -> 0
+                *reinterpret_cast<u32x4 *>(s_xm + (size_t)b * a.lr_chunk + q * 8) = o;
             }
-            for (int q = tid; q < len / 8; q += nthr) {
-                u32x4 v[RU];
+        }
+        __syncthreads();
 #pragma unroll
-                for (int ru = 0; ru < RU; ++ru)
-                    v[ru] = (i0 + ru < row_hi) ? ldg16<false>(L.SVt + (size_t)(i0 + ru) * d_in + c0 + q * 8)
-                                               : u32x4{0, 0, 0, 0};
-                float xf[BT][8];
+        for (int sl = 0; sl < kRowsPerWave; ++sl) {
+            const int i = row_lo + w + sl * nw;
+            if (i < row_hi) {
+                const uint16_t *row = L.SVt + (size_t)i * d_in + c0;
+                for (int q0 = lane; q0 < nq; q0 += 64 * LU) {
+                    u32x4 v[LU];
 #pragma unroll
-                for (int b = 0; b < BT; ++b)
-                    unpack8<DT>(*reinterpret_cast<const u32x4 *>(s_xm + (size_t)b * a.lr_chunk + q * 8), xf[b]);
+                    for (int u = 0; u < LU; ++u) {
+                        const int q = q0 + u * 64;
+                        v[u] = (q < nq) ? ldg16<false>(row + q * 8) : u32x4{0, 0, 0, 0};
+                    }
 #pragma unroll
-                for (int ru = 0; ru < RU; ++ru) {
-                    float f[8];
-                    unpack8<DT>(v[ru], f);
+                    for (int u = 0; u < LU; ++u) {
+                        const int q = q0 + u * 64;
+                        if (q < nq) {
+                            float f[8];
+                            unpack8<DT>(v[u], f);
 #pragma unroll
-                    for (int b = 0; b < BT; ++b)
+                            for (int b = 0; b < BT; ++b) {
+                                float xf[8];
+                                unpack8<DT>(*reinterpret_cast<const u32x4 *>(s_xm + (size_t)b * a.lr_chunk + q * 8), xf);
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) part[ru][b] = __builtin_fmaf(f[e], xf[b][e], part[ru][b]);
+                                for (int e = 0; e < 8; ++e) part[sl][b] = __builtin_fmaf(f[e], xf[e], part[sl][b]);
+                            }
+                        }
+                    }
                 }
             }
         }
-        __syncthreads();                                    // s_part is free again
+    }
 #pragma unroll
-        for (int ru = 0; ru < RU; ++ru)
+    for (int sl = 0; sl < kRowsPerWave; ++sl) {
+        const int i = row_lo + w + sl * nw;
 #pragma unroll
-            for (int b = 0; b < BT; ++b) {
-                float v = wave_sum(part[ru][b]);
-                if (lane == 0) s_part[w * (RU * BT) + ru * BT + b] = v;
-            }
-        __syncthreads();
-        if (tid < RU * BT) {
-            const int ru = tid / BT, b = tid % BT;
-            if (i0 + ru < row_hi) {
-                float v = 0.f;
-                for (int i = 0; i < nw; ++i) v += s_part[i * (RU * BT) + tid];
-                L.t[((size_t)z * BT + b) * r + i0 + ru] = v;
-            }
+        for (int b = 0; b < BT; ++b) {
+            const float v = wave_sum(part[sl][b]);
+            if (lane == 0 && i < row_hi) L.t[((size_t)z * BT + b) * r + i] = v;
         }
     }
 }
@@ -386,54 +396,44 @@ __global__ __launch_bounds__(512) void k_sparse_and_t(const GatherArgs a)
     const bool union_all = L.batch_mask_mode == 1;
     const GatherLds s = carve(smem, a.cap, BT, nw);
 
-    // ---- mask + count over my contiguous chunk of channels
-    const int CH = 8 * ((d_in + 8 * nthr - 1) / (8 * nthr));
-    const int c_begin = tid * CH, c_end = min(d_in, c_begin + CH);
-    int cnt = 0;
-    for (int c = c_begin; c < c_end; c += 8) {
+    // ---- pass 1, coalesced over the token(s): keep-bits of every 8 channels (union over the batch
+    //      tile, or over the whole batch with the union mask) -> one byte each in LDS
+    const int nq = d_in / 8;
+    uint8_t *s_u = reinterpret_cast<uint8_t *>(s.misc + 16);
+    for (int q = tid; q < nq; q += nthr) {
         u32x4 raw[BT]; float xv[BT][8]; uint32_t m[BT];
-        uint32_t u = load_tokens8<DT, BT>(a.X, a.batch, b0, nb, d_in, c, L.tau, L.cmp_mode, union_all, raw, xv, m);
-        cnt += __popc(u);
+        const uint32_t u = load_tokens8<DT, BT>(a.X, a.batch, b0, nb, d_in, q * 8, L.tau, L.cmp_mode, union_all, raw, xv, m);
+        s_u[q] = (uint8_t)u;
     }
+    __syncthreads();
+
+    // ---- pass 2: each thread owns a contiguous run of those bytes; block scan gives list positions
+    const int QC = (nq + nthr - 1) / nthr;
+    const int q_begin = min(nq, tid * QC), q_end = min(nq, q_begin + QC);
+    int cnt = 0;
+    for (int q = q_begin; q < q_end; ++q) cnt += __popc((uint32_t)s_u[q]);
     int k;
     int pos = block_exclusive_scan(cnt, s.misc, k);
 
-    // ---- my balanced share of the kept list
+    // ---- my balanced share [lo, hi) of the ascending kept list
     const int lo = (int)(((long long)split * k) / a.splits);
     const int hi = (int)(((long long)(split + 1) * k) / a.splits);
     const int n = hi - lo;
-
     if (cnt > 0 && pos < hi && pos + cnt > lo) {
-        for (int c = c_begin; c < c_end; c += 8) {
-            u32x4 raw[BT]; float xv[BT][8]; uint32_t m[BT];
-            uint32_t u = load_tokens8<DT, BT>(a.X, a.batch, b0, nb, d_in, c, L.tau, L.cmp_mode, union_all, raw, xv, m);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                if ((u >> e) & 1u) {
-                    const int p = pos++;
-                    if (p >= lo && p < hi) {
-                        const int j = p - lo;
-                        s.idx[j] = c + e;
-                        uint32_t bits = 0;
-#pragma unroll
-                        for (int b = 0; b < BT; ++b) {
-                            const bool kb = (m[b] >> e) & 1u;
-                            s.coef[j * BT + b] = kb ? xv[b][e] : 0.f;
-                            bits |= (uint32_t)kb << b;
-                        }
-                        if (tile == 0) {          // the tile-0 workgroups publish the list for read-back
-                            L.act_list[(size_t)z * d_in + p] = c + e;
-                            L.act_bits[(size_t)z * d_in + p] = bits;
-                        }
-                    }
-                }
+        for (int q = q_begin; q < q_end; ++q) {
+            uint32_t u = s_u[q];
+            while (u) {
+                const int e = __builtin_ctz(u);
+                u &= u - 1;
+                const int p = pos++;
+                if (p >= lo && p < hi) s.idx[p - lo] = q * 8 + e;
             }
         }
     }
     if (tile == 0 && split == 0 && tid == 0) L.act_count[z] = k;
     __syncthreads();
 
-    // ---- stream my rows
+    // ---- issue the first batch of weight loads (they need only the indices) ...
     const int col = tile * kTile + lane * 8;
     const bool colok = col < d_out;
     float acc[BT][8];
@@ -441,7 +441,34 @@ __global__ __launch_bounds__(512) void k_sparse_and_t(const GatherArgs a)
     for (int b = 0; b < BT; ++b)
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[b][e] = 0.f;
-    stream_rows<DT, BT, NT>(L.M, (size_t)d_out, col, colok, s.idx, s.coef, n, w, nw, acc);
+    u32x4 va[kUnroll];
+    const int j_first = w * kUnroll, step = nw * kUnroll;
+    load_batch<NT>(L.M, (size_t)d_out, col, colok, s.idx, n, j_first, va);
+
+    // ---- ... and fetch the coefficients x[b, c] * m[b, c] of my rows while those loads fly
+    for (int j = tid; j < n; j += nthr) {
+        const int c = s.idx[j];
+        uint32_t bits = 0;
+#pragma unroll
+        for (int b = 0; b < BT; ++b) {
+            float xf = 0.f;
+            bool kb = false;
+            if (b < nb) {
+                const uint16_t h = a.X[(size_t)(b0 + b) * d_in + c];
+                xf = (DT == F16) ? (float)__builtin_bit_cast(_Float16, h) : as_f((uint32_t)h << 16);
+                kb = union_all ? true : keep(xf, L.tau, L.cmp_mode);
+            }
+            s.coef[j * BT + b] = kb ? xf : 0.f;
+            bits |= (uint32_t)kb << b;
+        }
+        if (tile == 0) {          // the tile-0 workgroups publish the list for read-back
+            L.act_list[(size_t)z * d_in + lo + j] = c;
+            L.act_bits[(size_t)z * d_in + lo + j] = bits;
+        }
+    }
+    __syncthreads();
+
+    stream_rest<DT, BT, NT>(L.M, (size_t)d_out, col, colok, s.idx, s.coef, n, j_first, step, va, acc);
     reduce_to_yacc<BT>(acc, s.red, L.yacc, b0, nb, d_out, tile);
 }
 
@@ -486,7 +513,9 @@ __global__ __launch_bounds__(512) void k_dense_axpy(const GatherArgs a)
     for (int b = 0; b < BT; ++b)
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[b][e] = 0.f;
-    stream_rows<DT, BT, NT>(L.M, (size_t)d_out, col, colok, s.idx, s.coef, n, w, nw, acc);
+    u32x4 va[kUnroll];
+    load_batch<NT>(L.M, (size_t)d_out, col, colok, s.idx, n, w * kUnroll, va);
+    stream_rest<DT, BT, NT>(L.M, (size_t)d_out, col, colok, s.idx, s.coef, n, w * kUnroll, nw * kUnroll, va, acc);
     reduce_to_yacc<BT>(acc, s.red, L.yacc, b0, nb, d_out, tile);
 }
 
@@ -503,7 +532,10 @@ struct FinishArgs {
     int batch, lpr, passes, use_rank;
 };
 
-template <int DT, int BT>
+constexpr int kFinishGroups = 4;     // row groups per wave, all loads issued up front
+
+// PASSES = 16-byte pieces per lane and row (rank <= 512 * PASSES); 0 = any rank, loads not batched.
+template <int DT, int BT, int PASSES>
 __global__ __launch_bounds__(256) void k_finish(const FinishArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -514,25 +546,45 @@ __global__ __launch_bounds__(256) void k_finish(const FinishArgs a)
     const int b0 = z * BT;
     const int nb = min(BT, a.batch - b0);
     float *s_t = reinterpret_cast<float *>(smem);             // [BT][r]
+    const int lpr = a.lpr, rpi = 64 / lpr;                    // lanes per row, rows per wave and group
+    const int sub = lane % lpr, rsel = lane / lpr;
+    const int o_wave = (blockIdx.x * 4 + w) * (rpi * kFinishGroups);
+    constexpr int NP = PASSES > 0 ? PASSES : 1;
+
+    // U_r rows and the accumulators first: their latency covers the staging of t
+    u32x4 v[kFinishGroups][NP];
+    float ya[kFinishGroups][BT];
+#pragma unroll
+    for (int g = 0; g < kFinishGroups; ++g) {
+        const int o = o_wave + g * rpi + rsel;
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int i = (p * lpr + sub) * 8;
+            v[g][p] = (PASSES > 0 && o < d_out && i < r) ? ldg16<false>(L.U + (size_t)o * r + i) : u32x4{0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int b = 0; b < BT; ++b)
+            ya[g][b] = (sub == 0 && o < d_out && b < nb) ? L.yacc[(size_t)(b0 + b) * d_out + o] : 0.f;
+    }
     for (int i = tid; i < BT * r; i += 256) {
         const int b = i / r;
         s_t[i] = (b < nb) ? L.t[((size_t)z * BT) * r + i] : 0.f;
     }
     __syncthreads();
-    const int lpr = a.lpr, rpi = 64 / lpr;                    // lanes per row, rows per wave pass
-    const int sub = lane % lpr, rsel = lane / lpr;
-    const int rows_per_wg = 4 * rpi;
-    for (int o0 = blockIdx.x * rows_per_wg; o0 < d_out; o0 += gridDim.x * rows_per_wg) {
-        const int o = o0 + w * rpi + rsel;
+
+#pragma unroll
+    for (int g = 0; g < kFinishGroups; ++g) {
+        const int o = o_wave + g * rpi + rsel;
         float acc[BT];
 #pragma unroll
         for (int b = 0; b < BT; ++b) acc[b] = 0.f;
-        if (o < d_out) {
-            for (int p = 0; p < a.passes; ++p) {
+        if (PASSES > 0) {
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
                 const int i = (p * lpr + sub) * 8;
-                if (i < r) {
+                if (o < d_out && i < r) {
                     float f[8];
-                    unpack8<DT>(ldg16<false>(L.U + (size_t)o * r + i), f);
+                    unpack8<DT>(v[g][p], f);
 #pragma unroll
                     for (int b = 0; b < BT; ++b) {
                         const float4 t0 = *reinterpret_cast<const float4 *>(s_t + b * r + i);
@@ -544,15 +596,26 @@ __global__ __launch_bounds__(256) void k_finish(const FinishArgs a)
                     }
                 }
             }
+        } else if (o < d_out) {
+            for (int p = 0; p < a.passes; ++p) {
+                const int i = (p * lpr + sub) * 8;
+                if (i < r) {
+                    float f[8];
+                    unpack8<DT>(ldg16<false>(L.U + (size_t)o * r + i), f);
+#pragma unroll
+                    for (int b = 0; b < BT; ++b)
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) acc[b] = __builtin_fmaf(f[e], s_t[b * r + i + e], acc[b]);
+                }
+            }
         }
 #pragma unroll
         for (int b = 0; b < BT; ++b) {
-            float v = acc[b];
-            for (int d = lpr >> 1; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+            float s = acc[b];
+            for (int d = lpr >> 1; d >= 1; d >>= 1) s += __shfl_xor(s, d, 64);
             if (sub == 0 && o < d_out && b < nb) {
-                float *ya = L.yacc + (size_t)(b0 + b) * d_out + o;
-                store_out(a.Y, (size_t)(b0 + b) * d_out + o, *ya + v, L.out_dtype);
-                *ya = 0.f;
+                store_out(a.Y, (size_t)(b0 + b) * d_out + o, ya[g][b] + s, L.out_dtype);
+                L.yacc[(size_t)(b0 + b) * d_out + o] = 0.f;
             }
         }
     }
@@ -642,12 +705,12 @@ int lowrank_chunk(int d_in, int bt)
 size_t gather_lds_bytes(int d_in, int splits, int waves, int bt)
 {
     const size_t cap = gather_cap(d_in, splits);
-    return (waves > 1 ? (size_t)waves * kTile * 4 : 0) + cap * bt * 4 + cap * 4 + 16 * 4;
+    return (waves > 1 ? (size_t)waves * kTile * 4 : 0) + cap * bt * 4 + cap * 4 + 16 * 4 + (size_t)d_in / 8 + 16;
 }
 
 size_t lowrank_lds_bytes(int d_in, int bt)
 {
-    return (size_t)bt * lowrank_chunk(d_in, bt) * 2 + 8 * 4 * kMaxBT * 4;
+    return (size_t)bt * lowrank_chunk(d_in, bt) * 2 + 16;
 }
 
 bool rowdot_supported(int d_in, int batch)
@@ -702,12 +765,16 @@ hipError_t launch_finish(const LayerView &L, int batch, void *Y, bool use_rank, 
     while (lpr < chunks && lpr < 64) lpr <<= 1;
     a.lpr = lpr;
     a.passes = chunks == 0 ? 0 : (chunks + lpr - 1) / lpr;
-    const int rows_per_wg = 4 * (64 / lpr);
-    int wgs = (L.d_out + rows_per_wg - 1) / rows_per_wg;
-    if (wgs > 2048) wgs = 2048;
+    const int rows_per_wg = 4 * (64 / lpr) * kFinishGroups;
+    const int wgs = (L.d_out + rows_per_wg - 1) / rows_per_wg;
     const size_t lds = (size_t)bt * a.use_rank * 4 + 16;
     dim3 grid(wgs, 1, nz), block(256);
-#define RS_F(DT) RS_DISPATCH_BT(bt, { hipLaunchKernelGGL((k_finish<DT, BT>), grid, block, lds, stream, a); })
+#define RS_F(DT)                                                                                          \
+    RS_DISPATCH_BT(bt, {                                                                                  \
+        if (a.passes <= 1) hipLaunchKernelGGL((k_finish<DT, BT, 1>), grid, block, lds, stream, a);        \
+        else if (a.passes == 2) hipLaunchKernelGGL((k_finish<DT, BT, 2>), grid, block, lds, stream, a);   \
+        else hipLaunchKernelGGL((k_finish<DT, BT, 0>), grid, block, lds, stream, a);                      \
+    })
     if (L.dtype == F16) { RS_F(F16) } else { RS_F(BF16) }
 #undef RS_F
     return hipGetLastError();

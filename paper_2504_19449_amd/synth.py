@@ -113,7 +113,8 @@ class Layer:
         perm = np.asarray(perm)
         out = object.__new__(Layer)
         out.d_in, out.d_out, out.rank, out.dtype = self.d_in, self.d_out, self.rank, self.dtype
-        out.U, out.sigma, out.V = self.U, self.sigma, self.V[perm]
+        out.U, out.sigma = self.U, self.sigma
+        out.V = None if self.V is None else self.V[perm]
         out.W16 = np.ascontiguousarray(self.W16[:, perm])
         out.U16 = self.U16
         out.SV16 = np.ascontiguousarray(self.SV16[:, perm])
