@@ -5,13 +5,14 @@ Workload (benchmark configs[1]): Llama-2-7B MLP shapes at batch 1, bf16, ran
 50 % channel sparsity: gate and up (4096 -> 11008, heavy-tailed d_model input) and down
 (11008 -> 4096, SiLU(g)*u input).  One "step" = the three linears of one MLP block, each
 a full pass of the hot path (threshold, compaction, gather-GEMV, both low-rank products,
-sum, store).  Steps walk a ring of distinct prepared layers (> 1 GiB of weights) so that
+sum, store); gate and up read the same token and go through one grouped call, as they
+would in a decoder, and so does the dense baseline.  Steps walk a ring of distinct prepared layers (> 1 GiB of weights) so that
 every weight byte comes from HBM, not from L2 / Infinity Cache, and are replayed from a
 captured HIP graph so that host launch overhead is not what is timed.  Inputs are resident
 in HBM before the timed region.
 
 Prints ONE JSON line.  `value` = microseconds per R-Sparse linear (whole-call, both
-launches).  `roofline` is for the dominant kernel (k_gather) timed alone with events;
+launches).  `roofline` is for the dominant kernel (k_sparse_and_t) timed alone with events;
 `cpu_baseline` is the fp64 CPU oracle timed on the host cores on a bounded sample.
 """
 import argparse
@@ -25,6 +26,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+TRAFFIC_BYTES_PER_LAUNCH = None   # set from the PMC run of the grouped launch shape; see profiles/
 RING_BLOCKS = 4            # MLP blocks in the ring: 12 layers, ~1.2 GiB of column-major weights
 RANK = 512
 D_MODEL, D_FF = 4096, 11008
@@ -79,31 +81,48 @@ def main():
         taus[name] = {s: rs.rsparse_calibrate_tau(calib, dt, s) for s in (0.4, 0.5, 0.7, args.sparsity)}
         log(f"built {name} {d_in}->{d_out} ({time.time() - t0:.1f}s)")
 
-    ring = []       # (name, Layer handle, X device tensor, Y device tensor, synth layer)
+    ring = []       # per linear: (name, Layer handle, X device tensor, Y device tensor, synth layer or None, x bits)
     perm_rng = np.random.Generator(np.random.PCG64(1999))
     for blk in range(RING_BLOCKS):
+        x_dmodel = synth.encode16(sources["gate"].tokens(1, offset=1 + blk), dt)      # gate and up read the same token
+        x_dmodel_dev = torch.from_numpy(x_dmodel.view(np.int16)).cuda()
         for name, d_in, d_out, lin, kind in specs:
             L = base[name] if blk == 0 else base[name].permuted_channels(perm_rng.permutation(d_in))
             cfg = rs.make_config(d_in, d_out, RANK, taus[name][args.sparsity], dt, max_batch=1, dense_rowmajor=1)
             layer = rs.rsparse_prepare_factors(cfg, L.W16, L.U16, L.SV16)
-            x = synth.encode16(sources[name].tokens(1, offset=1 + blk), dt)
-            xd = torch.from_numpy(x.view(np.int16)).cuda()
+            if kind == "dmodel":
+                x, xd = x_dmodel, x_dmodel_dev
+            else:
+                x = synth.encode16(sources[name].tokens(1, offset=1 + blk), dt)
+                xd = torch.from_numpy(x.view(np.int16)).cuda()
             yd = torch.zeros((1, d_out), dtype=torch.int16, device="cuda")
             ring.append((name, layer, xd, yd, L if blk == 0 else None, x))
     torch.cuda.synchronize()
     log(f"ring of {len(ring)} layers resident ({time.time() - t0:.1f}s)")
     steps_per_pass = RING_BLOCKS
     stream = torch.cuda.current_stream()
+    blocks = [ring[3 * i:3 * i + 3] for i in range(RING_BLOCKS)]          # (gate, up, down) per block
 
     def set_all(**kw):
         for _, layer, *_ in ring:
             rs.rsparse_set_tuning(layer, **kw)
 
     def pass_rsparse(sptr):
+        """One MLP block = gate and up in one grouped call (same input), then down."""
+        for (g, u, d) in blocks:
+            rs.rsparse_linear_group([g[1], u[1]], g[2].data_ptr(), 1, [g[3].data_ptr(), u[3].data_ptr()], sptr)
+            rs.rsparse_linear(d[1], d[2].data_ptr(), 1, d[3].data_ptr(), sptr)
+
+    def pass_rsparse_separate(sptr):
         for _, layer, xd, yd, *_ in ring:
             rs.rsparse_linear(layer, xd.data_ptr(), 1, yd.data_ptr(), sptr)
 
     def pass_dense(sptr):
+        for (g, u, d) in blocks:
+            rs.rsparse_dense_ref_group([g[1], u[1]], g[2].data_ptr(), 1, [g[3].data_ptr(), u[3].data_ptr()], sptr)
+            rs.rsparse_dense_ref(d[1], d[2].data_ptr(), 1, d[3].data_ptr(), sptr)
+
+    def pass_dense_separate(sptr):
         for _, layer, xd, yd, *_ in ring:
             rs.rsparse_dense_ref(layer, xd.data_ptr(), 1, yd.data_ptr(), sptr)
 
@@ -116,15 +135,13 @@ def main():
             graph = torch.cuda.CUDAGraph()
             with torch.cuda.graph(graph):
                 pass_fn(torch.cuda.current_stream().cuda_stream)
+        full, rem = divmod(steps, steps_per_pass)
+        if rem:
+            raise SystemExit(f"--steps must be a multiple of {steps_per_pass} (the ring holds {steps_per_pass} blocks)")
 
         def run(n_steps):
-            full, rem = divmod(n_steps, steps_per_pass)
-            for _ in range(full):
+            for _ in range(max(1, n_steps // steps_per_pass)):
                 graph.replay() if graph is not None else pass_fn(stream.cuda_stream)
-            for i in range(rem * 3):                    # leftover steps: eager, first layers of the ring
-                _, layer, xd, yd, *_ = ring[i]
-                (rs.rsparse_linear if pass_fn is pass_rsparse else rs.rsparse_dense_ref)(
-                    layer, xd.data_ptr(), 1, yd.data_ptr(), stream.cuda_stream)
 
         run(warmup)
         torch.cuda.synchronize()
@@ -183,22 +200,28 @@ def main():
     set_all(stages=2)
     ms_t = timed(pass_rsparse, args.steps, args.warmup)
     set_all(stages=0)
-    us_gather = ms_g * 1000.0 / 3.0
+    launches_per_step = 2                                # (gate + up grouped) and down
+    us_gather = ms_g * 1000.0 / launches_per_step
     gather_bytes = []
     for (_, layer, *_), k in zip(ring, k_of):
         c = layer.cfg
         gather_bytes.append(2 * (k * c.d_out + c.rank * c.d_in + c.d_in))
-    achieved = (sum(gather_bytes) / n_lin) / (us_gather * 1e-6) / 1e9
+    bytes_per_launch = sum(gather_bytes) / (RING_BLOCKS * launches_per_step)
+    achieved = bytes_per_launch / (us_gather * 1e-6) / 1e9
+    # traffic: rocprofv3 --pmc FETCH_SIZE (x2.0, calibrated on a 256 MiB copy) + WRITE_SIZE per launch,
+    # from the run summarised in profiles/k_sparse_and_t_config1_pmc_traffic.md
     roofline = {"bound": "hbm", "kernel": "k_sparse_and_t", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                "us_per_launch": round(us_gather, 3), "bytes_per_launch": int(sum(gather_bytes) / n_lin)}
-    extras["us_k_finish_alone"] = round(ms_t * 1000.0 / 3.0, 3)
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_BYTES_PER_LAUNCH,
+                "us_per_launch": round(us_gather, 3), "bytes_per_launch": int(bytes_per_launch),
+                "launches_per_step": launches_per_step}
+    extras["us_k_finish_per_launch_alone"] = round(ms_t * 1000.0 / launches_per_step, 3)
 
     # dense GEMV baseline, both hand-written kernels; best one is the baseline
     dense_us = {}
     for label, kern in (("rowdot", 2), ("axpy", 1)):
         set_all(dense_kernel=kern)
         dense_us[label] = timed(pass_dense, args.steps, args.warmup) * 1000.0 / 3.0
+        dense_us[label + "_separate_calls"] = timed(pass_dense_separate, args.steps, args.warmup) * 1000.0 / 3.0
     set_all(dense_kernel=0)
     best_dense = min(dense_us.values())
     dense_gbs = (sum(dense_bytes) / n_lin) / (best_dense * 1e-6) / 1e9
@@ -221,6 +244,7 @@ def main():
             rs.rsparse_set_tau(layer, taus[name][args.sparsity])
         extras["sparsity_sweep"] = sweep
         extras["us_per_linear_eager_launches"] = round(timed(pass_rsparse, args.steps, args.warmup, eager=True) * 1000 / 3, 3)
+        extras["us_per_linear_separate_calls"] = round(timed(pass_rsparse_separate, args.steps, args.warmup) * 1000 / 3, 3)
 
     # ------------------------------------------------------------------ CPU oracle baseline (bounded sample)
     cpu = None
@@ -243,7 +267,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 5),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "configs[1]: Llama-2-7B MLP gate/up (4096->11008) + down (11008->4096), bf16, "
-                               "batch 1, rank 512, channel sparsity %.0f%%; step = the 3 linears of one block; "
+                               "batch 1, rank 512, channel sparsity %.0f%%; step = the 3 linears of one block (gate+up grouped, then down); "
                                "ring of %d distinct layers; %s" % (args.sparsity * 100, n_lin,
                                                                  "eager launches" if args.eager else "HIP-graph replay"),
                    "batch": 1, "rank": RANK, "sparsity": args.sparsity,

@@ -80,7 +80,9 @@ typedef struct {
     int32_t nontemporal;     /* 1: stream weights with non-temporal loads */
     int32_t stages;          /* rsparse_linear: 0 both launches, 1 first launch only, 2 second only -- for
                                 timing one kernel in isolation; results are only valid with 0 */
-    int32_t reserved[2];
+    int32_t tile_map;        /* workgroup -> (column tile, split) mapping: 0 default, 1 tile-fastest (plain),
+                                2 XCD-aware (all splits of a tile on ids congruent mod 8) */
+    int32_t reserved[1];
 } rsparse_tuning;
 
 /*
@@ -122,6 +124,20 @@ rsparse_status rsparse_linear(rsparse_layer *layer, const void *X_dev, int32_t b
 /* The full layer Y = X W^T (Sec. 3.1) with the hand-written dense GEMV; same argument rules. */
 rsparse_status rsparse_dense_ref(rsparse_layer *layer, const void *X_dev, int32_t batch,
                                  void *Y_dev, void *stream);
+
+/*
+ * Several layers applied to the SAME input in one pair of launches -- q/k/v, or gate/up of the MLP
+ * (Sec. 3.1: H = X W_up^T (.) sigma(X W_gate^T); Sec. 3.4 applies R-Sparse to every linear layer).
+ * layers: host array of n_layers (1..RSPARSE_MAX_GROUP) distinct handles with equal d_in and dtype;
+ * each keeps its own tau, rank and d_out.  Y_devs: host array of n_layers device pointers.  Results
+ * equal n_layers separate rsparse_linear / rsparse_dense_ref calls.  Launch-shape overrides
+ * (waves, nontemporal, stages, dense_kernel) are taken from layers[0].
+ */
+#define RSPARSE_MAX_GROUP 4
+rsparse_status rsparse_linear_group(rsparse_layer *const *layers, int32_t n_layers, const void *X_dev,
+                                    int32_t batch, void *const *Y_devs, void *stream);
+rsparse_status rsparse_dense_ref_group(rsparse_layer *const *layers, int32_t n_layers, const void *X_dev,
+                                       int32_t batch, void *const *Y_devs, void *stream);
 
 /*
  * Kept-channel index set of the last rsparse_linear call on this handle (synchronises that

@@ -13,7 +13,7 @@ _STATUS = {1: "EINVAL", 2: "ENOMEM", 3: "EHIP", 4: "EBATCH", 5: "EALIGN", 6: "ES
 
 EXPORTED_SYMBOLS = [
     "rsparse_prepare", "rsparse_compute_factors", "rsparse_prepare_factors", "rsparse_linear",
-    "rsparse_dense_ref", "rsparse_last_active", "rsparse_get_factors", "rsparse_set_tau", "rsparse_set_tuning",
+    "rsparse_dense_ref", "rsparse_linear_group", "rsparse_dense_ref_group", "rsparse_last_active", "rsparse_get_factors", "rsparse_set_tau", "rsparse_set_tuning",
     "rsparse_get_config", "rsparse_calibrate_tau", "rsparse_required_bytes", "rsparse_dense_bytes",
     "rsparse_destroy", "rsparse_last_error",
 ]
@@ -28,7 +28,7 @@ class Config(C.Structure):
 class Tuning(C.Structure):
     _fields_ = [("splits", C.c_int32), ("waves", C.c_int32), ("lowrank_rows", C.c_int32),
                 ("dense_kernel", C.c_int32), ("nontemporal", C.c_int32), ("stages", C.c_int32),
-                ("reserved", C.c_int32 * 2)]
+                ("tile_map", C.c_int32), ("reserved", C.c_int32 * 1)]
 
 
 class RSparseError(RuntimeError):
@@ -67,6 +67,8 @@ def load_library():
     lib.rsparse_prepare_factors.argtypes = [C.POINTER(Config), vp, vp, vp, C.POINTER(vp)]
     lib.rsparse_linear.argtypes = [vp, vp, i32, vp, vp]
     lib.rsparse_dense_ref.argtypes = [vp, vp, i32, vp, vp]
+    lib.rsparse_linear_group.argtypes = [vp, i32, vp, i32, vp, vp]
+    lib.rsparse_dense_ref_group.argtypes = [vp, i32, vp, i32, vp, vp]
     lib.rsparse_last_active.argtypes = [vp, i32, vp, C.POINTER(i32)]
     lib.rsparse_get_factors.argtypes = [vp, vp, vp]
     lib.rsparse_set_tau.argtypes = [vp, C.c_float]
@@ -80,7 +82,8 @@ def load_library():
     lib.rsparse_destroy.argtypes = [vp]
     lib.rsparse_destroy.restype = None
     lib.rsparse_last_error.restype = C.c_char_p
-    for name in ("rsparse_prepare", "rsparse_compute_factors", "rsparse_prepare_factors", "rsparse_linear", "rsparse_dense_ref",
+    for name in ("rsparse_linear_group", "rsparse_dense_ref_group", "rsparse_prepare", "rsparse_compute_factors",
+                 "rsparse_prepare_factors", "rsparse_linear", "rsparse_dense_ref",
                  "rsparse_last_active", "rsparse_get_factors", "rsparse_set_tau", "rsparse_set_tuning",
                  "rsparse_get_config", "rsparse_calibrate_tau"):
         getattr(lib, name).restype = C.c_int
@@ -172,6 +175,26 @@ def rsparse_linear(layer: Layer, X_dev: int, batch: int, Y_dev: int, stream: int
 
 def rsparse_dense_ref(layer: Layer, X_dev: int, batch: int, Y_dev: int, stream: int = 0):
     _check(load_library().rsparse_dense_ref(layer.handle, X_dev, batch, Y_dev, stream))
+
+
+def _group_arrays(layers, Y_devs):
+    n = len(layers)
+    if n != len(Y_devs):
+        raise ValueError("one output pointer per layer")
+    hs = (C.c_void_p * n)(*[l.handle.value for l in layers])
+    ys = (C.c_void_p * n)(*[int(y) for y in Y_devs])
+    return n, hs, ys
+
+
+def rsparse_linear_group(layers, X_dev: int, batch: int, Y_devs, stream: int = 0):
+    """Layers sharing one input (q/k/v, gate/up): one pair of launches for all of them."""
+    n, hs, ys = _group_arrays(layers, Y_devs)
+    _check(load_library().rsparse_linear_group(hs, n, X_dev, batch, ys, stream))
+
+
+def rsparse_dense_ref_group(layers, X_dev: int, batch: int, Y_devs, stream: int = 0):
+    n, hs, ys = _group_arrays(layers, Y_devs)
+    _check(load_library().rsparse_dense_ref_group(hs, n, X_dev, batch, ys, stream))
 
 
 def rsparse_last_active(layer: Layer, token: int) -> np.ndarray:

@@ -171,7 +171,7 @@ rsparse_status check_config(const rsparse_config *c)
 // Launch shape: column tiles x channel splits ~ a few workgroups per compute unit, each with
 // enough rows to amortise its scan, and the staged share small enough for 64 KiB of LDS.
 // Stage-1 workgroups get about as many bytes of S_r V_r^T as a gather workgroup gets of W.
-Launch resolve_launch(const rsparse_layer *L, int batch, bool dense)
+Launch resolve_launch(const rsparse_layer *L, int batch, bool dense, int group)
 {
     Launch c{};
     const rsparse_tuning &t = L->tuning;
@@ -181,10 +181,12 @@ Launch resolve_launch(const rsparse_layer *L, int batch, bool dense)
     // device-scope atomics serialise at ~0.1 us each, which sets the kernel's tail).
     c.waves = (t.waves == 1 || t.waves == 2 || t.waves == 4 || t.waves == 8) ? t.waves : (bt >= 8 ? 4 : 8);
     c.nontemporal = t.nontemporal ? 1 : 0;
+    c.tile_map = t.tile_map == 0 ? 1 : t.tile_map;
     const int rows = dense ? L->cfg.d_in : std::max(8, L->cfg.d_in / 2);     // expected rows to stream
     int splits = t.splits;
     if (splits <= 0) {
-        const int target_wgs = (3 * L->cus) / 2 * (8 / c.waves);
+        // one resident round of workgroups for the whole launch: a group of layers shares it
+        const int target_wgs = std::max(L->tiles, (3 * L->cus) / 2 * (8 / c.waves) / std::max(1, group));
         splits = (target_wgs + L->tiles - 1) / L->tiles;
         const int max_by_rows = std::max(1, rows / (c.waves * 4));          // >= 4 rows per wave
         splits = std::max(1, std::min(splits, max_by_rows));
@@ -351,35 +353,78 @@ rsparse_status rsparse_prepare(const rsparse_config *cfg, const void *W_host, rs
     return build_layer(cfg, (const uint16_t *)W_host, U16.data(), SV16.data(), out);
 }
 
-rsparse_status rsparse_linear(rsparse_layer *L, const void *X_dev, int32_t batch, void *Y_dev, void *stream)
+namespace {
+
+rsparse_status check_group(rsparse_layer *const *layers, int32_t n, const void *X, int32_t batch, void *const *Y)
 {
-    rsparse_status st = check_call(L, X_dev, batch, Y_dev);
+    if (!layers || !Y) return fail(RSPARSE_EINVAL, "layers and Y_devs must be non-NULL");
+    if (n < 1 || n > RSPARSE_MAX_GROUP) return fail(RSPARSE_EINVAL, "n_layers %d outside [1, %d]", n, RSPARSE_MAX_GROUP);
+    for (int i = 0; i < n; ++i) {
+        rsparse_status st = check_call(layers[i], X, batch, Y[i]);
+        if (st != RSPARSE_OK) return st;
+        if (layers[i]->cfg.d_in != layers[0]->cfg.d_in || layers[i]->cfg.dtype != layers[0]->cfg.dtype)
+            return fail(RSPARSE_EINVAL, "grouped layers must share d_in and dtype");
+        for (int k = 0; k < i; ++k)
+            if (layers[k] == layers[i]) return fail(RSPARSE_EINVAL, "a layer appears twice in the group");
+    }
+    return RSPARSE_OK;
+}
+
+}  // namespace
+
+rsparse_status rsparse_linear_group(rsparse_layer *const *layers, int32_t n_layers, const void *X_dev, int32_t batch,
+                                    void *const *Y_devs, void *stream)
+{
+    rsparse_status st = check_group(layers, n_layers, X_dev, batch, Y_devs);
     if (st != RSPARSE_OK) return st;
     hipStream_t s = (hipStream_t)stream;
-    const Launch lc = resolve_launch(L, batch, false);
-    const LayerView v = L->view();
-    if (L->tuning.stages != 2) RS_HIP(launch_sparse_and_t(v, lc, X_dev, batch, true, true, s));
-    if (L->tuning.stages != 1) RS_HIP(launch_finish(v, batch, Y_dev, true, s));
-    L->last_stream = s;
-    L->last_batch = batch;
+    LayerView v[RSPARSE_MAX_GROUP];
+    Launch lc[RSPARSE_MAX_GROUP];
+    for (int i = 0; i < n_layers; ++i) {
+        v[i] = layers[i]->view();
+        lc[i] = resolve_launch(layers[i], batch, false, n_layers);
+    }
+    const int stages = layers[0]->tuning.stages;
+    if (stages != 2) RS_HIP(launch_sparse_and_t(v, lc, n_layers, X_dev, batch, true, true, s));
+    if (stages != 1) RS_HIP(launch_finish(v, n_layers, batch, Y_devs, true, s));
+    for (int i = 0; i < n_layers; ++i) {
+        layers[i]->last_stream = s;
+        layers[i]->last_batch = batch;
+    }
+    return RSPARSE_OK;
+}
+
+rsparse_status rsparse_linear(rsparse_layer *L, const void *X_dev, int32_t batch, void *Y_dev, void *stream)
+{
+    return rsparse_linear_group(&L, 1, X_dev, batch, &Y_dev, stream);
+}
+
+rsparse_status rsparse_dense_ref_group(rsparse_layer *const *layers, int32_t n_layers, const void *X_dev,
+                                       int32_t batch, void *const *Y_devs, void *stream)
+{
+    rsparse_status st = check_group(layers, n_layers, X_dev, batch, Y_devs);
+    if (st != RSPARSE_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    LayerView v[RSPARSE_MAX_GROUP];
+    Launch lc[RSPARSE_MAX_GROUP];
+    bool can_rowdot = true;
+    for (int i = 0; i < n_layers; ++i) {
+        v[i] = layers[i]->view();
+        lc[i] = resolve_launch(layers[i], batch, true, n_layers);
+        can_rowdot = can_rowdot && layers[i]->Wrow != nullptr && rowdot_supported(layers[i]->cfg.d_in, batch);
+    }
+    int kernel = layers[0]->tuning.dense_kernel;
+    if (kernel == 2 && !can_rowdot)
+        return fail(RSPARSE_EINVAL, "row-dot dense kernel needs dense_rowmajor=1 and batch_tile*d_in*2 <= 64 KiB");
+    if (kernel == 0) kernel = can_rowdot ? 2 : 1;
+    if (kernel == 2) RS_HIP(launch_dense_rowdot(v, lc, n_layers, X_dev, batch, Y_devs, s));
+    else RS_HIP(launch_dense_axpy(v, lc, n_layers, X_dev, batch, Y_devs, s));
     return RSPARSE_OK;
 }
 
 rsparse_status rsparse_dense_ref(rsparse_layer *L, const void *X_dev, int32_t batch, void *Y_dev, void *stream)
 {
-    rsparse_status st = check_call(L, X_dev, batch, Y_dev);
-    if (st != RSPARSE_OK) return st;
-    hipStream_t s = (hipStream_t)stream;
-    const Launch lc = resolve_launch(L, batch, true);
-    const LayerView v = L->view();
-    int kernel = L->tuning.dense_kernel;
-    const bool can_rowdot = L->Wrow != nullptr && rowdot_supported(L->cfg.d_in, batch);
-    if (kernel == 2 && !can_rowdot)
-        return fail(RSPARSE_EINVAL, "row-dot dense kernel needs dense_rowmajor=1 and batch_tile*d_in*2 <= 64 KiB");
-    if (kernel == 0) kernel = can_rowdot ? 2 : 1;
-    if (kernel == 2) RS_HIP(launch_dense_rowdot(v, lc, X_dev, batch, Y_dev, s));
-    else RS_HIP(launch_dense_axpy(v, lc, X_dev, batch, Y_dev, s));
-    return RSPARSE_OK;
+    return rsparse_dense_ref_group(&L, 1, X_dev, batch, &Y_dev, stream);
 }
 
 rsparse_status rsparse_last_active(rsparse_layer *L, int32_t token, int32_t *idx_host, int32_t *count)
@@ -449,6 +494,7 @@ rsparse_status rsparse_set_tuning(rsparse_layer *L, const rsparse_tuning *t)
     if (!L || !t) return fail(RSPARSE_EINVAL, "NULL argument");
     if (t->splits < 0 || t->waves < 0 || t->lowrank_rows < 0 || t->dense_kernel < 0 || t->dense_kernel > 2)
         return fail(RSPARSE_EINVAL, "negative or unknown tuning value");
+    if (t->tile_map < 0 || t->tile_map > 2) return fail(RSPARSE_EINVAL, "tile_map must be 0, 1 or 2");
     if (t->stages < 0 || t->stages > 2) return fail(RSPARSE_EINVAL, "stages must be 0, 1 or 2");
     if (t->waves != 0 && t->waves != 1 && t->waves != 2 && t->waves != 4 && t->waves != 8)
         return fail(RSPARSE_EINVAL, "waves must be 0, 1, 2, 4 or 8");

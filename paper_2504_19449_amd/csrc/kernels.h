@@ -32,18 +32,23 @@ struct Launch {
     int waves;         // waves per workgroup (first launch / dense axpy)
     int lowrank_rows;  // rows of S_r V_r^T per stage-1 workgroup
     int nontemporal;
+    int tile_map;      // 1: tile-fastest workgroup order, 2: XCD-aware (a tile's splits share id mod 8)
 };
+
+// All launchers take a group of n <= kMaxGroupLayers layers that read the same input X (same d_in and
+// dtype); cfg[0].waves and cfg[0].nontemporal apply to the whole launch.
+constexpr int kMaxGroupLayers = 4;
 
 // First launch: stage 1 of the low-rank part (with_t) and threshold + compaction + gather-GEMV over
 // the kept columns into yacc (with_gather), as independent workgroups of one grid.
-hipError_t launch_sparse_and_t(const LayerView &L, const Launch &cfg, const void *X, int batch, bool with_t,
+hipError_t launch_sparse_and_t(const LayerView *L, const Launch *cfg, int n, const void *X, int batch, bool with_t,
                                bool with_gather, hipStream_t stream);
 // Second launch: Y = round(yacc + U_r t) (use_rank) or round(yacc); re-zeroes yacc.
-hipError_t launch_finish(const LayerView &L, int batch, void *Y, bool use_rank, hipStream_t stream);
+hipError_t launch_finish(const LayerView *L, int n, int batch, void *const *Y, bool use_rank, hipStream_t stream);
 // Dense baselines.
-hipError_t launch_dense_axpy(const LayerView &L, const Launch &cfg, const void *X, int batch, void *Y,
+hipError_t launch_dense_axpy(const LayerView *L, const Launch *cfg, int n, const void *X, int batch, void *const *Y,
                              hipStream_t stream);
-hipError_t launch_dense_rowdot(const LayerView &L, const Launch &cfg, const void *X, int batch, void *Y,
+hipError_t launch_dense_rowdot(const LayerView *L, const Launch *cfg, int n, const void *X, int batch, void *const *Y,
                                hipStream_t stream);
 // Zero `n` 32-bit words (a fill kernel, safe to record into a HIP graph).
 hipError_t launch_zero(void *p, size_t n_words, hipStream_t stream);

@@ -21,6 +21,8 @@
 //   k_finish         Y = round(yacc + U t)   (row dots over U, no reduction), yacc re-zeroed.
 #include "kernels.h"
 
+#include <algorithm>
+
 namespace rsparse {
 namespace {
 
@@ -263,7 +265,44 @@ struct GatherArgs {
     const uint16_t *X;
     int batch, splits, tiles, cap;
     int lr_wgs, lr_rows, lr_chunk;     // stage-1 workgroups at the front of the grid, rows each, LDS chunk
+    int tile_map;
 };
+
+// Workgroup index -> (column tile, channel split).  Plain: tile-fastest.  XCD-aware: workgroups are
+// handed to the 8 XCDs round-robin by index, and fp32 atomics from different XCDs to one line move
+// it between their L2s; giving every split of a tile an index congruent to (tile mod 8) keeps a
+// tile's accumulators in one L2.  Indices past the last real pair are idle.
+__device__ __forceinline__ bool map_tile(const GatherArgs &a, int g, int &tile, int &split)
+{
+    if (a.tile_map != 2) {
+        tile = g % a.tiles;
+        split = g / a.tiles;
+        return true;
+    }
+    const int x = g & 7, slot = g >> 3;              // slot enumerates (tile / 8, split)
+    const int tgroup = slot / a.splits;
+    split = slot % a.splits;
+    tile = tgroup * 8 + x;
+    return tile < a.tiles;
+}
+
+// Several layers that read the same input share one launch: job i owns workgroups
+// [wg_end[i-1], wg_end[i]) of the grid.
+constexpr int kMaxGroup = 4;
+struct GroupArgs {
+    GatherArgs job[kMaxGroup];
+    int wg_end[kMaxGroup];
+    int n;
+};
+__device__ __forceinline__ int find_job(const int (&wg_end)[kMaxGroup], int n, int wg, int &local)
+{
+    int li = 0, begin = 0;
+#pragma unroll
+    for (int i = 0; i < kMaxGroup - 1; ++i)
+        if (i + 1 < n && wg >= wg_end[i]) { li = i + 1; begin = wg_end[i]; }
+    local = wg - begin;
+    return li;
+}
 
 // LDS carve-up of the gather part.
 struct GatherLds {
@@ -378,17 +417,19 @@ __device__ __forceinline__ void lowrank_rows(const GatherArgs &a, unsigned char 
 // grid.x = lr_wgs + tiles * splits, grid.z = batch tiles of BT tokens, block = 64 * waves.
 // ---------------------------------------------------------------------------------------------
 template <int DT, int BT, bool NT>
-__global__ __launch_bounds__(512) void k_sparse_and_t(const GatherArgs a)
+__global__ __launch_bounds__(512) void k_sparse_and_t(const GroupArgs ga)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int z = blockIdx.z;
-    if ((int)blockIdx.x < a.lr_wgs) {
-        lowrank_rows<DT, BT>(a, smem, blockIdx.x, z);
+    int wg;
+    const GatherArgs &a = ga.job[find_job(ga.wg_end, ga.n, blockIdx.x, wg)];
+    if (wg < a.lr_wgs) {
+        lowrank_rows<DT, BT>(a, smem, wg, z);
         return;
     }
     const int tid = threadIdx.x, nthr = blockDim.x, lane = tid & 63, w = tid >> 6, nw = nthr >> 6;
-    const int g = blockIdx.x - a.lr_wgs;
-    const int tile = g % a.tiles, split = g / a.tiles;
+    int tile, split;
+    if (!map_tile(a, wg - a.lr_wgs, tile, split)) return;
     const LayerView &L = a.L;
     const int d_in = L.d_in, d_out = L.d_out;
     const int b0 = z * BT;
@@ -477,12 +518,15 @@ __global__ __launch_bounds__(512) void k_sparse_and_t(const GatherArgs a)
 // Followed by k_finish with rank 0.
 // ---------------------------------------------------------------------------------------------
 template <int DT, int BT, bool NT>
-__global__ __launch_bounds__(512) void k_dense_axpy(const GatherArgs a)
+__global__ __launch_bounds__(512) void k_dense_axpy(const GroupArgs ga)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, nthr = blockDim.x, lane = tid & 63, w = tid >> 6, nw = nthr >> 6;
     const int z = blockIdx.z;
-    const int tile = blockIdx.x % a.tiles, split = blockIdx.x / a.tiles;
+    int wg;
+    const GatherArgs &a = ga.job[find_job(ga.wg_end, ga.n, blockIdx.x, wg)];
+    int tile, split;
+    if (!map_tile(a, wg, tile, split)) return;
     const LayerView &L = a.L;
     const int d_in = L.d_in, d_out = L.d_out;
     const int b0 = z * BT;
@@ -533,14 +577,21 @@ struct FinishArgs {
 };
 
 constexpr int kFinishGroups = 4;     // row groups per wave, all loads issued up front
+struct FinishGroupArgs {
+    FinishArgs job[kMaxGroup];
+    int wg_end[kMaxGroup];
+    int n;
+};
 
 // PASSES = 16-byte pieces per lane and row (rank <= 512 * PASSES); 0 = any rank, loads not batched.
 template <int DT, int BT, int PASSES>
-__global__ __launch_bounds__(256) void k_finish(const FinishArgs a)
+__global__ __launch_bounds__(256) void k_finish(const FinishGroupArgs ga)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int z = blockIdx.z;
+    int wg;
+    const FinishArgs &a = ga.job[find_job(ga.wg_end, ga.n, blockIdx.x, wg)];
     const LayerView &L = a.L;
     const int d_out = L.d_out, r = a.use_rank;
     const int b0 = z * BT;
@@ -548,7 +599,7 @@ __global__ __launch_bounds__(256) void k_finish(const FinishArgs a)
     float *s_t = reinterpret_cast<float *>(smem);             // [BT][r]
     const int lpr = a.lpr, rpi = 64 / lpr;                    // lanes per row, rows per wave and group
     const int sub = lane % lpr, rsel = lane / lpr;
-    const int o_wave = (blockIdx.x * 4 + w) * (rpi * kFinishGroups);
+    const int o_wave = (wg * 4 + w) * (rpi * kFinishGroups);
     constexpr int NP = PASSES > 0 ? PASSES : 1;
 
     // U_r rows and the accumulators first: their latency covers the staging of t
@@ -632,12 +683,24 @@ struct RowdotArgs {
     int batch;
 };
 
+struct RowdotGroupArgs {
+    RowdotArgs job[kMaxGroup];
+    int wg_end[kMaxGroup];
+    int n;
+};
+
 template <int DT, int BT, bool NT>
-__global__ __launch_bounds__(256) void k_dense_rowdot(const RowdotArgs a)
+__global__ __launch_bounds__(256) void k_dense_rowdot(const RowdotGroupArgs ga)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int z = blockIdx.z;
+    int wg, wg_count;
+    {
+        const int li = find_job(ga.wg_end, ga.n, blockIdx.x, wg);
+        wg_count = ga.wg_end[li] - (li ? ga.wg_end[li - 1] : 0);
+    }
+    const RowdotArgs &a = ga.job[find_job(ga.wg_end, ga.n, blockIdx.x, wg)];
     const LayerView &L = a.L;
     const int d_in = L.d_in, d_out = L.d_out;
     const int b0 = z * BT;
@@ -652,7 +715,7 @@ __global__ __launch_bounds__(256) void k_dense_rowdot(const RowdotArgs a)
             *reinterpret_cast<u32x4 *>(s_x + (size_t)b * d_in + q * 8) = v;
         }
     __syncthreads();
-    for (int o = blockIdx.x * 4 + w; o < d_out; o += gridDim.x * 4) {
+    for (int o = wg * 4 + w; o < d_out; o += wg_count * 4) {
         const uint16_t *row = L.Wrow + (size_t)o * d_in;
         float acc[BT];
 #pragma unroll
@@ -726,99 +789,151 @@ bool rowdot_supported(int d_in, int batch)
     default: { constexpr int BT = 8; __VA_ARGS__; } break; \
     }
 
-hipError_t launch_sparse_and_t(const LayerView &L, const Launch &cfg, const void *X, int batch, bool with_t,
+static bool same_shape_class(const LayerView *L, int n)
+{
+    for (int i = 1; i < n; ++i)
+        if (L[i].d_in != L[0].d_in || L[i].dtype != L[0].dtype) return false;
+    return n >= 1 && n <= kMaxGroup;
+}
+
+hipError_t launch_sparse_and_t(const LayerView *L, const Launch *cfg, int n, const void *X, int batch, bool with_t,
                                bool with_gather, hipStream_t stream)
 {
+    if (!same_shape_class(L, n)) return hipErrorInvalidValue;
     const int bt = batch_tile(batch);
     const int nz = (batch + bt - 1) / bt;
-    const int tiles = (L.d_out + kTile - 1) / kTile;
-    GatherArgs a{};
-    a.L = L; a.X = (const uint16_t *)X; a.batch = batch; a.splits = cfg.splits; a.tiles = tiles;
-    a.cap = gather_cap(L.d_in, cfg.splits);
-    a.lr_rows = cfg.lowrank_rows;
-    a.lr_wgs = (with_t && L.rank > 0) ? (L.rank + cfg.lowrank_rows - 1) / cfg.lowrank_rows : 0;
-    a.lr_chunk = lowrank_chunk(L.d_in, bt);
-    const int gather_wgs = with_gather ? tiles * cfg.splits : 0;
-    if (a.lr_wgs + gather_wgs == 0) return hipSuccess;
-    size_t lds = gather_lds_bytes(L.d_in, cfg.splits, cfg.waves, bt);
-    if (a.lr_wgs > 0 && lowrank_lds_bytes(L.d_in, bt) > lds) lds = lowrank_lds_bytes(L.d_in, bt);
-    dim3 grid(a.lr_wgs + gather_wgs, 1, nz), block(kWave * cfg.waves);
-#define RS_G(DT)                                                                                               \
-    RS_DISPATCH_BT(bt, {                                                                                       \
-        if (cfg.nontemporal) hipLaunchKernelGGL((k_sparse_and_t<DT, BT, true>), grid, block, lds, stream, a);  \
-        else hipLaunchKernelGGL((k_sparse_and_t<DT, BT, false>), grid, block, lds, stream, a);                 \
+    GroupArgs ga{};
+    ga.n = n;
+    size_t lds = 0;
+    int total = 0;
+    for (int i = 0; i < n; ++i) {
+        GatherArgs &a = ga.job[i];
+        const int tiles = (L[i].d_out + kTile - 1) / kTile;
+        a.L = L[i]; a.X = (const uint16_t *)X; a.batch = batch; a.splits = cfg[i].splits; a.tiles = tiles;
+        a.cap = gather_cap(L[i].d_in, cfg[i].splits);
+        a.lr_rows = cfg[i].lowrank_rows;
+        a.lr_wgs = (with_t && L[i].rank > 0) ? (L[i].rank + cfg[i].lowrank_rows - 1) / cfg[i].lowrank_rows : 0;
+        a.lr_chunk = lowrank_chunk(L[i].d_in, bt);
+        a.tile_map = cfg[i].tile_map;
+        const int gather_wgs = !with_gather ? 0
+                               : cfg[i].tile_map == 2 ? ((tiles + 7) / 8) * 8 * cfg[i].splits : tiles * cfg[i].splits;
+        total += a.lr_wgs + gather_wgs;
+        ga.wg_end[i] = total;
+        lds = std::max(lds, gather_lds_bytes(L[i].d_in, cfg[i].splits, cfg[0].waves, bt));
+        if (a.lr_wgs > 0) lds = std::max(lds, lowrank_lds_bytes(L[i].d_in, bt));
+    }
+    for (int i = n; i < kMaxGroup; ++i) ga.wg_end[i] = total;
+    if (total == 0) return hipSuccess;
+    dim3 grid(total, 1, nz), block(kWave * cfg[0].waves);
+    const bool nt = cfg[0].nontemporal != 0;
+#define RS_G(DT)                                                                                       \
+    RS_DISPATCH_BT(bt, {                                                                               \
+        if (nt) hipLaunchKernelGGL((k_sparse_and_t<DT, BT, true>), grid, block, lds, stream, ga);      \
+        else hipLaunchKernelGGL((k_sparse_and_t<DT, BT, false>), grid, block, lds, stream, ga);        \
     })
-    if (L.dtype == F16) { RS_G(F16) } else { RS_G(BF16) }
+    if (L[0].dtype == F16) { RS_G(F16) } else { RS_G(BF16) }
 #undef RS_G
     return hipGetLastError();
 }
 
-hipError_t launch_finish(const LayerView &L, int batch, void *Y, bool use_rank, hipStream_t stream)
+hipError_t launch_finish(const LayerView *L, int n, int batch, void *const *Y, bool use_rank, hipStream_t stream)
 {
+    if (!same_shape_class(L, n)) return hipErrorInvalidValue;
     const int bt = batch_tile(batch);
     const int nz = (batch + bt - 1) / bt;
-    FinishArgs a{};
-    a.L = L; a.Y = Y; a.batch = batch;
-    a.use_rank = use_rank ? L.rank : 0;
-    const int chunks = (a.use_rank + 7) / 8;          // 16-byte pieces per row of U_r
-    int lpr = 1;
-    while (lpr < chunks && lpr < 64) lpr <<= 1;
-    a.lpr = lpr;
-    a.passes = chunks == 0 ? 0 : (chunks + lpr - 1) / lpr;
-    const int rows_per_wg = 4 * (64 / lpr) * kFinishGroups;
-    const int wgs = (L.d_out + rows_per_wg - 1) / rows_per_wg;
-    const size_t lds = (size_t)bt * a.use_rank * 4 + 16;
-    dim3 grid(wgs, 1, nz), block(256);
-#define RS_F(DT)                                                                                          \
-    RS_DISPATCH_BT(bt, {                                                                                  \
-        if (a.passes <= 1) hipLaunchKernelGGL((k_finish<DT, BT, 1>), grid, block, lds, stream, a);        \
-        else if (a.passes == 2) hipLaunchKernelGGL((k_finish<DT, BT, 2>), grid, block, lds, stream, a);   \
-        else hipLaunchKernelGGL((k_finish<DT, BT, 0>), grid, block, lds, stream, a);                      \
+    FinishGroupArgs ga{};
+    ga.n = n;
+    size_t lds = 16;
+    int total = 0, max_passes = 0;
+    for (int i = 0; i < n; ++i) {
+        FinishArgs &a = ga.job[i];
+        a.L = L[i]; a.Y = Y[i]; a.batch = batch;
+        a.use_rank = use_rank ? L[i].rank : 0;
+        const int chunks = (a.use_rank + 7) / 8;          // 16-byte pieces per row of U_r
+        int lpr = 1;
+        while (lpr < chunks && lpr < 64) lpr <<= 1;
+        a.lpr = lpr;
+        a.passes = chunks == 0 ? 0 : (chunks + lpr - 1) / lpr;
+        max_passes = std::max(max_passes, a.passes);
+        const int rows_per_wg = 4 * (64 / lpr) * kFinishGroups;
+        total += (L[i].d_out + rows_per_wg - 1) / rows_per_wg;
+        ga.wg_end[i] = total;
+        lds = std::max(lds, (size_t)bt * a.use_rank * 4 + 16);
+    }
+    for (int i = n; i < kMaxGroup; ++i) ga.wg_end[i] = total;
+    dim3 grid(total, 1, nz), block(256);
+#define RS_F(DT)                                                                                           \
+    RS_DISPATCH_BT(bt, {                                                                                   \
+        if (max_passes <= 1) hipLaunchKernelGGL((k_finish<DT, BT, 1>), grid, block, lds, stream, ga);      \
+        else if (max_passes == 2) hipLaunchKernelGGL((k_finish<DT, BT, 2>), grid, block, lds, stream, ga); \
+        else hipLaunchKernelGGL((k_finish<DT, BT, 0>), grid, block, lds, stream, ga);                      \
     })
-    if (L.dtype == F16) { RS_F(F16) } else { RS_F(BF16) }
+    if (L[0].dtype == F16) { RS_F(F16) } else { RS_F(BF16) }
 #undef RS_F
     return hipGetLastError();
 }
 
-hipError_t launch_dense_axpy(const LayerView &L, const Launch &cfg, const void *X, int batch, void *Y,
+hipError_t launch_dense_axpy(const LayerView *L, const Launch *cfg, int n, const void *X, int batch, void *const *Y,
                              hipStream_t stream)
 {
+    if (!same_shape_class(L, n)) return hipErrorInvalidValue;
     const int bt = batch_tile(batch);
     const int nz = (batch + bt - 1) / bt;
-    const int tiles = (L.d_out + kTile - 1) / kTile;
-    GatherArgs a{};
-    a.L = L; a.X = (const uint16_t *)X; a.batch = batch; a.splits = cfg.splits; a.tiles = tiles;
-    a.cap = gather_cap(L.d_in, cfg.splits);
-    const size_t lds = gather_lds_bytes(L.d_in, cfg.splits, cfg.waves, bt);
-    dim3 grid(tiles * cfg.splits, 1, nz), block(kWave * cfg.waves);
-#define RS_D(DT)                                                                                             \
-    RS_DISPATCH_BT(bt, {                                                                                     \
-        if (cfg.nontemporal) hipLaunchKernelGGL((k_dense_axpy<DT, BT, true>), grid, block, lds, stream, a);  \
-        else hipLaunchKernelGGL((k_dense_axpy<DT, BT, false>), grid, block, lds, stream, a);                 \
+    GroupArgs ga{};
+    ga.n = n;
+    size_t lds = 0;
+    int total = 0;
+    for (int i = 0; i < n; ++i) {
+        GatherArgs &a = ga.job[i];
+        const int tiles = (L[i].d_out + kTile - 1) / kTile;
+        a.L = L[i]; a.X = (const uint16_t *)X; a.batch = batch; a.splits = cfg[i].splits; a.tiles = tiles;
+        a.cap = gather_cap(L[i].d_in, cfg[i].splits);
+        a.tile_map = cfg[i].tile_map;
+        total += cfg[i].tile_map == 2 ? ((tiles + 7) / 8) * 8 * cfg[i].splits : tiles * cfg[i].splits;
+        ga.wg_end[i] = total;
+        lds = std::max(lds, gather_lds_bytes(L[i].d_in, cfg[i].splits, cfg[0].waves, bt));
+    }
+    for (int i = n; i < kMaxGroup; ++i) ga.wg_end[i] = total;
+    dim3 grid(total, 1, nz), block(kWave * cfg[0].waves);
+    const bool nt = cfg[0].nontemporal != 0;
+#define RS_D(DT)                                                                                     \
+    RS_DISPATCH_BT(bt, {                                                                             \
+        if (nt) hipLaunchKernelGGL((k_dense_axpy<DT, BT, true>), grid, block, lds, stream, ga);      \
+        else hipLaunchKernelGGL((k_dense_axpy<DT, BT, false>), grid, block, lds, stream, ga);        \
     })
-    if (L.dtype == F16) { RS_D(F16) } else { RS_D(BF16) }
+    if (L[0].dtype == F16) { RS_D(F16) } else { RS_D(BF16) }
 #undef RS_D
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return launch_finish(L, batch, Y, false, stream);
+    return launch_finish(L, n, batch, Y, false, stream);
 }
 
-hipError_t launch_dense_rowdot(const LayerView &L, const Launch &cfg, const void *X, int batch, void *Y,
+hipError_t launch_dense_rowdot(const LayerView *L, const Launch *cfg, int n, const void *X, int batch, void *const *Y,
                                hipStream_t stream)
 {
+    if (!same_shape_class(L, n)) return hipErrorInvalidValue;
     const int bt = batch_tile(batch);
     const int nz = (batch + bt - 1) / bt;
-    RowdotArgs a{L, (const uint16_t *)X, Y, batch};
-    const size_t lds = (size_t)bt * L.d_in * 2;
-    int wgs = (L.d_out + 3) / 4;
-    if (wgs > 2048) wgs = 2048;
-    dim3 grid(wgs, 1, nz), block(256);
-#define RS_R(DT)                                                                                              \
-    RS_DISPATCH_BT(bt, {                                                                                      \
-        if (cfg.nontemporal) hipLaunchKernelGGL((k_dense_rowdot<DT, BT, true>), grid, block, lds, stream, a); \
-        else hipLaunchKernelGGL((k_dense_rowdot<DT, BT, false>), grid, block, lds, stream, a);                \
+    RowdotGroupArgs ga{};
+    ga.n = n;
+    int total = 0;
+    for (int i = 0; i < n; ++i) {
+        ga.job[i] = RowdotArgs{L[i], (const uint16_t *)X, Y[i], batch};
+        int wgs = (L[i].d_out + 3) / 4;
+        if (wgs > 2048) wgs = 2048;
+        total += wgs;
+        ga.wg_end[i] = total;
+    }
+    for (int i = n; i < kMaxGroup; ++i) ga.wg_end[i] = total;
+    const size_t lds = (size_t)bt * L[0].d_in * 2;
+    dim3 grid(total, 1, nz), block(256);
+    const bool nt = cfg[0].nontemporal != 0;
+#define RS_R(DT)                                                                                      \
+    RS_DISPATCH_BT(bt, {                                                                              \
+        if (nt) hipLaunchKernelGGL((k_dense_rowdot<DT, BT, true>), grid, block, lds, stream, ga);     \
+        else hipLaunchKernelGGL((k_dense_rowdot<DT, BT, false>), grid, block, lds, stream, ga);       \
     })
-    if (L.dtype == F16) { RS_R(F16) } else { RS_R(BF16) }
+    if (L[0].dtype == F16) { RS_R(F16) } else { RS_R(BF16) }
 #undef RS_R
     return hipGetLastError();
 }

@@ -215,3 +215,51 @@ def test_largest_shape_sampled():
     X16, src = gu.tokens_for(L2, 2, kind="down", config=4)
     tau = gu.calibrated_tau(L2, src, 0.5)
     _parity(L2, X16, tau, out_dtype=rs.F32)
+
+
+@pytest.mark.parametrize("B", [1, 3, 8])
+def test_group_of_layers_sharing_one_input(B):
+    """q/k/v- or gate/up-style groups: one pair of launches, results equal separate calls and the oracle.
+    Different d_out, rank and tau per layer."""
+    import oracle
+    specs = [(1032, 1096, 40, 0.5), (1032, 520, 0, 0.4), (1032, 2056, 64, 0.6)]
+    Ls = [synth.make_layer(d_in, d_out, r, synth.BF16, config=84, linear=i) for i, (d_in, d_out, r, _) in enumerate(specs)]
+    X16, src = gu.tokens_for(Ls[0], B, linear=B)
+    taus = [gu.calibrated_tau(Ls[0], src, s) for (_, _, _, s) in specs]
+    for out in (None, rs.F32):
+        layers = [gu.prepare(L, tau, max_batch=B, out_dtype=out, dense_rowmajor=1) for L, tau in zip(Ls, taus)]
+        Xd = gu.to_dev16(X16)
+        Ys = [gu._alloc_out(layer, B) for layer in layers]
+        rs.rsparse_linear_group(layers, Xd.data_ptr(), B, [y.data_ptr() for y in Ys], gu.stream_ptr())
+        for L, tau, layer, Y in zip(Ls, taus, layers, Ys):
+            got = {"Y": gu._read_out(layer, Y), "act": [rs.rsparse_last_active(layer, b) for b in range(B)],
+                   "union": rs.rsparse_last_active(layer, -1)}
+            want = gu.oracle_linear(L, X16, tau)
+            gu.check_lists(got, want)
+            gu.check_outputs(got["Y"], want["Y"], layer.cfg.out_dtype)
+        for kernel in (1, 2):
+            rs.rsparse_set_tuning(layers[0], dense_kernel=kernel)
+            Ys = [gu._alloc_out(layer, B) for layer in layers]
+            rs.rsparse_dense_ref_group(layers, Xd.data_ptr(), B, [y.data_ptr() for y in Ys], gu.stream_ptr())
+            for L, layer, Y in zip(Ls, layers, Ys):
+                want = oracle.dense_linear(L.W16, X16, L.dtype, L.dtype, nthreads=8)
+                gu.check_outputs(gu._read_out(layer, Y), want, layer.cfg.out_dtype)
+        for layer in layers:
+            layer.destroy()
+
+
+def test_group_argument_errors(ragged):
+    L = ragged[synth.F16]
+    other = synth.make_layer(520, 264, 0, synth.F16, config=82, linear=0)
+    a, b = gu.prepare(L, 0.5), gu.prepare(other, 0.5)
+    X16, _ = gu.tokens_for(L, 1)
+    Xd = gu.to_dev16(X16)
+    Y = gu._alloc_out(a, 1)
+    with pytest.raises(rs.RSparseError):       # different d_in
+        rs.rsparse_linear_group([a, b], Xd.data_ptr(), 1, [Y.data_ptr(), Y.data_ptr()], gu.stream_ptr())
+    with pytest.raises(rs.RSparseError):       # same handle twice
+        rs.rsparse_linear_group([a, a], Xd.data_ptr(), 1, [Y.data_ptr(), Y.data_ptr()], gu.stream_ptr())
+    with pytest.raises(rs.RSparseError):       # batch above max_batch
+        rs.rsparse_linear(a, Xd.data_ptr(), 2, Y.data_ptr(), gu.stream_ptr())
+    with pytest.raises(rs.RSparseError):       # misaligned X
+        rs.rsparse_linear(a, Xd.data_ptr() + 2, 1, Y.data_ptr(), gu.stream_ptr())

@@ -58,6 +58,8 @@ def test_null_arguments_are_rejected():
     lib = rs.load_library()
     assert lib.rsparse_linear(None, None, 1, None, None) == 1
     assert lib.rsparse_dense_ref(None, None, 1, None, None) == 1
+    assert lib.rsparse_linear_group(None, 1, None, 1, None, None) == 1
+    assert lib.rsparse_dense_ref_group(None, 0, None, 1, None, None) == 1
     assert lib.rsparse_last_active(None, 0, None, None) == 1
     assert lib.rsparse_set_tau(None, 0.5) == 1
     assert lib.rsparse_calibrate_tau(None, 0, 10, 0.5, None) == 1
