@@ -67,8 +67,10 @@ typedef struct {
     int32_t cmp_mode;        /* 0: keep |x| >= tau (the paper's definition)   1: keep |x| > tau */
     int32_t batch_mask_mode; /* 0: every token uses its own mask (sigma_t is elementwise)
                                 1: every token uses the union of the batch's masks */
-    int32_t dense_rowmajor;  /* 1: also keep W row-major on the device so that rsparse_dense_ref
-                                can use its row-dot kernel (doubles the weight footprint) */
+    int32_t dense_rowmajor;  /* 1: also keep W row-major on the device (doubles the weight footprint).  Needed by
+                                the row-dot kernel of rsparse_dense_ref and by the matrix-core path that
+                                rsparse_linear takes for 9..32 tokens; without it those batches run in
+                                tiles of 8 tokens on the vector ALU */
 } rsparse_config;
 
 /* Launch-shape overrides for measurements; 0 = library default. */
@@ -82,7 +84,7 @@ typedef struct {
                                 timing one kernel in isolation; results are only valid with 0 */
     int32_t tile_map;        /* workgroup -> (column tile, split) mapping: 0 default, 1 tile-fastest (plain),
                                 2 XCD-aware (all splits of a tile on ids congruent mod 8) */
-    int32_t reserved[1];
+    int32_t no_mfma;         /* 1: keep batches of 9..32 tokens on the vector-ALU path (tiles of 8 tokens) */
 } rsparse_tuning;
 
 /*

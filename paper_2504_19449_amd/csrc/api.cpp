@@ -125,7 +125,8 @@ struct rsparse_layer {
     int cus = 256;
     uint16_t *M = nullptr, *SVt = nullptr, *U = nullptr, *Wrow = nullptr;
     float *t = nullptr, *yacc = nullptr;
-    uint32_t *act_bits = nullptr;
+    uint32_t *act_bits = nullptr, *chan_bits = nullptr;
+    bool last_mfma = false;
     int32_t *act_list = nullptr, *act_count = nullptr;
     int tiles = 0, nz_max = 1;
     std::vector<uint16_t> U16, SV16;       // host copies of the stored factors
@@ -217,7 +218,7 @@ void free_layer(rsparse_layer *L)
 {
     if (!L) return;
     (void)hipFree(L->M); (void)hipFree(L->SVt); (void)hipFree(L->U); (void)hipFree(L->Wrow); (void)hipFree(L->t);
-    (void)hipFree(L->yacc); (void)hipFree(L->act_bits);
+    (void)hipFree(L->yacc); (void)hipFree(L->act_bits); (void)hipFree(L->chan_bits);
     (void)hipFree(L->act_list); (void)hipFree(L->act_count);
     delete L;
 }
@@ -268,6 +269,8 @@ rsparse_status build_layer(const rsparse_config *cfg, const uint16_t *W, const u
         RS_HIP(hipMalloc((void **)&L->act_list, n_list * 4));
         RS_HIP(hipMalloc((void **)&L->act_bits, n_list * 4));
         RS_HIP(hipMalloc((void **)&L->act_count, (size_t)L->nz_max * 4));
+        RS_HIP(hipMalloc((void **)&L->chan_bits, d_in * 4));
+        RS_HIP(hipMemset(L->chan_bits, 0, d_in * 4));
         RS_HIP(hipMemset(L->t, 0, n_t * 4));
         RS_HIP(hipMemset(L->yacc, 0, n_y * 4));
         RS_HIP(hipMemset(L->act_list, 0, n_list * 4));
@@ -385,11 +388,20 @@ rsparse_status rsparse_linear_group(rsparse_layer *const *layers, int32_t n_laye
         lc[i] = resolve_launch(layers[i], batch, false, n_layers);
     }
     const int stages = layers[0]->tuning.stages;
-    if (stages != 2) RS_HIP(launch_sparse_and_t(v, lc, n_layers, X_dev, batch, true, true, s));
-    if (stages != 1) RS_HIP(launch_finish(v, n_layers, batch, Y_devs, true, s));
+    bool mfma = batch > kMaxBT && layers[0]->tuning.no_mfma == 0;
+    for (int i = 0; i < n_layers; ++i) mfma = mfma && mfma_path_supported(v[i], batch);
+    if (mfma) {
+        // 9..32 tokens: matrix-core path, one layer at a time (each is already a full-chip launch)
+        for (int i = 0; i < n_layers; ++i)
+            RS_HIP(launch_mfma_linear(v[i], X_dev, batch, Y_devs[i], layers[i]->chan_bits, layers[i]->cus, stages, s));
+    } else {
+        if (stages != 2) RS_HIP(launch_sparse_and_t(v, lc, n_layers, X_dev, batch, true, true, s));
+        if (stages != 1) RS_HIP(launch_finish(v, n_layers, batch, Y_devs, true, s));
+    }
     for (int i = 0; i < n_layers; ++i) {
         layers[i]->last_stream = s;
         layers[i]->last_batch = batch;
+        layers[i]->last_mfma = mfma;
     }
     return RSPARSE_OK;
 }
@@ -433,6 +445,16 @@ rsparse_status rsparse_last_active(rsparse_layer *L, int32_t token, int32_t *idx
     if (L->last_batch == 0) return fail(RSPARSE_EINVAL, "no rsparse_linear call has been made on this layer");
     if (token < -1 || token >= L->last_batch) return fail(RSPARSE_EINVAL, "token %d outside [-1, %d)", token, L->last_batch);
     RS_HIP(hipStreamSynchronize(L->last_stream));
+    if (L->last_mfma) {
+        // the matrix-core path keeps per-channel token bits instead of compacted lists
+        std::vector<uint32_t> cb(L->cfg.d_in);
+        RS_HIP(hipMemcpy(cb.data(), L->chan_bits, cb.size() * 4, hipMemcpyDeviceToHost));
+        int32_t n = 0;
+        for (size_t c = 0; c < cb.size(); ++c)
+            if (token < 0 ? cb[c] != 0u : ((cb[c] >> token) & 1u) != 0u) idx_host[n++] = (int32_t)c;
+        *count = n;
+        return RSPARSE_OK;
+    }
     const int bt = batch_tile_of(L->last_batch);
     const int nz = (L->last_batch + bt - 1) / bt;
     const size_t d_in = L->cfg.d_in;
@@ -494,6 +516,7 @@ rsparse_status rsparse_set_tuning(rsparse_layer *L, const rsparse_tuning *t)
     if (!L || !t) return fail(RSPARSE_EINVAL, "NULL argument");
     if (t->splits < 0 || t->waves < 0 || t->lowrank_rows < 0 || t->dense_kernel < 0 || t->dense_kernel > 2)
         return fail(RSPARSE_EINVAL, "negative or unknown tuning value");
+    if (t->no_mfma < 0 || t->no_mfma > 1) return fail(RSPARSE_EINVAL, "no_mfma must be 0 or 1");
     if (t->tile_map < 0 || t->tile_map > 2) return fail(RSPARSE_EINVAL, "tile_map must be 0, 1 or 2");
     if (t->stages < 0 || t->stages > 2) return fail(RSPARSE_EINVAL, "stages must be 0, 1 or 2");
     if (t->waves != 0 && t->waves != 1 && t->waves != 2 && t->waves != 4 && t->waves != 8)

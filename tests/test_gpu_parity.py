@@ -263,3 +263,62 @@ def test_group_argument_errors(ragged):
         rs.rsparse_linear(a, Xd.data_ptr(), 2, Y.data_ptr(), gu.stream_ptr())
     with pytest.raises(rs.RSparseError):       # misaligned X
         rs.rsparse_linear(a, Xd.data_ptr() + 2, 1, Y.data_ptr(), gu.stream_ptr())
+
+
+@pytest.mark.parametrize("dt", [synth.F16, synth.BF16])
+@pytest.mark.parametrize("B", [9, 16, 17, 32])
+@pytest.mark.parametrize("mask_mode", [0, 1])
+def test_matrix_core_path_batches(ragged, dt, B, mask_mode):
+    """9..32 tokens with the row-major copy of W present: the MFMA path (dense masked GEMM, stage 1 and
+    stage 2 on matrix cores).  Same oracle, same tolerances; ragged K chunk (1032 = 32*32 + 8) and rows."""
+    L = ragged[dt]
+    X16, src = gu.tokens_for(L, B, linear=40 + B)
+    tau = gu.calibrated_tau(L, src, 0.5)
+    _parity(L, X16, tau, out_dtype=rs.F32, batch_mask_mode=mask_mode, dense_rowmajor=1)
+    _parity(L, X16, tau, batch_mask_mode=mask_mode, dense_rowmajor=1)
+
+
+def test_matrix_core_path_matches_vector_path_and_edges(ragged):
+    L = ragged[synth.BF16]
+    X16, src = gu.tokens_for(L, 20, linear=77)
+    tau = gu.calibrated_tau(L, src, 0.5)
+    layer = gu.prepare(L, tau, max_batch=32, out_dtype=rs.F32, dense_rowmajor=1)
+    a = gu.run_linear(layer, X16)
+    rs.rsparse_set_tuning(layer, no_mfma=1)
+    b = gu.run_linear(layer, X16)
+    gu.check_lists(a, b)
+    assert np.linalg.norm(a["Y"] - b["Y"]) <= 3e-5 * np.linalg.norm(b["Y"])
+    rs.rsparse_set_tuning(layer, no_mfma=0)
+    # same handle, smaller batches in between (vector path), then back: scratch stays consistent
+    for B in (3, 20, 1, 12):
+        got = gu.run_linear(layer, X16[:B])
+        want = gu.oracle_linear(L, X16[:B], tau)
+        gu.check_lists(got, want)
+        gu.check_outputs(got["Y"], want["Y"], rs.F32)
+    # thresholds at the extremes and a NaN token
+    for t2 in (-INF, INF):
+        rs.rsparse_set_tau(layer, t2)
+        got = gu.run_linear(layer, X16[:16])
+        want = gu.oracle_linear(L, X16[:16], t2)
+        gu.check_lists(got, want)
+        gu.check_outputs(got["Y"], want["Y"], rs.F32)
+    rs.rsparse_set_tau(layer, tau)
+    Xn = X16[:16].copy()
+    Xn[5, 9] = 0x7FC0
+    got = gu.run_linear(layer, Xn)
+    want = gu.oracle_linear(L, Xn, tau)
+    gu.check_lists(got, want)
+    gu.check_outputs(got["Y"], want["Y"], rs.F32)
+    assert np.all(np.isnan(got["Y"][5])) and np.all(np.isfinite(got["Y"][4]))
+    layer.destroy()
+
+
+@pytest.mark.parametrize("shape", [(4096, 1024, 128, 16), (4096, 4096, 512, 16), (8192, 8192, 1024, 32)])
+def test_matrix_core_path_llama3_shapes(shape):
+    """configs[3]/[4] shapes (GQA k/v 4096->1024, q/o 4096->4096, 70B q/o 8192->8192) at 16 / 32 tokens."""
+    d_in, d_out, r, B = shape
+    L = synth.random_layer(d_in, d_out, r, synth.BF16, seed=3000 + d_out)
+    X16, src = gu.tokens_for(L, B, config=3, linear=B)
+    tau = gu.calibrated_tau(L, src, 0.5)
+    _parity(L, X16, tau, dense_rowmajor=1)
+    _parity(L, X16, tau, out_dtype=rs.F32, dense_rowmajor=1)
