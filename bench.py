@@ -36,6 +36,72 @@ def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
+def shape_batch_sweep(args, torch, np, rs, synth):
+    """Other configs' shapes and batch sizes: us per linear for R-Sparse and for the dense baseline, each
+    over a ring of distinct layers (>= 0.9 GiB of weights), HIP-graph replay, 50 % per-token sparsity."""
+    cases = [  # (label, d_in, d_out, rank, dtype, input kind, batches)
+        ("c0 4096x4096 f16 r256", 4096, 4096, 256, synth.F16, "dmodel", (1,)),
+        ("c2 q/k/v/o 4096x4096 bf16 r256", 4096, 4096, 256, synth.BF16, "dmodel", (1, 2, 4, 8)),
+        ("c3 gate/up 4096x14336 bf16 r256", 4096, 14336, 256, synth.BF16, "dmodel", (1, 4, 16)),
+        ("c3 k/v 4096x1024 bf16 r128", 4096, 1024, 128, synth.BF16, "dmodel", (1, 16)),
+        ("c4 q/o 8192x8192 bf16 r1024", 8192, 8192, 1024, synth.BF16, "dmodel", (1, 8, 32)),
+        ("c4 gate/up 8192x28672 bf16 r1024", 8192, 28672, 1024, synth.BF16, "dmodel", (1, 8, 32)),
+        ("c4 down 28672x8192 bf16 r1024", 28672, 8192, 1024, synth.BF16, "down", (1, 32)),
+    ]
+    stream = torch.cuda.current_stream()
+    out = []
+    for label, d_in, d_out, rank, dt, kind, batches in cases:
+        n_ring = max(2, min(32, int(0.9 * 2 ** 30 / (d_in * d_out * 2)) + 1))
+        L = synth.random_layer(d_in, d_out, rank, dt, seed=d_in + d_out)
+        src = (synth.DModelInput if kind == "dmodel" else synth.DownInput)(d_in, config=5, linear=0)
+        tau = rs.rsparse_calibrate_tau(synth.encode16(src.tokens(64, stream=synth.STREAM_CALIB), dt), dt, 0.5)
+        maxb = max(batches)
+        layers = []
+        for i in range(n_ring):
+            cfg = rs.make_config(d_in, d_out, rank, tau, dt, max_batch=maxb, dense_rowmajor=1)
+            layers.append(rs.rsparse_prepare_factors(cfg, L.W16, L.U16, L.SV16))
+        for B in batches:
+            xs = [torch.from_numpy(synth.encode16(src.tokens(B, offset=10 + i), dt).view(np.int16)).cuda()
+                  for i in range(n_ring)]
+            ys = [torch.zeros((B, d_out), dtype=torch.int16, device="cuda") for _ in range(n_ring)]
+
+            def run(fn):
+                def one_pass(sptr):
+                    for layer, x, y in zip(layers, xs, ys):
+                        fn(layer, x.data_ptr(), B, y.data_ptr(), sptr)
+                one_pass(stream.cuda_stream)
+                torch.cuda.synchronize()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    one_pass(torch.cuda.current_stream().cuda_stream)
+                for _ in range(3):
+                    g.replay()
+                torch.cuda.synchronize()
+                reps = max(3, int(2000 / n_ring / max(1.0, d_in * d_out / 4096 / 4096)))
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for _ in range(reps):
+                    g.replay()
+                e1.record(stream)
+                torch.cuda.synchronize()
+                return e0.elapsed_time(e1) * 1000.0 / (reps * n_ring)
+
+            us_rs = run(rs.rsparse_linear)
+            k_union = len(rs.rsparse_last_active(layers[-1], -1))
+            us_dense = run(rs.rsparse_dense_ref)
+            req = rs.rsparse_required_bytes(layers[0], B, k_union)
+            out.append({"case": label, "batch": B, "ring_layers": n_ring, "k_union": k_union,
+                        "us_rsparse": round(us_rs, 2), "us_dense": round(us_dense, 2),
+                        "speedup": round(us_dense / us_rs, 3), "required_MB": round(req / 1e6, 2),
+                        "gbs_required": round(req / us_rs / 1e3, 1), "frac_of_8TBs": round(req / us_rs / 8e6, 3),
+                        "dense_gbs": round(rs.rsparse_dense_bytes(layers[0], B) / us_dense / 1e3, 1)})
+            log(str(out[-1]))
+        for layer in layers:
+            layer.destroy()
+        torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -48,6 +114,9 @@ def main():
     ap.add_argument("--fast-layers", action="store_true",
                     help="fill the layers with cheap i.i.d. values instead of the U diag(s) V^T construction "
                          "(for profiling passes: traffic and time do not depend on the values)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the headline run: other configs' shapes and batch sizes (i.i.d. operands), "
+                         "R-Sparse vs dense per linear; prints one JSON line with key 'sweep'")
     ap.add_argument("--pmc-pass", action="store_true",
                     help="for rocprofv3 --pmc: one 256 MiB device copy of known size, then 3 eager ring passes; no timing")
     args = ap.parse_args()
@@ -67,6 +136,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dt = synth.BF16
+
+    if args.sweep:
+        print(json.dumps({"sweep": shape_batch_sweep(args, torch, np, rs, synth)}), flush=True)
+        return
 
     # ------------------------------------------------------------------ layers, tokens, thresholds
     t0 = time.time()

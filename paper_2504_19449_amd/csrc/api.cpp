@@ -181,6 +181,7 @@ Launch resolve_launch(const rsparse_layer *L, int batch, bool dense, int group)
     // loads in flight, while each output column only receives `splits` atomic adds (same-address
     // device-scope atomics serialise at ~0.1 us each, which sets the kernel's tail).
     c.waves = (t.waves == 1 || t.waves == 2 || t.waves == 4 || t.waves == 8) ? t.waves : (bt >= 8 ? 4 : 8);
+    if (bt >= 8 && c.waves > 4) c.waves = 4;      // the 8-token kernels are built for at most 256 lanes
     c.nontemporal = t.nontemporal ? 1 : 0;
     c.tile_map = t.tile_map == 0 ? 1 : t.tile_map;
     const int rows = dense ? L->cfg.d_in : std::max(8, L->cfg.d_in / 2);     // expected rows to stream
@@ -393,7 +394,7 @@ rsparse_status rsparse_linear_group(rsparse_layer *const *layers, int32_t n_laye
     if (mfma) {
         // 9..32 tokens: matrix-core path, one layer at a time (each is already a full-chip launch)
         for (int i = 0; i < n_layers; ++i)
-            RS_HIP(launch_mfma_linear(v[i], X_dev, batch, Y_devs[i], layers[i]->chan_bits, layers[i]->cus, stages, s));
+            RS_HIP(launch_mfma_linear(v[i], X_dev, batch, Y_devs[i], layers[i]->chan_bits, layers[i]->cus, stages, false, s));
     } else {
         if (stages != 2) RS_HIP(launch_sparse_and_t(v, lc, n_layers, X_dev, batch, true, true, s));
         if (stages != 1) RS_HIP(launch_finish(v, n_layers, batch, Y_devs, true, s));
@@ -425,10 +426,18 @@ rsparse_status rsparse_dense_ref_group(rsparse_layer *const *layers, int32_t n_l
         lc[i] = resolve_launch(layers[i], batch, true, n_layers);
         can_rowdot = can_rowdot && layers[i]->Wrow != nullptr && rowdot_supported(layers[i]->cfg.d_in, batch);
     }
+    bool mfma = batch > kMaxBT && layers[0]->tuning.no_mfma == 0;
+    for (int i = 0; i < n_layers; ++i) mfma = mfma && mfma_path_supported(v[i], batch);
+    if (mfma) {
+        for (int i = 0; i < n_layers; ++i)
+            RS_HIP(launch_mfma_linear(v[i], X_dev, batch, Y_devs[i], layers[i]->chan_bits, layers[i]->cus, 0, true, s));
+        return RSPARSE_OK;
+    }
     int kernel = layers[0]->tuning.dense_kernel;
     if (kernel == 2 && !can_rowdot)
         return fail(RSPARSE_EINVAL, "row-dot dense kernel needs dense_rowmajor=1 and batch_tile*d_in*2 <= 64 KiB");
-    if (kernel == 0) kernel = can_rowdot ? 2 : 1;
+    // row dots win for short rows; for long rows (and for more than one token) the axpy form streams better
+    if (kernel == 0) kernel = (can_rowdot && layers[0]->cfg.d_in <= 8192 && batch == 1) ? 2 : 1;
     if (kernel == 2) RS_HIP(launch_dense_rowdot(v, lc, n_layers, X_dev, batch, Y_devs, s));
     else RS_HIP(launch_dense_axpy(v, lc, n_layers, X_dev, batch, Y_devs, s));
     return RSPARSE_OK;

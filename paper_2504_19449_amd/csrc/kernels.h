@@ -53,9 +53,10 @@ hipError_t launch_dense_rowdot(const LayerView *L, const Launch *cfg, int n, con
 // Matrix-core path for 8 < batch <= 32 (needs the row-major copy of W): both launches of one layer.
 // chan_bits [d_in] receives, per channel, the bit mask of the tokens that keep it.  stages as in
 // rsparse_tuning.  Zeroes L.t with a fill kernel first (its stage-1 partial sums meet in atomics).
+// dense = the dense baseline Y = X W^T through the same kernels (no masks, no low-rank part).
 bool mfma_path_supported(const LayerView &L, int batch);
 hipError_t launch_mfma_linear(const LayerView &L, const void *X, int batch, void *Y, uint32_t *chan_bits, int cus,
-                              int stages, hipStream_t stream);
+                              int stages, bool dense, hipStream_t stream);
 // Zero `n` 32-bit words (a fill kernel, safe to record into a HIP graph).
 hipError_t launch_zero(void *p, size_t n_words, hipStream_t stream);
 

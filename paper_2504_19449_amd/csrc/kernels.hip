@@ -163,7 +163,10 @@ __device__ __forceinline__ void reduce_to_yacc(float (&acc)[BT][8], float *s_red
 {
     const int tid = threadIdx.x, nthr = blockDim.x, lane = tid & 63, w = tid >> 6, nw = nthr >> 6;
     const int colbase = tile * kTile;
-    for (int b = 0; b < nb; ++b) {
+    // b must stay a compile-time index: a run-time subscript would push acc[][] into scratch memory
+#pragma unroll
+    for (int b = 0; b < BT; ++b) {
+        if (b >= nb) break;
         float *yrow = yacc + (size_t)(b0 + b) * d_out;
         if (nw > 1) {
             if (b > 0) __syncthreads();
@@ -345,8 +348,9 @@ __device__ __forceinline__ void lowrank_rows(const GatherArgs &a, unsigned char 
 // The two groups are independent, so they share one launch.
 // grid.x = lr_wgs + tiles * splits, grid.z = batch tiles of BT tokens, block = 64 * waves.
 // ---------------------------------------------------------------------------------------------
+// Eight tokens of accumulators need the full register file: 4 waves per workgroup, one per SIMD.
 template <int DT, int BT, bool NT>
-__global__ __launch_bounds__(512) void k_sparse_and_t(const GroupArgs ga)
+__global__ __launch_bounds__(BT >= 8 ? 256 : 512) void k_sparse_and_t(const GroupArgs ga)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int z = blockIdx.z;
@@ -447,7 +451,7 @@ __global__ __launch_bounds__(512) void k_sparse_and_t(const GroupArgs ga)
 // Followed by k_finish with rank 0.
 // ---------------------------------------------------------------------------------------------
 template <int DT, int BT, bool NT>
-__global__ __launch_bounds__(512) void k_dense_axpy(const GroupArgs ga)
+__global__ __launch_bounds__(BT >= 8 ? 256 : 512) void k_dense_axpy(const GroupArgs ga)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, nthr = blockDim.x, lane = tid & 63, w = tid >> 6, nw = nthr >> 6;

@@ -56,12 +56,16 @@ struct MfmaArgs {
     LayerView L;
     const uint16_t *X;
     int batch, tok_pad;          // tokens, padded to 16 or 32
-    int kc;                      // K chunk per workgroup, multiple of 32
-    int k_chunks;
-    int rows_per_wg;             // multiple of 16
-    int w_chunks, t_chunks;      // row chunks of W and of SVt; grid.x = (w_chunks + t_chunks) * k_chunks
+    int kc;                      // K chunk staged in LDS at a time, multiple of 32
+    int k_splits;                // workgroups along K; each loops over chunks_per_split chunks
+    int chunks_per_split;
+    int rows_per_wg;             // multiple of 16, at most 64 * kMaxBlocksPerWave
+    int w_chunks, t_chunks;      // row chunks of W and of SVt; grid.x = (w_chunks + t_chunks) * k_splits
     uint32_t *chan_bits;         // [d_in] bit b = token b keeps the channel (read-back)
+    int dense;                   // 1: dense baseline -- every channel kept, no masks, no stage 1
 };
+
+constexpr int kMaxBlocksPerWave = 4;
 
 // One 16-row block over the staged K chunk: acc0 = tokens 0-15, acc1 = tokens 16-31.
 template <int DT>
@@ -94,6 +98,10 @@ __device__ __forceinline__ void block_over_chunk(const uint16_t *__restrict__ ro
     }
 }
 
+// A workgroup owns rows_per_wg output rows (of W, or of S_r V_r^T) and one K split; it walks its K
+// range in LDS-sized chunks, re-staging the masked tokens for each, and keeps the D tiles in
+// registers throughout.  Results are stored directly when there is a single K split, else added
+// with fp32 atomics (k_splits adds per output).
 template <int DT>
 __global__ __launch_bounds__(256) void k_mfma_sparse_and_t(const MfmaArgs a)
 {
@@ -101,82 +109,112 @@ __global__ __launch_bounds__(256) void k_mfma_sparse_and_t(const MfmaArgs a)
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const LayerView &L = a.L;
     const int d_in = L.d_in;
-    const int kch = blockIdx.x % a.k_chunks;
-    int rc = blockIdx.x / a.k_chunks;
+    const int ksp = blockIdx.x % a.k_splits;
+    int rc = blockIdx.x / a.k_splits;
     const bool is_t = rc >= a.w_chunks;
     if (is_t) rc -= a.w_chunks;
-    const int k0 = kch * a.kc;
-    const int klen = min(a.kc, d_in - k0);
-    const int nq = a.kc / 8;                            // 16-byte pieces per token in the chunk
+    const int nq = a.kc / 8;                            // 16-byte pieces per token in a chunk
     const int pitch = a.kc * 2 + 16;                    // odd multiple of 16 bytes: conflict-free B reads
     unsigned char *s_act = smem;                        // [tok_pad][pitch]
     uint32_t *s_bits = reinterpret_cast<uint32_t *>(smem + (size_t)a.tok_pad * pitch);   // [kc] per-channel token bits
-    const bool union_all = L.batch_mask_mode == 1;
-    const bool publish = !is_t && rc == 0;              // these workgroups cover every channel once
-
-    for (int i = tid; i < a.kc; i += 256) s_bits[i] = 0u;
-    __syncthreads();
-    // pass A: per-channel keep bits of every token (needed for the union mask and for read-back)
-    if (union_all || publish) {
-        for (int q = tid; q < a.tok_pad * nq; q += 256) {
-            const int tok = q / nq, kq = q % nq;
-            if (tok < a.batch && kq * 8 < klen) {
-                float f[8];
-                unpack8<DT>(*reinterpret_cast<const u32x4 *>(a.X + (size_t)tok * d_in + k0 + kq * 8), f);
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (keep(f[e], L.tau, L.cmp_mode)) atomicOr(&s_bits[kq * 8 + e], 1u << tok);
-            }
-        }
-        __syncthreads();
-        if (union_all) {
-            const uint32_t all = a.batch >= 32 ? 0xffffffffu : ((1u << a.batch) - 1u);
-            for (int i = tid; i < a.kc; i += 256) s_bits[i] = s_bits[i] ? all : 0u;
-            __syncthreads();
-        }
-        if (publish)
-            for (int i = tid; i < klen; i += 256) a.chan_bits[k0 + i] = s_bits[i];
-    }
-    // pass B: stage the kept part (W rows) or the dropped part (SVt rows) of every token
-    for (int q = tid; q < a.tok_pad * nq; q += 256) {
-        const int tok = q / nq, kq = q % nq;
-        u32x4 o = u32x4{0, 0, 0, 0};
-        if (tok < a.batch && kq * 8 < klen) {
-            const u32x4 raw = *reinterpret_cast<const u32x4 *>(a.X + (size_t)tok * d_in + k0 + kq * 8);
-            float f[8];
-            unpack8<DT>(raw, f);
-            o = raw;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const bool kept = union_all ? ((s_bits[kq * 8 + e] >> tok) & 1u) != 0u : keep(f[e], L.tau, L.cmp_mode);
-                if (kept == is_t) o[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;   // zero what this part must not see
-            }
-        }
-        *reinterpret_cast<u32x4 *>(s_act + (size_t)tok * pitch + kq * 16) = o;
-    }
-    __syncthreads();
+    const bool union_all = L.batch_mask_mode == 1 && !a.dense;
+    const bool publish = !is_t && rc == 0 && !a.dense;  // these workgroups cover every channel once
 
     const uint16_t *Mat = is_t ? L.SVt : L.Wrow;
     const int nrows = is_t ? L.rank : L.d_out;
     float *out = is_t ? L.t : L.yacc;                   // [token][nrows]
     const int blocks = a.rows_per_wg / kRowsPerBlock;
-    for (int blk = w; blk < blocks; blk += 4) {
-        const int row0 = rc * a.rows_per_wg + blk * kRowsPerBlock;
-        if (row0 >= nrows) break;
-        const int row = row0 + (lane & 15);
-        const bool row_ok = row < nrows;
-        const uint16_t *rowptr = Mat + (size_t)(row_ok ? row : 0) * d_in + k0;
-        f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
-        block_over_chunk<DT>(rowptr, row_ok, klen, a.kc, s_act, pitch, a.tok_pad, lane, acc0, acc1);
-        const int tok = lane & 15;
+
+    f32x4 acc0[kMaxBlocksPerWave], acc1[kMaxBlocksPerWave];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int orow = row0 + 4 * (lane >> 4) + j;
-            if (orow < nrows) {
-                if (tok < a.batch)
-                    __hip_atomic_fetch_add(out + (size_t)tok * nrows + orow, acc0[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (tok + 16 < a.batch)
-                    __hip_atomic_fetch_add(out + (size_t)(tok + 16) * nrows + orow, acc1[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int bi = 0; bi < kMaxBlocksPerWave; ++bi) {
+        acc0[bi] = f32x4{0.f, 0.f, 0.f, 0.f};
+        acc1[bi] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    const int chunk_lo = ksp * a.chunks_per_split;
+    for (int ci = 0; ci < a.chunks_per_split; ++ci) {
+        const int k0 = (chunk_lo + ci) * a.kc;
+        if (k0 >= d_in) break;
+        const int klen = min(a.kc, d_in - k0);
+        if (ci > 0) __syncthreads();
+        // pass A: per-channel keep bits of every token (needed for the union mask and for read-back)
+        if (union_all || publish) {
+            for (int i = tid; i < a.kc; i += 256) s_bits[i] = 0u;
+            __syncthreads();
+            for (int q = tid; q < a.tok_pad * nq; q += 256) {
+                const int tok = q / nq, kq = q % nq;
+                if (tok < a.batch && kq * 8 < klen) {
+                    float f[8];
+                    unpack8<DT>(*reinterpret_cast<const u32x4 *>(a.X + (size_t)tok * d_in + k0 + kq * 8), f);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (keep(f[e], L.tau, L.cmp_mode)) atomicOr(&s_bits[kq * 8 + e], 1u << tok);
+                }
+            }
+            __syncthreads();
+            if (union_all) {
+                const uint32_t all = a.batch >= 32 ? 0xffffffffu : ((1u << a.batch) - 1u);
+                for (int i = tid; i < a.kc; i += 256) s_bits[i] = s_bits[i] ? all : 0u;
+                __syncthreads();
+            }
+            if (publish)
+                for (int i = tid; i < klen; i += 256) a.chan_bits[k0 + i] = s_bits[i];
+        }
+        // pass B: stage the kept part (W rows) or the dropped part (SVt rows) of every token
+        for (int q = tid; q < a.tok_pad * nq; q += 256) {
+            const int tok = q / nq, kq = q % nq;
+            u32x4 o = u32x4{0, 0, 0, 0};
+            if (tok < a.batch && kq * 8 < klen) {
+                const u32x4 raw = *reinterpret_cast<const u32x4 *>(a.X + (size_t)tok * d_in + k0 + kq * 8);
+                float f[8];
+                unpack8<DT>(raw, f);
+                o = raw;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const bool kept = a.dense ? true
+                                      : union_all ? ((s_bits[kq * 8 + e] >> tok) & 1u) != 0u : keep(f[e], L.tau, L.cmp_mode);
+                    if (kept == is_t) o[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;   // zero what this part must not see
+                }
+            }
+            *reinterpret_cast<u32x4 *>(s_act + (size_t)tok * pitch + kq * 16) = o;
+        }
+        __syncthreads();
+
+#pragma unroll
+        for (int bi = 0; bi < kMaxBlocksPerWave; ++bi) {
+            const int blk = w + 4 * bi;
+            const int row0 = rc * a.rows_per_wg + blk * kRowsPerBlock;
+            if (blk < blocks && row0 < nrows) {
+                const int row = row0 + (lane & 15);
+                const bool row_ok = row < nrows;
+                const uint16_t *rowptr = Mat + (size_t)(row_ok ? row : 0) * d_in + k0;
+                block_over_chunk<DT>(rowptr, row_ok, klen, a.kc, s_act, pitch, a.tok_pad, lane, acc0[bi], acc1[bi]);
+            }
+        }
+    }
+
+    const int tok = lane & 15;
+    const bool direct = a.k_splits == 1;
+#pragma unroll
+    for (int bi = 0; bi < kMaxBlocksPerWave; ++bi) {
+        const int blk = w + 4 * bi;
+        const int row0 = rc * a.rows_per_wg + blk * kRowsPerBlock;
+        if (blk < blocks && row0 < nrows) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int orow = row0 + 4 * (lane >> 4) + j;
+                if (orow < nrows) {
+                    float *p0 = out + (size_t)tok * nrows + orow;
+                    float *p1 = out + (size_t)(tok + 16) * nrows + orow;
+                    if (direct) {
+                        if (tok < a.batch) *p0 = acc0[bi][j];
+                        if (tok + 16 < a.batch) *p1 = acc1[bi][j];
+                    } else {
+                        if (tok < a.batch) __hip_atomic_fetch_add(p0, acc0[bi][j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        if (tok + 16 < a.batch) __hip_atomic_fetch_add(p1, acc1[bi][j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                }
             }
         }
     }
@@ -257,29 +295,33 @@ bool mfma_path_supported(const LayerView &L, int batch)
 }
 
 hipError_t launch_mfma_linear(const LayerView &L, const void *X, int batch, void *Y, uint32_t *chan_bits, int cus,
-                              int stages, hipStream_t stream)
+                              int stages, bool dense, hipStream_t stream)
 {
     const int tok_pad = batch > 16 ? 32 : 16;
+    const int rank = dense ? 0 : L.rank;
     if (stages != 2) {
-        if (L.rank > 0) {
+        MfmaArgs a{};
+        a.L = L; a.X = (const uint16_t *)X; a.batch = batch; a.tok_pad = tok_pad; a.chan_bits = chan_bits;
+        a.dense = dense ? 1 : 0;
+        a.kc = tok_pad > 16 ? 512 : 1024;
+        if (a.kc > ((L.d_in + 31) / 32) * 32) a.kc = ((L.d_in + 31) / 32) * 32;
+        const int n_kchunks = (L.d_in + a.kc - 1) / a.kc;
+        // 64 output rows per workgroup (one 16-row block per wave), 128 for very wide layers; K is split
+        // only as far as needed for ~3 workgroups per compute unit (k_splits atomic adds per output)
+        const int rows_per_wg = L.d_out / 128 >= 3 * cus ? 128 : 64;
+        a.rows_per_wg = rows_per_wg;
+        a.w_chunks = (L.d_out + rows_per_wg - 1) / rows_per_wg;
+        a.t_chunks = rank > 0 ? (rank + rows_per_wg - 1) / rows_per_wg : 0;
+        int k_splits = (3 * cus + a.w_chunks - 1) / a.w_chunks;
+        k_splits = std::max(1, std::min(k_splits, n_kchunks));
+        a.chunks_per_split = (n_kchunks + k_splits - 1) / k_splits;
+        a.k_splits = (n_kchunks + a.chunks_per_split - 1) / a.chunks_per_split;
+        const size_t lds = (size_t)tok_pad * (a.kc * 2 + 16) + (size_t)a.kc * 4;
+        if (rank > 0 && a.k_splits > 1) {             // stage-1 partial sums meet in atomics: start from zero
             hipError_t e = launch_zero(L.t, (size_t)batch * L.rank, stream);
             if (e != hipSuccess) return e;
         }
-        MfmaArgs a{};
-        a.L = L; a.X = (const uint16_t *)X; a.batch = batch; a.tok_pad = tok_pad; a.chan_bits = chan_bits;
-        a.kc = tok_pad > 16 ? 512 : 1024;
-        if (a.kc > ((L.d_in + 31) / 32) * 32) a.kc = ((L.d_in + 31) / 32) * 32;
-        a.k_chunks = (L.d_in + a.kc - 1) / a.kc;
-        // ~1.5 workgroups per compute unit over (row chunks x K chunks); rows per workgroup a multiple of 64
-        int rows_per_wg = 256;
-        while (rows_per_wg > 64 &&
-               (long long)((L.d_out + rows_per_wg - 1) / rows_per_wg) * a.k_chunks < (long long)cus * 3 / 2)
-            rows_per_wg /= 2;
-        a.rows_per_wg = rows_per_wg;
-        a.w_chunks = (L.d_out + rows_per_wg - 1) / rows_per_wg;
-        a.t_chunks = L.rank > 0 ? (L.rank + rows_per_wg - 1) / rows_per_wg : 0;
-        const size_t lds = (size_t)tok_pad * (a.kc * 2 + 16) + (size_t)a.kc * 4;
-        dim3 grid((a.w_chunks + a.t_chunks) * a.k_chunks), block(256);
+        dim3 grid((a.w_chunks + a.t_chunks) * a.k_splits), block(256);
         if (L.dtype == F16) hipLaunchKernelGGL(k_mfma_sparse_and_t<F16>, grid, block, lds, stream, a);
         else hipLaunchKernelGGL(k_mfma_sparse_and_t<BF16>, grid, block, lds, stream, a);
         hipError_t e = hipGetLastError();
@@ -287,7 +329,7 @@ hipError_t launch_mfma_linear(const LayerView &L, const void *X, int batch, void
     }
     if (stages != 1) {
         MfmaFinishArgs f{};
-        f.L = L; f.Y = Y; f.batch = batch; f.tok_pad = tok_pad; f.use_rank = L.rank;
+        f.L = L; f.Y = Y; f.batch = batch; f.tok_pad = tok_pad; f.use_rank = rank;
         f.rc = tok_pad > 16 ? 256 : 512;
         const size_t lds = 2 * (size_t)tok_pad * (f.rc * 2 + 16);
         dim3 grid((L.d_out + 63) / 64), block(256);
