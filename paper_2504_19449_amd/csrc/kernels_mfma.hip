@@ -14,10 +14,11 @@
 // (one 16-byte load) of row l%16 at k-group l/16.  A = 16 weight rows x 32 k, B = 32 k x 16
 // tokens (from LDS), D[row][token] fp32: lane l, register j holds row 4*(l/16)+j, token l%16.
 //
-// Launch 1 (k_mfma_sparse_and_t): grid = (row chunks of W + row chunks of SVt) x K chunks.  A
-// workgroup stages its K chunk of the masked tokens in LDS (kept part for W rows, dropped part for
-// SVt rows), each wave runs 16-row blocks over the chunk, and the partial D tiles go to yacc /
-// tacc with fp32 atomics (one add per output and K chunk).  tacc is zeroed by a fill kernel first.
+// Launch 1 (k_mfma_sparse_and_t): grid = (row chunks of W + row chunks of SVt) x K splits.  A
+// workgroup walks its K range in LDS-sized chunks: it stages the masked tokens of the chunk (kept
+// part for W rows, dropped part for SVt rows), each wave runs its 16-row blocks over it, and the D
+// tiles stay in registers until the end; they are stored directly (one K split) or added to yacc / t
+// with fp32 atomics (k_splits adds per output; t is then zeroed by a fill kernel first).
 // Launch 2 (k_mfma_finish): t is split into hi + lo 16-bit halves (so the contraction keeps ~16
 // mantissa bits of the fp32 t), D = U_r t, Y = round(yacc + D), yacc re-zeroed.
 #include "kernels.h"
@@ -66,6 +67,7 @@ struct MfmaArgs {
 };
 
 constexpr int kMaxBlocksPerWave = 4;
+constexpr int kStageBatch = 8;      // 16-byte token loads in flight per thread while staging
 
 // One 16-row block over the staged K chunk: acc0 = tokens 0-15, acc1 = tokens 16-31.
 template <int DT>
@@ -161,23 +163,38 @@ __global__ __launch_bounds__(256) void k_mfma_sparse_and_t(const MfmaArgs a)
             if (publish)
                 for (int i = tid; i < klen; i += 256) a.chan_bits[k0 + i] = s_bits[i];
         }
-        // pass B: stage the kept part (W rows) or the dropped part (SVt rows) of every token
-        for (int q = tid; q < a.tok_pad * nq; q += 256) {
-            const int tok = q / nq, kq = q % nq;
-            u32x4 o = u32x4{0, 0, 0, 0};
-            if (tok < a.batch && kq * 8 < klen) {
-                const u32x4 raw = *reinterpret_cast<const u32x4 *>(a.X + (size_t)tok * d_in + k0 + kq * 8);
-                float f[8];
-                unpack8<DT>(raw, f);
-                o = raw;
+        // pass B: stage the kept part (W rows) or the dropped part (SVt rows) of every token.
+        // All of a batch's loads are issued before the first is used (one L2 round trip per batch).
+        const int total = a.tok_pad * nq;
+        for (int q0 = tid; q0 < total; q0 += 256 * kStageBatch) {
+            u32x4 raw[kStageBatch];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const bool kept = a.dense ? true
-                                      : union_all ? ((s_bits[kq * 8 + e] >> tok) & 1u) != 0u : keep(f[e], L.tau, L.cmp_mode);
-                    if (kept == is_t) o[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;   // zero what this part must not see
+            for (int u = 0; u < kStageBatch; ++u) {
+                const int q = q0 + u * 256;
+                const int tok = q / nq, kq = q % nq;
+                raw[u] = (q < total && tok < a.batch && kq * 8 < klen)
+                             ? *reinterpret_cast<const u32x4 *>(a.X + (size_t)tok * d_in + k0 + kq * 8)
+                             : u32x4{0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int u = 0; u < kStageBatch; ++u) {
+                const int q = q0 + u * 256;
+                if (q < total) {
+                    const int tok = q / nq, kq = q % nq;
+                    u32x4 o = raw[u];
+                    if (!a.dense) {
+                        float f[8];
+                        unpack8<DT>(o, f);
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const bool kept = union_all ? ((s_bits[kq * 8 + e] >> (tok & 31)) & 1u) != 0u
+                                                        : keep(f[e], L.tau, L.cmp_mode);
+                            if (kept == is_t) o[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;   // not this part's
+                        }
+                    }
+                    *reinterpret_cast<u32x4 *>(s_act + (size_t)tok * pitch + kq * 16) = o;
                 }
             }
-            *reinterpret_cast<u32x4 *>(s_act + (size_t)tok * pitch + kq * 16) = o;
         }
         __syncthreads();
 
@@ -246,15 +263,38 @@ __global__ __launch_bounds__(256) void k_mfma_finish(const MfmaFinishArgs a)
     for (int c0 = 0; c0 < r; c0 += a.rc) {
         const int clen = min(a.rc, r - c0);
         if (c0 > 0) __syncthreads();
-        // t = hi + lo in the storage type: the MFMA contraction then carries ~16 mantissa bits of t
-        for (int i = tid; i < a.tok_pad * a.rc; i += 256) {
-            const int tok = i / a.rc, k = i % a.rc;
-            float v = 0.f;
-            if (tok < a.batch && k < clen) v = L.t[(size_t)tok * r + c0 + k];
-            const uint16_t hi = narrow<DT>(v);
-            const uint16_t lo = narrow<DT>(v - widen<DT>(hi));
-            *reinterpret_cast<uint16_t *>(s_hi + (size_t)tok * pitch + k * 2) = hi;
-            *reinterpret_cast<uint16_t *>(s_lo + (size_t)tok * pitch + k * 2) = lo;
+        // t = hi + lo in the storage type: the MFMA contraction then carries ~16 mantissa bits of t.
+        // Four values per thread and step, a batch of loads issued before the first conversion.
+        const int rc4 = a.rc / 4, total4 = a.tok_pad * rc4;
+        for (int i0 = tid; i0 < total4; i0 += 256 * kStageBatch) {
+            float4 tv[kStageBatch];
+#pragma unroll
+            for (int u = 0; u < kStageBatch; ++u) {
+                const int i = i0 + u * 256;
+                const int tok = i / rc4, k = (i % rc4) * 4;
+                tv[u] = (i < total4 && tok < a.batch && k < clen)
+                            ? *reinterpret_cast<const float4 *>(L.t + (size_t)tok * r + c0 + k)
+                            : float4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int u = 0; u < kStageBatch; ++u) {
+                const int i = i0 + u * 256;
+                if (i < total4) {
+                    const int tok = i / rc4, k = (i % rc4) * 4;
+                    const float v[4] = {tv[u].x, tv[u].y, tv[u].z, tv[u].w};
+                    uint16_t hi[4], lo[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        hi[e] = narrow<DT>(v[e]);
+                        lo[e] = narrow<DT>(v[e] - widen<DT>(hi[e]));
+                    }
+                    uint2 ph, pl;
+                    ph.x = (uint32_t)hi[0] | ((uint32_t)hi[1] << 16); ph.y = (uint32_t)hi[2] | ((uint32_t)hi[3] << 16);
+                    pl.x = (uint32_t)lo[0] | ((uint32_t)lo[1] << 16); pl.y = (uint32_t)lo[2] | ((uint32_t)lo[3] << 16);
+                    *reinterpret_cast<uint2 *>(s_hi + (size_t)tok * pitch + k * 2) = ph;
+                    *reinterpret_cast<uint2 *>(s_lo + (size_t)tok * pitch + k * 2) = pl;
+                }
+            }
         }
         __syncthreads();
         const uint16_t *rowptr = L.U + (size_t)(row_ok ? row : 0) * r + c0;
