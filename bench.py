@@ -26,7 +26,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-TRAFFIC_BYTES_PER_LAUNCH = None   # set from the PMC run of the grouped launch shape; see profiles/
+TRAFFIC_BYTES_PER_LAUNCH = 78.5e6  # rocprofv3 PMC: (98.2 + 57.2) / 2 MB fetched + 0.8 MB written per launch; see profiles/
 RING_BLOCKS = 4            # MLP blocks in the ring: 12 layers, ~1.2 GiB of column-major weights
 RANK = 512
 D_MODEL, D_FF = 4096, 11008
