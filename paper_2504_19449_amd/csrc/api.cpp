@@ -187,8 +187,10 @@ Launch resolve_launch(const rsparse_layer *L, int batch, bool dense, int group)
     const int rows = dense ? L->cfg.d_in : std::max(8, L->cfg.d_in / 2);     // expected rows to stream
     int splits = t.splits;
     if (splits <= 0) {
-        // one resident round of workgroups for the whole launch: a group of layers shares it
-        const int target_wgs = std::max(L->tiles, (3 * L->cus) / 2 * (8 / c.waves) / std::max(1, group));
+        // one resident round of workgroups for the whole launch (a group of layers shares it):
+        // ~1.5 per compute unit, for the 8-wave kernels and for the 4-wave 8-token kernels alike
+        // (those hold two workgroups per compute unit at their register count)
+        const int target_wgs = std::max(L->tiles, (3 * L->cus) / 2 / std::max(1, group));
         splits = (target_wgs + L->tiles - 1) / L->tiles;
         const int max_by_rows = std::max(1, rows / (c.waves * 4));          // >= 4 rows per wave
         splits = std::max(1, std::min(splits, max_by_rows));

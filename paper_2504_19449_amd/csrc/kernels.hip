@@ -550,18 +550,32 @@ __global__ __launch_bounds__(256) void k_finish(const FinishGroupArgs ga)
         for (int b = 0; b < BT; ++b)
             ya[g][b] = (sub == 0 && o < d_out && b < nb) ? L.yacc[(size_t)(b0 + b) * d_out + o] : 0.f;
     }
-    for (int i = tid; i < BT * r; i += 256) {
-        const int b = i / r;
-        s_t[i] = (b < nb) ? L.t[((size_t)z * BT) * r + i] : 0.f;
+    {   // stage t [BT][r] in LDS: four values per thread and step, eight steps of loads in flight
+        constexpr int SB = 8;
+        const int total4 = BT * r / 4;                     // r is a multiple of 8
+        const float4 *src = reinterpret_cast<const float4 *>(L.t + ((size_t)z * BT) * r);
+        for (int i0 = tid; i0 < total4; i0 += 256 * SB) {
+            float4 tv[SB];
+#pragma unroll
+            for (int u = 0; u < SB; ++u) {
+                const int i = i0 + u * 256;
+                tv[u] = (i < total4 && (i * 4) / r < nb) ? src[i] : float4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int u = 0; u < SB; ++u) {
+                const int i = i0 + u * 256;
+                if (i < total4) reinterpret_cast<float4 *>(s_t)[i] = tv[u];
+            }
+        }
     }
     __syncthreads();
 
+    float acc[kFinishGroups][BT];
 #pragma unroll
     for (int g = 0; g < kFinishGroups; ++g) {
         const int o = o_wave + g * rpi + rsel;
-        float acc[BT];
 #pragma unroll
-        for (int b = 0; b < BT; ++b) acc[b] = 0.f;
+        for (int b = 0; b < BT; ++b) acc[g][b] = 0.f;
         if (PASSES > 0) {
 #pragma unroll
             for (int p = 0; p < NP; ++p) {
@@ -573,10 +587,12 @@ __global__ __launch_bounds__(256) void k_finish(const FinishGroupArgs ga)
                     for (int b = 0; b < BT; ++b) {
                         const float4 t0 = *reinterpret_cast<const float4 *>(s_t + b * r + i);
                         const float4 t1 = *reinterpret_cast<const float4 *>(s_t + b * r + i + 4);
-                        acc[b] = __builtin_fmaf(f[0], t0.x, acc[b]); acc[b] = __builtin_fmaf(f[1], t0.y, acc[b]);
-                        acc[b] = __builtin_fmaf(f[2], t0.z, acc[b]); acc[b] = __builtin_fmaf(f[3], t0.w, acc[b]);
-                        acc[b] = __builtin_fmaf(f[4], t1.x, acc[b]); acc[b] = __builtin_fmaf(f[5], t1.y, acc[b]);
-                        acc[b] = __builtin_fmaf(f[6], t1.z, acc[b]); acc[b] = __builtin_fmaf(f[7], t1.w, acc[b]);
+                        float s = acc[g][b];
+                        s = __builtin_fmaf(f[0], t0.x, s); s = __builtin_fmaf(f[1], t0.y, s);
+                        s = __builtin_fmaf(f[2], t0.z, s); s = __builtin_fmaf(f[3], t0.w, s);
+                        s = __builtin_fmaf(f[4], t1.x, s); s = __builtin_fmaf(f[5], t1.y, s);
+                        s = __builtin_fmaf(f[6], t1.z, s); s = __builtin_fmaf(f[7], t1.w, s);
+                        acc[g][b] = s;
                     }
                 }
             }
@@ -589,16 +605,30 @@ __global__ __launch_bounds__(256) void k_finish(const FinishGroupArgs ga)
 #pragma unroll
                     for (int b = 0; b < BT; ++b)
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) acc[b] = __builtin_fmaf(f[e], s_t[b * r + i + e], acc[b]);
+                        for (int e = 0; e < 8; ++e) acc[g][b] = __builtin_fmaf(f[e], s_t[b * r + i + e], acc[g][b]);
                 }
             }
         }
+    }
+    // Segmented butterfly over the lpr lanes of a row.  The distance is a compile-time constant and
+    // all groups x tokens move together, so the cross-lane operations of one step overlap instead of
+    // each waiting for the previous one.
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        if (d < lpr) {
+#pragma unroll
+            for (int g = 0; g < kFinishGroups; ++g)
+#pragma unroll
+                for (int b = 0; b < BT; ++b) acc[g][b] += __shfl_xor(acc[g][b], d, 64);
+        }
+    }
+#pragma unroll
+    for (int g = 0; g < kFinishGroups; ++g) {
+        const int o = o_wave + g * rpi + rsel;
 #pragma unroll
         for (int b = 0; b < BT; ++b) {
-            float s = acc[b];
-            for (int d = lpr >> 1; d >= 1; d >>= 1) s += __shfl_xor(s, d, 64);
             if (sub == 0 && o < d_out && b < nb) {
-                store_out(a.Y, (size_t)(b0 + b) * d_out + o, ya[g][b] + s, L.out_dtype);
+                store_out(a.Y, (size_t)(b0 + b) * d_out + o, ya[g][b] + acc[g][b], L.out_dtype);
                 L.yacc[(size_t)(b0 + b) * d_out + o] = 0.f;
             }
         }
