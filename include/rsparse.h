@@ -84,7 +84,9 @@ typedef struct {
                                 timing one kernel in isolation; results are only valid with 0 */
     int32_t tile_map;        /* workgroup -> (column tile, split) mapping: 0 default, 1 tile-fastest (plain),
                                 2 XCD-aware (all splits of a tile on ids congruent mod 8) */
-    int32_t no_mfma;         /* 1: keep batches of 9..32 tokens on the vector-ALU path (tiles of 8 tokens) */
+    int32_t mfma_min_batch;  /* smallest batch that takes the matrix-core path (needs dense_rowmajor = 1):
+                                0 = default (5 for rsparse_linear, 2 for rsparse_dense_ref), 33 = never (9..32 tokens
+                                then run in tiles of 8 on the vector ALU) */
 } rsparse_tuning;
 
 /*

@@ -391,7 +391,7 @@ rsparse_status rsparse_linear_group(rsparse_layer *const *layers, int32_t n_laye
         lc[i] = resolve_launch(layers[i], batch, false, n_layers);
     }
     const int stages = layers[0]->tuning.stages;
-    bool mfma = batch > kMaxBT && layers[0]->tuning.no_mfma == 0;
+    bool mfma = batch >= (layers[0]->tuning.mfma_min_batch > 0 ? layers[0]->tuning.mfma_min_batch : kMfmaDefaultMinBatch);
     for (int i = 0; i < n_layers; ++i) mfma = mfma && mfma_path_supported(v[i], batch);
     if (mfma) {
         // 9..32 tokens: matrix-core path, one layer at a time (each is already a full-chip launch)
@@ -428,7 +428,7 @@ rsparse_status rsparse_dense_ref_group(rsparse_layer *const *layers, int32_t n_l
         lc[i] = resolve_launch(layers[i], batch, true, n_layers);
         can_rowdot = can_rowdot && layers[i]->Wrow != nullptr && rowdot_supported(layers[i]->cfg.d_in, batch);
     }
-    bool mfma = batch > kMaxBT && layers[0]->tuning.no_mfma == 0;
+    bool mfma = batch >= (layers[0]->tuning.mfma_min_batch > 0 ? layers[0]->tuning.mfma_min_batch : kMfmaDefaultMinBatchDense);
     for (int i = 0; i < n_layers; ++i) mfma = mfma && mfma_path_supported(v[i], batch);
     if (mfma) {
         for (int i = 0; i < n_layers; ++i)
@@ -527,7 +527,7 @@ rsparse_status rsparse_set_tuning(rsparse_layer *L, const rsparse_tuning *t)
     if (!L || !t) return fail(RSPARSE_EINVAL, "NULL argument");
     if (t->splits < 0 || t->waves < 0 || t->lowrank_rows < 0 || t->dense_kernel < 0 || t->dense_kernel > 2)
         return fail(RSPARSE_EINVAL, "negative or unknown tuning value");
-    if (t->no_mfma < 0 || t->no_mfma > 1) return fail(RSPARSE_EINVAL, "no_mfma must be 0 or 1");
+    if (t->mfma_min_batch < 0 || t->mfma_min_batch > 33) return fail(RSPARSE_EINVAL, "mfma_min_batch must be in [0, 33]");
     if (t->tile_map < 0 || t->tile_map > 2) return fail(RSPARSE_EINVAL, "tile_map must be 0, 1 or 2");
     if (t->stages < 0 || t->stages > 2) return fail(RSPARSE_EINVAL, "stages must be 0, 1 or 2");
     if (t->waves != 0 && t->waves != 1 && t->waves != 2 && t->waves != 4 && t->waves != 8)

@@ -331,7 +331,7 @@ __global__ __launch_bounds__(256) void k_mfma_finish(const MfmaFinishArgs a)
 
 bool mfma_path_supported(const LayerView &L, int batch)
 {
-    return batch > kMaxBT && batch <= 32 && L.Wrow != nullptr && (L.d_in % 8) == 0 && (L.d_out % 8) == 0;
+    return batch >= 1 && batch <= 32 && L.Wrow != nullptr && (L.d_in % 8) == 0 && (L.d_out % 8) == 0;
 }
 
 hipError_t launch_mfma_linear(const LayerView &L, const void *X, int batch, void *Y, uint32_t *chan_bits, int cus,

@@ -168,8 +168,8 @@ def test_dense_ref_both_kernels(ragged, dt):
     want = oracle.dense_linear(L.W16, X16, L.dtype, L.dtype, nthreads=8)
     for out in (None, rs.F32):
         layer = gu.prepare(L, 0.5, max_batch=8, out_dtype=out, dense_rowmajor=1)
-        for kernel in (1, 2, 0):
-            rs.rsparse_set_tuning(layer, dense_kernel=kernel)
+        for kernel, min_b in ((1, 33), (2, 33), (0, 33), (0, 0)):     # vector kernels, then default (MFMA from 2 tokens)
+            rs.rsparse_set_tuning(layer, dense_kernel=kernel, mfma_min_batch=min_b)
             for B in (1, 5):
                 got = gu.run_dense(layer, X16[:B])
                 gu.check_outputs(got, want[:B], layer.cfg.out_dtype)
@@ -266,10 +266,10 @@ def test_group_argument_errors(ragged):
 
 
 @pytest.mark.parametrize("dt", [synth.F16, synth.BF16])
-@pytest.mark.parametrize("B", [9, 16, 17, 32])
+@pytest.mark.parametrize("B", [5, 8, 9, 16, 17, 32])
 @pytest.mark.parametrize("mask_mode", [0, 1])
 def test_matrix_core_path_batches(ragged, dt, B, mask_mode):
-    """9..32 tokens with the row-major copy of W present: the MFMA path (dense masked GEMM, stage 1 and
+    """5..32 tokens with the row-major copy of W present: the MFMA path (dense masked GEMM, stage 1 and
     stage 2 on matrix cores).  Same oracle, same tolerances; ragged K chunk (1032 = 32*32 + 8) and rows."""
     L = ragged[dt]
     X16, src = gu.tokens_for(L, B, linear=40 + B)
@@ -284,11 +284,11 @@ def test_matrix_core_path_matches_vector_path_and_edges(ragged):
     tau = gu.calibrated_tau(L, src, 0.5)
     layer = gu.prepare(L, tau, max_batch=32, out_dtype=rs.F32, dense_rowmajor=1)
     a = gu.run_linear(layer, X16)
-    rs.rsparse_set_tuning(layer, no_mfma=1)
+    rs.rsparse_set_tuning(layer, mfma_min_batch=33)
     b = gu.run_linear(layer, X16)
     gu.check_lists(a, b)
     assert np.linalg.norm(a["Y"] - b["Y"]) <= 3e-5 * np.linalg.norm(b["Y"])
-    rs.rsparse_set_tuning(layer, no_mfma=0)
+    rs.rsparse_set_tuning(layer, mfma_min_batch=0)
     # same handle, smaller batches in between (vector path), then back: scratch stays consistent
     for B in (3, 20, 1, 12):
         got = gu.run_linear(layer, X16[:B])
