@@ -173,6 +173,18 @@ rsparse_status rsparse_calibrate_tau(const void *X_host, int32_t dtype, size_t n
 size_t rsparse_required_bytes(const rsparse_layer *layer, int32_t batch, int32_t k_union);
 size_t rsparse_dense_bytes(const rsparse_layer *layer, int32_t batch);
 
+/*
+ * Sparsification recipe of one layer (Sec. 3.5): a budget C (memory I/O relative to the full layer)
+ * is split by rho in [0,1] into a sparse part s = rho * C -- the fraction of weight columns that may
+ * be loaded -- and a rank r = (1 - rho) * C * d_in*d_out / (d_in + d_out).  Host code.
+ * *keep_fraction_out = s (so the threshold belongs at channel sparsity 1 - s, see rsparse_calibrate_tau);
+ * *rank_out = r rounded down to a multiple of 8 (this library's rank granularity), clamped to
+ * [0, min(d_in, d_out)].  *io_out (may be NULL) = the relative I/O of the rounded recipe,
+ * r (d_in + d_out) / (d_in d_out) + s, the paper's cost model (Sec. 3.4).
+ */
+rsparse_status rsparse_recipe(int32_t d_in, int32_t d_out, double budget_c, double rho,
+                              double *keep_fraction_out, int32_t *rank_out, double *io_out);
+
 void rsparse_destroy(rsparse_layer *layer);
 
 const char *rsparse_last_error(void);

@@ -15,7 +15,7 @@ EXPORTED_SYMBOLS = [
     "rsparse_prepare", "rsparse_compute_factors", "rsparse_prepare_factors", "rsparse_linear",
     "rsparse_dense_ref", "rsparse_linear_group", "rsparse_dense_ref_group", "rsparse_last_active", "rsparse_get_factors", "rsparse_set_tau", "rsparse_set_tuning",
     "rsparse_get_config", "rsparse_calibrate_tau", "rsparse_required_bytes", "rsparse_dense_bytes",
-    "rsparse_destroy", "rsparse_last_error",
+    "rsparse_recipe", "rsparse_destroy", "rsparse_last_error",
 ]
 
 
@@ -79,6 +79,9 @@ def load_library():
     lib.rsparse_required_bytes.restype = C.c_size_t
     lib.rsparse_dense_bytes.argtypes = [vp, i32]
     lib.rsparse_dense_bytes.restype = C.c_size_t
+    lib.rsparse_recipe.argtypes = [i32, i32, C.c_double, C.c_double, C.POINTER(C.c_double), C.POINTER(i32),
+                                   C.POINTER(C.c_double)]
+    lib.rsparse_recipe.restype = C.c_int
     lib.rsparse_destroy.argtypes = [vp]
     lib.rsparse_destroy.restype = None
     lib.rsparse_last_error.restype = C.c_char_p
@@ -242,6 +245,13 @@ def rsparse_required_bytes(layer: Layer, batch: int, k_union: int) -> int:
 
 def rsparse_dense_bytes(layer: Layer, batch: int) -> int:
     return int(load_library().rsparse_dense_bytes(layer.handle, batch))
+
+
+def rsparse_recipe(d_in: int, d_out: int, budget_c: float, rho: float):
+    """(keep_fraction s, rank r, relative I/O) of the Sec. 3.5 recipe; r is a multiple of 8."""
+    s, r, io = C.c_double(0), C.c_int32(0), C.c_double(0)
+    _check(load_library().rsparse_recipe(d_in, d_out, float(budget_c), float(rho), C.byref(s), C.byref(r), C.byref(io)))
+    return s.value, r.value, io.value
 
 
 def rsparse_destroy(layer: Layer):

@@ -576,6 +576,25 @@ size_t rsparse_dense_bytes(const rsparse_layer *L, int32_t batch)
     return e * (d_in * d_out + B * d_in) + eo * B * d_out;
 }
 
+rsparse_status rsparse_recipe(int32_t d_in, int32_t d_out, double budget_c, double rho, double *keep_fraction_out,
+                              int32_t *rank_out, double *io_out)
+{
+    if (!keep_fraction_out || !rank_out) return fail(RSPARSE_EINVAL, "NULL argument");
+    if (d_in < 1 || d_out < 1) return fail(RSPARSE_EINVAL, "dimensions must be positive");
+    if (!(budget_c >= 0.0) || budget_c > 1.0 || !(rho >= 0.0) || rho > 1.0)
+        return fail(RSPARSE_EINVAL, "budget and rho must be in [0, 1]");
+    const double mn = (double)d_in * (double)d_out, m_plus_n = (double)d_in + (double)d_out;
+    const double s = rho * budget_c;
+    long long r = (long long)std::floor((1.0 - rho) * budget_c * mn / m_plus_n + 1e-9);
+    r -= r % 8;
+    const long long rmax = std::min(d_in, d_out) - std::min(d_in, d_out) % 8;
+    r = std::max(0LL, std::min(r, rmax));
+    *keep_fraction_out = s;
+    *rank_out = (int32_t)r;
+    if (io_out) *io_out = (double)r * m_plus_n / mn + s;
+    return RSPARSE_OK;
+}
+
 void rsparse_destroy(rsparse_layer *L) { free_layer(L); }
 
 }  // extern "C"

@@ -8,7 +8,6 @@ namespace rsparse {
 
 constexpr int kWave = 64;        // CDNA wavefront width
 constexpr int kTile = 512;       // output columns per wave: 64 lanes x one 16-byte load (8 x 16-bit)
-constexpr int kScanThreads = 256;
 constexpr int kMaxBT = 8;        // tokens held in registers per workgroup (batch tile)
 // Smallest batch that takes the matrix-core path by default (measured cross-over on MI355X: the
 // vector path wins up to 4 tokens for R-Sparse; the dense baseline is faster on MFMA from 2 tokens).

@@ -113,3 +113,22 @@ def test_compute_factors_power_law_spectrum_fp16():
     approx = synth.decode16(U16, L.dtype) @ synth.decode16(SV16, L.dtype)
     tail = np.sum(s_true[16:] ** 2)
     assert np.linalg.norm(Wd - approx) ** 2 <= tail * 1.01 + 1e-6
+
+
+def test_recipe_mapping_of_sec_3_5():
+    """s = rho C, r = (1 - rho) C mn / (m + n).  The uniform recipe the paper uses (rho = 0.95) at a 50 %
+    budget gives s = 0.475 and r = 0.025 * mn/(m+n): 51.2 for 4096x4096, 74.6 for 4096x11008; the library
+    rounds r down to its granularity of 8.  The relative I/O of the result follows the cost model of
+    Sec. 3.4, r (m + n) / (mn) + s, and never exceeds the budget."""
+    s, r, io = rs.rsparse_recipe(4096, 4096, 0.5, 0.95)
+    assert s == pytest.approx(0.475) and r == 48 and 0.025 * 4096 * 4096 / 8192 == pytest.approx(51.2)
+    assert io == pytest.approx(48 * 8192 / 4096 ** 2 + 0.475) and io <= 0.5
+    s, r, io = rs.rsparse_recipe(4096, 11008, 0.5, 0.95)
+    assert r == 72 and 0.025 * 4096 * 11008 / (4096 + 11008) == pytest.approx(74.63, abs=0.01) and io <= 0.5
+    assert rs.rsparse_recipe(4096, 4096, 0.5, 1.0)[:2] == (0.5, 0)            # "Sparse" baseline of Sec. 4.4
+    s, r, io = rs.rsparse_recipe(4096, 4096, 0.5, 0.0)                        # "Low-Rank" baseline
+    assert s == 0.0 and r == 1024 and io == pytest.approx(0.5)
+    assert rs.rsparse_recipe(64, 64, 1.0, 0.0)[1] == 32                       # mn/(m+n) = 32 <= min(m, n)
+    for bad in ((0, 8, 0.5, 0.5), (8, 8, 1.5, 0.5), (8, 8, 0.5, -0.1), (8, 8, float("nan"), 0.5)):
+        with pytest.raises(rs.RSparseError):
+            rs.rsparse_recipe(*bad)
