@@ -87,6 +87,7 @@ typedef struct {
     int32_t mfma_min_batch;  /* smallest batch that takes the matrix-core path (needs dense_rowmajor = 1):
                                 0 = default (5 for rsparse_linear, 2 for rsparse_dense_ref), 33 = never (9..32 tokens
                                 then run in tiles of 8 on the vector ALU) */
+    int32_t mfma_rows;       /* output rows per workgroup of the matrix-core kernels: 0 default, or 64, 128, 256 */
 } rsparse_tuning;
 
 /*

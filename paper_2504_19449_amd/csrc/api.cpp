@@ -172,7 +172,7 @@ rsparse_status check_config(const rsparse_config *c)
 // Launch shape: column tiles x channel splits ~ a few workgroups per compute unit, each with
 // enough rows to amortise its scan, and the staged share small enough for 64 KiB of LDS.
 // Stage-1 workgroups get about as many bytes of S_r V_r^T as a gather workgroup gets of W.
-Launch resolve_launch(const rsparse_layer *L, int batch, bool dense, int group)
+Launch resolve_launch(const rsparse_layer *L, int batch, bool dense, int group, int waves_of_group = 0)
 {
     Launch c{};
     const rsparse_tuning &t = L->tuning;
@@ -181,6 +181,7 @@ Launch resolve_launch(const rsparse_layer *L, int batch, bool dense, int group)
     // loads in flight, while each output column only receives `splits` atomic adds (same-address
     // device-scope atomics serialise at ~0.1 us each, which sets the kernel's tail).
     c.waves = (t.waves == 1 || t.waves == 2 || t.waves == 4 || t.waves == 8) ? t.waves : (bt >= 8 ? 4 : 8);
+    if (waves_of_group > 0) c.waves = waves_of_group;   // one block size per launch: the first layer's
     if (bt >= 8 && c.waves > 4) c.waves = 4;      // the 8-token kernels are built for at most 256 lanes
     c.nontemporal = t.nontemporal ? 1 : 0;
     c.tile_map = t.tile_map == 0 ? 1 : t.tile_map;
@@ -388,7 +389,7 @@ rsparse_status rsparse_linear_group(rsparse_layer *const *layers, int32_t n_laye
     Launch lc[RSPARSE_MAX_GROUP];
     for (int i = 0; i < n_layers; ++i) {
         v[i] = layers[i]->view();
-        lc[i] = resolve_launch(layers[i], batch, false, n_layers);
+        lc[i] = resolve_launch(layers[i], batch, false, n_layers, i ? lc[0].waves : 0);
     }
     const int stages = layers[0]->tuning.stages;
     bool mfma = batch >= (layers[0]->tuning.mfma_min_batch > 0 ? layers[0]->tuning.mfma_min_batch : kMfmaDefaultMinBatch);
@@ -396,7 +397,7 @@ rsparse_status rsparse_linear_group(rsparse_layer *const *layers, int32_t n_laye
     if (mfma) {
         // 9..32 tokens: matrix-core path, one layer at a time (each is already a full-chip launch)
         for (int i = 0; i < n_layers; ++i)
-            RS_HIP(launch_mfma_linear(v[i], X_dev, batch, Y_devs[i], layers[i]->chan_bits, layers[i]->cus, stages, false, s));
+            RS_HIP(launch_mfma_linear(v[i], X_dev, batch, Y_devs[i], layers[i]->chan_bits, layers[i]->cus, stages, false, layers[0]->tuning.mfma_rows, s));
     } else {
         if (stages != 2) RS_HIP(launch_sparse_and_t(v, lc, n_layers, X_dev, batch, true, true, s));
         if (stages != 1) RS_HIP(launch_finish(v, n_layers, batch, Y_devs, true, s));
@@ -425,14 +426,14 @@ rsparse_status rsparse_dense_ref_group(rsparse_layer *const *layers, int32_t n_l
     bool can_rowdot = true;
     for (int i = 0; i < n_layers; ++i) {
         v[i] = layers[i]->view();
-        lc[i] = resolve_launch(layers[i], batch, true, n_layers);
+        lc[i] = resolve_launch(layers[i], batch, true, n_layers, i ? lc[0].waves : 0);
         can_rowdot = can_rowdot && layers[i]->Wrow != nullptr && rowdot_supported(layers[i]->cfg.d_in, batch);
     }
     bool mfma = batch >= (layers[0]->tuning.mfma_min_batch > 0 ? layers[0]->tuning.mfma_min_batch : kMfmaDefaultMinBatchDense);
     for (int i = 0; i < n_layers; ++i) mfma = mfma && mfma_path_supported(v[i], batch);
     if (mfma) {
         for (int i = 0; i < n_layers; ++i)
-            RS_HIP(launch_mfma_linear(v[i], X_dev, batch, Y_devs[i], layers[i]->chan_bits, layers[i]->cus, 0, true, s));
+            RS_HIP(launch_mfma_linear(v[i], X_dev, batch, Y_devs[i], layers[i]->chan_bits, layers[i]->cus, 0, true, layers[0]->tuning.mfma_rows, s));
         return RSPARSE_OK;
     }
     int kernel = layers[0]->tuning.dense_kernel;
@@ -527,6 +528,8 @@ rsparse_status rsparse_set_tuning(rsparse_layer *L, const rsparse_tuning *t)
     if (!L || !t) return fail(RSPARSE_EINVAL, "NULL argument");
     if (t->splits < 0 || t->waves < 0 || t->lowrank_rows < 0 || t->dense_kernel < 0 || t->dense_kernel > 2)
         return fail(RSPARSE_EINVAL, "negative or unknown tuning value");
+    if (t->mfma_rows != 0 && t->mfma_rows != 64 && t->mfma_rows != 128 && t->mfma_rows != 256)
+        return fail(RSPARSE_EINVAL, "mfma_rows must be 0, 64, 128 or 256");
     if (t->mfma_min_batch < 0 || t->mfma_min_batch > 33) return fail(RSPARSE_EINVAL, "mfma_min_batch must be in [0, 33]");
     if (t->tile_map < 0 || t->tile_map > 2) return fail(RSPARSE_EINVAL, "tile_map must be 0, 1 or 2");
     if (t->stages < 0 || t->stages > 2) return fail(RSPARSE_EINVAL, "stages must be 0, 1 or 2");

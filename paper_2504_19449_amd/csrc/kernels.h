@@ -59,7 +59,7 @@ hipError_t launch_dense_rowdot(const LayerView *L, const Launch *cfg, int n, con
 // dense = the dense baseline Y = X W^T through the same kernels (no masks, no low-rank part).
 bool mfma_path_supported(const LayerView &L, int batch);
 hipError_t launch_mfma_linear(const LayerView &L, const void *X, int batch, void *Y, uint32_t *chan_bits, int cus,
-                              int stages, bool dense, hipStream_t stream);
+                              int stages, bool dense, int rows_per_wg_hint, hipStream_t stream);
 // Zero `n` 32-bit words (a fill kernel, safe to record into a HIP graph).
 hipError_t launch_zero(void *p, size_t n_words, hipStream_t stream);
 

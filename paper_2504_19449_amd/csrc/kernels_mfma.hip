@@ -335,7 +335,7 @@ bool mfma_path_supported(const LayerView &L, int batch)
 }
 
 hipError_t launch_mfma_linear(const LayerView &L, const void *X, int batch, void *Y, uint32_t *chan_bits, int cus,
-                              int stages, bool dense, hipStream_t stream)
+                              int stages, bool dense, int rows_per_wg_hint, hipStream_t stream)
 {
     const int tok_pad = batch > 16 ? 32 : 16;
     const int rank = dense ? 0 : L.rank;
@@ -348,7 +348,8 @@ hipError_t launch_mfma_linear(const LayerView &L, const void *X, int batch, void
         const int n_kchunks = (L.d_in + a.kc - 1) / a.kc;
         // 64 output rows per workgroup (one 16-row block per wave), 128 for very wide layers; K is split
         // only as far as needed for ~3 workgroups per compute unit (k_splits atomic adds per output)
-        const int rows_per_wg = L.d_out / 128 >= 3 * cus ? 128 : 64;
+        const int rows_per_wg = (rows_per_wg_hint == 64 || rows_per_wg_hint == 128 || rows_per_wg_hint == 256)
+                                    ? rows_per_wg_hint : (L.d_out / 128 >= 3 * cus ? 128 : 64);
         a.rows_per_wg = rows_per_wg;
         a.w_chunks = (L.d_out + rows_per_wg - 1) / rows_per_wg;
         a.t_chunks = rank > 0 ? (rank + rows_per_wg - 1) / rows_per_wg : 0;

@@ -228,6 +228,9 @@ def test_group_of_layers_sharing_one_input(B):
     taus = [gu.calibrated_tau(Ls[0], src, s) for (_, _, _, s) in specs]
     for out in (None, rs.F32):
         layers = [gu.prepare(L, tau, max_batch=B, out_dtype=out, dense_rowmajor=1) for L, tau in zip(Ls, taus)]
+        if out is None:      # mixed launch-shape overrides inside one group: the first layer's block size rules
+            rs.rsparse_set_tuning(layers[0], waves=4, splits=5)
+            rs.rsparse_set_tuning(layers[2], waves=8, splits=3, lowrank_rows=32)
         Xd = gu.to_dev16(X16)
         Ys = [gu._alloc_out(layer, B) for layer in layers]
         rs.rsparse_linear_group(layers, Xd.data_ptr(), B, [y.data_ptr() for y in Ys], gu.stream_ptr())
