@@ -325,3 +325,38 @@ def test_matrix_core_path_llama3_shapes(shape):
     tau = gu.calibrated_tau(L, src, 0.5)
     _parity(L, X16, tau, dense_rowmajor=1)
     _parity(L, X16, tau, out_dtype=rs.F32, dense_rowmajor=1)
+
+
+@pytest.mark.parametrize("B", [1, 8])
+def test_hip_graph_replays_match_eager_and_oracle(ragged, B):
+    """The hot calls are capturable: a captured graph of one call is replayed several times, with new
+    token values written into the same input buffer and eager work in between; every replay must equal
+    the eager call on the same input and the oracle (scratch is re-zeroed by the kernels themselves)."""
+    torch = gu.torch_mod()
+    L = ragged[synth.BF16]
+    X16, src = gu.tokens_for(L, 4 * B, linear=60 + B)
+    tau = gu.calibrated_tau(L, src, 0.5)
+    layer = gu.prepare(L, tau, max_batch=B, out_dtype=rs.F32, dense_rowmajor=1)
+    Xd = gu.to_dev16(X16[:B])
+    Y = gu._alloc_out(layer, B)
+    Ye = gu._alloc_out(layer, B)
+    rs.rsparse_linear(layer, Xd.data_ptr(), B, Y.data_ptr(), gu.stream_ptr())      # load everything first
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        rs.rsparse_linear(layer, Xd.data_ptr(), B, Y.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    for rep in range(4):
+        xb = X16[rep * B:(rep + 1) * B]
+        Xd.copy_(torch.from_numpy(np.ascontiguousarray(xb).view(np.int16)))
+        Y.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        got = Y.cpu().numpy().astype(np.float64)
+        rs.rsparse_linear(layer, Xd.data_ptr(), B, Ye.data_ptr(), gu.stream_ptr())  # eager, between replays
+        torch.cuda.synchronize()
+        eager = Ye.cpu().numpy().astype(np.float64)
+        want = gu.oracle_linear(L, xb, tau)
+        gu.check_outputs(got, want["Y"], rs.F32)
+        assert np.linalg.norm(got - eager) <= 1e-5 * np.linalg.norm(eager)
+        assert np.array_equal(rs.rsparse_last_active(layer, 0), want["act"][0])
+    layer.destroy()
