@@ -7,6 +7,7 @@ Rectangular layers are used throughout so that a transposed operand fails.
 """
 import itertools
 import math
+import os
 
 import numpy as np
 import pytest
@@ -42,21 +43,48 @@ def test_bf16_decode_all_bit_patterns():
 
 # --------------------------------------------------------------------------- hand-worked example
 
-def test_hand_worked_2x3():
-    """W = [[1,2,3],[4,5,6]], x = (1,-3,0.5), t = 1: kept channels {0,1} (|1| >= 1 keeps the tie).
-    Rank-1 factors U = (1,2)^T, SV = (1,1,2).  By hand:
-      Y_s = 1*(1,4) + (-3)*(2,5) = (-5,-11);  t = 2*0.5 = 1;  Y_r = (1,2);  Y = (-4,-9)."""
-    W = np.array([[1, 2, 3], [4, 5, 6]], dtype=np.float64)
-    U = np.array([[1.0], [2.0]])
-    SV = np.array([[1.0, 1.0, 2.0]])
-    x = np.array([1.0, -3.0, 0.5])
-    out = oracle.rsparse_linear(W, U, SV, x, oracle.F64, oracle.F64, 1.0)
-    assert out["act"][0].tolist() == [0, 1]
-    assert out["Y"][0].tolist() == [-4.0, -9.0]
-    # strict compare drops the tie: kept {1}; Y_s = (-6,-15); t = 1*1 + 2*0.5 = 2; Y = (-4,-11)
-    out = oracle.rsparse_linear(W, U, SV, x, oracle.F64, oracle.F64, 1.0, cmp_mode=1)
-    assert out["act"][0].tolist() == [1]
-    assert out["Y"][0].tolist() == [-4.0, -11.0]
+def _read_golden(path):
+    """Parse tests/golden/*.txt: 'case:' starts a case, 'key: numbers' lines fill it (rows split by ';')."""
+    cases, cur = [], None
+    for line in open(path):
+        line = line.split("#")[0].strip()
+        if not line:
+            continue
+        key, val = (p.strip() for p in line.split(":", 1))
+        if key == "case":
+            cur = {"name": val, "expect": []}
+            cases.append(cur)
+            continue
+        rows = [[float(v) for v in row.split()] for row in val.split(";")]
+        if key.startswith("expect"):
+            _, cmp_s, union_s, what = key.split()
+            cur["expect"].append((int(cmp_s.split("=")[1]), int(union_s.split("=")[1]), what, rows))
+        else:
+            cur[key] = rows
+    return cases
+
+
+def test_hand_worked_golden():
+    """Cases worked by hand from the definition of Sec. 3.4 (ties, strict compare, two tokens with
+    different masks, rank 2, union mode); the fixture states how each number was obtained."""
+    path = os.path.join(os.path.dirname(__file__), "golden", "hand_worked_sec3_4.txt")
+    cases = _read_golden(path)
+    assert [c["name"] for c in cases] == ["tie_2x3", "batch2_rank2_3x4"]
+    for c in cases:
+        W, U, SV, X = (np.array(c[k], dtype=np.float64) for k in ("W", "U", "SV", "X"))
+        tau = c["tau"][0][0]
+        assert c["expect"], c["name"]
+        for cmp_mode, union, what, rows in c["expect"]:
+            out = oracle.rsparse_linear(W, U, SV, X, oracle.F64, oracle.F64, tau, cmp_mode=cmp_mode,
+                                        batch_mask_mode=union)
+            if what == "kept":
+                if union:
+                    assert out["union"].tolist() == [int(v) for v in rows[0]], (c["name"], cmp_mode)
+                else:
+                    assert [a.tolist() for a in out["act"]] == [[int(v) for v in r] for r in rows], \
+                        (c["name"], cmp_mode)
+            else:
+                assert out["Y"].tolist() == rows, (c["name"], cmp_mode, union)
 
 
 # --------------------------------------------------------------------------- mask / index sets
