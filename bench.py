@@ -11,9 +11,10 @@ every weight byte comes from HBM, not from L2 / Infinity Cache, and are replayed
 captured HIP graph so that host launch overhead is not what is timed.  Inputs are resident
 in HBM before the timed region.
 
-Prints ONE JSON line.  `value` = microseconds per R-Sparse linear (whole-call, both
-launches).  `roofline` is for the dominant kernel (k_sparse_and_t) timed alone with events;
-`cpu_baseline` is the fp64 CPU oracle timed on the host cores on a bounded sample.
+Prints ONE JSON line.  `value` = microseconds per R-Sparse linear (the whole call: one launch of
+k_rsparse_fused).  `roofline` is for that kernel: the bytes the method must move per launch over
+its event-timed duration; `cpu_baseline` is the fp64 CPU oracle timed on the host cores on a
+bounded sample.  The two-launch form of the layer is timed as an extra.
 """
 import argparse
 import json
@@ -26,7 +27,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-TRAFFIC_BYTES_PER_LAUNCH = 78.5e6  # rocprofv3 PMC: (98.2 + 57.2) / 2 MB fetched + 0.8 MB written per launch; see profiles/
+TRAFFIC_BYTES_PER_LAUNCH = None    # set from the rocprofv3 PMC run summarised in profiles/
 REPEATS = 5                # timed brackets of `steps` steps each; the median is reported
 RING_BLOCKS = 4            # MLP blocks in the ring: 12 layers, ~1.2 GiB of column-major weights
 RANK = 512
@@ -279,28 +280,28 @@ def main():
     log(f"rsparse: {us_linear:.2f} us/linear, {gbs_required:.0f} GB/s on required bytes")
 
     extras = {}
-    # dominant kernel alone (k_sparse_and_t, the first launch): algorithmic bytes = kept W columns
-    # + S_r V_r^T + X; the second launch (k_finish) moves U_r + Y.
-    set_all(stages=1)
-    ms_g = timed(pass_rsparse, args.steps, args.warmup)
-    set_all(stages=2)
-    ms_t = timed(pass_rsparse, args.steps, args.warmup)
-    set_all(stages=0)
-    launches_per_step = 2                                # (gate + up grouped) and down
-    us_gather = ms_g * 1000.0 / launches_per_step
-    gather_bytes = []
-    for (_, layer, *_), k in zip(ring, k_of):
-        c = layer.cfg
-        gather_bytes.append(2 * (k * c.d_out + c.rank * c.d_in + c.d_in))
-    bytes_per_launch = sum(gather_bytes) / (RING_BLOCKS * launches_per_step)
-    achieved = bytes_per_launch / (us_gather * 1e-6) / 1e9
+    # The call is one launch of k_rsparse_fused, so the timed region above IS that kernel: two launches
+    # per step, (gate + up grouped) and down.  Algorithmic bytes per launch = the bytes the method must
+    # move (kept W columns + U_r + S_r V_r^T + X + Y) of the linears it covers.
+    launches_per_step = 2
+    us_launch = ms_step * 1000.0 / launches_per_step
+    bytes_per_launch = sum(req_bytes) / (RING_BLOCKS * launches_per_step)
+    achieved = bytes_per_launch / (us_launch * 1e-6) / 1e9
     # traffic: rocprofv3 --pmc FETCH_SIZE (x2.0, calibrated on a 256 MiB copy) + WRITE_SIZE per launch,
-    # from the run summarised in profiles/k_sparse_and_t_config1_pmc_traffic.md
-    roofline = {"bound": "hbm", "kernel": "k_sparse_and_t", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+    # from the run summarised in profiles/
+    roofline = {"bound": "hbm", "kernel": "k_rsparse_fused", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_BYTES_PER_LAUNCH,
-                "us_per_launch": round(us_gather, 3), "bytes_per_launch": int(bytes_per_launch),
+                "us_per_launch": round(us_launch, 3), "bytes_per_launch": int(bytes_per_launch),
                 "launches_per_step": launches_per_step}
-    extras["us_k_finish_per_launch_alone"] = round(ms_t * 1000.0 / launches_per_step, 3)
+    if not args.no_extras:
+        # the two-launch form (stage 2 and the rounding in a second kernel), whole and per kernel
+        set_all(launches=2)
+        extras["us_per_linear_two_launches"] = round(timed(pass_rsparse, args.steps, args.warmup) * 1000.0 / 3.0, 3)
+        set_all(launches=2, stages=1)
+        extras["us_k_sparse_and_t_per_launch_alone"] = round(timed(pass_rsparse, args.steps, args.warmup) * 1000.0 / launches_per_step, 3)
+        set_all(launches=2, stages=2)
+        extras["us_k_finish_per_launch_alone"] = round(timed(pass_rsparse, args.steps, args.warmup) * 1000.0 / launches_per_step, 3)
+        set_all()
 
     # dense GEMV baseline, both hand-written kernels; best one is the baseline
     dense_us = {}

@@ -88,6 +88,9 @@ typedef struct {
                                 0 = default (5 for rsparse_linear, 2 for rsparse_dense_ref), 33 = never (9..32 tokens
                                 then run in tiles of 8 on the vector ALU) */
     int32_t mfma_rows;       /* output rows per workgroup of the matrix-core kernels: 0 default, or 64, 128, 256 */
+    int32_t launches;        /* rsparse_linear up to 8 tokens (and beyond without the row-major copy): 0 default
+                                (one launch), 1 one launch, 2 two launches (stage 2 and the rounding in a second
+                                kernel).  stages != 0 implies two launches */
 } rsparse_tuning;
 
 /*
@@ -151,6 +154,14 @@ rsparse_status rsparse_dense_ref_group(rsparse_layer *const *layers, int32_t n_l
  */
 rsparse_status rsparse_last_active(rsparse_layer *layer, int32_t token, int32_t *idx_host,
                                    int32_t *count);
+
+/*
+ * Wait for the last rsparse_linear call on this handle (synchronises that call's stream) and report
+ * device-side trouble: RSPARSE_EHIP if a bounded cross-workgroup wait of the one-launch kernel ran
+ * out (the result of that call is then invalid; the handle stays usable).  For callers that want a
+ * checked result; the hot path itself never synchronises.
+ */
+rsparse_status rsparse_synchronize(rsparse_layer *layer);
 
 /* Stored 16-bit factors, host buffers U16 [d_out][rank] and SV16 [rank][d_in] (either may be NULL). */
 rsparse_status rsparse_get_factors(const rsparse_layer *layer, void *U16_host, void *SV16_host);

@@ -13,7 +13,8 @@ _STATUS = {1: "EINVAL", 2: "ENOMEM", 3: "EHIP", 4: "EBATCH", 5: "EALIGN", 6: "ES
 
 EXPORTED_SYMBOLS = [
     "rsparse_prepare", "rsparse_compute_factors", "rsparse_prepare_factors", "rsparse_linear",
-    "rsparse_dense_ref", "rsparse_linear_group", "rsparse_dense_ref_group", "rsparse_last_active", "rsparse_get_factors", "rsparse_set_tau", "rsparse_set_tuning",
+    "rsparse_dense_ref", "rsparse_linear_group", "rsparse_dense_ref_group", "rsparse_last_active", "rsparse_synchronize",
+    "rsparse_get_factors", "rsparse_set_tau", "rsparse_set_tuning",
     "rsparse_get_config", "rsparse_calibrate_tau", "rsparse_required_bytes", "rsparse_dense_bytes",
     "rsparse_recipe", "rsparse_destroy", "rsparse_last_error",
 ]
@@ -28,7 +29,8 @@ class Config(C.Structure):
 class Tuning(C.Structure):
     _fields_ = [("splits", C.c_int32), ("waves", C.c_int32), ("lowrank_rows", C.c_int32),
                 ("dense_kernel", C.c_int32), ("nontemporal", C.c_int32), ("stages", C.c_int32),
-                ("tile_map", C.c_int32), ("mfma_min_batch", C.c_int32), ("mfma_rows", C.c_int32)]
+                ("tile_map", C.c_int32), ("mfma_min_batch", C.c_int32), ("mfma_rows", C.c_int32),
+                ("launches", C.c_int32)]
 
 
 class RSparseError(RuntimeError):
@@ -70,6 +72,7 @@ def load_library():
     lib.rsparse_linear_group.argtypes = [vp, i32, vp, i32, vp, vp]
     lib.rsparse_dense_ref_group.argtypes = [vp, i32, vp, i32, vp, vp]
     lib.rsparse_last_active.argtypes = [vp, i32, vp, C.POINTER(i32)]
+    lib.rsparse_synchronize.argtypes = [vp]
     lib.rsparse_get_factors.argtypes = [vp, vp, vp]
     lib.rsparse_set_tau.argtypes = [vp, C.c_float]
     lib.rsparse_set_tuning.argtypes = [vp, C.POINTER(Tuning)]
@@ -88,7 +91,7 @@ def load_library():
     for name in ("rsparse_linear_group", "rsparse_dense_ref_group", "rsparse_prepare", "rsparse_compute_factors",
                  "rsparse_prepare_factors", "rsparse_linear", "rsparse_dense_ref",
                  "rsparse_last_active", "rsparse_get_factors", "rsparse_set_tau", "rsparse_set_tuning",
-                 "rsparse_get_config", "rsparse_calibrate_tau"):
+                 "rsparse_get_config", "rsparse_calibrate_tau", "rsparse_synchronize"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -198,6 +201,10 @@ def rsparse_linear_group(layers, X_dev: int, batch: int, Y_devs, stream: int = 0
 def rsparse_dense_ref_group(layers, X_dev: int, batch: int, Y_devs, stream: int = 0):
     n, hs, ys = _group_arrays(layers, Y_devs)
     _check(load_library().rsparse_dense_ref_group(hs, n, X_dev, batch, ys, stream))
+
+
+def rsparse_synchronize(layer: Layer) -> None:
+    _check(load_library().rsparse_synchronize(layer.handle))
 
 
 def rsparse_last_active(layer: Layer, token: int) -> np.ndarray:

@@ -128,6 +128,10 @@ struct rsparse_layer {
     uint32_t *act_bits = nullptr, *chan_bits = nullptr;
     bool last_mfma = false;
     int32_t *act_list = nullptr, *act_count = nullptr;
+    int *sync = nullptr;
+    uint32_t *t_pub = nullptr;
+    size_t n_t = 0;
+    bool last_fused = false;
     int tiles = 0, nz_max = 1;
     std::vector<uint16_t> U16, SV16;       // host copies of the stored factors
     hipStream_t last_stream = nullptr;
@@ -137,7 +141,7 @@ struct rsparse_layer {
     {
         LayerView v{};
         v.M = M; v.SVt = SVt; v.U = U; v.Wrow = Wrow; v.t = t; v.yacc = yacc;
-        v.act_list = act_list; v.act_bits = act_bits; v.act_count = act_count;
+        v.act_list = act_list; v.act_bits = act_bits; v.act_count = act_count; v.sync = sync; v.t_pub = t_pub;
         v.d_in = cfg.d_in; v.d_out = cfg.d_out; v.rank = cfg.rank;
         v.dtype = cfg.dtype; v.out_dtype = cfg.out_dtype; v.cmp_mode = cfg.cmp_mode;
         v.batch_mask_mode = cfg.batch_mask_mode; v.tau = cfg.tau;
@@ -172,7 +176,8 @@ rsparse_status check_config(const rsparse_config *c)
 // Launch shape: column tiles x channel splits ~ a few workgroups per compute unit, each with
 // enough rows to amortise its scan, and the staged share small enough for 64 KiB of LDS.
 // Stage-1 workgroups get about as many bytes of S_r V_r^T as a gather workgroup gets of W.
-Launch resolve_launch(const rsparse_layer *L, int batch, bool dense, int group, int waves_of_group = 0)
+Launch resolve_launch(const rsparse_layer *L, int batch, bool dense, int group, int waves_of_group = 0,
+                      bool fused = false)
 {
     Launch c{};
     const rsparse_tuning &t = L->tuning;
@@ -197,7 +202,7 @@ Launch resolve_launch(const rsparse_layer *L, int batch, bool dense, int group, 
         splits = std::max(1, std::min(splits, max_by_rows));
     }
     splits = std::min(splits, 4096);
-    while (gather_lds_bytes(L->cfg.d_in, splits, c.waves, bt) > 60 * 1024) splits *= 2;
+    while (gather_lds_bytes(L->cfg.d_in, splits, c.waves, bt, fused ? L->cfg.rank : 0) > 60 * 1024) splits *= 2;
     c.splits = splits;
     int lr = t.lowrank_rows;
     if (lr <= 0) {
@@ -205,6 +210,8 @@ Launch resolve_launch(const rsparse_layer *L, int batch, bool dense, int group, 
         lr = (int)(wg_bytes / (2.0 * L->cfg.d_in) + 0.5);
     }
     c.lowrank_rows = std::max(1, std::min(lr, 4 * c.waves));                  // at most 4 rows per wave
+    // one launch: the gather workgroups end with rows that need t, so stage 1 is cut finer (one row per wave)
+    if (fused && t.lowrank_rows <= 0) c.lowrank_rows = std::min(c.lowrank_rows, c.waves);
     return c;
 }
 
@@ -223,7 +230,7 @@ void free_layer(rsparse_layer *L)
     if (!L) return;
     (void)hipFree(L->M); (void)hipFree(L->SVt); (void)hipFree(L->U); (void)hipFree(L->Wrow); (void)hipFree(L->t);
     (void)hipFree(L->yacc); (void)hipFree(L->act_bits); (void)hipFree(L->chan_bits);
-    (void)hipFree(L->act_list); (void)hipFree(L->act_count);
+    (void)hipFree(L->act_list); (void)hipFree(L->act_count); (void)hipFree(L->sync); (void)hipFree(L->t_pub);
     delete L;
 }
 
@@ -244,13 +251,15 @@ rsparse_status build_layer(const rsparse_config *cfg, const uint16_t *W, const u
         RS_HIP(hipGetDeviceProperties(&prop, L->device));
         L->cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
 
-        // pack W column-major: row c of M = W[:, c]
+        // pack W column-major: row c of M = W[:, c]; rows d_in.. = U_r^T (row d_in + j = U_r[:, j]), which the
+        // one-launch kernel streams as r more channels
         std::vector<uint16_t> host;
         try {
-            host.resize(d_in * d_out);
+            host.resize((d_in + r) * d_out);
             if (r) { L->U16.assign(U16, U16 + d_out * r); L->SV16.assign(SV16, SV16 + r * d_in); }
         } catch (const std::bad_alloc &) { return fail(RSPARSE_ENOMEM, "host allocation failed"); }
         transpose16(W, d_out, d_in, host.data());
+        if (r) transpose16(U16, d_out, r, host.data() + d_in * d_out);
 
         RS_HIP(hipMalloc((void **)&L->M, host.size() * 2));
         RS_HIP(hipMemcpy(L->M, host.data(), host.size() * 2, hipMemcpyHostToDevice));
@@ -274,6 +283,11 @@ rsparse_status build_layer(const rsparse_config *cfg, const uint16_t *W, const u
         RS_HIP(hipMalloc((void **)&L->act_bits, n_list * 4));
         RS_HIP(hipMalloc((void **)&L->act_count, (size_t)L->nz_max * 4));
         RS_HIP(hipMalloc((void **)&L->chan_bits, d_in * 4));
+        RS_HIP(hipMalloc((void **)&L->sync, sync_words(L->tiles) * 4));
+        RS_HIP(hipMemset(L->sync, 0, sync_words(L->tiles) * 4));
+        L->n_t = n_t;
+        RS_HIP(hipMalloc((void **)&L->t_pub, n_t * 4));
+        RS_HIP(hipMemset(L->t_pub, 0xff, n_t * 4));          // every entry "not ready"
         RS_HIP(hipMemset(L->chan_bits, 0, d_in * 4));
         RS_HIP(hipMemset(L->t, 0, n_t * 4));
         RS_HIP(hipMemset(L->yacc, 0, n_y * 4));
@@ -387,17 +401,21 @@ rsparse_status rsparse_linear_group(rsparse_layer *const *layers, int32_t n_laye
     hipStream_t s = (hipStream_t)stream;
     LayerView v[RSPARSE_MAX_GROUP];
     Launch lc[RSPARSE_MAX_GROUP];
+    const int stages = layers[0]->tuning.stages;
+    // one launch unless asked otherwise (timing a stage alone needs the two-launch form)
+    const bool fused = layers[0]->tuning.launches != 2 && stages == 0;
     for (int i = 0; i < n_layers; ++i) {
         v[i] = layers[i]->view();
-        lc[i] = resolve_launch(layers[i], batch, false, n_layers, i ? lc[0].waves : 0);
+        lc[i] = resolve_launch(layers[i], batch, false, n_layers, i ? lc[0].waves : 0, fused);
     }
-    const int stages = layers[0]->tuning.stages;
     bool mfma = batch >= (layers[0]->tuning.mfma_min_batch > 0 ? layers[0]->tuning.mfma_min_batch : kMfmaDefaultMinBatch);
     for (int i = 0; i < n_layers; ++i) mfma = mfma && mfma_path_supported(v[i], batch);
     if (mfma) {
         // 9..32 tokens: matrix-core path, one layer at a time (each is already a full-chip launch)
         for (int i = 0; i < n_layers; ++i)
             RS_HIP(launch_mfma_linear(v[i], X_dev, batch, Y_devs[i], layers[i]->chan_bits, layers[i]->cus, stages, false, layers[0]->tuning.mfma_rows, s));
+    } else if (fused) {
+        RS_HIP(launch_fused(v, lc, n_layers, X_dev, batch, Y_devs, s));
     } else {
         if (stages != 2) RS_HIP(launch_sparse_and_t(v, lc, n_layers, X_dev, batch, true, true, s));
         if (stages != 1) RS_HIP(launch_finish(v, n_layers, batch, Y_devs, true, s));
@@ -406,6 +424,7 @@ rsparse_status rsparse_linear_group(rsparse_layer *const *layers, int32_t n_laye
         layers[i]->last_stream = s;
         layers[i]->last_batch = batch;
         layers[i]->last_mfma = mfma;
+        layers[i]->last_fused = !mfma && fused;
     }
     return RSPARSE_OK;
 }
@@ -451,12 +470,32 @@ rsparse_status rsparse_dense_ref(rsparse_layer *L, const void *X_dev, int32_t ba
     return rsparse_dense_ref_group(&L, 1, X_dev, batch, &Y_dev, stream);
 }
 
+rsparse_status rsparse_synchronize(rsparse_layer *L)
+{
+    if (!L) return fail(RSPARSE_EINVAL, "layer is NULL");
+    if (L->last_batch == 0) return RSPARSE_OK;
+    RS_HIP(hipStreamSynchronize(L->last_stream));
+    if (L->last_fused) {
+        int flag = 0;
+        RS_HIP(hipMemcpy(&flag, L->sync + kSyncError, 4, hipMemcpyDeviceToHost));
+        if (flag != 0) {
+            // leave the counters usable for the next call
+            RS_HIP(hipMemset(L->sync, 0, sync_words(L->tiles) * 4));
+            RS_HIP(hipMemset(L->t_pub, 0xff, L->n_t * 4));
+            RS_HIP(hipMemset(L->yacc, 0, (size_t)L->cfg.max_batch * L->cfg.d_out * 4));
+            return fail(RSPARSE_EHIP, "a cross-workgroup wait of the one-launch kernel ran out; the last result is invalid");
+        }
+    }
+    return RSPARSE_OK;
+}
+
 rsparse_status rsparse_last_active(rsparse_layer *L, int32_t token, int32_t *idx_host, int32_t *count)
 {
     if (!L || !idx_host || !count) return fail(RSPARSE_EINVAL, "NULL argument");
     if (L->last_batch == 0) return fail(RSPARSE_EINVAL, "no rsparse_linear call has been made on this layer");
     if (token < -1 || token >= L->last_batch) return fail(RSPARSE_EINVAL, "token %d outside [-1, %d)", token, L->last_batch);
-    RS_HIP(hipStreamSynchronize(L->last_stream));
+    rsparse_status sst = rsparse_synchronize(L);
+    if (sst != RSPARSE_OK) return sst;
     if (L->last_mfma) {
         // the matrix-core path keeps per-channel token bits instead of compacted lists
         std::vector<uint32_t> cb(L->cfg.d_in);
@@ -533,6 +572,7 @@ rsparse_status rsparse_set_tuning(rsparse_layer *L, const rsparse_tuning *t)
     if (t->mfma_min_batch < 0 || t->mfma_min_batch > 33) return fail(RSPARSE_EINVAL, "mfma_min_batch must be in [0, 33]");
     if (t->tile_map < 0 || t->tile_map > 2) return fail(RSPARSE_EINVAL, "tile_map must be 0, 1 or 2");
     if (t->stages < 0 || t->stages > 2) return fail(RSPARSE_EINVAL, "stages must be 0, 1 or 2");
+    if (t->launches < 0 || t->launches > 2) return fail(RSPARSE_EINVAL, "launches must be 0, 1 or 2");
     if (t->waves != 0 && t->waves != 1 && t->waves != 2 && t->waves != 4 && t->waves != 8)
         return fail(RSPARSE_EINVAL, "waves must be 0, 1, 2, 4 or 8");
     L->tuning = *t;

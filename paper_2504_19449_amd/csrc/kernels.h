@@ -16,7 +16,7 @@ constexpr int kMfmaDefaultMinBatchDense = 2;
 
 // Device-side view of one prepared layer plus its per-call scratch.
 struct LayerView {
-    const uint16_t *M;      // [d_in][d_out]: W column-major (row c = W[:, c])
+    const uint16_t *M;      // [d_in + rank][d_out]: W column-major (row c = W[:, c]), then U_r^T (row d_in + j = U_r[:, j])
     const uint16_t *SVt;    // [rank][d_in]  = S_r V_r^T
     const uint16_t *U;      // [d_out][rank] = U_r, row-major
     const uint16_t *Wrow;   // [d_out][d_in] row-major copy of W, or nullptr
@@ -25,6 +25,8 @@ struct LayerView {
     int32_t *act_list;      // [nz][d_in] ascending kept channels of batch tile z (union over its tokens)
     uint32_t *act_bits;     // [nz][d_in] per list entry: bit b = token b of the tile keeps it
     int32_t *act_count;     // [nz]
+    int *sync;              // arrival counters of the one-launch path (layout: kSync* below); zero between calls
+    uint32_t *t_pub;        // [nz][BT][rank] one-launch path: t as fp32 bits; all-ones (not ready) between calls
     int d_in, d_out, rank;
     int dtype, out_dtype, cmp_mode, batch_mask_mode;
     float tau;
@@ -38,6 +40,13 @@ struct Launch {
     int tile_map;      // 1: tile-fastest workgroup order, 2: XCD-aware (a tile's splits share id mod 8)
 };
 
+// Arrival counters of the one-launch path, as offsets into LayerView::sync (32-bit words).
+constexpr int kSyncTilesDone = 0;   // column tiles (over all batch tiles) whose outputs have been stored
+constexpr int kSyncError = 1;       // set when a bounded wait ran out (results of that call are invalid)
+constexpr int kSyncMaxZ = 4;        // batch tiles per launch
+constexpr int kSyncTile = 8;        // [nz][tiles] channel splits of the tile that have added their sums
+inline size_t sync_words(int tiles) { return (size_t)kSyncTile + (size_t)kSyncMaxZ * tiles; }
+
 // All launchers take a group of n <= kMaxGroupLayers layers that read the same input X (same d_in and
 // dtype); cfg[0].waves and cfg[0].nontemporal apply to the whole launch.
 constexpr int kMaxGroupLayers = 4;
@@ -46,6 +55,12 @@ constexpr int kMaxGroupLayers = 4;
 // the kept columns into yacc (with_gather), as independent workgroups of one grid.
 hipError_t launch_sparse_and_t(const LayerView *L, const Launch *cfg, int n, const void *X, int batch, bool with_t,
                                bool with_gather, hipStream_t stream);
+// The whole layer in ONE launch: the stage-1 workgroups publish t, every gather workgroup also streams
+// its share of the rows of U_r^T (as channels d_in.. with coefficients t), and the last workgroup to
+// arrive at a column tile rounds and stores that tile of Y.  cfg[i].splits must satisfy
+// gather_lds_bytes(d_in, splits, waves, bt, rank) <= 64 KiB.
+hipError_t launch_fused(const LayerView *L, const Launch *cfg, int n, const void *X, int batch, void *const *Y,
+                        hipStream_t stream);
 // Second launch: Y = round(yacc + U_r t) (use_rank) or round(yacc); re-zeroes yacc.
 hipError_t launch_finish(const LayerView *L, int n, int batch, void *const *Y, bool use_rank, hipStream_t stream);
 // Dense baselines.
@@ -63,7 +78,7 @@ hipError_t launch_mfma_linear(const LayerView &L, const void *X, int batch, void
 // Zero `n` 32-bit words (a fill kernel, safe to record into a HIP graph).
 hipError_t launch_zero(void *p, size_t n_words, hipStream_t stream);
 
-size_t gather_lds_bytes(int d_in, int splits, int waves, int bt);
+size_t gather_lds_bytes(int d_in, int splits, int waves, int bt, int fused_rank = 0);
 size_t lowrank_lds_bytes(int d_in, int bt);
 bool rowdot_supported(int d_in, int batch);
 

@@ -19,6 +19,19 @@
 //                    kept list), so there is no compaction launch.  Column tiles x channel splits
 //                    fill the chip; partial sums meet in fp32 atomics.
 //   k_finish         Y = round(yacc + U t)   (row dots over U, no reduction), yacc re-zeroed.
+//
+// or ONE launch (k_rsparse_fused), which removes the second kernel's launch and start-up latency:
+// M carries r more rows, U_r^T, so that stage 2 of the low-rank part is r more "channels" whose
+// coefficients are t.  Every gather workgroup appends its share of those rows to its list; only the
+// FMAs of those rows need t, which the stage-1 workgroups (at the front of the grid, so dispatched
+// first) publish into t_pub.  An entry of t_pub holds an all-ones bit pattern until it is written, so
+// a consumer needs no separate flag: it requests its entries one batch ahead and re-reads (bounded)
+// while it still sees that pattern.  All cross-workgroup data (t_pub, yacc, arrival counters) moves
+// through agent-scope relaxed atomics, which are performed at the device's coherence point, so no
+// cache write-back or invalidate is needed; a workgroup waits for its own atomics to be acknowledged
+// (s_waitcnt) before it bumps a counter.  The last workgroup to arrive at a column tile swaps the
+// tile's sums out of yacc (which re-zeroes them), rounds once and stores Y; the last tile of the
+// layer puts t_pub and the counters back.
 #include "kernels.h"
 #include "device_common.h"
 
@@ -137,18 +150,22 @@ __device__ __forceinline__ void fma_batch(const u32x4 (&v)[kUnroll], const float
 }
 
 // Consume the already-issued batch `va` (rows j0..) and stream the rest of the wave's rows.
-template <int DT, int BT, bool NT>
+// before_fma(j0) runs ahead of the FMAs of the batch that starts at row j0 (its loads, and those of
+// the following batch, are already in flight).
+template <int DT, int BT, bool NT, typename Hook>
 __device__ __forceinline__ void stream_rest(const uint16_t *__restrict__ M, size_t ld, int col, bool colok,
                                             const int *s_idx, const float *s_coef, int n, int j0, int step,
-                                            u32x4 (&va)[kUnroll], float (&acc)[BT][8])
+                                            u32x4 (&va)[kUnroll], float (&acc)[BT][8], Hook &&before_fma)
 {
     u32x4 vb[kUnroll];
     while (j0 < n) {
         load_batch<NT>(M, ld, col, colok, s_idx, n, j0 + step, vb);
+        before_fma(j0);
         fma_batch<DT, BT>(va, s_coef, n, j0, acc);
         j0 += step;
         if (j0 >= n) break;
         load_batch<NT>(M, ld, col, colok, s_idx, n, j0 + step, va);
+        before_fma(j0);
         fma_batch<DT, BT>(vb, s_coef, n, j0, acc);
         j0 += step;
     }
@@ -198,7 +215,26 @@ struct GatherArgs {
     int batch, splits, tiles, cap;
     int lr_wgs, lr_rows, lr_chunk;     // stage-1 workgroups at the front of the grid, rows each, LDS chunk
     int tile_map;
+    void *Y;                           // one-launch path only: the output, [batch][d_out]
+    int nz;                            // one-launch path only: batch tiles in the grid
 };
+
+// t_pub entries hold this pattern until the stage-1 workgroups have written them.  No computed
+// value has it: NaNs made by the ALU are canonical, and NaNs widened from 16-bit inputs have zero
+// low bits; the producer maps it to the canonical NaN anyway.
+constexpr uint32_t kNotReady = 0xffffffffu;
+// Bound on re-reads of an entry that is not ready.  The producers are workgroups with lower
+// indices (dispatched before the caller), so the wait ends; the bound only turns an impossible
+// schedule into an error flag instead of a hang.
+constexpr long long kWaitLimitTicks = 50000000;      // 0.5 s of the 100 MHz wall clock
+constexpr int kWaitLimitPolls = 1 << 20;
+
+// All of this wave's earlier atomics and stores have been acknowledged by the memory system.
+__device__ __forceinline__ void wait_own_writes()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);
+}
 
 // Workgroup index -> (column tile, channel split).  Plain: tile-fastest.  XCD-aware: workgroups are
 // handed to the 8 XCDs round-robin by index, and fp32 atomics from different XCDs to one line move
@@ -262,7 +298,7 @@ __device__ __forceinline__ GatherLds carve(unsigned char *smem, int cap, int bt,
 // ---------------------------------------------------------------------------------------------
 constexpr int kRowsPerWave = 4;
 
-template <int DT, int BT>
+template <int DT, int BT, bool FUSED>
 __device__ __forceinline__ void lowrank_rows(const GatherArgs &a, unsigned char *smem, int wg, int z)
 {
     constexpr int LU = 8;
@@ -335,7 +371,16 @@ __device__ __forceinline__ void lowrank_rows(const GatherArgs &a, unsigned char 
 #pragma unroll
         for (int b = 0; b < BT; ++b) {
             const float v = wave_sum(part[sl][b]);
-            if (lane == 0 && i < row_hi) L.t[((size_t)z * BT + b) * r + i] = v;
+            if (lane == 0 && i < row_hi) {
+                const size_t at = ((size_t)z * BT + b) * r + i;
+                if (FUSED) {
+                    uint32_t bits = as_u(v);
+                    if (bits == kNotReady) bits = 0x7fc00000u;
+                    __hip_atomic_store(L.t_pub + at, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                } else {
+                    L.t[at] = v;
+                }
+            }
         }
     }
 }
@@ -348,16 +393,14 @@ __device__ __forceinline__ void lowrank_rows(const GatherArgs &a, unsigned char 
 // The two groups are independent, so they share one launch.
 // grid.x = lr_wgs + tiles * splits, grid.z = batch tiles of BT tokens, block = 64 * waves.
 // ---------------------------------------------------------------------------------------------
-// Eight tokens of accumulators need the full register file: 4 waves per workgroup, one per SIMD.
-template <int DT, int BT, bool NT>
-__global__ __launch_bounds__(BT >= 8 ? 256 : 512) void k_sparse_and_t(const GroupArgs ga)
+template <int DT, int BT, bool NT, bool FUSED>
+__device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *smem)
 {
-    extern __shared__ __align__(16) unsigned char smem[];
     const int z = blockIdx.z;
     int wg;
     const GatherArgs &a = ga.job[find_job(ga.wg_end, ga.n, blockIdx.x, wg)];
     if (wg < a.lr_wgs) {
-        lowrank_rows<DT, BT>(a, smem, wg, z);
+        lowrank_rows<DT, BT, FUSED>(a, smem, wg, z);
         return;
     }
     const int tid = threadIdx.x, nthr = blockDim.x, lane = tid & 63, w = tid >> 6, nw = nthr >> 6;
@@ -369,6 +412,8 @@ __global__ __launch_bounds__(BT >= 8 ? 256 : 512) void k_sparse_and_t(const Grou
     const int nb = min(BT, a.batch - b0);
     const bool union_all = L.batch_mask_mode == 1;
     const GatherLds s = carve(smem, a.cap, BT, nw);
+    const int col = tile * kTile + lane * 8;
+    const bool colok = col < d_out;
 
     // ---- pass 1, coalesced over the token(s): keep-bits of every 8 channels (union over the batch
     //      tile, or over the whole batch with the union mask) -> one byte each in LDS
@@ -404,12 +449,18 @@ __global__ __launch_bounds__(BT >= 8 ? 256 : 512) void k_sparse_and_t(const Grou
             }
         }
     }
+    // ---- one launch: my share of the rows of U_r^T follows the kept channels as rows d_in + j of M
+    int n_all = n;
+    if (FUSED) {
+        const int r_lo = (int)(((long long)split * L.rank) / a.splits);
+        const int r_hi = (int)(((long long)(split + 1) * L.rank) / a.splits);
+        for (int i = tid; i < r_hi - r_lo; i += nthr) s.idx[n + i] = d_in + r_lo + i;
+        n_all = n + (r_hi - r_lo);
+    }
     if (tile == 0 && split == 0 && tid == 0) L.act_count[z] = k;
     __syncthreads();
 
     // ---- issue the first batch of weight loads (they need only the indices) ...
-    const int col = tile * kTile + lane * 8;
-    const bool colok = col < d_out;
     float acc[BT][8];
 #pragma unroll
     for (int b = 0; b < BT; ++b)
@@ -417,7 +468,7 @@ __global__ __launch_bounds__(BT >= 8 ? 256 : 512) void k_sparse_and_t(const Grou
         for (int e = 0; e < 8; ++e) acc[b][e] = 0.f;
     u32x4 va[kUnroll];
     const int j_first = w * kUnroll, step = nw * kUnroll;
-    load_batch<NT>(L.M, (size_t)d_out, col, colok, s.idx, n, j_first, va);
+    load_batch<NT>(L.M, (size_t)d_out, col, colok, s.idx, n_all, j_first, va);
 
     // ---- ... and fetch the coefficients x[b, c] * m[b, c] of my rows while those loads fly
     for (int j = tid; j < n; j += nthr) {
@@ -442,8 +493,111 @@ __global__ __launch_bounds__(BT >= 8 ? 256 : 512) void k_sparse_and_t(const Grou
     }
     __syncthreads();
 
-    stream_rest<DT, BT, NT>(L.M, (size_t)d_out, col, colok, s.idx, s.coef, n, j_first, step, va, acc);
+    if (!FUSED) {
+        stream_rest<DT, BT, NT>(L.M, (size_t)d_out, col, colok, s.idx, s.coef, n, j_first, step, va, acc, [](int) {});
+        reduce_to_yacc<BT>(acc, s.red, L.yacc, b0, nb, d_out, tile);
+        return;
+    }
+
+    // ---- one launch.  The coefficients of the U_r^T rows are t.  Lane l of a wave looks after row
+    //      l / BT, token l % BT of a batch; the entries of a batch are requested while the batch
+    //      before it is consumed, and written to this wave's own coefficient slots when it is due.
+    const uint32_t *t_pub = L.t_pub + (size_t)z * BT * L.rank;
+    uint32_t tq = 0u;
+    int tq_at = 0;
+    bool tq_valid = false;
+    auto request_t = [&](int jb) {
+        const int j = jb + lane / BT, b = lane % BT;
+        tq = 0u;
+        tq_valid = jb < n_all && jb + kUnroll > n && lane < kUnroll * BT && j >= n && j < n_all && b < nb;
+        if (tq_valid) {
+            tq_at = b * L.rank + (s.idx[j] - d_in);
+            tq = __hip_atomic_load(t_pub + tq_at, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    };
+    auto settle_t = [&]() {
+        if (!__any(tq_valid && tq == kNotReady)) return;
+        const long long t0 = wall_clock64();             // rare: stage 1 has not finished yet
+        bool ok = false;
+        for (int polls = 0; polls < kWaitLimitPolls && !ok; ++polls) {
+            __builtin_amdgcn_s_sleep(8);
+            if (tq_valid && tq == kNotReady) tq = __hip_atomic_load(t_pub + tq_at, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            ok = !__any(tq_valid && tq == kNotReady);
+            if (!ok && wall_clock64() - t0 > kWaitLimitTicks) break;
+        }
+        if (!ok && lane == 0) __hip_atomic_store(L.sync + kSyncError, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    };
+    request_t(j_first);
+    auto need_t = [&](int j0) {
+        if (j0 + kUnroll > n) {                      // this batch holds rows of U_r^T
+            settle_t();
+            const int j = j0 + lane / BT;
+            if (lane < kUnroll * BT && j >= n && j < n_all) s.coef[j * BT + lane % BT] = tq_valid ? as_f(tq) : 0.f;
+            __builtin_amdgcn_wave_barrier();          // read back by this wave only
+        }
+        request_t(j0 + step);
+    };
+    stream_rest<DT, BT, NT>(L.M, (size_t)d_out, col, colok, s.idx, s.coef, n_all, j_first, step, va, acc, need_t);
     reduce_to_yacc<BT>(acc, s.red, L.yacc, b0, nb, d_out, tile);
+
+    // ---- arrive at the tile; the last of its `splits` workgroups owns the finish
+    wait_own_writes();
+    __syncthreads();
+    int *tile_ctr = L.sync + kSyncTile + z * a.tiles + tile;
+    if (tid == 0) {
+        const int arrived = __hip_atomic_fetch_add(tile_ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int last_of_layer = 0;
+        if (arrived == a.splits - 1) {
+            // every workgroup of this tile has consumed t; when that holds for all tiles, t_pub can go back
+            __hip_atomic_store(tile_ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int done = __hip_atomic_fetch_add(L.sync + kSyncTilesDone, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (done == a.tiles * a.nz - 1) {
+                __hip_atomic_store(L.sync + kSyncTilesDone, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                last_of_layer = 1;
+            }
+        }
+        s.misc[12] = arrived;
+        s.misc[13] = last_of_layer;
+    }
+    __syncthreads();
+    if (s.misc[12] != a.splits - 1) return;
+
+    // ---- Y = round(Y_s + Y_r): swap the sums out (this re-zeroes yacc for the next call), round once
+    for (int c = tid; c < kTile; c += nthr) {
+        const int o = tile * kTile + c;
+        if (o < d_out) {
+            float v[BT];
+#pragma unroll
+            for (int b = 0; b < BT; ++b)
+                v[b] = b < nb ? __hip_atomic_exchange(L.yacc + (size_t)(b0 + b) * d_out + o, 0.f, __ATOMIC_RELAXED,
+                                                      __HIP_MEMORY_SCOPE_AGENT)
+                              : 0.f;
+#pragma unroll
+            for (int b = 0; b < BT; ++b)
+                if (b < nb) store_out(a.Y, (size_t)(b0 + b) * d_out + o, v[b], L.out_dtype);
+        }
+    }
+    if (s.misc[13]) {
+        const int words = a.nz * BT * L.rank;
+        for (int i = tid; i < words; i += nthr)
+            __hip_atomic_store(L.t_pub + i, kNotReady, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// Eight tokens of accumulators need the full register file: 4 waves per workgroup, one per SIMD.
+template <int DT, int BT, bool NT>
+__global__ __launch_bounds__(BT >= 8 ? 256 : 512) void k_sparse_and_t(const GroupArgs ga)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    sparse_body<DT, BT, NT, false>(ga, smem);
+}
+
+// The whole layer in one launch (see the file header).  Same grid as k_sparse_and_t.
+template <int DT, int BT, bool NT>
+__global__ __launch_bounds__(BT >= 8 ? 256 : 512, BT >= 8 ? 3 : 4) void k_rsparse_fused(const GroupArgs ga)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    sparse_body<DT, BT, NT, true>(ga, smem);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -492,7 +646,8 @@ __global__ __launch_bounds__(BT >= 8 ? 256 : 512) void k_dense_axpy(const GroupA
         for (int e = 0; e < 8; ++e) acc[b][e] = 0.f;
     u32x4 va[kUnroll];
     load_batch<NT>(L.M, (size_t)d_out, col, colok, s.idx, n, w * kUnroll, va);
-    stream_rest<DT, BT, NT>(L.M, (size_t)d_out, col, colok, s.idx, s.coef, n, w * kUnroll, nw * kUnroll, va, acc);
+    stream_rest<DT, BT, NT>(L.M, (size_t)d_out, col, colok, s.idx, s.coef, n, w * kUnroll, nw * kUnroll, va, acc,
+                            [](int) {});
     reduce_to_yacc<BT>(acc, s.red, L.yacc, b0, nb, d_out, tile);
 }
 
@@ -718,7 +873,10 @@ int batch_tile(int batch)
     return 8;
 }
 
-int gather_cap(int d_in, int splits) { return (d_in + splits - 1) / splits + 2; }
+int gather_cap(int d_in, int splits, int fused_rank = 0)
+{
+    return (d_in + splits - 1) / splits + 2 + (fused_rank > 0 ? (fused_rank + splits - 1) / splits + 1 : 0);
+}
 
 int lowrank_chunk(int d_in, int bt)
 {
@@ -728,9 +886,9 @@ int lowrank_chunk(int d_in, int bt)
 
 }  // namespace
 
-size_t gather_lds_bytes(int d_in, int splits, int waves, int bt)
+size_t gather_lds_bytes(int d_in, int splits, int waves, int bt, int fused_rank)
 {
-    const size_t cap = gather_cap(d_in, splits);
+    const size_t cap = gather_cap(d_in, splits, fused_rank);
     return (waves > 1 ? (size_t)waves * kTile * 4 : 0) + cap * bt * 4 + cap * 4 + 16 * 4 + (size_t)d_in / 8 + 16;
 }
 
@@ -796,6 +954,50 @@ hipError_t launch_sparse_and_t(const LayerView *L, const Launch *cfg, int n, con
     })
     if (L[0].dtype == F16) { RS_G(F16) } else { RS_G(BF16) }
 #undef RS_G
+    return hipGetLastError();
+}
+
+hipError_t launch_fused(const LayerView *L, const Launch *cfg, int n, const void *X, int batch, void *const *Y,
+                        hipStream_t stream)
+{
+    if (!same_shape_class(L, n)) return hipErrorInvalidValue;
+    const int bt = batch_tile(batch);
+    const int nz = (batch + bt - 1) / bt;
+    if (nz > kSyncMaxZ) return hipErrorInvalidValue;
+    GroupArgs ga{};
+    ga.n = n;
+    size_t lds = 0;
+    int total = 0;
+    for (int i = 0; i < n; ++i) {
+        if (!L[i].sync || !Y[i]) return hipErrorInvalidValue;
+        GatherArgs &a = ga.job[i];
+        const int tiles = (L[i].d_out + kTile - 1) / kTile;
+        a.L = L[i]; a.X = (const uint16_t *)X; a.batch = batch; a.splits = cfg[i].splits; a.tiles = tiles;
+        a.cap = gather_cap(L[i].d_in, cfg[i].splits, L[i].rank);
+        a.lr_rows = cfg[i].lowrank_rows;
+        a.lr_wgs = L[i].rank > 0 ? (L[i].rank + cfg[i].lowrank_rows - 1) / cfg[i].lowrank_rows : 0;
+        a.lr_chunk = lowrank_chunk(L[i].d_in, bt);
+        a.tile_map = cfg[i].tile_map;
+        a.Y = Y[i];
+        a.nz = nz;
+        const int gather_wgs = cfg[i].tile_map == 2 ? ((tiles + 7) / 8) * 8 * cfg[i].splits : tiles * cfg[i].splits;
+        total += a.lr_wgs + gather_wgs;
+        ga.wg_end[i] = total;
+        const size_t need = gather_lds_bytes(L[i].d_in, cfg[i].splits, cfg[0].waves, bt, L[i].rank);
+        if (need > 64 * 1024) return hipErrorInvalidValue;
+        lds = std::max(lds, need);
+        if (a.lr_wgs > 0) lds = std::max(lds, lowrank_lds_bytes(L[i].d_in, bt));
+    }
+    for (int i = n; i < kMaxGroup; ++i) ga.wg_end[i] = total;
+    dim3 grid(total, 1, nz), block(kWave * cfg[0].waves);
+    const bool nt = cfg[0].nontemporal != 0;
+#define RS_U(DT)                                                                                        \
+    RS_DISPATCH_BT(bt, {                                                                                \
+        if (nt) hipLaunchKernelGGL((k_rsparse_fused<DT, BT, true>), grid, block, lds, stream, ga);      \
+        else hipLaunchKernelGGL((k_rsparse_fused<DT, BT, false>), grid, block, lds, stream, ga);        \
+    })
+    if (L[0].dtype == F16) { RS_U(F16) } else { RS_U(BF16) }
+#undef RS_U
     return hipGetLastError();
 }
 

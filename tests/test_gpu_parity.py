@@ -151,6 +151,7 @@ def test_batch_smaller_than_max_batch_and_reuse(ragged):
 @pytest.mark.parametrize("tuning", [
     dict(splits=1), dict(splits=3, waves=1), dict(splits=7, waves=2), dict(splits=64, waves=8),
     dict(splits=500, waves=4), dict(lowrank_rows=2), dict(lowrank_rows=4, nontemporal=1),
+    dict(launches=2), dict(launches=2, splits=7, waves=2), dict(launches=2, lowrank_rows=4, nontemporal=1),
 ])
 def test_launch_shapes(ragged, tuning):
     L = ragged[synth.F16]
@@ -158,6 +159,27 @@ def test_launch_shapes(ragged, tuning):
     tau = gu.calibrated_tau(L, src, 0.5)
     _parity(L, X16[0], tau, out_dtype=rs.F32, tuning=tuning)
     _parity(L, X16, tau, out_dtype=rs.F32, tuning=tuning)
+
+
+@pytest.mark.parametrize("launches", [1, 2])
+@pytest.mark.parametrize("B", [1, 3, 8, 12])
+def test_one_and_two_launch_forms_on_a_reused_handle(ragged, launches, B):
+    """Both forms of the vector path (stage 2 inside the gather launch, or in a second kernel), called
+    back to back on one handle with different kept sets: the arrival counters and accumulators of the
+    one-launch form must be back at zero after every call.  12 tokens = two batch tiles."""
+    L = ragged[synth.BF16]
+    X16, src = gu.tokens_for(L, B, linear=40 + B)
+    tau = gu.calibrated_tau(L, src, 0.5)
+    layer = gu.prepare(L, tau, max_batch=B, out_dtype=rs.F32)
+    rs.rsparse_set_tuning(layer, launches=launches, mfma_min_batch=33)
+    for t in (tau, -INF, gu.calibrated_tau(L, src, 0.7), INF, tau):
+        rs.rsparse_set_tau(layer, t)
+        got = gu.run_linear(layer, X16)
+        rs.rsparse_synchronize(layer)
+        want = gu.oracle_linear(L, X16, t)
+        gu.check_lists(got, want)
+        gu.check_outputs(got["Y"], want["Y"], rs.F32)
+    layer.destroy()
 
 
 @pytest.mark.parametrize("dt", [synth.F16, synth.BF16])
