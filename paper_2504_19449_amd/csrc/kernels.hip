@@ -63,27 +63,32 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int *s_wave, int &tot
     return base + inc - v;
 }
 
-// Load channels [c, c+8) of the nb tokens of one batch tile; per-token keep masks (bit e =
-// channel c+e kept).  With union_all (batch_mask_mode 1) every token's mask becomes the union
-// over the WHOLE batch.  Returns the union over the tile's tokens.
+// Channels [c, c+8) of the nb tokens of one batch tile, in two steps so that callers can put the
+// loads of several channel groups in flight before the first compare.
+template <int BT>
+__device__ __forceinline__ void load_raw8(const uint16_t *X, int b0, int nb, int d_in, int c, u32x4 (&raw)[BT])
+{
+#pragma unroll
+    for (int b = 0; b < BT; ++b)
+        raw[b] = b < nb ? *reinterpret_cast<const u32x4 *>(X + (size_t)(b0 + b) * d_in + c) : u32x4{0, 0, 0, 0};
+}
+
+// Per-token keep masks (bit e = channel c+e kept) of loaded channels.  With union_all
+// (batch_mask_mode 1) every token's mask becomes the union over the WHOLE batch.  Returns the union
+// over the tile's tokens.
 template <int DT, int BT>
-__device__ __forceinline__ uint32_t load_tokens8(const uint16_t *X, int batch, int b0, int nb, int d_in,
-                                                 int c, float tau, int mode, bool union_all,
-                                                 u32x4 (&raw)[BT], float (&xv)[BT][8], uint32_t (&m)[BT])
+__device__ __forceinline__ uint32_t masks_of8(const uint16_t *X, int batch, int b0, int nb, int d_in, int c, float tau,
+                                              int mode, bool union_all, const u32x4 (&raw)[BT], uint32_t (&m)[BT])
 {
     uint32_t u = 0;
 #pragma unroll
     for (int b = 0; b < BT; ++b) {
         m[b] = 0;
         if (b < nb) {
-            raw[b] = *reinterpret_cast<const u32x4 *>(X + (size_t)(b0 + b) * d_in + c);
-            unpack8<DT>(raw[b], xv[b]);
+            float xv[8];
+            unpack8<DT>(raw[b], xv);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) m[b] |= (uint32_t)keep(xv[b][e], tau, mode) << e;
-        } else {
-            raw[b] = u32x4{0, 0, 0, 0};
-#pragma unroll
-            for (int e = 0; e < 8; ++e) xv[b][e] = 0.f;
+            for (int e = 0; e < 8; ++e) m[b] |= (uint32_t)keep(xv[e], tau, mode) << e;
         }
         u |= m[b];
     }
@@ -101,6 +106,10 @@ __device__ __forceinline__ uint32_t load_tokens8(const uint16_t *X, int batch, i
     }
     return u;
 }
+
+// Channel groups a thread keeps in flight while it reads the token(s): 8 loads of 16 bytes.
+template <int BT>
+struct TokenBatch { static constexpr int kGroups = BT >= 8 ? 1 : 8 / BT; };
 
 // ---------------------------------------------------------------------------------------------
 // Streaming primitive: acc[b][0:8] += sum_j coef[j][b] * M[idx[j], col:col+8] over the n staged rows.
@@ -321,16 +330,27 @@ __device__ __forceinline__ void lowrank_rows(const GatherArgs &a, unsigned char 
         const int len = min(a.lr_chunk, d_in - c0);
         const int nq = len / 8;
         if (c0 > 0) __syncthreads();
-        for (int q = tid; q < nq; q += nthr) {
-            u32x4 raw[BT]; float xv[BT][8]; uint32_t m[BT];
-            load_tokens8<DT, BT>(a.X, a.batch, b0, nb, d_in, c0 + q * 8, L.tau, L.cmp_mode, union_all, raw, xv, m);
+        constexpr int PB = TokenBatch<BT>::kGroups;
+        for (int q0 = tid; q0 < nq; q0 += nthr * PB) {
+            u32x4 raw[PB][BT];
 #pragma unroll
-            for (int b = 0; b < BT; ++b) {
-                u32x4 o = raw[b];
+            for (int p = 0; p < PB; ++p)
+                if (q0 + p * nthr < nq) load_raw8<BT>(a.X, b0, nb, d_in, c0 + (q0 + p * nthr) * 8, raw[p]);
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if ((m[b] >> e) & 1u) o[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;   // kept -> 0
-                *reinterpret_cast<u32x4 *>(s_xm + (size_t)b * a.lr_chunk + q * 8) = o;
+            for (int p = 0; p < PB; ++p) {
+                const int q = q0 + p * nthr;
+                if (q < nq) {
+                    uint32_t m[BT];
+                    masks_of8<DT, BT>(a.X, a.batch, b0, nb, d_in, c0 + q * 8, L.tau, L.cmp_mode, union_all, raw[p], m);
+#pragma unroll
+                    for (int b = 0; b < BT; ++b) {
+                        u32x4 o = raw[p][b];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if ((m[b] >> e) & 1u) o[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;   // kept -> 0
+                        *reinterpret_cast<u32x4 *>(s_xm + (size_t)b * a.lr_chunk + q * 8) = o;
+                    }
+                }
             }
         }
         __syncthreads();
@@ -419,10 +439,20 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
     //      tile, or over the whole batch with the union mask) -> one byte each in LDS
     const int nq = d_in / 8;
     uint8_t *s_u = reinterpret_cast<uint8_t *>(s.misc + 16);
-    for (int q = tid; q < nq; q += nthr) {
-        u32x4 raw[BT]; float xv[BT][8]; uint32_t m[BT];
-        const uint32_t u = load_tokens8<DT, BT>(a.X, a.batch, b0, nb, d_in, q * 8, L.tau, L.cmp_mode, union_all, raw, xv, m);
-        s_u[q] = (uint8_t)u;
+    constexpr int PB = TokenBatch<BT>::kGroups;
+    for (int q0 = tid; q0 < nq; q0 += nthr * PB) {
+        u32x4 raw[PB][BT];
+#pragma unroll
+        for (int p = 0; p < PB; ++p)
+            if (q0 + p * nthr < nq) load_raw8<BT>(a.X, b0, nb, d_in, (q0 + p * nthr) * 8, raw[p]);
+#pragma unroll
+        for (int p = 0; p < PB; ++p) {
+            const int q = q0 + p * nthr;
+            if (q < nq) {
+                uint32_t m[BT];
+                s_u[q] = (uint8_t)masks_of8<DT, BT>(a.X, a.batch, b0, nb, d_in, q * 8, L.tau, L.cmp_mode, union_all, raw[p], m);
+            }
+        }
     }
     __syncthreads();
 
