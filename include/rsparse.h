@@ -21,7 +21,8 @@
  *     the ABI.  rsparse_last_error() gives a thread-local message for the last failure.
  *   - "host" / "device" is stated for every pointer.  The caller owns everything it
  *     passes in; the handle owns its packed weights and scratch (all allocated at
- *     prepare time -- the hot calls never allocate and never synchronise).
+ *     prepare time -- the hot calls never allocate and never synchronise, and they
+ *     leave the scratch ready for the next call, so they can be captured into a HIP graph).
  *   - A handle must not be used by two calls at once (its scratch is shared); calls
  *     on one stream are ordered by the stream.
  */
@@ -69,8 +70,8 @@ typedef struct {
                                 1: every token uses the union of the batch's masks */
     int32_t dense_rowmajor;  /* 1: also keep W row-major on the device (doubles the weight footprint).  Needed by
                                 the row-dot kernel of rsparse_dense_ref and by the matrix-core path that
-                                rsparse_linear takes for 9..32 tokens; without it those batches run in
-                                tiles of 8 tokens on the vector ALU */
+                                rsparse_linear takes from 5 tokens on (see mfma_min_batch); without it those
+                                batches run in tiles of up to 8 tokens on the vector ALU */
 } rsparse_config;
 
 /* Launch-shape overrides for measurements; 0 = library default. */
@@ -80,13 +81,13 @@ typedef struct {
     int32_t lowrank_rows;    /* rows of S_r V_r^T per stage-1 workgroup */
     int32_t dense_kernel;    /* rsparse_dense_ref: 0 auto, 1 axpy over column-major W, 2 row-dot */
     int32_t nontemporal;     /* 1: stream weights with non-temporal loads */
-    int32_t stages;          /* rsparse_linear: 0 both launches, 1 first launch only, 2 second only -- for
-                                timing one kernel in isolation; results are only valid with 0 */
+    int32_t stages;          /* rsparse_linear, two-launch form: 0 the whole layer, 1 first launch only, 2 second
+                                only -- for timing one kernel in isolation; results are only valid with 0 */
     int32_t tile_map;        /* workgroup -> (column tile, split) mapping: 0 default, 1 tile-fastest (plain),
                                 2 XCD-aware (all splits of a tile on ids congruent mod 8) */
     int32_t mfma_min_batch;  /* smallest batch that takes the matrix-core path (needs dense_rowmajor = 1):
-                                0 = default (5 for rsparse_linear, 2 for rsparse_dense_ref), 33 = never (9..32 tokens
-                                then run in tiles of 8 on the vector ALU) */
+                                0 = default (5 for rsparse_linear, 2 for rsparse_dense_ref), 33 = never (all batches
+                                then run in tiles of up to 8 tokens on the vector ALU) */
     int32_t mfma_rows;       /* output rows per workgroup of the matrix-core kernels: 0 default, or 64, 128, 256 */
     int32_t launches;        /* rsparse_linear up to 8 tokens (and beyond without the row-major copy): 0 default
                                 (one launch), 1 one launch, 2 two launches (stage 2 and the rounding in a second

@@ -411,7 +411,7 @@ rsparse_status rsparse_linear_group(rsparse_layer *const *layers, int32_t n_laye
     bool mfma = batch >= (layers[0]->tuning.mfma_min_batch > 0 ? layers[0]->tuning.mfma_min_batch : kMfmaDefaultMinBatch);
     for (int i = 0; i < n_layers; ++i) mfma = mfma && mfma_path_supported(v[i], batch);
     if (mfma) {
-        // 9..32 tokens: matrix-core path, one layer at a time (each is already a full-chip launch)
+        // matrix-core path, one layer at a time (each is already a full-chip launch)
         for (int i = 0; i < n_layers; ++i)
             RS_HIP(launch_mfma_linear(v[i], X_dev, batch, Y_devs[i], layers[i]->chan_bits, layers[i]->cus, stages, false, layers[0]->tuning.mfma_rows, s));
     } else if (fused) {

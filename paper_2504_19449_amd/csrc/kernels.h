@@ -68,7 +68,7 @@ hipError_t launch_dense_axpy(const LayerView *L, const Launch *cfg, int n, const
                              hipStream_t stream);
 hipError_t launch_dense_rowdot(const LayerView *L, const Launch *cfg, int n, const void *X, int batch, void *const *Y,
                                hipStream_t stream);
-// Matrix-core path for 8 < batch <= 32 (needs the row-major copy of W): both launches of one layer.
+// Matrix-core path for 2 <= batch <= 32 (needs the row-major copy of W): both launches of one layer.
 // chan_bits [d_in] receives, per channel, the bit mask of the tokens that keep it.  stages as in
 // rsparse_tuning.  Zeroes L.t with a fill kernel first (its stage-1 partial sums meet in atomics).
 // dense = the dense baseline Y = X W^T through the same kernels (no masks, no low-rank part).

@@ -10,7 +10,7 @@
 //   SVt  [r][d_in]       S_r V_r^T, one singular component per row
 //   U    [d_out][r]      U_r row-major
 //
-// One call is two launches, ordered by the stream (no intra-kernel cross-workgroup waits):
+// One call is either two launches, ordered by the stream (no intra-kernel cross-workgroup waits):
 //
 //   k_sparse_and_t   workgroups [0, lr_wgs):  t_i = SVt[i,:] . (x - sigma_t(x))      (row dots)
 //                    the others:              yacc += sum_{c kept} x_c M[c,:]         (gather-axpy)
