@@ -200,6 +200,10 @@ Launch resolve_launch(const rsparse_layer *L, int batch, bool dense, int group, 
         splits = (target_wgs + L->tiles - 1) / L->tiles;
         const int max_by_rows = std::max(1, rows / (c.waves * 4));          // >= 4 rows per wave
         splits = std::max(1, std::min(splits, max_by_rows));
+        // every output receives `splits` same-address atomic adds, which serialise at the end of the
+        // kernel: beyond 32 they cost more than the extra workgroups bring, as long as one workgroup
+        // per compute unit remains (measured on 11008 -> 4096: 32 splits beat 48)
+        if (fused) splits = std::min(splits, std::max(32, (L->cus + L->tiles - 1) / L->tiles));
     }
     splits = std::min(splits, 4096);
     while (gather_lds_bytes(L->cfg.d_in, splits, c.waves, bt, fused ? L->cfg.rank : 0) > 60 * 1024) splits *= 2;
@@ -210,8 +214,16 @@ Launch resolve_launch(const rsparse_layer *L, int batch, bool dense, int group, 
         lr = (int)(wg_bytes / (2.0 * L->cfg.d_in) + 0.5);
     }
     c.lowrank_rows = std::max(1, std::min(lr, 4 * c.waves));                  // at most 4 rows per wave
-    // one launch: the gather workgroups end with rows that need t, so stage 1 is cut finer (one row per wave)
-    if (fused && t.lowrank_rows <= 0) c.lowrank_rows = std::min(c.lowrank_rows, c.waves);
+    // one launch: the gather workgroups end with rows that need t, so stage 1 is cut as fine as the
+    // launch allows: its workgroups get the resident slots (two per compute unit, shared by the
+    // layers of a group) that the gather workgroups leave free, with one row per wave on at least
+    // half of the waves.  A launch that needs a second round of workgroups loses more than finer
+    // stage-1 workgroups gain (measured on 4096 -> 11008 and 28672 -> 8192).
+    if (fused && t.lowrank_rows <= 0) {
+        const int free_slots = 2 * L->cus / std::max(1, group) - L->tiles * splits;
+        const int need = free_slots > 0 ? (L->cfg.rank + free_slots - 1) / free_slots : 4 * c.waves;
+        c.lowrank_rows = std::max(std::max(1, c.waves / 2), std::min(4 * c.waves, need));
+    }
     return c;
 }
 
