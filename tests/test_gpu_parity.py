@@ -226,6 +226,51 @@ def test_config1_shapes_sparsity_sweep(shape):
     _parity(L, X16[1], tau, out_dtype=rs.F32)
 
 
+def test_config1_as_benchmarked_grouped_and_replayed():
+    """The launch configuration bench.py times: gate and up (4096 -> 11008) in one grouped call, then
+    down (11008 -> 4096), bf16, r = 512, 50 % sparsity, default launch shapes, captured into a HIP
+    graph and replayed; every output of every replay against the oracle, both launch forms."""
+    import oracle
+    torch = gu.torch_mod()
+    dt = synth.BF16
+    specs = [(4096, 11008, "dmodel", 0), (4096, 11008, "dmodel", 1), (11008, 4096, "down", 2)]
+    Ls = [synth.random_layer(d_in, d_out, 512, dt, seed=1100 + lin) for d_in, d_out, _, lin in specs]
+    src_m = synth.DModelInput(4096, config=1, linear=0)
+    src_d = synth.DownInput(11008, config=1, linear=2)
+    taus = [gu.calibrated_tau(Ls[0], src_m, 0.5), gu.calibrated_tau(Ls[1], src_m, 0.5), gu.calibrated_tau(Ls[2], src_d, 0.5)]
+    xm = synth.encode16(src_m.tokens(1, offset=3), dt)
+    xd = synth.encode16(src_d.tokens(1, offset=3), dt)
+    want = [oracle.rsparse_linear(L.W16, L.U16, L.SV16, x, dt, dt, tau, nthreads=8)
+            for L, x, tau in zip(Ls, (xm, xm, xd), taus)]
+    layers = [gu.prepare(L, tau, max_batch=1, dense_rowmajor=1) for L, tau in zip(Ls, taus)]
+    xm_d, xd_d = gu.to_dev16(xm), gu.to_dev16(xd)
+    Ys = [gu._alloc_out(layer, 1) for layer in layers]
+
+    def step(sptr):
+        rs.rsparse_linear_group(layers[:2], xm_d.data_ptr(), 1, [Ys[0].data_ptr(), Ys[1].data_ptr()], sptr)
+        rs.rsparse_linear(layers[2], xd_d.data_ptr(), 1, Ys[2].data_ptr(), sptr)
+
+    for launches in (1, 2):
+        for layer in layers:
+            rs.rsparse_set_tuning(layer, launches=launches)
+        step(gu.stream_ptr())
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step(torch.cuda.current_stream().cuda_stream)
+        for rep in range(3):
+            for Y in Ys:
+                Y.fill_(0x7FFF)
+            graph.replay()
+            torch.cuda.synchronize()
+            for layer, Y, w in zip(layers, Ys, want):
+                rs.rsparse_synchronize(layer)
+                gu.check_outputs(gu._read_out(layer, Y), w["Y"], layer.cfg.out_dtype)
+                assert np.array_equal(rs.rsparse_last_active(layer, 0), w["act"][0])
+    for layer in layers:
+        layer.destroy()
+
+
 def test_largest_shape_sampled():
     """Llama-3-70B gate/up shape (8192 -> 28672, r = 1024), cheap random operands; the oracle checks
     every output of one token (about a second of CPU)."""
