@@ -92,6 +92,11 @@ typedef struct {
     int32_t launches;        /* rsparse_linear up to 8 tokens (and beyond without the row-major copy): 0 default
                                 (one launch), 1 one launch, 2 two launches (stage 2 and the rounding in a second
                                 kernel).  stages != 0 implies two launches */
+    int32_t debug_wait_polls;   /* one-launch kernel: bound on the re-reads of a low-rank intermediate that stage 1 has
+                                   not published yet; 0 = default (2^20, or 0.5 s) */
+    int32_t debug_skip_stage1;  /* test hook for the error path, needs debug_wait_polls in [1, 64]: stage 1 publishes
+                                   nothing, every bounded wait runs out, the kernel still finishes, the result is
+                                   invalid and rsparse_synchronize reports RSPARSE_EHIP */
 } rsparse_tuning;
 
 /*

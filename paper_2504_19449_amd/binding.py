@@ -30,7 +30,7 @@ class Tuning(C.Structure):
     _fields_ = [("splits", C.c_int32), ("waves", C.c_int32), ("lowrank_rows", C.c_int32),
                 ("dense_kernel", C.c_int32), ("nontemporal", C.c_int32), ("stages", C.c_int32),
                 ("tile_map", C.c_int32), ("mfma_min_batch", C.c_int32), ("mfma_rows", C.c_int32),
-                ("launches", C.c_int32)]
+                ("launches", C.c_int32), ("debug_wait_polls", C.c_int32), ("debug_skip_stage1", C.c_int32)]
 
 
 class RSparseError(RuntimeError):

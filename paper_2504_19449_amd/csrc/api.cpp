@@ -189,6 +189,8 @@ Launch resolve_launch(const rsparse_layer *L, int batch, bool dense, int group, 
     if (waves_of_group > 0) c.waves = waves_of_group;   // one block size per launch: the first layer's
     if (bt >= 8 && c.waves > 4) c.waves = 4;      // the 8-token kernels are built for at most 256 lanes
     c.nontemporal = t.nontemporal ? 1 : 0;
+    c.wait_polls = t.debug_wait_polls;
+    c.skip_stage1 = t.debug_skip_stage1 ? 1 : 0;
     c.tile_map = t.tile_map == 0 ? 1 : t.tile_map;
     const int rows = dense ? L->cfg.d_in : std::max(8, L->cfg.d_in / 2);     // expected rows to stream
     int splits = t.splits;
@@ -585,6 +587,10 @@ rsparse_status rsparse_set_tuning(rsparse_layer *L, const rsparse_tuning *t)
     if (t->tile_map < 0 || t->tile_map > 2) return fail(RSPARSE_EINVAL, "tile_map must be 0, 1 or 2");
     if (t->stages < 0 || t->stages > 2) return fail(RSPARSE_EINVAL, "stages must be 0, 1 or 2");
     if (t->launches < 0 || t->launches > 2) return fail(RSPARSE_EINVAL, "launches must be 0, 1 or 2");
+    if (t->debug_wait_polls < 0 || t->debug_skip_stage1 < 0 || t->debug_skip_stage1 > 1)
+        return fail(RSPARSE_EINVAL, "debug_wait_polls must be >= 0 and debug_skip_stage1 0 or 1");
+    if (t->debug_skip_stage1 && (t->debug_wait_polls < 1 || t->debug_wait_polls > 64))
+        return fail(RSPARSE_EINVAL, "debug_skip_stage1 needs debug_wait_polls in [1, 64] (a short, bounded wait)");
     if (t->waves != 0 && t->waves != 1 && t->waves != 2 && t->waves != 4 && t->waves != 8)
         return fail(RSPARSE_EINVAL, "waves must be 0, 1, 2, 4 or 8");
     L->tuning = *t;

@@ -38,6 +38,8 @@ struct Launch {
     int lowrank_rows;  // rows of S_r V_r^T per stage-1 workgroup
     int nontemporal;
     int tile_map;      // 1: tile-fastest workgroup order, 2: XCD-aware (a tile's splits share id mod 8)
+    int wait_polls;    // one-launch kernel: bound on re-reads of an unpublished t entry; 0 = default
+    int skip_stage1;   // one-launch kernel, test hook: stage 1 publishes nothing, so every wait runs out
 };
 
 // Arrival counters of the one-launch path, as offsets into LayerView::sync (32-bit words).

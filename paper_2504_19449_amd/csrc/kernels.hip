@@ -226,6 +226,8 @@ struct GatherArgs {
     int tile_map;
     void *Y;                           // one-launch path only: the output, [batch][d_out]
     int nz;                            // one-launch path only: batch tiles in the grid
+    int wait_polls;                    // one-launch path only: bound on re-reads of a t entry that is not ready
+    int skip_stage1;                   // test hook: the stage-1 workgroups publish nothing (exercises the bound)
 };
 
 // t_pub entries hold this pattern until the stage-1 workgroups have written them.  No computed
@@ -394,6 +396,7 @@ __device__ __forceinline__ void lowrank_rows(const GatherArgs &a, unsigned char 
             if (lane == 0 && i < row_hi) {
                 const size_t at = ((size_t)z * BT + b) * r + i;
                 if (FUSED) {
+                    if (a.skip_stage1) continue;
                     uint32_t bits = as_u(v);
                     if (bits == kNotReady) bits = 0x7fc00000u;
                     __hip_atomic_store(L.t_pub + at, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -549,7 +552,7 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
         if (!__any(tq_valid && tq == kNotReady)) return;
         const long long t0 = wall_clock64();             // rare: stage 1 has not finished yet
         bool ok = false;
-        for (int polls = 0; polls < kWaitLimitPolls && !ok; ++polls) {
+        for (int polls = 0; polls < a.wait_polls && !ok; ++polls) {
             __builtin_amdgcn_s_sleep(8);
             if (tq_valid && tq == kNotReady) tq = __hip_atomic_load(t_pub + tq_at, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             ok = !__any(tq_valid && tq == kNotReady);
@@ -1010,6 +1013,8 @@ hipError_t launch_fused(const LayerView *L, const Launch *cfg, int n, const void
         a.tile_map = cfg[i].tile_map;
         a.Y = Y[i];
         a.nz = nz;
+        a.wait_polls = cfg[i].wait_polls > 0 ? cfg[i].wait_polls : kWaitLimitPolls;
+        a.skip_stage1 = cfg[i].skip_stage1;
         const int gather_wgs = cfg[i].tile_map == 2 ? ((tiles + 7) / 8) * 8 * cfg[i].splits : tiles * cfg[i].splits;
         total += a.lr_wgs + gather_wgs;
         ga.wg_end[i] = total;

@@ -182,6 +182,33 @@ def test_one_and_two_launch_forms_on_a_reused_handle(ragged, launches, B):
     layer.destroy()
 
 
+def test_bounded_wait_runs_out_and_the_handle_recovers(ragged):
+    """Error path of the one-launch kernel, forced from the host: stage 1 publishes nothing and the
+    wait bound is a few polls, so every kernel still ends normally; the call is reported invalid by
+    rsparse_synchronize and by rsparse_last_active, and the next call on the handle is correct again."""
+    L = ragged[synth.BF16]
+    X16, src = gu.tokens_for(L, 2, linear=77)
+    tau = gu.calibrated_tau(L, src, 0.5)
+    layer = gu.prepare(L, tau, max_batch=2, out_dtype=rs.F32)
+    with pytest.raises(rs.RSparseError):
+        rs.rsparse_set_tuning(layer, launches=1, debug_skip_stage1=1)              # needs a short bound
+    rs.rsparse_set_tuning(layer, launches=1, debug_skip_stage1=1, debug_wait_polls=4)
+    Xd = gu.to_dev16(X16)
+    Y = gu._alloc_out(layer, 2)
+    rs.rsparse_linear(layer, Xd.data_ptr(), 2, Y.data_ptr(), gu.stream_ptr())
+    with pytest.raises(rs.RSparseError) as e:
+        rs.rsparse_synchronize(layer)
+    assert e.value.status == rs.binding.EHIP
+    rs.rsparse_set_tuning(layer, launches=1)
+    for _ in range(2):
+        got = gu.run_linear(layer, X16)
+        rs.rsparse_synchronize(layer)
+        want = gu.oracle_linear(L, X16, tau)
+        gu.check_lists(got, want)
+        gu.check_outputs(got["Y"], want["Y"], rs.F32)
+    layer.destroy()
+
+
 @pytest.mark.parametrize("dt", [synth.F16, synth.BF16])
 def test_dense_ref_both_kernels(ragged, dt):
     import oracle
