@@ -130,7 +130,7 @@ struct rsparse_layer {
     int32_t *act_list = nullptr, *act_count = nullptr;
     int *sync = nullptr;
     uint32_t *t_pub = nullptr;
-    size_t n_t = 0;
+    size_t n_t = 0, n_y = 0;
     bool last_fused = false;
     int tiles = 0, nz_max = 1;
     std::vector<uint16_t> U16, SV16;       // host copies of the stored factors
@@ -289,7 +289,10 @@ rsparse_status build_layer(const rsparse_config *cfg, const uint16_t *W, const u
         }
         const size_t bpad = (size_t)L->nz_max * kMaxBT;
         const size_t n_t = std::max<size_t>(1, r * bpad);
-        const size_t n_y = (size_t)cfg->max_batch * d_out;
+        // the matrix-core kernels keep these accumulators as [d_out][16 or 32 tokens]
+        const size_t n_y = (size_t)(cfg->dense_rowmajor ? std::max(cfg->max_batch, cfg->max_batch > 16 ? 32 : 16)
+                                                          : cfg->max_batch) * d_out;
+        L->n_y = n_y;
         const size_t n_list = (size_t)L->nz_max * d_in;
         RS_HIP(hipMalloc((void **)&L->t, n_t * 4));
         RS_HIP(hipMalloc((void **)&L->yacc, n_y * 4));
@@ -496,7 +499,7 @@ rsparse_status rsparse_synchronize(rsparse_layer *L)
             // leave the counters usable for the next call
             RS_HIP(hipMemset(L->sync, 0, sync_words(L->tiles) * 4));
             RS_HIP(hipMemset(L->t_pub, 0xff, L->n_t * 4));
-            RS_HIP(hipMemset(L->yacc, 0, (size_t)L->cfg.max_batch * L->cfg.d_out * 4));
+            RS_HIP(hipMemset(L->yacc, 0, L->n_y * 4));
             return fail(RSPARSE_EHIP, "a cross-workgroup wait of the one-launch kernel ran out; the last result is invalid");
         }
     }

@@ -14,11 +14,12 @@
 // (one 16-byte load) of row l%16 at k-group l/16.  A = 16 weight rows x 32 k, B = 32 k x 16
 // tokens (from LDS), D[row][token] fp32: lane l, register j holds row 4*(l/16)+j, token l%16.
 //
-// Launch 1 (k_mfma_sparse_and_t): grid = (row chunks of W + row chunks of SVt) x K splits.  A
-// workgroup walks its K range in LDS-sized chunks: it stages the masked tokens of the chunk (kept
-// part for W rows, dropped part for SVt rows), each wave runs its 16-row blocks over it, and the D
-// tiles stay in registers until the end; they are stored directly (one K split) or added to yacc / t
-// with fp32 atomics (k_splits adds per output; t is then zeroed by a fill kernel first).
+// Launch 1 (k_mfma_sparse_and_t): grid = (row groups of W + row groups of SVt) x K slices.  A
+// workgroup stages the masked tokens of ITS K slice once (kept part for W rows, dropped part for SVt
+// rows; the slice is sized to fill the 64 KiB of LDS a workgroup may use) and then streams all its
+// 16-row blocks against it with no further barrier: eight 16-byte weight loads per lane and batch,
+// two batches in flight, a block's D tile in registers until its slice is done, then added to
+// yacc / t with fp32 atomics (one add per K slice and output; stored directly when there is one slice).
 // Launch 2 (k_mfma_finish): t is split into hi + lo 16-bit halves (so the contraction keeps ~16
 // mantissa bits of the fp32 t), D = U_r t, Y = round(yacc + D), yacc re-zeroed.
 #include "kernels.h"
@@ -57,53 +58,39 @@ struct MfmaArgs {
     LayerView L;
     const uint16_t *X;
     int batch, tok_pad;          // tokens, padded to 16 or 32
-    int kc;                      // K chunk staged in LDS at a time, multiple of 32
-    int k_splits;                // workgroups along K; each loops over chunks_per_split chunks
-    int chunks_per_split;
-    int rows_per_wg;             // multiple of 16, at most 64 * kMaxBlocksPerWave
-    int w_chunks, t_chunks;      // row chunks of W and of SVt; grid.x = (w_chunks + t_chunks) * k_splits
+    int ks;                      // K slice staged in LDS, multiple of 32 * kMfmaUnroll
+    int k_slices;
+    int rows_per_wg;             // multiple of 64
+    int w_chunks, t_chunks;      // row groups of W and of SVt; grid.x = (w_chunks + t_chunks) * k_slices
     uint32_t *chan_bits;         // [d_in] bit b = token b keeps the channel (read-back)
     int dense;                   // 1: dense baseline -- every channel kept, no masks, no stage 1
 };
 
-constexpr int kMaxBlocksPerWave = 4;
 constexpr int kStageBatch = 8;      // 16-byte token loads in flight per thread while staging
 
-// One 16-row block over the staged K chunk: acc0 = tokens 0-15, acc1 = tokens 16-31.
-template <int DT>
-__device__ __forceinline__ void block_over_chunk(const uint16_t *__restrict__ rowptr, bool row_ok, int klen, int kc,
-                                                 const unsigned char *s_act, int pitch, int tok_pad, int lane,
-                                                 f32x4 &acc0, f32x4 &acc1)
+// One batch of weight loads of a 16-row block: kMfmaUnroll steps of 32 k, starting at step s0.
+__device__ __forceinline__ void load_a_batch(const uint16_t *__restrict__ rowptr, bool row_ok, int klen, int s0, int kg,
+                                             u32x4 (&v)[kMfmaUnroll])
 {
-    const int kg = (lane >> 4) * 8;                     // this lane's k offset inside a 32-deep step
-    const unsigned char *b_lo = s_act + (size_t)(lane & 15) * pitch + kg * 2;
-    const unsigned char *b_hi = b_lo + (size_t)16 * pitch;
-    for (int ks = 0; ks < kc; ks += kMfmaK * kMfmaUnroll) {
-        u32x4 v[kMfmaUnroll];
 #pragma unroll
-        for (int u = 0; u < kMfmaUnroll; ++u) {
-            const int k = ks + u * kMfmaK + kg;
-            v[u] = (row_ok && k < klen) ? *reinterpret_cast<const u32x4 *>(rowptr + k) : u32x4{0, 0, 0, 0};
-        }
-#pragma unroll
-        for (int u = 0; u < kMfmaUnroll; ++u) {
-            const int k = ks + u * kMfmaK;
-            if (k < kc) {
-                const u32x4 b0 = *reinterpret_cast<const u32x4 *>(b_lo + (size_t)k * 2);
-                acc0 = mfma16<DT>(v[u], b0, acc0);
-                if (tok_pad > 16) {
-                    const u32x4 b1 = *reinterpret_cast<const u32x4 *>(b_hi + (size_t)k * 2);
-                    acc1 = mfma16<DT>(v[u], b1, acc1);
-                }
-            }
-        }
+    for (int u = 0; u < kMfmaUnroll; ++u) {
+        const int k = (s0 + u) * kMfmaK + kg;
+        v[u] = (row_ok && k < klen) ? *reinterpret_cast<const u32x4 *>(rowptr + k) : u32x4{0, 0, 0, 0};
     }
 }
 
-// A workgroup owns rows_per_wg output rows (of W, or of S_r V_r^T) and one K split; it walks its K
-// range in LDS-sized chunks, re-staging the masked tokens for each, and keeps the D tiles in
-// registers throughout.  Results are stored directly when there is a single K split, else added
-// with fp32 atomics (k_splits adds per output).
+template <int DT>
+__device__ __forceinline__ void mfma_a_batch(const u32x4 (&v)[kMfmaUnroll], int s0, const unsigned char *b_lo,
+                                             const unsigned char *b_hi, bool two, f32x4 &acc0, f32x4 &acc1)
+{
+#pragma unroll
+    for (int u = 0; u < kMfmaUnroll; ++u) {
+        const size_t off = (size_t)(s0 + u) * kMfmaK * 2;
+        acc0 = mfma16<DT>(v[u], *reinterpret_cast<const u32x4 *>(b_lo + off), acc0);
+        if (two) acc1 = mfma16<DT>(v[u], *reinterpret_cast<const u32x4 *>(b_hi + off), acc1);
+    }
+}
+
 template <int DT>
 __global__ __launch_bounds__(256) void k_mfma_sparse_and_t(const MfmaArgs a)
 {
@@ -111,129 +98,139 @@ __global__ __launch_bounds__(256) void k_mfma_sparse_and_t(const MfmaArgs a)
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const LayerView &L = a.L;
     const int d_in = L.d_in;
-    const int ksp = blockIdx.x % a.k_splits;
-    int rc = blockIdx.x / a.k_splits;
+    const int ksl = blockIdx.x % a.k_slices;
+    int rc = blockIdx.x / a.k_slices;
     const bool is_t = rc >= a.w_chunks;
     if (is_t) rc -= a.w_chunks;
-    const int nq = a.kc / 8;                            // 16-byte pieces per token in a chunk
-    const int pitch = a.kc * 2 + 16;                    // odd multiple of 16 bytes: conflict-free B reads
+    const int nq = a.ks / 8;                            // 16-byte pieces per token in the slice
+    const int pitch = a.ks * 2 + 16;                    // odd multiple of 16 bytes: conflict-free B reads
     unsigned char *s_act = smem;                        // [tok_pad][pitch]
-    uint32_t *s_bits = reinterpret_cast<uint32_t *>(smem + (size_t)a.tok_pad * pitch);   // [kc] per-channel token bits
     const bool union_all = L.batch_mask_mode == 1 && !a.dense;
     const bool publish = !is_t && rc == 0 && !a.dense;  // these workgroups cover every channel once
+    const int k0 = ksl * a.ks;
+    const int klen = min(a.ks, d_in - k0);              // > 0 by construction of k_slices
+    const uint32_t all_tokens = a.batch >= 32 ? 0xffffffffu : ((1u << a.batch) - 1u);
 
-    const uint16_t *Mat = is_t ? L.SVt : L.Wrow;
-    const int nrows = is_t ? L.rank : L.d_out;
-    float *out = is_t ? L.t : L.yacc;                   // [token][nrows]
-    const int blocks = a.rows_per_wg / kRowsPerBlock;
-
-    f32x4 acc0[kMaxBlocksPerWave], acc1[kMaxBlocksPerWave];
+    // ---- per-channel keep bits of every token: needed for the union mask and for read-back
+    uint32_t *s_bits = reinterpret_cast<uint32_t *>(smem + (size_t)a.tok_pad * pitch);   // [ks]
+    if (union_all || publish) {
+        for (int i = tid; i < a.ks; i += 256) s_bits[i] = 0u;
+        __syncthreads();
+        for (int q = tid; q < a.tok_pad * nq; q += 256) {
+            const int tok = q / nq, kq = q % nq;
+            if (tok < a.batch && kq * 8 < klen) {
+                float f[8];
+                unpack8<DT>(*reinterpret_cast<const u32x4 *>(a.X + (size_t)tok * d_in + k0 + kq * 8), f);
 #pragma unroll
-    for (int bi = 0; bi < kMaxBlocksPerWave; ++bi) {
-        acc0[bi] = f32x4{0.f, 0.f, 0.f, 0.f};
-        acc1[bi] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
-
-    const int chunk_lo = ksp * a.chunks_per_split;
-    for (int ci = 0; ci < a.chunks_per_split; ++ci) {
-        const int k0 = (chunk_lo + ci) * a.kc;
-        if (k0 >= d_in) break;
-        const int klen = min(a.kc, d_in - k0);
-        if (ci > 0) __syncthreads();
-        // pass A: per-channel keep bits of every token (needed for the union mask and for read-back)
-        if (union_all || publish) {
-            for (int i = tid; i < a.kc; i += 256) s_bits[i] = 0u;
-            __syncthreads();
-            for (int q = tid; q < a.tok_pad * nq; q += 256) {
-                const int tok = q / nq, kq = q % nq;
-                if (tok < a.batch && kq * 8 < klen) {
-                    float f[8];
-                    unpack8<DT>(*reinterpret_cast<const u32x4 *>(a.X + (size_t)tok * d_in + k0 + kq * 8), f);
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (keep(f[e], L.tau, L.cmp_mode)) atomicOr(&s_bits[kq * 8 + e], 1u << tok);
-                }
-            }
-            __syncthreads();
-            if (union_all) {
-                const uint32_t all = a.batch >= 32 ? 0xffffffffu : ((1u << a.batch) - 1u);
-                for (int i = tid; i < a.kc; i += 256) s_bits[i] = s_bits[i] ? all : 0u;
-                __syncthreads();
-            }
-            if (publish)
-                for (int i = tid; i < klen; i += 256) a.chan_bits[k0 + i] = s_bits[i];
-        }
-        // pass B: stage the kept part (W rows) or the dropped part (SVt rows) of every token.
-        // All of a batch's loads are issued before the first is used (one L2 round trip per batch).
-        const int total = a.tok_pad * nq;
-        for (int q0 = tid; q0 < total; q0 += 256 * kStageBatch) {
-            u32x4 raw[kStageBatch];
-#pragma unroll
-            for (int u = 0; u < kStageBatch; ++u) {
-                const int q = q0 + u * 256;
-                const int tok = q / nq, kq = q % nq;
-                raw[u] = (q < total && tok < a.batch && kq * 8 < klen)
-                             ? *reinterpret_cast<const u32x4 *>(a.X + (size_t)tok * d_in + k0 + kq * 8)
-                             : u32x4{0, 0, 0, 0};
-            }
-#pragma unroll
-            for (int u = 0; u < kStageBatch; ++u) {
-                const int q = q0 + u * 256;
-                if (q < total) {
-                    const int tok = q / nq, kq = q % nq;
-                    u32x4 o = raw[u];
-                    if (!a.dense) {
-                        float f[8];
-                        unpack8<DT>(o, f);
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) {
-                            const bool kept = union_all ? ((s_bits[kq * 8 + e] >> (tok & 31)) & 1u) != 0u
-                                                        : keep(f[e], L.tau, L.cmp_mode);
-                            if (kept == is_t) o[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;   // not this part's
-                        }
-                    }
-                    *reinterpret_cast<u32x4 *>(s_act + (size_t)tok * pitch + kq * 16) = o;
-                }
+                for (int e = 0; e < 8; ++e)
+                    if (keep(f[e], L.tau, L.cmp_mode)) atomicOr(&s_bits[kq * 8 + e], 1u << tok);
             }
         }
         __syncthreads();
+        if (publish)
+            for (int i = tid; i < klen; i += 256) a.chan_bits[k0 + i] = union_all && s_bits[i] ? all_tokens : s_bits[i];
+    }
 
+    // ---- stage the kept part (W rows) or the dropped part (SVt rows) of every token, once.
+    //      All of a round's loads are issued before the first is used (one L2 round trip per round).
+    const int total = a.tok_pad * nq;
+    for (int q0 = tid; q0 < total; q0 += 256 * kStageBatch) {
+        u32x4 raw[kStageBatch];
 #pragma unroll
-        for (int bi = 0; bi < kMaxBlocksPerWave; ++bi) {
-            const int blk = w + 4 * bi;
-            const int row0 = rc * a.rows_per_wg + blk * kRowsPerBlock;
-            if (blk < blocks && row0 < nrows) {
-                const int row = row0 + (lane & 15);
-                const bool row_ok = row < nrows;
-                const uint16_t *rowptr = Mat + (size_t)(row_ok ? row : 0) * d_in + k0;
-                block_over_chunk<DT>(rowptr, row_ok, klen, a.kc, s_act, pitch, a.tok_pad, lane, acc0[bi], acc1[bi]);
+        for (int u = 0; u < kStageBatch; ++u) {
+            const int q = q0 + u * 256;
+            const int tok = q / nq, kq = q % nq;
+            raw[u] = (q < total && tok < a.batch && kq * 8 < klen)
+                         ? *reinterpret_cast<const u32x4 *>(a.X + (size_t)tok * d_in + k0 + kq * 8)
+                         : u32x4{0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int u = 0; u < kStageBatch; ++u) {
+            const int q = q0 + u * 256;
+            if (q < total) {
+                const int tok = q / nq, kq = q % nq;
+                u32x4 o = raw[u];
+                if (!a.dense) {
+                    float f[8];
+                    unpack8<DT>(o, f);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const bool kept = union_all ? s_bits[kq * 8 + e] != 0u : keep(f[e], L.tau, L.cmp_mode);
+                        if (kept == is_t) o[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;   // not this part's
+                    }
+                }
+                *reinterpret_cast<u32x4 *>(s_act + (size_t)tok * pitch + kq * 16) = o;
             }
         }
     }
+    __syncthreads();
 
+    // ---- stream my 16-row blocks against the staged slice: no barrier from here on
+    const uint16_t *Mat = is_t ? L.SVt : L.Wrow;
+    const int nrows = is_t ? L.rank : L.d_out;
+    float *out = is_t ? L.t : L.yacc;                   // [token][nrows]
+    const int kg = (lane >> 4) * 8;
+    const unsigned char *b_lo = s_act + (size_t)(lane & 15) * pitch + kg * 2;
+    const unsigned char *b_hi = b_lo + (size_t)16 * pitch;
+    const bool two = a.tok_pad > 16;
+    const bool direct = a.k_slices == 1;
     const int tok = lane & 15;
-    const bool direct = a.k_splits == 1;
+    const int bpb = a.ks / (kMfmaK * kMfmaUnroll);      // batches per block
+    const int row_base = rc * a.rows_per_wg;
+    const int blocks = (min(a.rows_per_wg, nrows - row_base) + kRowsPerBlock - 1) / kRowsPerBlock;   // >= 1
+    const int my_blocks = blocks > w ? (blocks - w + 3) / 4 : 0;                                     // blocks w, w+4, ...
+    const int n_batches = my_blocks * bpb;
+
+    auto row_of = [&](int batch_i, const uint16_t *&rowptr, bool &row_ok) {
+        const int row = row_base + (w + 4 * (batch_i / bpb)) * kRowsPerBlock + (lane & 15);
+        row_ok = row < nrows;
+        rowptr = Mat + (size_t)(row_ok ? row : 0) * d_in + k0;
+    };
+    auto flush = [&](int batch_i, f32x4 &acc0, f32x4 &acc1) {
+        const int row0 = row_base + (w + 4 * (batch_i / bpb)) * kRowsPerBlock;
 #pragma unroll
-    for (int bi = 0; bi < kMaxBlocksPerWave; ++bi) {
-        const int blk = w + 4 * bi;
-        const int row0 = rc * a.rows_per_wg + blk * kRowsPerBlock;
-        if (blk < blocks && row0 < nrows) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int orow = row0 + 4 * (lane >> 4) + j;
-                if (orow < nrows) {
-                    float *p0 = out + (size_t)tok * nrows + orow;
-                    float *p1 = out + (size_t)(tok + 16) * nrows + orow;
-                    if (direct) {
-                        if (tok < a.batch) *p0 = acc0[bi][j];
-                        if (tok + 16 < a.batch) *p1 = acc1[bi][j];
-                    } else {
-                        if (tok < a.batch) __hip_atomic_fetch_add(p0, acc0[bi][j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        if (tok + 16 < a.batch) __hip_atomic_fetch_add(p1, acc1[bi][j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    }
+        for (int j = 0; j < 4; ++j) {
+            const int orow = row0 + 4 * (lane >> 4) + j;
+            if (orow < nrows) {
+                // t is [token][rank]; the accumulators of Y are [row][tok_pad] here, so that the 16 lanes
+                // of one D register hit one 64-byte run instead of 16 lines
+                float *p0 = is_t ? out + (size_t)tok * nrows + orow : out + (size_t)orow * a.tok_pad + tok;
+                float *p1 = is_t ? out + (size_t)(tok + 16) * nrows + orow : p0 + 16;
+                if (direct) {
+                    if (tok < a.batch) *p0 = acc0[j];
+                    if (tok + 16 < a.batch) *p1 = acc1[j];
+                } else {
+                    if (tok < a.batch) __hip_atomic_fetch_add(p0, acc0[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (tok + 16 < a.batch) __hip_atomic_fetch_add(p1, acc1[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
         }
+        acc0 = f32x4{0.f, 0.f, 0.f, 0.f};
+        acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
+    };
+
+    f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+    u32x4 va[kMfmaUnroll], vb[kMfmaUnroll];
+    const uint16_t *rowptr;
+    bool row_ok;
+    if (n_batches > 0) {
+        row_of(0, rowptr, row_ok);
+        load_a_batch(rowptr, row_ok, klen, 0, kg, va);
+    }
+    for (int i = 0; i < n_batches; i += 2) {
+        if (i + 1 < n_batches) {
+            row_of(i + 1, rowptr, row_ok);
+            load_a_batch(rowptr, row_ok, klen, ((i + 1) % bpb) * kMfmaUnroll, kg, vb);
+        }
+        mfma_a_batch<DT>(va, (i % bpb) * kMfmaUnroll, b_lo, b_hi, two, acc0, acc1);
+        if (i % bpb == bpb - 1) flush(i, acc0, acc1);
+        if (i + 1 >= n_batches) break;
+        if (i + 2 < n_batches) {
+            row_of(i + 2, rowptr, row_ok);
+            load_a_batch(rowptr, row_ok, klen, ((i + 2) % bpb) * kMfmaUnroll, kg, va);
+        }
+        mfma_a_batch<DT>(vb, ((i + 1) % bpb) * kMfmaUnroll, b_lo, b_hi, two, acc0, acc1);
+        if ((i + 1) % bpb == bpb - 1) flush(i + 1, acc0, acc1);
     }
 }
 
@@ -260,9 +257,14 @@ __global__ __launch_bounds__(256) void k_mfma_finish(const MfmaFinishArgs a)
     const bool row_ok = row < d_out;
     f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 
-    for (int c0 = 0; c0 < r; c0 += a.rc) {
-        const int clen = min(a.rc, r - c0);
-        if (c0 > 0) __syncthreads();
+    // One chunk = one batch of kMfmaUnroll weight loads per lane (a.rc = 32 * kMfmaUnroll).  The loads of
+    // a chunk do not depend on the staged t: they are issued before the staging of that chunk, so their
+    // latency and the staging overlap.
+    const int kg = (lane >> 4) * 8;
+    const size_t lane_off = (size_t)(lane & 15) * pitch + kg * 2;
+    const bool two = a.tok_pad > 16;
+    const uint16_t *urow = L.U + (size_t)(row_ok ? row : 0) * r;
+    auto stage_t = [&](int c0, int clen) {
         // t = hi + lo in the storage type: the MFMA contraction then carries ~16 mantissa bits of t.
         // Four values per thread and step, a batch of loads issued before the first conversion.
         const int rc4 = a.rc / 4, total4 = a.tok_pad * rc4;
@@ -296,10 +298,25 @@ __global__ __launch_bounds__(256) void k_mfma_finish(const MfmaFinishArgs a)
                 }
             }
         }
+    };
+    auto both_halves = [&](const u32x4 (&v)[kMfmaUnroll]) {
+        mfma_a_batch<DT>(v, 0, s_hi + lane_off, s_hi + lane_off + (size_t)16 * pitch, two, acc0, acc1);
+        mfma_a_batch<DT>(v, 0, s_lo + lane_off, s_lo + lane_off + (size_t)16 * pitch, two, acc0, acc1);
+    };
+    u32x4 va[kMfmaUnroll], vb[kMfmaUnroll];
+    if (r > 0) load_a_batch(urow, row_ok, min(a.rc, r), 0, kg, va);
+    for (int c0 = 0; c0 < r; c0 += 2 * a.rc) {
+        if (c0 > 0) __syncthreads();
+        if (c0 + a.rc < r) load_a_batch(urow + c0 + a.rc, row_ok, min(a.rc, r - c0 - a.rc), 0, kg, vb);
+        stage_t(c0, min(a.rc, r - c0));
         __syncthreads();
-        const uint16_t *rowptr = L.U + (size_t)(row_ok ? row : 0) * r + c0;
-        block_over_chunk<DT>(rowptr, row_ok, clen, a.rc, s_hi, pitch, a.tok_pad, lane, acc0, acc1);
-        block_over_chunk<DT>(rowptr, row_ok, clen, a.rc, s_lo, pitch, a.tok_pad, lane, acc0, acc1);
+        both_halves(va);
+        if (c0 + a.rc >= r) break;
+        __syncthreads();
+        if (c0 + 2 * a.rc < r) load_a_batch(urow + c0 + 2 * a.rc, row_ok, min(a.rc, r - c0 - 2 * a.rc), 0, kg, va);
+        stage_t(c0 + a.rc, min(a.rc, r - c0 - a.rc));
+        __syncthreads();
+        both_halves(vb);
     }
     // lane l holds rows row0 + 4*(l/16) + 0..3 of token l%16 (and l%16 + 16): 4 consecutive outputs
     const int orow = row0 + 4 * (lane >> 4);
@@ -309,19 +326,24 @@ __global__ __launch_bounds__(256) void k_mfma_finish(const MfmaFinishArgs a)
             const int tok = (lane & 15) + 16 * half;
             if (tok < a.batch) {
                 const f32x4 acc = half ? acc1 : acc0;
-                float4 *yp = reinterpret_cast<float4 *>(L.yacc + (size_t)tok * d_out + orow);
-                const float4 ya = *yp;
-                const float o0 = ya.x + acc[0], o1 = ya.y + acc[1], o2 = ya.z + acc[2], o3 = ya.w + acc[3];
+                float *yp = L.yacc + (size_t)orow * a.tok_pad + tok;          // [row][tok_pad], see launch 1
+                float o[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) o[j] = orow + j < d_out ? yp[(size_t)j * a.tok_pad] : 0.f;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) o[j] += acc[j];
                 const size_t oi = (size_t)tok * d_out + orow;
                 if (L.out_dtype == F32) {
-                    *reinterpret_cast<float4 *>((float *)a.Y + oi) = float4{o0, o1, o2, o3};
+                    *reinterpret_cast<float4 *>((float *)a.Y + oi) = float4{o[0], o[1], o[2], o[3]};
                 } else {
                     uint2 pk;
-                    pk.x = (uint32_t)narrow<DT>(o0) | ((uint32_t)narrow<DT>(o1) << 16);
-                    pk.y = (uint32_t)narrow<DT>(o2) | ((uint32_t)narrow<DT>(o3) << 16);
+                    pk.x = (uint32_t)narrow<DT>(o[0]) | ((uint32_t)narrow<DT>(o[1]) << 16);
+                    pk.y = (uint32_t)narrow<DT>(o[2]) | ((uint32_t)narrow<DT>(o[3]) << 16);
                     *reinterpret_cast<uint2 *>((uint16_t *)a.Y + oi) = pk;
                 }
-                *yp = float4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (orow + j < d_out) yp[(size_t)j * a.tok_pad] = 0.f;
             }
         }
     }
@@ -343,26 +365,29 @@ hipError_t launch_mfma_linear(const LayerView &L, const void *X, int batch, void
         MfmaArgs a{};
         a.L = L; a.X = (const uint16_t *)X; a.batch = batch; a.tok_pad = tok_pad; a.chan_bits = chan_bits;
         a.dense = dense ? 1 : 0;
-        a.kc = tok_pad > 16 ? 512 : 1024;
-        if (a.kc > ((L.d_in + 31) / 32) * 32) a.kc = ((L.d_in + 31) / 32) * 32;
-        const int n_kchunks = (L.d_in + a.kc - 1) / a.kc;
-        // 64 output rows per workgroup (one 16-row block per wave), 128 for very wide layers; K is split
-        // only as far as needed for ~3 workgroups per compute unit (k_splits atomic adds per output)
-        const int rows_per_wg = (rows_per_wg_hint == 64 || rows_per_wg_hint == 128 || rows_per_wg_hint == 256)
-                                    ? rows_per_wg_hint : (L.d_out / 128 >= 3 * cus ? 128 : 64);
-        a.rows_per_wg = rows_per_wg;
-        a.w_chunks = (L.d_out + rows_per_wg - 1) / rows_per_wg;
-        a.t_chunks = rank > 0 ? (rank + rows_per_wg - 1) / rows_per_wg : 0;
-        int k_splits = (3 * cus + a.w_chunks - 1) / a.w_chunks;
-        k_splits = std::max(1, std::min(k_splits, n_kchunks));
-        a.chunks_per_split = (n_kchunks + k_splits - 1) / k_splits;
-        a.k_splits = (n_kchunks + a.chunks_per_split - 1) / a.chunks_per_split;
-        const size_t lds = (size_t)tok_pad * (a.kc * 2 + 16) + (size_t)a.kc * 4;
-        if (rank > 0 && a.k_splits > 1) {             // stage-1 partial sums meet in atomics: start from zero
+        // K slice: a few load batches (256 k each) of every token in LDS next to the keep-bit words,
+        // so that 3-4 workgroups fit a compute unit; slices are evened out over d_in
+        constexpr int kStep = kMfmaK * kMfmaUnroll;
+        // (measured: 768 k for 17-32 tokens, 1024 k for up to 16; larger slices cost occupancy)
+        const int ks_max = tok_pad > 16 ? 3 * kStep : 4 * kStep;
+        a.k_slices = (L.d_in + ks_max - 1) / ks_max;
+        a.ks = (((L.d_in + a.k_slices - 1) / a.k_slices + kStep - 1) / kStep) * kStep;
+        a.k_slices = (L.d_in + a.ks - 1) / a.ks;
+        // row groups: about 2.5 workgroups per compute unit over all slices, whole 64-row units
+        const int units = (L.d_out + 63) / 64 + (rank + 63) / 64;
+        int groups = std::max(1, (5 * cus / 2) / a.k_slices);
+        int upg = std::max(1, (units + groups - 1) / groups);                  // 64-row units per workgroup
+        if (rows_per_wg_hint == 64 || rows_per_wg_hint == 128 || rows_per_wg_hint == 256) upg = rows_per_wg_hint / 64;
+        a.rows_per_wg = upg * 64;
+        a.w_chunks = (L.d_out + a.rows_per_wg - 1) / a.rows_per_wg;
+        a.t_chunks = rank > 0 ? (rank + a.rows_per_wg - 1) / a.rows_per_wg : 0;
+        const size_t lds = (size_t)tok_pad * (a.ks * 2 + 16) + (size_t)a.ks * 4;
+        if (lds > 64 * 1024) return hipErrorInvalidValue;
+        if (rank > 0 && a.k_slices > 1) {             // stage-1 partial sums meet in atomics: start from zero
             hipError_t e = launch_zero(L.t, (size_t)batch * L.rank, stream);
             if (e != hipSuccess) return e;
         }
-        dim3 grid((a.w_chunks + a.t_chunks) * a.k_splits), block(256);
+        dim3 grid((a.w_chunks + a.t_chunks) * a.k_slices), block(256);
         if (L.dtype == F16) hipLaunchKernelGGL(k_mfma_sparse_and_t<F16>, grid, block, lds, stream, a);
         else hipLaunchKernelGGL(k_mfma_sparse_and_t<BF16>, grid, block, lds, stream, a);
         hipError_t e = hipGetLastError();
@@ -371,7 +396,7 @@ hipError_t launch_mfma_linear(const LayerView &L, const void *X, int batch, void
     if (stages != 1) {
         MfmaFinishArgs f{};
         f.L = L; f.Y = Y; f.batch = batch; f.tok_pad = tok_pad; f.use_rank = rank;
-        f.rc = tok_pad > 16 ? 256 : 512;
+        f.rc = kMfmaK * kMfmaUnroll;                  // one load batch per staged chunk
         const size_t lds = 2 * (size_t)tok_pad * (f.rc * 2 + 16);
         dim3 grid((L.d_out + 63) / 64), block(256);
         if (L.dtype == F16) hipLaunchKernelGGL(k_mfma_finish<F16>, grid, block, lds, stream, f);
