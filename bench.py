@@ -418,6 +418,41 @@ def main():
         extras["sparsity_sweep"] = sweep
         extras["us_per_linear_separate_calls"] = round(timed(pass_rsparse_separate, args.steps, args.warmup) * 1000 / 3, 3)
 
+    # ------------------------------------------------------------------ what this card streams at this size
+    if not args.no_extras:
+        # Context for the roofline fraction: a plain device copy and a plain read (sum) over buffers of
+        # one launch's size, rotated over a ring > L2 + Infinity Cache, same timing protocol.  These are
+        # library kernels, not ours; they bound what any kernel can stream at this launch size.
+        n_el = int(bytes_per_launch) // 4
+        srcs = [torch.ones(n_el, dtype=torch.float32, device="cuda") for _ in range(12)]
+        dst = torch.empty(n_el, dtype=torch.float32, device="cuda")
+
+        def time_ring(fn, reps=20):
+            for t_ in srcs:
+                fn(t_)
+            torch.cuda.synchronize()
+            best = 1e30
+            for _ in range(3):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for _ in range(reps):
+                    for t_ in srcs:
+                        fn(t_)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                best = min(best, e0.elapsed_time(e1) * 1e-3 / (reps * len(srcs)))
+            return best
+
+        t_copy = time_ring(lambda t_: dst.copy_(t_))
+        t_read = time_ring(lambda t_: torch.sum(t_))
+        extras["same_size_streaming_reference"] = {
+            "bytes": n_el * 4,
+            "copy_us": round(t_copy * 1e6, 2), "copy_gbs_read_plus_write": round(2 * n_el * 4 / t_copy / 1e9, 1),
+            "read_sum_us": round(t_read * 1e6, 2), "read_sum_gbs": round(n_el * 4 / t_read / 1e9, 1),
+            "note": "torch copy_ / sum over a ring of 12 buffers of one launch's size; per-call time includes the launch"}
+        del srcs, dst
+        torch.cuda.empty_cache()
+
     # ------------------------------------------------------------------ CPU oracle baseline (bounded sample)
     cpu = None
     if not args.no_cpu_baseline:
