@@ -14,7 +14,7 @@ def build(force: bool = True) -> str:
     if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
         return LIB
     cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
-           "-fno-fast-math", "-o", LIB, SRC, "-lm"]
+           "-fno-fast-math", "-ffp-contract=off", "-o", LIB, SRC, "-lm"]
     subprocess.run(cmd, check=True)
     return LIB
 

@@ -236,6 +236,91 @@ double orc_quantile_tau(const void *x, int x_kind, size_t n, double s)
     return tau;
 }
 
+/* ---- gated MLP input (Sec. 3.1: H = X W_up^T (.) sigma(X W_gate^T), sigma = SiLU) --------------
+ *
+ * The down projection's input is h = silu(g) * u, rounded once to the 16-bit storage type, and the
+ * sparsification function then compares |h| with t.  That compare decides an index set, so both
+ * sides must produce the same 16-bit h: the activation is DEFINED as the following fp32 recipe
+ * (every operation a single correctly rounded IEEE fp32 operation, no contraction), which this
+ * function writes out step by step:
+ *
+ *   NaN -> NaN;  g < -87 -> -0
+ *   x = max(-g, -86);  n = rint(x * log2(e));  r = x - n ln2, with ln2 = hi + lo and two fused
+ *   multiply-adds (hi has few enough bits that n * hi is exact)            (|r| <= ln2 / 2)
+ *   p = exp(r) by the degree-7 Taylor polynomial (Horner, fused multiply-adds)
+ *   e = p * 2^n (exponent-field addition);  silu = g / (1 + e);  h = round16(silu * u)
+ *
+ * Pins: silu32 against the fp64 value g / (1 + exp(-g)) to a few ulp; the rounding step against
+ * numpy's fp16 / bf16 conversions.
+ */
+static inline uint32_t f32_bits(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
+static inline float f32_from(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }
+
+float orc_silu32(float g)
+{
+    if (g != g) return g;
+    if (!(g >= -87.0f)) return -0.0f;
+    float x = -g;
+    if (x < -86.0f) x = -86.0f;
+    const float n = rintf(x * 1.44269504f);
+    float r = fmaf(-n, 0.693145752f, x);
+    r = fmaf(-n, 1.42860677e-6f, r);
+    float p = 1.98412698e-4f;
+    p = fmaf(p, r, 1.38888889e-3f);
+    p = fmaf(p, r, 8.33333333e-3f);
+    p = fmaf(p, r, 4.16666667e-2f);
+    p = fmaf(p, r, 1.66666667e-1f);
+    p = fmaf(p, r, 0.5f);
+    p = fmaf(p, r, 1.0f);
+    p = fmaf(p, r, 1.0f);
+    const float e = f32_from(f32_bits(p) + ((uint32_t)(int32_t)n << 23));
+    const float d = 1.0f + e;
+    return g / d;
+}
+
+static uint16_t f32_to_bf16_rne(float f)
+{
+    uint32_t u = f32_bits(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+static uint16_t f32_to_f16_rne(float f)
+{
+    const uint32_t x = f32_bits(f);
+    const uint16_t sign = (uint16_t)((x >> 16) & 0x8000u);
+    const uint32_t a = x & 0x7fffffffu;
+    if (a > 0x7f800000u) return (uint16_t)(sign | 0x7e00u);              /* NaN */
+    if (a >= 0x47800000u) return (uint16_t)(sign | 0x7c00u);             /* >= 65536, inf */
+    if (a < 0x38800000u) {                                               /* below 2^-14: fp16 subnormal or zero */
+        const float m = rintf(fabsf(f) * 16777216.0f);                   /* units of 2^-24, ties to even */
+        return (uint16_t)(sign | (uint16_t)m);                           /* m = 1024 is the smallest normal */
+    }
+    uint32_t h = (((a >> 23) - 112u) << 10) | ((a & 0x7fffffu) >> 13);
+    const uint32_t rem = a & 0x1fffu;
+    if (rem > 0x1000u || (rem == 0x1000u && (h & 1u))) ++h;              /* may carry into the exponent, up to inf */
+    return (uint16_t)(sign | h);
+}
+
+/* out16[i] = round16( silu32(g16[i]) * u16[i] ); kind = ORC_F16 or ORC_BF16. */
+int orc_gated_input(const uint16_t *g16, const uint16_t *u16, int kind, size_t n, uint16_t *out16)
+{
+    if (kind != ORC_F16 && kind != ORC_BF16) return 1;
+    for (size_t i = 0; i < n; ++i) {
+        const float g = (float)(kind == ORC_F16 ? orc_half_to_double(g16[i]) : orc_bf16_to_double(g16[i]));
+        const float u = (float)(kind == ORC_F16 ? orc_half_to_double(u16[i]) : orc_bf16_to_double(u16[i]));
+        const float h = orc_silu32(g) * u;
+        out16[i] = kind == ORC_F16 ? f32_to_f16_rne(h) : f32_to_bf16_rne(h);
+    }
+    return 0;
+}
+
+void orc_silu32_array(const float *g, size_t n, float *out)
+{
+    for (size_t i = 0; i < n; ++i) out[i] = orc_silu32(g[i]);
+}
+
 int orc_max_threads(void)
 {
 #ifdef _OPENMP

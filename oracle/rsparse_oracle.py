@@ -35,6 +35,10 @@ def _load():
         lib.orc_decode16.restype = None
         lib.orc_decode16.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_void_p]
         lib.orc_max_threads.restype = C.c_int
+        lib.orc_gated_input.restype = C.c_int
+        lib.orc_gated_input.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_size_t, C.c_void_p]
+        lib.orc_silu32_array.restype = None
+        lib.orc_silu32_array.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
         _lib = lib
     return _lib
 
@@ -57,6 +61,25 @@ def decode16(bits, dtype) -> np.ndarray:
     bits = _arr(bits, dtype)
     out = np.empty(bits.shape, dtype=np.float64)
     _load().orc_decode16(_ptr(bits), bits.size, dtype, _ptr(out))
+    return out
+
+
+def silu32(g) -> np.ndarray:
+    """The fp32 SiLU recipe that defines the gated input (see the C source)."""
+    g = np.ascontiguousarray(g, dtype=np.float32)
+    out = np.empty_like(g)
+    _load().orc_silu32_array(_ptr(g), g.size, _ptr(out))
+    return out
+
+
+def gated_input(G16, U16, dtype) -> np.ndarray:
+    """h = round16(silu32(g) * u) as uint16 bits (Sec. 3.1, the input of the MLP down projection)."""
+    G16 = _arr(G16, dtype)
+    U16 = _arr(U16, dtype)
+    assert G16.shape == U16.shape
+    out = np.empty(G16.shape, dtype=np.uint16)
+    rc = _load().orc_gated_input(_ptr(G16), _ptr(U16), dtype, G16.size, _ptr(out))
+    assert rc == 0
     return out
 
 

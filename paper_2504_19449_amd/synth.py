@@ -167,6 +167,21 @@ class DownInput:
         return g / (1.0 + np.exp(-g)) * u
 
 
+class GateUpPair:
+    """The two operands of the gated MLP input (Sec. 3.1), as a decoder would hand them over: g (gate
+    branch) and u (up branch), i.i.d. N(0,1), the same draws DownInput multiplies together.  The
+    product itself is the method's business and is not formed here."""
+
+    def __init__(self, d: int, config: int = 0, linear: int = 0):
+        self.d, self.config, self.linear = d, config, linear
+
+    def tokens(self, n: int, stream: int = STREAM_TOKENS, offset: int = 0):
+        rng = _rng(seed_for(self.config, self.linear, stream) + 100_000 * offset)
+        g = rng.standard_normal((n, self.d))
+        u = rng.standard_normal((n, self.d))
+        return g, u
+
+
 def random_layer(d_in: int, d_out: int, rank: int, dtype: int, seed: int) -> Layer:
     """Cheap stand-in for very large shapes where the QR construction is too slow for a test:
     i.i.d. Gaussian W and factors with the same entry scales as make_layer's (W rms

@@ -313,3 +313,46 @@ def test_quantile_tau_is_the_order_statistic(s):
     if 0 < s < 1:
         frac = np.mean(a < tau)
         assert abs(frac - s) < 2e-3
+
+
+# --------------------------------------------------------------------------- gated MLP input (Sec. 3.1)
+
+def test_silu32_recipe_against_fp64():
+    """The fp32 recipe that defines the activation stays within a few ulp of g / (1 + exp(-g))."""
+    g = np.concatenate([np.linspace(-87.0, 87.0, 400001), np.random.default_rng(3).standard_normal(200000) * 3.0,
+                        np.array([0.0, -0.0, 1e-30, -1e-30, 1e-3, 20.0, 60.0, 88.0, 1e30])]).astype(np.float32)
+    got = oracle.silu32(g).astype(np.float64)
+    g64 = g.astype(np.float64)
+    want = g64 / (1.0 + np.exp(-g64))
+    ulp = np.spacing(np.abs(want).astype(np.float32)).astype(np.float64)
+    assert np.max(np.abs(got - want) / ulp) <= 4.0
+    # special values
+    sp = oracle.silu32(np.array([np.nan, np.inf, -np.inf, -88.0, -1e30, 0.0], dtype=np.float32))
+    assert np.isnan(sp[0]) and sp[1] == np.inf
+    assert all(v == 0.0 and np.signbit(v) for v in sp[2:5])
+    assert sp[5] == 0.0
+    # shape of the function: minimum about -0.2785 near g = -1.2785, identity for large g
+    dense = oracle.silu32(np.linspace(-10, 10, 20001).astype(np.float32))
+    assert abs(dense.min() + 0.27846) < 1e-4 and abs(np.linspace(-10, 10, 20001)[dense.argmin()] + 1.2785) < 2e-3
+    assert oracle.silu32(np.array([50.0], dtype=np.float32))[0] == 50.0
+
+
+@pytest.mark.parametrize("dt", [synth.F16, synth.BF16])
+def test_gated_input_is_one_rounding_of_the_fp32_product(dt):
+    """h = round16(silu32(g) * u): the multiply and the single rounding, against numpy's own fp32
+    product and 16-bit conversions (synth.encode16), including fp16 subnormals, overflow and NaN."""
+    rng = np.random.default_rng(11)
+    g = rng.standard_normal(100000) * 2.0
+    u = rng.standard_normal(100000) * np.exp(rng.uniform(-12, 8, 100000))      # wide range: subnormals to overflow
+    g[:4] = [np.nan, 1.0, 3.0, -2.0]
+    u[:4] = [1.0, np.nan, np.inf, 60000.0]
+    G16, U16 = synth.encode16(g, dt), synth.encode16(u, dt)
+    got = oracle.gated_input(G16, U16, dt)
+    gf = synth.decode16(G16, dt).astype(np.float32)
+    uf = synth.decode16(U16, dt).astype(np.float32)
+    with np.errstate(over="ignore", invalid="ignore"):
+        want = synth.encode16(oracle.silu32(gf) * uf, dt)
+    nan = np.isnan(synth.decode16(want, dt))
+    assert np.array_equal(np.isnan(synth.decode16(got, dt)), nan)
+    assert np.array_equal(got[~nan], want[~nan])
+    assert nan[:2].all() and np.isinf(synth.decode16(got[2:3], dt))[0]
