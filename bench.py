@@ -418,6 +418,31 @@ def main():
         extras["sparsity_sweep"] = sweep
         extras["us_per_linear_separate_calls"] = round(timed(pass_rsparse_separate, args.steps, args.warmup) * 1000 / 3, 3)
 
+    # ------------------------------------------------------------------ down projection on the gated MLP input
+    if not args.no_extras:
+        downs = [d for (_, _, d) in blocks]
+        pair = synth.GateUpPair(D_FF, config=1, linear=2)
+        gus = []
+        for i in range(len(downs)):
+            g, u = pair.tokens(1, offset=1 + i)
+            gus.append((torch.from_numpy(synth.encode16(g, dt).view(np.int16)).cuda(),
+                        torch.from_numpy(synth.encode16(u, dt).view(np.int16)).cuda()))
+
+        def pass_gated(sptr):
+            for d, (gd, ud) in zip(downs, gus):
+                rs.rsparse_linear_gated(d[1], gd.data_ptr(), ud.data_ptr(), 1, d[3].data_ptr(), sptr)
+
+        def pass_down_only(sptr):
+            for d in downs:
+                rs.rsparse_linear(d[1], d[2].data_ptr(), 1, d[3].data_ptr(), sptr)
+
+        per = 1000.0 / 1.0      # timed() returns ms per step; here one step = one down projection
+        extras["down_projection_gated_input"] = {
+            "gated_us": round(min(timed(pass_gated, args.steps, args.warmup, eager=e) for e in (False, True)) * per, 3),
+            "plain_input_us": round(min(timed(pass_down_only, args.steps, args.warmup, eager=e) for e in (False, True)) * per, 3),
+            "note": "11008 -> 4096, batch 1: rsparse_linear_gated (x = round(silu(g) * u) by one small launch, then the "
+                    "layer) vs rsparse_linear on a ready input"}
+
     # ------------------------------------------------------------------ what this card streams at this size
     if not args.no_extras:
         # Context for the roofline fraction: a plain device copy and a plain read (sum) over buffers of

@@ -135,6 +135,27 @@ rsparse_status rsparse_prepare_factors(const rsparse_config *cfg, const void *W_
 rsparse_status rsparse_linear(rsparse_layer *layer, const void *X_dev, int32_t batch,
                               void *Y_dev, void *stream);
 
+/*
+ * The same layer applied to the gated MLP input (Sec. 3.1: H = X W_up^T (.) sigma(X W_gate^T) feeds the
+ * down projection; Sec. 3.4 sparsifies that input like any other): x = round(silu(g) * u), rounded
+ * once to the layer's 16-bit type and written to the handle's scratch by one small launch ahead of
+ * the layer's own.  G_dev, Up_dev: device, [batch][d_in] 16-bit of cfg.dtype, 16-byte aligned (the
+ * outputs of the gate and up projections).  silu is evaluated by a fixed fp32 recipe (range
+ * reduction x = -g = n ln2 + r, degree-7 polynomial for exp(r), one division) so that the 16-bit x,
+ * and with it the kept-channel sets, are reproducible bit for bit; it is within 2.2 ulp of
+ * g / (1 + exp(-g)).  Everything else as rsparse_linear (rsparse_last_active reports the kept
+ * channels of x).
+ */
+rsparse_status rsparse_linear_gated(rsparse_layer *layer, const void *G_dev, const void *Up_dev,
+                                    int32_t batch, void *Y_dev, void *stream);
+
+/*
+ * The gated input on its own: out[i] = round(silu(G[i]) * Up[i]) for n values (n a multiple of 8), all
+ * three device buffers of 16-bit `dtype`, 16-byte aligned; the recipe of rsparse_linear_gated (Sec. 3.1).  Asynchronous on `stream`.
+ */
+rsparse_status rsparse_gated_input(const void *G_dev, const void *Up_dev, void *out_dev, size_t n,
+                                   int32_t dtype, void *stream);
+
 /* The full layer Y = X W^T (Sec. 3.1) with the hand-written dense GEMV; same argument rules. */
 rsparse_status rsparse_dense_ref(rsparse_layer *layer, const void *X_dev, int32_t batch,
                                  void *Y_dev, void *stream);

@@ -13,7 +13,7 @@ _STATUS = {1: "EINVAL", 2: "ENOMEM", 3: "EHIP", 4: "EBATCH", 5: "EALIGN", 6: "ES
 
 EXPORTED_SYMBOLS = [
     "rsparse_prepare", "rsparse_compute_factors", "rsparse_prepare_factors", "rsparse_linear",
-    "rsparse_dense_ref", "rsparse_linear_group", "rsparse_dense_ref_group", "rsparse_last_active", "rsparse_synchronize",
+    "rsparse_linear_gated", "rsparse_gated_input", "rsparse_dense_ref", "rsparse_linear_group", "rsparse_dense_ref_group", "rsparse_last_active", "rsparse_synchronize",
     "rsparse_get_factors", "rsparse_set_tau", "rsparse_set_tuning",
     "rsparse_get_config", "rsparse_calibrate_tau", "rsparse_required_bytes", "rsparse_dense_bytes",
     "rsparse_recipe", "rsparse_destroy", "rsparse_last_error",
@@ -69,6 +69,8 @@ def load_library():
     lib.rsparse_prepare_factors.argtypes = [C.POINTER(Config), vp, vp, vp, C.POINTER(vp)]
     lib.rsparse_linear.argtypes = [vp, vp, i32, vp, vp]
     lib.rsparse_dense_ref.argtypes = [vp, vp, i32, vp, vp]
+    lib.rsparse_linear_gated.argtypes = [vp, vp, vp, i32, vp, vp]
+    lib.rsparse_gated_input.argtypes = [vp, vp, vp, C.c_size_t, i32, vp]
     lib.rsparse_linear_group.argtypes = [vp, i32, vp, i32, vp, vp]
     lib.rsparse_dense_ref_group.argtypes = [vp, i32, vp, i32, vp, vp]
     lib.rsparse_last_active.argtypes = [vp, i32, vp, C.POINTER(i32)]
@@ -91,7 +93,7 @@ def load_library():
     for name in ("rsparse_linear_group", "rsparse_dense_ref_group", "rsparse_prepare", "rsparse_compute_factors",
                  "rsparse_prepare_factors", "rsparse_linear", "rsparse_dense_ref",
                  "rsparse_last_active", "rsparse_get_factors", "rsparse_set_tau", "rsparse_set_tuning",
-                 "rsparse_get_config", "rsparse_calibrate_tau", "rsparse_synchronize"):
+                 "rsparse_get_config", "rsparse_calibrate_tau", "rsparse_synchronize", "rsparse_linear_gated", "rsparse_gated_input"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -177,6 +179,15 @@ def rsparse_prepare_factors(cfg: Config, W16, U16, SV16) -> Layer:
 def rsparse_linear(layer: Layer, X_dev: int, batch: int, Y_dev: int, stream: int = 0):
     """X_dev / Y_dev / stream are raw device pointers / a hipStream_t as integers."""
     _check(load_library().rsparse_linear(layer.handle, X_dev, batch, Y_dev, stream))
+
+
+def rsparse_linear_gated(layer: Layer, G_dev: int, Up_dev: int, batch: int, Y_dev: int, stream: int = 0):
+    """The layer on x = round(silu(g) * u); G_dev / Up_dev are the gate and up branches [batch][d_in]."""
+    _check(load_library().rsparse_linear_gated(layer.handle, G_dev, Up_dev, batch, Y_dev, stream))
+
+
+def rsparse_gated_input(G_dev: int, Up_dev: int, out_dev: int, n: int, dtype: int, stream: int = 0):
+    _check(load_library().rsparse_gated_input(G_dev, Up_dev, out_dev, n, dtype, stream))
 
 
 def rsparse_dense_ref(layer: Layer, X_dev: int, batch: int, Y_dev: int, stream: int = 0):

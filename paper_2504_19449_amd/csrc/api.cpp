@@ -130,6 +130,7 @@ struct rsparse_layer {
     int32_t *act_list = nullptr, *act_count = nullptr;
     int *sync = nullptr;
     uint32_t *t_pub = nullptr;
+    uint16_t *xg = nullptr;                // [max_batch][d_in] gated input x = round16(silu(g) * u), written out per call
     size_t n_t = 0, n_y = 0;
     bool last_fused = false;
     int tiles = 0, nz_max = 1;
@@ -244,7 +245,7 @@ void free_layer(rsparse_layer *L)
     if (!L) return;
     (void)hipFree(L->M); (void)hipFree(L->SVt); (void)hipFree(L->U); (void)hipFree(L->Wrow); (void)hipFree(L->t);
     (void)hipFree(L->yacc); (void)hipFree(L->act_bits); (void)hipFree(L->chan_bits);
-    (void)hipFree(L->act_list); (void)hipFree(L->act_count); (void)hipFree(L->sync); (void)hipFree(L->t_pub);
+    (void)hipFree(L->act_list); (void)hipFree(L->act_count); (void)hipFree(L->sync); (void)hipFree(L->t_pub); (void)hipFree(L->xg);
     delete L;
 }
 
@@ -287,6 +288,7 @@ rsparse_status build_layer(const rsparse_config *cfg, const uint16_t *W, const u
             RS_HIP(hipMalloc((void **)&L->Wrow, d_in * d_out * 2));
             RS_HIP(hipMemcpy(L->Wrow, W, d_in * d_out * 2, hipMemcpyHostToDevice));
         }
+        RS_HIP(hipMalloc((void **)&L->xg, (size_t)cfg->max_batch * d_in * 2));
         const size_t bpad = (size_t)L->nz_max * kMaxBT;
         const size_t n_t = std::max<size_t>(1, r * bpad);
         // the matrix-core kernels keep these accumulators as [d_out][16 or 32 tokens]
@@ -410,8 +412,40 @@ rsparse_status check_group(rsparse_layer *const *layers, int32_t n, const void *
 
 }  // namespace
 
+namespace {
+rsparse_status linear_group_impl(rsparse_layer *const *layers, int32_t n_layers, const void *X_dev, const void *G_dev,
+                                 int32_t batch, void *const *Y_devs, void *stream);
+}
+
 rsparse_status rsparse_linear_group(rsparse_layer *const *layers, int32_t n_layers, const void *X_dev, int32_t batch,
                                     void *const *Y_devs, void *stream)
+{
+    return linear_group_impl(layers, n_layers, X_dev, nullptr, batch, Y_devs, stream);
+}
+
+rsparse_status rsparse_gated_input(const void *G_dev, const void *Up_dev, void *out_dev, size_t n, int32_t dtype,
+                                   void *stream)
+{
+    if (!G_dev || !Up_dev || !out_dev) return fail(RSPARSE_EINVAL, "NULL device pointer");
+    if (dtype != RSPARSE_F16 && dtype != RSPARSE_BF16) return fail(RSPARSE_EINVAL, "dtype must be F16 or BF16");
+    if (n == 0 || (n % 8) != 0) return fail(RSPARSE_EINVAL, "n must be a positive multiple of 8");
+    if (((uintptr_t)G_dev | (uintptr_t)Up_dev | (uintptr_t)out_dev) & 15u)
+        return fail(RSPARSE_EALIGN, "buffers must be 16-byte aligned");
+    RS_HIP(launch_gated_input(G_dev, Up_dev, out_dev, n, dtype, (hipStream_t)stream));
+    return RSPARSE_OK;
+}
+
+rsparse_status rsparse_linear_gated(rsparse_layer *L, const void *G_dev, const void *Up_dev, int32_t batch, void *Y_dev,
+                                    void *stream)
+{
+    if (!G_dev) return fail(RSPARSE_EINVAL, "G_dev is NULL");
+    if ((uintptr_t)G_dev & 15u) return fail(RSPARSE_EALIGN, "G_dev must be 16-byte aligned");
+    return linear_group_impl(&L, 1, Up_dev, G_dev, batch, &Y_dev, stream);
+}
+
+namespace {
+rsparse_status linear_group_impl(rsparse_layer *const *layers, int32_t n_layers, const void *X_dev, const void *G_dev,
+                                 int32_t batch, void *const *Y_devs, void *stream)
 {
     rsparse_status st = check_group(layers, n_layers, X_dev, batch, Y_devs);
     if (st != RSPARSE_OK) return st;
@@ -427,6 +461,11 @@ rsparse_status rsparse_linear_group(rsparse_layer *const *layers, int32_t n_laye
     }
     bool mfma = batch >= (layers[0]->tuning.mfma_min_batch > 0 ? layers[0]->tuning.mfma_min_batch : kMfmaDefaultMinBatch);
     for (int i = 0; i < n_layers; ++i) mfma = mfma && mfma_path_supported(v[i], batch);
+    // a gated input is written out once first (one small launch), then the layer runs on it
+    if (G_dev) {
+        RS_HIP(launch_gated_input(G_dev, X_dev, layers[0]->xg, (size_t)batch * layers[0]->cfg.d_in, layers[0]->cfg.dtype, s));
+        X_dev = layers[0]->xg;
+    }
     if (mfma) {
         // matrix-core path, one layer at a time (each is already a full-chip launch)
         for (int i = 0; i < n_layers; ++i)
@@ -445,6 +484,7 @@ rsparse_status rsparse_linear_group(rsparse_layer *const *layers, int32_t n_laye
     }
     return RSPARSE_OK;
 }
+}  // namespace
 
 rsparse_status rsparse_linear(rsparse_layer *L, const void *X_dev, int32_t batch, void *Y_dev, void *stream)
 {

@@ -54,6 +54,64 @@ __device__ __forceinline__ void store_out(void *Y, size_t i, float v, int out_dt
     else ((uint16_t *)Y)[i] = to_bf16(v);
 }
 
+// SiLU of the gated MLP input (Sec. 3.1), as a fixed fp32 recipe so that the 16-bit product and with it
+// the kept-channel sets do not depend on a math library: x = max(-g, -86), n = rint(x log2 e),
+// r = x - n ln2 (two-constant reduction, fused multiply-adds), exp(r) by its degree-7 Taylor
+// polynomial, e = exp(r) 2^n by exponent addition, silu = g / (1 + e).  Every step is one correctly
+// rounded fp32 operation; contraction is off so that no step is merged with its neighbour.
+__device__ __forceinline__ float silu32(float g)
+{
+#pragma clang fp contract(off)
+    if (g != g) return g;
+    if (!(g >= -87.0f)) return -0.0f;
+    float x = -g;
+    if (x < -86.0f) x = -86.0f;
+    const float n = __builtin_rintf(x * 1.44269504f);
+    float r = __builtin_fmaf(-n, 0.693145752f, x);
+    r = __builtin_fmaf(-n, 1.42860677e-6f, r);
+    float p = 1.98412698e-4f;
+    p = __builtin_fmaf(p, r, 1.38888889e-3f);
+    p = __builtin_fmaf(p, r, 8.33333333e-3f);
+    p = __builtin_fmaf(p, r, 4.16666667e-2f);
+    p = __builtin_fmaf(p, r, 1.66666667e-1f);
+    p = __builtin_fmaf(p, r, 0.5f);
+    p = __builtin_fmaf(p, r, 1.0f);
+    p = __builtin_fmaf(p, r, 1.0f);
+    const float e = as_f(as_u(p) + ((uint32_t)(int32_t)n << 23));
+    const float d = 1.0f + e;
+    return __fdiv_rn(g, d);
+}
+
+// One element of the gated input: round16(silu(g) * u), 16-bit patterns in and out.
+template <int DT>
+__device__ __forceinline__ uint16_t gated1(uint16_t g, uint16_t u)
+{
+    const float gf = DT == F16 ? (float)__builtin_bit_cast(_Float16, g) : as_f((uint32_t)g << 16);
+    const float uf = DT == F16 ? (float)__builtin_bit_cast(_Float16, u) : as_f((uint32_t)u << 16);
+    float h = silu32(gf) * uf;
+    // The product is rounded to fp32 first and to 16 bits second, on purpose: without this barrier the
+    // compiler merges the multiply and the fp16 conversion into one mixed-precision instruction with a
+    // single rounding (and loses the sign of a zero product).
+    __asm__ volatile("" : "+v"(h));
+    return DT == F16 ? to_f16(h) : to_bf16(h);
+}
+
+// Eight consecutive input values: X[off..off+8), or, with a gate operand, round16(silu(G) * X).
+template <int DT>
+__device__ __forceinline__ u32x4 load_x8(const uint16_t *X, const uint16_t *G, size_t off)
+{
+    const u32x4 xu = *reinterpret_cast<const u32x4 *>(X + off);
+    if (!G) return xu;
+    const u32x4 xg = *reinterpret_cast<const u32x4 *>(G + off);
+    u32x4 o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t gw = xg[i], uw = xu[i];
+        o[i] = (uint32_t)gated1<DT>((uint16_t)gw, (uint16_t)uw) |
+               ((uint32_t)gated1<DT>((uint16_t)(gw >> 16), (uint16_t)(uw >> 16)) << 16);
+    }
+    return o;
+}
 // Keep-predicate of the sparsification function: |x| >= t (mode 0) or |x| > t (mode 1).
 // NaN compares false and is never kept.
 __device__ __forceinline__ bool keep(float x, float tau, int mode)

@@ -77,6 +77,8 @@ hipError_t launch_dense_rowdot(const LayerView *L, const Launch *cfg, int n, con
 bool mfma_path_supported(const LayerView &L, int batch);
 hipError_t launch_mfma_linear(const LayerView &L, const void *X, int batch, void *Y, uint32_t *chan_bits, int cus,
                               int stages, bool dense, int rows_per_wg_hint, hipStream_t stream);
+// out[0:n) = round16(silu(G) * Up), n a multiple of 8, all 16-byte aligned.
+hipError_t launch_gated_input(const void *G, const void *Up, void *out, size_t n, int dtype, hipStream_t stream);
 // Zero `n` 32-bit words (a fill kernel, safe to record into a HIP graph).
 hipError_t launch_zero(void *p, size_t n_words, hipStream_t stream);
 

@@ -260,6 +260,9 @@ __global__ __launch_bounds__(256) void k_mfma_finish(const MfmaFinishArgs a)
     // One chunk = one batch of kMfmaUnroll weight loads per lane (a.rc = 32 * kMfmaUnroll).  The loads of
     // a chunk do not depend on the staged t: they are issued before the staging of that chunk, so their
     // latency and the staging overlap.
+    // The lo half is stored scaled by a power of two (exact): in fp16 the remainder t - hi would
+    // otherwise fall into the subnormals for |t| below ~0.1 and lose the bits it is there to keep.
+    constexpr float kLoScale = DT == F16 ? 2048.0f : 1.0f;
     const int kg = (lane >> 4) * 8;
     const size_t lane_off = (size_t)(lane & 15) * pitch + kg * 2;
     const bool two = a.tok_pad > 16;
@@ -288,7 +291,7 @@ __global__ __launch_bounds__(256) void k_mfma_finish(const MfmaFinishArgs a)
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         hi[e] = narrow<DT>(v[e]);
-                        lo[e] = narrow<DT>(v[e] - widen<DT>(hi[e]));
+                        lo[e] = narrow<DT>((v[e] - widen<DT>(hi[e])) * kLoScale);
                     }
                     uint2 ph, pl;
                     ph.x = (uint32_t)hi[0] | ((uint32_t)hi[1] << 16); ph.y = (uint32_t)hi[2] | ((uint32_t)hi[3] << 16);
@@ -299,9 +302,10 @@ __global__ __launch_bounds__(256) void k_mfma_finish(const MfmaFinishArgs a)
             }
         }
     };
+    f32x4 lo0 = {0.f, 0.f, 0.f, 0.f}, lo1 = {0.f, 0.f, 0.f, 0.f};      // the lo halves' products, scaled by kLoScale
     auto both_halves = [&](const u32x4 (&v)[kMfmaUnroll]) {
         mfma_a_batch<DT>(v, 0, s_hi + lane_off, s_hi + lane_off + (size_t)16 * pitch, two, acc0, acc1);
-        mfma_a_batch<DT>(v, 0, s_lo + lane_off, s_lo + lane_off + (size_t)16 * pitch, two, acc0, acc1);
+        mfma_a_batch<DT>(v, 0, s_lo + lane_off, s_lo + lane_off + (size_t)16 * pitch, two, lo0, lo1);
     };
     u32x4 va[kMfmaUnroll], vb[kMfmaUnroll];
     if (r > 0) load_a_batch(urow, row_ok, min(a.rc, r), 0, kg, va);
@@ -317,6 +321,11 @@ __global__ __launch_bounds__(256) void k_mfma_finish(const MfmaFinishArgs a)
         stage_t(c0 + a.rc, min(a.rc, r - c0 - a.rc));
         __syncthreads();
         both_halves(vb);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        acc0[j] += lo0[j] * (1.0f / kLoScale);
+        acc1[j] += lo1[j] * (1.0f / kLoScale);
     }
     // lane l holds rows row0 + 4*(l/16) + 0..3 of token l%16 (and l%16 + 16): 4 consecutive outputs
     const int orow = row0 + 4 * (lane >> 4);

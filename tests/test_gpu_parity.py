@@ -182,6 +182,86 @@ def test_one_and_two_launch_forms_on_a_reused_handle(ragged, launches, B):
     layer.destroy()
 
 
+@pytest.mark.parametrize("dt", [synth.F16, synth.BF16])
+def test_gated_input_bits_equal_the_oracle_for_every_gate_value(dt):
+    """rsparse_gated_input against the oracle's own copy of the recipe, bit for bit: all 65 536 gate
+    patterns (NaNs compared as NaN) times up-values that reach subnormals, overflow, zero, Inf."""
+    import oracle
+    torch = gu.torch_mod()
+    ups = synth.encode16(np.array([1.0, -0.37, 3.1, 1e-4, 250.0, 7e-3, 0.11, -33.0, 0.0, -0.0, 6e4, -2e-7,
+                                   np.inf, 1.0009765625, -7.5, 2e-3]), dt)
+    G = np.repeat(np.arange(65536, dtype=np.uint16), len(ups))
+    U = np.tile(ups, 65536)
+    want = oracle.gated_input(G, U, dt)
+    Gd, Ud = gu.to_dev16(G), gu.to_dev16(U)
+    out = torch.zeros_like(Gd)
+    rs.rsparse_gated_input(Gd.data_ptr(), Ud.data_ptr(), out.data_ptr(), G.size, dt, gu.stream_ptr())
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().view(np.uint16)
+    both_nan = np.isnan(synth.decode16(got, dt)) & np.isnan(synth.decode16(want, dt))
+    assert np.array_equal(got[~both_nan], want[~both_nan])
+    assert both_nan.sum() >= 2 * 1000
+
+
+@pytest.mark.parametrize("dt", [synth.F16, synth.BF16])
+@pytest.mark.parametrize("B", [1, 3, 4, 8, 12, 32])
+def test_gated_mlp_input(ragged, dt, B):
+    """rsparse_linear_gated: x = round16(silu(g) * u) formed on the device (Sec. 3.1).  The oracle
+    forms x by its own copy of the fp32 recipe; kept-channel lists must be equal, outputs within the
+    usual bounds.  1-4 tokens: vector path (both launch forms); 8-32: matrix-core path and, with
+    the row-major copy left out, the vector path in tiles of 8.  Values span fp16 subnormals to
+    overflow, NaN and Inf included."""
+    import oracle
+    L = ragged[dt]
+    pair = synth.GateUpPair(L.d_in, config=86, linear=B)
+    g, u = pair.tokens(B)
+    u *= np.exp(np.random.default_rng(B).uniform(-3, 3, size=u.shape))
+    g[0, 1:3] = [40.0, -95.0]
+    u[0, 4:6] = [1e-7, -3e4]
+    if B > 1:                      # a NaN or Inf input turns every output of its token into NaN: keep token 0 finite at B = 1
+        g[1, 0] = np.nan
+        u[1, 3] = np.inf
+    G16, U16 = synth.encode16(g, dt), synth.encode16(u, dt)
+    X16 = oracle.gated_input(G16, U16, dt)
+    tau = oracle.quantile_tau(oracle.gated_input(*[synth.encode16(a, dt) for a in pair.tokens(64, stream=synth.STREAM_CALIB)], dt), dt, 0.5)
+    want = gu.oracle_linear(L, X16, tau)
+    for rowmajor in (1, 0):
+        layer = gu.prepare(L, tau, max_batch=B, out_dtype=rs.F32, dense_rowmajor=rowmajor)
+        for launches in (1, 2):
+            rs.rsparse_set_tuning(layer, launches=launches)
+            Gd, Ud = gu.to_dev16(G16), gu.to_dev16(U16)
+            Y = gu._alloc_out(layer, B)
+            rs.rsparse_linear_gated(layer, Gd.data_ptr(), Ud.data_ptr(), B, Y.data_ptr(), gu.stream_ptr())
+            got = {"Y": gu._read_out(layer, Y), "act": [rs.rsparse_last_active(layer, b) for b in range(B)],
+                   "union": rs.rsparse_last_active(layer, -1)}
+            gu.check_lists(got, want)
+            gu.check_outputs(got["Y"], want["Y"], rs.F32)
+        layer.destroy()
+
+
+def test_gated_matches_ungated_on_the_materialised_input(ragged):
+    """The gated entry equals rsparse_linear on x written out by the oracle's recipe: same lists, and
+    outputs equal up to the order of the atomic adds."""
+    import oracle
+    L = ragged[synth.BF16]
+    g, u = synth.GateUpPair(L.d_in, config=86, linear=99).tokens(2)
+    G16, U16 = synth.encode16(g, L.dtype), synth.encode16(u, L.dtype)
+    X16 = oracle.gated_input(G16, U16, L.dtype)
+    tau = oracle.quantile_tau(X16, L.dtype, 0.5)
+    layer = gu.prepare(L, tau, max_batch=2, out_dtype=rs.F32)
+    plain = gu.run_linear(layer, X16)
+    Gd, Ud = gu.to_dev16(G16), gu.to_dev16(U16)
+    Y = gu._alloc_out(layer, 2)
+    rs.rsparse_linear_gated(layer, Gd.data_ptr(), Ud.data_ptr(), 2, Y.data_ptr(), gu.stream_ptr())
+    fused = gu._read_out(layer, Y)
+    for b in range(2):
+        assert np.array_equal(rs.rsparse_last_active(layer, b), plain["act"][b])
+    assert np.linalg.norm(fused - plain["Y"]) <= 1e-5 * np.linalg.norm(plain["Y"])
+    with pytest.raises(rs.RSparseError):
+        rs.rsparse_linear_gated(layer, 0, Ud.data_ptr(), 2, Y.data_ptr(), gu.stream_ptr())
+    layer.destroy()
+
+
 def test_bounded_wait_runs_out_and_the_handle_recovers(ragged):
     """Error path of the one-launch kernel, forced from the host: stage 1 publishes nothing and the
     wait bound is a few polls, so every kernel still ends normally; the call is reported invalid by
