@@ -436,6 +436,29 @@ def main():
             for d in downs:
                 rs.rsparse_linear(d[1], d[2].data_ptr(), 1, d[3].data_ptr(), sptr)
 
+        hbuf = torch.zeros((1, D_FF), dtype=torch.int16, device="cuda")
+
+        def pass_gate_up_fused(sptr):
+            for (g_, u_, _) in blocks:
+                rs.rsparse_mlp_gate_up(g_[1], u_[1], g_[2].data_ptr(), 1, hbuf.data_ptr(), sptr)
+
+        def pass_gate_up_then_act(sptr):
+            for (g_, u_, _) in blocks:
+                rs.rsparse_linear_group([g_[1], u_[1]], g_[2].data_ptr(), 1, [g_[3].data_ptr(), u_[3].data_ptr()], sptr)
+                rs.rsparse_gated_input(g_[3].data_ptr(), u_[3].data_ptr(), hbuf.data_ptr(), D_FF, dt, sptr)
+
+        def pass_gate_up_only(sptr):
+            for (g_, u_, _) in blocks:
+                rs.rsparse_linear_group([g_[1], u_[1]], g_[2].data_ptr(), 1, [g_[3].data_ptr(), u_[3].data_ptr()], sptr)
+
+        def best_us(fn):
+            return round(min(timed(fn, args.steps, args.warmup, eager=e) for e in (False, True)) * 1000.0, 3)
+
+        extras["gate_up_with_activation"] = {
+            "one_launch_us": best_us(pass_gate_up_fused), "group_then_activation_kernel_us": best_us(pass_gate_up_then_act),
+            "group_only_us": best_us(pass_gate_up_only),
+            "note": "gate + up (2 x 4096 -> 11008), batch 1: rsparse_mlp_gate_up (H = silu(g) * u stored by the kernel's "
+                    "finish) vs rsparse_linear_group + rsparse_gated_input vs the two projections alone"}
         per = 1000.0 / 1.0      # timed() returns ms per step; here one step = one down projection
         extras["down_projection_gated_input"] = {
             "gated_us": round(min(timed(pass_gated, args.steps, args.warmup, eager=e) for e in (False, True)) * per, 3),

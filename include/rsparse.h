@@ -150,6 +150,19 @@ rsparse_status rsparse_linear_gated(rsparse_layer *layer, const void *G_dev, con
                                     int32_t batch, void *Y_dev, void *stream);
 
 /*
+ * The first half of the MLP (Sec. 3.1: H = X W_up^T (.) silu(X W_gate^T)) with R-Sparse on both
+ * projections (Sec. 3.4): H_dev [batch][d_out] receives round(silu(g) * u), where g and u are the two
+ * layers' outputs, each rounded once to the 16-bit type first -- i.e. what rsparse_linear on `gate` and on
+ * `up` followed by rsparse_gated_input would store, without storing g and u.  gate, up: distinct
+ * handles with equal d_in, d_out and dtype, out_dtype == dtype; X_dev, H_dev as in rsparse_linear.
+ * Up to 8 tokens on the vector path this is ONE launch (the last workgroup of each column tile applies
+ * the activation); other cases run the two layers into the handles' scratch and then one elementwise
+ * launch.  rsparse_last_active works on either handle afterwards.
+ */
+rsparse_status rsparse_mlp_gate_up(rsparse_layer *gate, rsparse_layer *up, const void *X_dev,
+                                   int32_t batch, void *H_dev, void *stream);
+
+/*
  * The gated input on its own: out[i] = round(silu(G[i]) * Up[i]) for n values (n a multiple of 8), all
  * three device buffers of 16-bit `dtype`, 16-byte aligned; the recipe of rsparse_linear_gated (Sec. 3.1).  Asynchronous on `stream`.
  */

@@ -13,7 +13,7 @@ _STATUS = {1: "EINVAL", 2: "ENOMEM", 3: "EHIP", 4: "EBATCH", 5: "EALIGN", 6: "ES
 
 EXPORTED_SYMBOLS = [
     "rsparse_prepare", "rsparse_compute_factors", "rsparse_prepare_factors", "rsparse_linear",
-    "rsparse_linear_gated", "rsparse_gated_input", "rsparse_dense_ref", "rsparse_linear_group", "rsparse_dense_ref_group", "rsparse_last_active", "rsparse_synchronize",
+    "rsparse_linear_gated", "rsparse_gated_input", "rsparse_mlp_gate_up", "rsparse_dense_ref", "rsparse_linear_group", "rsparse_dense_ref_group", "rsparse_last_active", "rsparse_synchronize",
     "rsparse_get_factors", "rsparse_set_tau", "rsparse_set_tuning",
     "rsparse_get_config", "rsparse_calibrate_tau", "rsparse_required_bytes", "rsparse_dense_bytes",
     "rsparse_recipe", "rsparse_destroy", "rsparse_last_error",
@@ -71,6 +71,7 @@ def load_library():
     lib.rsparse_dense_ref.argtypes = [vp, vp, i32, vp, vp]
     lib.rsparse_linear_gated.argtypes = [vp, vp, vp, i32, vp, vp]
     lib.rsparse_gated_input.argtypes = [vp, vp, vp, C.c_size_t, i32, vp]
+    lib.rsparse_mlp_gate_up.argtypes = [vp, vp, vp, i32, vp, vp]
     lib.rsparse_linear_group.argtypes = [vp, i32, vp, i32, vp, vp]
     lib.rsparse_dense_ref_group.argtypes = [vp, i32, vp, i32, vp, vp]
     lib.rsparse_last_active.argtypes = [vp, i32, vp, C.POINTER(i32)]
@@ -93,7 +94,7 @@ def load_library():
     for name in ("rsparse_linear_group", "rsparse_dense_ref_group", "rsparse_prepare", "rsparse_compute_factors",
                  "rsparse_prepare_factors", "rsparse_linear", "rsparse_dense_ref",
                  "rsparse_last_active", "rsparse_get_factors", "rsparse_set_tau", "rsparse_set_tuning",
-                 "rsparse_get_config", "rsparse_calibrate_tau", "rsparse_synchronize", "rsparse_linear_gated", "rsparse_gated_input"):
+                 "rsparse_get_config", "rsparse_calibrate_tau", "rsparse_synchronize", "rsparse_linear_gated", "rsparse_gated_input", "rsparse_mlp_gate_up"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -184,6 +185,11 @@ def rsparse_linear(layer: Layer, X_dev: int, batch: int, Y_dev: int, stream: int
 def rsparse_linear_gated(layer: Layer, G_dev: int, Up_dev: int, batch: int, Y_dev: int, stream: int = 0):
     """The layer on x = round(silu(g) * u); G_dev / Up_dev are the gate and up branches [batch][d_in]."""
     _check(load_library().rsparse_linear_gated(layer.handle, G_dev, Up_dev, batch, Y_dev, stream))
+
+
+def rsparse_mlp_gate_up(gate: Layer, up: Layer, X_dev: int, batch: int, H_dev: int, stream: int = 0):
+    """H = round(silu(g) * u) with g, u the R-Sparse outputs of `gate` and `up` on X (Sec. 3.1)."""
+    _check(load_library().rsparse_mlp_gate_up(gate.handle, up.handle, X_dev, batch, H_dev, stream))
 
 
 def rsparse_gated_input(G_dev: int, Up_dev: int, out_dev: int, n: int, dtype: int, stream: int = 0):

@@ -130,6 +130,7 @@ struct rsparse_layer {
     int32_t *act_list = nullptr, *act_count = nullptr;
     int *sync = nullptr;
     uint32_t *t_pub = nullptr;
+    uint16_t *hy = nullptr;                // [max_batch][d_out] 16-bit output scratch (gate / up results of rsparse_mlp_gate_up's fallback)
     uint16_t *xg = nullptr;                // [max_batch][d_in] gated input x = round16(silu(g) * u), written out per call
     size_t n_t = 0, n_y = 0;
     bool last_fused = false;
@@ -245,7 +246,7 @@ void free_layer(rsparse_layer *L)
     if (!L) return;
     (void)hipFree(L->M); (void)hipFree(L->SVt); (void)hipFree(L->U); (void)hipFree(L->Wrow); (void)hipFree(L->t);
     (void)hipFree(L->yacc); (void)hipFree(L->act_bits); (void)hipFree(L->chan_bits);
-    (void)hipFree(L->act_list); (void)hipFree(L->act_count); (void)hipFree(L->sync); (void)hipFree(L->t_pub); (void)hipFree(L->xg);
+    (void)hipFree(L->act_list); (void)hipFree(L->act_count); (void)hipFree(L->sync); (void)hipFree(L->t_pub); (void)hipFree(L->xg); (void)hipFree(L->hy);
     delete L;
 }
 
@@ -289,6 +290,7 @@ rsparse_status build_layer(const rsparse_config *cfg, const uint16_t *W, const u
             RS_HIP(hipMemcpy(L->Wrow, W, d_in * d_out * 2, hipMemcpyHostToDevice));
         }
         RS_HIP(hipMalloc((void **)&L->xg, (size_t)cfg->max_batch * d_in * 2));
+        RS_HIP(hipMalloc((void **)&L->hy, (size_t)cfg->max_batch * d_out * 2));
         const size_t bpad = (size_t)L->nz_max * kMaxBT;
         const size_t n_t = std::max<size_t>(1, r * bpad);
         // the matrix-core kernels keep these accumulators as [d_out][16 or 32 tokens]
@@ -485,6 +487,46 @@ rsparse_status linear_group_impl(rsparse_layer *const *layers, int32_t n_layers,
     return RSPARSE_OK;
 }
 }  // namespace
+
+rsparse_status rsparse_mlp_gate_up(rsparse_layer *gate, rsparse_layer *up, const void *X_dev, int32_t batch,
+                                   void *H_dev, void *stream)
+{
+    rsparse_layer *pair[2] = {gate, up};
+    void *outs[2] = {H_dev, H_dev};
+    rsparse_status st = check_group(pair, 2, X_dev, batch, outs);
+    if (st != RSPARSE_OK) return st;
+    if (gate->cfg.d_out != up->cfg.d_out) return fail(RSPARSE_EINVAL, "gate and up must have the same d_out");
+    if (gate->cfg.out_dtype != gate->cfg.dtype || up->cfg.out_dtype != up->cfg.dtype)
+        return fail(RSPARSE_EINVAL, "rsparse_mlp_gate_up needs out_dtype == dtype on both layers");
+    hipStream_t s = (hipStream_t)stream;
+    const int stages = gate->tuning.stages;
+    const bool fused = gate->tuning.launches != 2 && stages == 0;
+    LayerView v[2];
+    Launch lc[2];
+    for (int i = 0; i < 2; ++i) {
+        v[i] = pair[i]->view();
+        lc[i] = resolve_launch(pair[i], batch, false, 2, i ? lc[0].waves : 0, fused);
+    }
+    bool mfma = batch >= (gate->tuning.mfma_min_batch > 0 ? gate->tuning.mfma_min_batch : kMfmaDefaultMinBatch);
+    for (int i = 0; i < 2; ++i) mfma = mfma && mfma_path_supported(v[i], batch);
+    const int bt = batch_tile_of(batch);
+    const bool one_tile = (batch + bt - 1) / bt == 1;
+    if (fused && !mfma && one_tile && lc[0].tile_map != 2 && lc[1].tile_map != 2) {
+        // both projections and the activation in one launch: the last workgroup of a column tile
+        // rounds g and u, applies silu(g) * u and stores H
+        RS_HIP(launch_fused(v, lc, 2, X_dev, batch, outs, s, true));
+        for (int i = 0; i < 2; ++i) {
+            pair[i]->last_stream = s; pair[i]->last_batch = batch; pair[i]->last_mfma = false; pair[i]->last_fused = true;
+        }
+        return RSPARSE_OK;
+    }
+    // otherwise: the two layers into scratch, then the elementwise recipe
+    void *tmp[2] = {gate->hy, up->hy};
+    st = rsparse_linear_group(pair, 2, X_dev, batch, tmp, stream);
+    if (st != RSPARSE_OK) return st;
+    RS_HIP(launch_gated_input(gate->hy, up->hy, H_dev, (size_t)batch * gate->cfg.d_out, gate->cfg.dtype, s));
+    return RSPARSE_OK;
+}
 
 rsparse_status rsparse_linear(rsparse_layer *L, const void *X_dev, int32_t batch, void *Y_dev, void *stream)
 {

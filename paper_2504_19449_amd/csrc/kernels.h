@@ -61,8 +61,10 @@ hipError_t launch_sparse_and_t(const LayerView *L, const Launch *cfg, int n, con
 // its share of the rows of U_r^T (as channels d_in.. with coefficients t), and the last workgroup to
 // arrive at a column tile rounds and stores that tile of Y.  cfg[i].splits must satisfy
 // gather_lds_bytes(d_in, splits, waves, bt, rank) <= 64 KiB.
+// gate_up: L[0], L[1] are the gate and up projections of an MLP (same d_out, out_dtype == dtype); the kernel
+// stores H = round(silu(round(g)) * round(u)) to Y[0] instead of the two outputs (Y[1] is not written).
 hipError_t launch_fused(const LayerView *L, const Launch *cfg, int n, const void *X, int batch, void *const *Y,
-                        hipStream_t stream);
+                        hipStream_t stream, bool gate_up = false);
 // Second launch: Y = round(yacc + U_r t) (use_rank) or round(yacc); re-zeroes yacc.
 hipError_t launch_finish(const LayerView *L, int n, int batch, void *const *Y, bool use_rank, hipStream_t stream);
 // Dense baselines.

@@ -272,6 +272,8 @@ struct GroupArgs {
     GatherArgs job[kMaxGroup];
     int wg_end[kMaxGroup];
     int n;
+    int gate_up;       // one-launch kernel: jobs 0 and 1 are the gate and up projections of an MLP (same d_out);
+                       // the column tiles are finished jointly and H = round(silu(g) * u) is stored to job[0].Y
 };
 __device__ __forceinline__ int find_job(const int (&wg_end)[kMaxGroup], int n, int wg, int &local)
 {
@@ -573,19 +575,25 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
     stream_rest<DT, BT, NT>(L.M, (size_t)d_out, col, colok, s.idx, s.coef, n_all, j_first, step, va, acc, need_t);
     reduce_to_yacc<BT>(acc, s.red, L.yacc, b0, nb, d_out, tile);
 
-    // ---- arrive at the tile; the last of its `splits` workgroups owns the finish
+    // ---- arrive at the tile; the last of its `splits` workgroups owns the finish.  For a gate/up pair
+    //      the two layers share the gate layer's counters and the tile is finished once, by the last
+    //      of both layers' workgroups (Sec. 3.1: H = X W_up^T (.) silu(X W_gate^T)).
     wait_own_writes();
     __syncthreads();
-    int *tile_ctr = L.sync + kSyncTile + z * a.tiles + tile;
+    const bool pair = ga.gate_up != 0;
+    int *const sync = pair ? ga.job[0].L.sync : L.sync;    // owner of the counters: the gate layer
+    float *const yacc_g = pair ? ga.job[0].L.yacc : L.yacc;
+    const int arrivals = pair ? ga.job[0].splits + ga.job[1].splits : a.splits;
+    int *tile_ctr = sync + kSyncTile + z * a.tiles + tile;
     if (tid == 0) {
         const int arrived = __hip_atomic_fetch_add(tile_ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         int last_of_layer = 0;
-        if (arrived == a.splits - 1) {
+        if (arrived == arrivals - 1) {
             // every workgroup of this tile has consumed t; when that holds for all tiles, t_pub can go back
             __hip_atomic_store(tile_ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const int done = __hip_atomic_fetch_add(L.sync + kSyncTilesDone, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int done = __hip_atomic_fetch_add(sync + kSyncTilesDone, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (done == a.tiles * a.nz - 1) {
-                __hip_atomic_store(L.sync + kSyncTilesDone, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(sync + kSyncTilesDone, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 last_of_layer = 1;
             }
         }
@@ -593,27 +601,48 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
         s.misc[13] = last_of_layer;
     }
     __syncthreads();
-    if (s.misc[12] != a.splits - 1) return;
+    if (s.misc[12] != arrivals - 1) return;
 
     // ---- Y = round(Y_s + Y_r): swap the sums out (this re-zeroes yacc for the next call), round once
     for (int c = tid; c < kTile; c += nthr) {
         const int o = tile * kTile + c;
         if (o < d_out) {
-            float v[BT];
+            float v[BT], vu[BT];
 #pragma unroll
-            for (int b = 0; b < BT; ++b)
-                v[b] = b < nb ? __hip_atomic_exchange(L.yacc + (size_t)(b0 + b) * d_out + o, 0.f, __ATOMIC_RELAXED,
-                                                      __HIP_MEMORY_SCOPE_AGENT)
-                              : 0.f;
+            for (int b = 0; b < BT; ++b) {
+                const size_t at = (size_t)(b0 + b) * d_out + o;
+                v[b] = b < nb ? __hip_atomic_exchange(yacc_g + at, 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
+                vu[b] = (pair && b < nb)
+                            ? __hip_atomic_exchange(ga.job[1].L.yacc + at, 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                            : 0.f;
+            }
 #pragma unroll
-            for (int b = 0; b < BT; ++b)
-                if (b < nb) store_out(a.Y, (size_t)(b0 + b) * d_out + o, v[b], L.out_dtype);
+            for (int b = 0; b < BT; ++b) {
+                if (b >= nb) continue;
+                const size_t at = (size_t)(b0 + b) * d_out + o;
+                if (!pair) {
+                    store_out(a.Y, at, v[b], L.out_dtype);
+                } else {
+                    // g and u are rounded to the storage type first, as the two projections would store them
+                    const uint16_t g16 = DT == F16 ? to_f16(v[b]) : to_bf16(v[b]);
+                    const uint16_t u16 = DT == F16 ? to_f16(vu[b]) : to_bf16(vu[b]);
+                    ((uint16_t *)ga.job[0].Y)[at] = gated1<DT>(g16, u16);
+                }
+            }
         }
     }
     if (s.misc[13]) {
-        const int words = a.nz * BT * L.rank;
-        for (int i = tid; i < words; i += nthr)
-            __hip_atomic_store(L.t_pub + i, kNotReady, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        auto reset_t = [&](uint32_t *t_pub, int rank) {
+            const int words = a.nz * BT * rank;
+            for (int i = tid; i < words; i += nthr)
+                __hip_atomic_store(t_pub + i, kNotReady, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        };
+        if (pair) {
+            reset_t(ga.job[0].L.t_pub, ga.job[0].L.rank);
+            reset_t(ga.job[1].L.t_pub, ga.job[1].L.rank);
+        } else {
+            reset_t(L.t_pub, L.rank);
+        }
     }
 }
 
@@ -991,9 +1020,12 @@ hipError_t launch_sparse_and_t(const LayerView *L, const Launch *cfg, int n, con
 }
 
 hipError_t launch_fused(const LayerView *L, const Launch *cfg, int n, const void *X, int batch, void *const *Y,
-                        hipStream_t stream)
+                        hipStream_t stream, bool gate_up)
 {
     if (!same_shape_class(L, n)) return hipErrorInvalidValue;
+    if (gate_up && (n != 2 || L[0].d_out != L[1].d_out || L[0].out_dtype != L[0].dtype || cfg[0].tile_map == 2 ||
+                    cfg[1].tile_map == 2))
+        return hipErrorInvalidValue;
     const int bt = batch_tile(batch);
     const int nz = (batch + bt - 1) / bt;
     if (nz > kSyncMaxZ) return hipErrorInvalidValue;
@@ -1024,6 +1056,7 @@ hipError_t launch_fused(const LayerView *L, const Launch *cfg, int n, const void
         if (a.lr_wgs > 0) lds = std::max(lds, lowrank_lds_bytes(L[i].d_in, bt));
     }
     for (int i = n; i < kMaxGroup; ++i) ga.wg_end[i] = total;
+    ga.gate_up = gate_up ? 1 : 0;
     dim3 grid(total, 1, nz), block(kWave * cfg[0].waves);
     const bool nt = cfg[0].nontemporal != 0;
 #define RS_U(DT)                                                                                        \

@@ -262,6 +262,45 @@ def test_gated_matches_ungated_on_the_materialised_input(ragged):
     layer.destroy()
 
 
+@pytest.mark.parametrize("dt", [synth.F16, synth.BF16])
+@pytest.mark.parametrize("B", [1, 3, 8, 12])
+def test_mlp_gate_up_with_fused_activation(dt, B):
+    """rsparse_mlp_gate_up: H = round(silu(round g) * round u) (Sec. 3.1) from the two R-Sparse
+    projections.  One launch on the vector path (1-8 tokens without the row-major copy), the
+    two-layers-then-elementwise fallback elsewhere; kept-channel lists of both layers must equal the
+    oracle's, H within the 16-bit output bounds.  Different rank and threshold per layer."""
+    import oracle
+    torch = gu.torch_mod()
+    Lg = synth.make_layer(1032, 1096, 40, dt, config=87, linear=0)
+    Lu = synth.make_layer(1032, 1096, 24, dt, config=87, linear=1)
+    X16, src = gu.tokens_for(Lg, B, linear=60 + B)
+    tg, tu = gu.calibrated_tau(Lg, src, 0.5), gu.calibrated_tau(Lg, src, 0.6)
+    wg, wu = gu.oracle_linear(Lg, X16, tg), gu.oracle_linear(Lu, X16, tu)
+    h_want = synth.decode16(oracle.gated_input(synth.encode16(wg["Y"], dt), synth.encode16(wu["Y"], dt), dt), dt)
+    for rowmajor, launches in ((0, 1), (0, 2), (1, 1)):
+        gate = gu.prepare(Lg, tg, max_batch=B, dense_rowmajor=rowmajor)
+        up = gu.prepare(Lu, tu, max_batch=B, dense_rowmajor=rowmajor)
+        rs.rsparse_set_tuning(gate, launches=launches)
+        Xd = gu.to_dev16(X16)
+        H = gu._alloc_out(gate, B)
+        for rep in range(2):                                  # twice: the shared counters must be back at zero
+            H.fill_(0x7FFF)
+            rs.rsparse_mlp_gate_up(gate, up, Xd.data_ptr(), B, H.data_ptr(), gu.stream_ptr())
+            rs.rsparse_synchronize(gate)
+            rs.rsparse_synchronize(up)
+            gu.check_outputs(gu._read_out(gate, H), h_want, gate.cfg.out_dtype)
+            for layer, w in ((gate, wg), (up, wu)):
+                got = {"act": [rs.rsparse_last_active(layer, b) for b in range(B)], "union": rs.rsparse_last_active(layer, -1)}
+                gu.check_lists(got, w)
+        # the handles still work on their own afterwards
+        one = gu.run_linear(up, X16)
+        gu.check_outputs(one["Y"], wu["Y"], up.cfg.out_dtype)
+        with pytest.raises(rs.RSparseError):
+            rs.rsparse_mlp_gate_up(gate, gate, Xd.data_ptr(), B, H.data_ptr(), gu.stream_ptr())
+        gate.destroy()
+        up.destroy()
+
+
 def test_bounded_wait_runs_out_and_the_handle_recovers(ragged):
     """Error path of the one-launch kernel, forced from the host: stage 1 publishes nothing and the
     wait bound is a few polls, so every kernel still ends normally; the call is reported invalid by
