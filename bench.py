@@ -197,6 +197,8 @@ def main():
                          "R-Sparse vs dense per linear; prints one JSON line with key 'sweep'")
     ap.add_argument("--pmc-pass", action="store_true",
                     help="for rocprofv3 --pmc: one 256 MiB device copy of known size, then 3 eager ring passes; no timing")
+    ap.add_argument("--pmc-mfma", action="store_true",
+                    help="with --pmc-pass: also 2 eager passes of the matrix-core kernels at 8192 -> 28672, r = 1024, 32 tokens")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (one MI355X); run with --gpus 1", file=sys.stderr)
@@ -328,6 +330,24 @@ def main():
         for _ in range(3):
             pass_dense(stream.cuda_stream)
             torch.cuda.synchronize()
+        if args.pmc_mfma:
+            # the matrix-core kernels at their largest shape: 8192 -> 28672, r = 1024, 32 tokens, eager launches
+            Lb = synth.random_layer(8192, 28672, 1024, dt, seed=4242)
+            srcb = synth.DModelInput(8192, config=4, linear=0)
+            taub = rs.rsparse_calibrate_tau(synth.encode16(srcb.tokens(64, stream=synth.STREAM_CALIB), dt), dt, 0.5)
+            big = [rs.rsparse_prepare_factors(rs.make_config(8192, 28672, 1024, taub, dt, max_batch=32, dense_rowmajor=1),
+                                              Lb.W16, Lb.U16, Lb.SV16) for _ in range(2)]
+            xb = torch.from_numpy(synth.encode16(srcb.tokens(32, offset=3), dt).view(np.int16)).cuda()
+            yb = torch.zeros((32, 28672), dtype=torch.int16, device="cuda")
+            for _ in range(2):
+                for layer in big:
+                    rs.rsparse_linear(layer, xb.data_ptr(), 32, yb.data_ptr(), stream.cuda_stream)
+                    torch.cuda.synchronize()
+                for layer in big:
+                    rs.rsparse_dense_ref(layer, xb.data_ptr(), 32, yb.data_ptr(), stream.cuda_stream)
+                    torch.cuda.synchronize()
+            for layer in big:
+                layer.destroy()
         print(json.dumps({"pmc_pass": True, "copy_bytes": int(a.numel() * 4)}), flush=True)
         return
 
