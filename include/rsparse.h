@@ -237,6 +237,24 @@ size_t rsparse_dense_bytes(const rsparse_layer *layer, int32_t batch);
 rsparse_status rsparse_recipe(int32_t d_in, int32_t d_out, double budget_c, double rho,
                               double *keep_fraction_out, int32_t *rank_out, double *io_out);
 
+/*
+ * Search for the per-layer shares rho_i of the sparse part (Sec. 3.5, the search algorithm for the
+ * sparsification recipe): a population of `population` recipes, `generations` rounds of mutation
+ * m = rho^{x1} + p_m (rho^{x2} - rho^{x3}) and coordinate-wise crossover (mutant where alpha > p_c), the
+ * lowest-loss `population` of parents and offspring survive; layers are optimised `group_size` at a
+ * time with the others held at the best recipe so far.  The paper runs population 32, 5 generations,
+ * p_m = p_c = 0.5, groups of 28 with the model's perplexity as loss; the loss here is the caller's:
+ * loss(rho, n_layers, user), called from this thread only.  Recipes stay in [lo, hi]; rho_start (may
+ * be NULL = random) seeds the best-so-far.  rho_out [n_layers], *loss_out receive the best recipe;
+ * history_out (may be NULL) has room for 1 + ceil(n_layers / group_size) * generations best-loss values.
+ * Deterministic for a given seed.  Host code, no device needed; feed the result to rsparse_recipe.
+ */
+typedef double (*rsparse_loss_fn)(const double *rho, int32_t n_layers, void *user);
+rsparse_status rsparse_search_recipe(rsparse_loss_fn loss, void *user, int32_t n_layers, int32_t population,
+                                     int32_t generations, double p_m, double p_c, int32_t group_size,
+                                     uint64_t seed, double lo, double hi, const double *rho_start,
+                                     double *rho_out, double *loss_out, double *history_out);
+
 void rsparse_destroy(rsparse_layer *layer);
 
 const char *rsparse_last_error(void);

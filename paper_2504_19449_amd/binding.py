@@ -16,7 +16,7 @@ EXPORTED_SYMBOLS = [
     "rsparse_linear_gated", "rsparse_gated_input", "rsparse_mlp_gate_up", "rsparse_dense_ref", "rsparse_linear_group", "rsparse_dense_ref_group", "rsparse_last_active", "rsparse_synchronize",
     "rsparse_get_factors", "rsparse_set_tau", "rsparse_set_tuning",
     "rsparse_get_config", "rsparse_calibrate_tau", "rsparse_required_bytes", "rsparse_dense_bytes",
-    "rsparse_recipe", "rsparse_destroy", "rsparse_last_error",
+    "rsparse_recipe", "rsparse_search_recipe", "rsparse_destroy", "rsparse_last_error",
 ]
 
 
@@ -31,6 +31,9 @@ class Tuning(C.Structure):
                 ("dense_kernel", C.c_int32), ("nontemporal", C.c_int32), ("stages", C.c_int32),
                 ("tile_map", C.c_int32), ("mfma_min_batch", C.c_int32), ("mfma_rows", C.c_int32),
                 ("launches", C.c_int32), ("debug_wait_polls", C.c_int32), ("debug_skip_stage1", C.c_int32)]
+
+
+LOSS_FN = C.CFUNCTYPE(C.c_double, C.POINTER(C.c_double), C.c_int32, C.c_void_p)
 
 
 class RSparseError(RuntimeError):
@@ -88,6 +91,9 @@ def load_library():
     lib.rsparse_recipe.argtypes = [i32, i32, C.c_double, C.c_double, C.POINTER(C.c_double), C.POINTER(i32),
                                    C.POINTER(C.c_double)]
     lib.rsparse_recipe.restype = C.c_int
+    lib.rsparse_search_recipe.argtypes = [LOSS_FN, vp, i32, i32, i32, C.c_double, C.c_double, i32, C.c_uint64,
+                                          C.c_double, C.c_double, vp, vp, vp, vp]
+    lib.rsparse_search_recipe.restype = C.c_int
     lib.rsparse_destroy.argtypes = [vp]
     lib.rsparse_destroy.restype = None
     lib.rsparse_last_error.restype = C.c_char_p
@@ -283,3 +289,25 @@ def rsparse_destroy(layer: Layer):
 
 
 make_config = _make_config
+
+
+def rsparse_search_recipe(loss, n_layers: int, population: int = 32, generations: int = 5, p_m: float = 0.5,
+                          p_c: float = 0.5, group_size: int = 28, seed: int = 0, lo: float = 0.0, hi: float = 1.0,
+                          rho_start=None):
+    """Sec. 3.5 recipe search; `loss` is a Python callable on a list of n_layers floats.
+    Returns (rho [n_layers], best loss, history)."""
+    def trampoline(rho_ptr, n, _user):
+        return float(loss([rho_ptr[i] for i in range(n)]))
+
+    cb = LOSS_FN(trampoline)
+    groups = (n_layers + group_size - 1) // group_size
+    rho = np.zeros(n_layers, dtype=np.float64)
+    best = C.c_double(0.0)
+    hist = np.zeros(1 + groups * generations, dtype=np.float64)
+    start = None if rho_start is None else np.ascontiguousarray(rho_start, dtype=np.float64)
+    st = load_library().rsparse_search_recipe(cb, None, n_layers, population, generations, p_m, p_c, group_size, seed,
+                                              lo, hi, None if start is None else start.ctypes.data_as(C.c_void_p),
+                                              rho.ctypes.data_as(C.c_void_p), C.byref(best), hist.ctypes.data_as(C.c_void_p))
+    if st != OK:
+        raise RSparseError(st, "rsparse_search_recipe: invalid argument" if st == EINVAL else "allocation failed")
+    return rho, best.value, hist

@@ -132,3 +132,28 @@ def test_recipe_mapping_of_sec_3_5():
     for bad in ((0, 8, 0.5, 0.5), (8, 8, 1.5, 0.5), (8, 8, 0.5, -0.1), (8, 8, float("nan"), 0.5)):
         with pytest.raises(rs.RSparseError):
             rs.rsparse_recipe(*bad)
+
+
+def test_recipe_search_matches_the_oracle_bit_for_bit():
+    """rsparse_search_recipe (host C++) against the plain-Python oracle of Sec. 3.5's algorithm: same
+    seed, same loss => the same recipe, best loss and per-generation history, exactly."""
+    from oracle.recipe_search import search_recipe
+    rng = np.random.default_rng(4)
+    for L, P, T, gs, seed, pm, pc in ((5, 8, 3, 2, 1, 0.5, 0.5), (30, 32, 5, 28, 7, 0.5, 0.5), (9, 6, 4, 9, 11, 0.8, 0.3)):
+        center = rng.uniform(0.0, 1.0, L)
+        w = rng.uniform(0.5, 2.0, L)
+
+        def loss(rho):
+            return float(np.sum(w * (np.asarray(rho) - center) ** 2) + 0.1 * np.sin(7.0 * np.sum(rho)))
+
+        want = search_recipe(loss, L, population=P, generations=T, p_m=pm, p_c=pc, group_size=gs, seed=seed, lo=0.02, hi=0.99)
+        got = rs.rsparse_search_recipe(loss, L, population=P, generations=T, p_m=pm, p_c=pc, group_size=gs, seed=seed,
+                                       lo=0.02, hi=0.99)
+        assert got[0].tolist() == want[0] and got[1] == want[1] and got[2].tolist() == want[2]
+    start = [0.3, 0.6, 0.9]
+    want = search_recipe(lambda r: abs(r[0] - 0.5) + r[1] * r[2], 3, population=4, generations=2, group_size=1, seed=3, rho_start=start)
+    got = rs.rsparse_search_recipe(lambda r: abs(r[0] - 0.5) + r[1] * r[2], 3, population=4, generations=2, group_size=1, seed=3,
+                                   rho_start=start)
+    assert got[0].tolist() == want[0] and got[2].tolist() == want[2]
+    with pytest.raises(rs.RSparseError):
+        rs.rsparse_search_recipe(lambda r: 0.0, 0)

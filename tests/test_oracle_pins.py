@@ -356,3 +356,68 @@ def test_gated_input_is_one_rounding_of_the_fp32_product(dt):
     assert np.array_equal(np.isnan(synth.decode16(got, dt)), nan)
     assert np.array_equal(got[~nan], want[~nan])
     assert nan[:2].all() and np.isinf(synth.decode16(got[2:3], dt))[0]
+
+
+# --------------------------------------------------------------------------- recipe search (Sec. 3.5)
+
+def _quad(center):
+    return lambda rho: float(sum((a - b) ** 2 for a, b in zip(rho, center)))
+
+
+def test_recipe_search_invariants():
+    """What the algorithm fixes regardless of its random draws: the best loss never gets worse from one
+    generation to the next (lowest-loss selection over parents and offspring); with no generations the
+    answer is the best of the initial population; with crossover rate 1 (alpha <= p_c always) every
+    offspring equals its parent, so generations change nothing; recipes stay inside [lo, hi]; only the
+    current group's coordinates differ from the best-so-far in any evaluated recipe."""
+    from oracle.recipe_search import search_recipe
+    center = [0.9, 0.2, 0.5, 0.7, 0.95, 0.1, 0.33]
+    seen = []
+
+    def loss(rho):
+        seen.append(list(rho))
+        return _quad(center)(rho)
+
+    S, best, hist = search_recipe(loss, 7, population=12, generations=6, group_size=3, seed=5, lo=0.05, hi=0.98)
+    assert all(b <= a for a, b in zip(hist, hist[1:])) and best == hist[-1] == _quad(center)(S)
+    assert len(hist) == 1 + 3 * 6 and best < hist[0]
+    assert all(0.05 <= v <= 0.98 for rho in seen for v in rho)
+    # group structure: evaluations of group g differ from the first evaluation (the start) only in groups <= g
+    n_eval_group = 11 + 6 * 12
+    for gi, (lo_c, hi_c) in enumerate(((0, 3), (3, 6), (6, 7))):
+        block = seen[1 + gi * n_eval_group: 1 + (gi + 1) * n_eval_group]
+        ref = block[0]
+        for rho in block:
+            outside = [c for c in range(7) if not lo_c <= c < hi_c]
+            assert all(rho[c] == ref[c] for c in outside)
+    S0, best0, hist0 = search_recipe(_quad(center), 7, population=12, generations=0, group_size=7, seed=5)
+    assert len(hist0) == 1
+    S1, best1, hist1 = search_recipe(_quad(center), 7, population=12, generations=4, p_c=1.0, group_size=7, seed=5)
+    assert hist1[1:] == [hist1[1]] * 4 and best1 == hist1[1]
+    # reproducible, and the seed matters
+    assert search_recipe(_quad(center), 7, seed=9)[0] == search_recipe(_quad(center), 7, seed=9)[0]
+    assert search_recipe(_quad(center), 7, seed=9)[0] != search_recipe(_quad(center), 7, seed=10)[0]
+
+
+def test_recipe_search_finds_the_minimiser_of_a_separable_loss():
+    """With the paper's settings (population 32, 5 generations, p_m = p_c = 0.5) but more generations,
+    the search closes in on the known minimiser of a convex separable loss, coordinate by coordinate."""
+    from oracle.recipe_search import search_recipe
+    rng = np.random.default_rng(2)
+    center = rng.uniform(0.1, 0.9, 12).tolist()
+    S, best, hist = search_recipe(_quad(center), 12, population=32, generations=40, group_size=4, seed=1)
+    assert best < 1e-3 * hist[0]
+    assert np.max(np.abs(np.array(S) - np.array(center))) < 0.02
+    # a start that is already optimal is kept
+    S2, best2, _ = search_recipe(_quad(center), 12, population=8, generations=3, group_size=4, seed=1, rho_start=center)
+    assert best2 == 0.0 and S2 == center
+
+
+def test_recipe_search_uniform_stream():
+    """The random stream: splitmix64 outputs for seed 0 are the published reference values; the
+    uniforms lie in [0, 1) with the right mean."""
+    from oracle.recipe_search import _splitmix64, _Uniform
+    assert _splitmix64(0, 0) == 0xE220A8397B1DCDAF and _splitmix64(0, 1) == 0x6E789E6AA1B965F4
+    u = _Uniform(123)
+    xs = np.array([u() for _ in range(20000)])
+    assert xs.min() >= 0.0 and xs.max() < 1.0 and abs(xs.mean() - 0.5) < 0.01
