@@ -527,7 +527,7 @@ def main():
         threads = min(oracle.max_threads(), os.cpu_count() or 1, 16)
         t_cpu, n_calls = 0.0, 0
         t_begin = time.time()
-        while time.time() - t_begin < 12.0 and n_calls < 30:
+        while time.time() - t_begin < 10.0 and n_calls < 6000:       # about 10 s of CPU work
             for name, layer, xd, yd, L, x in ring[:3]:
                 t1 = time.time()
                 oracle.rsparse_linear(L.W16, L.U16, L.SV16, x, dt, dt, taus[name][args.sparsity], nthreads=threads)
