@@ -198,7 +198,8 @@ def main():
     ap.add_argument("--pmc-pass", action="store_true",
                     help="for rocprofv3 --pmc: one 256 MiB device copy of known size, then 3 eager ring passes; no timing")
     ap.add_argument("--pmc-mfma", action="store_true",
-                    help="with --pmc-pass: also 2 eager passes of the matrix-core kernels at 8192 -> 28672, r = 1024, 32 tokens")
+                    help="with --pmc-pass: also 2 eager passes of the matrix-core kernels at 8192 -> 28672, r = 1024, 32 tokens, "
+                         "and 3 of the vector path at 4096 -> 11008, r = 512, 4 tokens")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (one MI355X); run with --gpus 1", file=sys.stderr)
@@ -347,6 +348,21 @@ def main():
                     rs.rsparse_dense_ref(layer, xb.data_ptr(), 32, yb.data_ptr(), stream.cuda_stream)
                     torch.cuda.synchronize()
             for layer in big:
+                layer.destroy()
+            # and the vector path at 4 tokens (4096 -> 11008, r = 512): VALU-busy and occupancy at the batch
+            # where arithmetic starts to matter
+            L4 = synth.random_layer(D_MODEL, D_FF, RANK, dt, seed=4243)
+            src4 = synth.DModelInput(D_MODEL, config=2, linear=0)
+            tau4 = rs.rsparse_calibrate_tau(synth.encode16(src4.tokens(64, stream=synth.STREAM_CALIB), dt), dt, 0.5)
+            four = [rs.rsparse_prepare_factors(rs.make_config(D_MODEL, D_FF, RANK, tau4, dt, max_batch=4, dense_rowmajor=1),
+                                               L4.W16, L4.U16, L4.SV16) for _ in range(4)]
+            x4 = torch.from_numpy(synth.encode16(src4.tokens(4, offset=3), dt).view(np.int16)).cuda()
+            y4 = torch.zeros((4, D_FF), dtype=torch.int16, device="cuda")
+            for _ in range(3):
+                for layer in four:
+                    rs.rsparse_linear(layer, x4.data_ptr(), 4, y4.data_ptr(), stream.cuda_stream)
+                    torch.cuda.synchronize()
+            for layer in four:
                 layer.destroy()
         print(json.dumps({"pmc_pass": True, "copy_bytes": int(a.numel() * 4)}), flush=True)
         return
