@@ -573,3 +573,35 @@ def test_hip_graph_replays_match_eager_and_oracle(ragged, B):
         assert np.linalg.norm(got - eager) <= 1e-5 * np.linalg.norm(eager)
         assert np.array_equal(rs.rsparse_last_active(layer, 0), want["act"][0])
     layer.destroy()
+
+
+@pytest.mark.parametrize("seed", list(range(6)))
+def test_random_shapes_and_settings(seed):
+    """Seeded sweep over small random layers: every dimension a multiple of 8 from 8 up, ranks from 0 to
+    full, 1-32 tokens, both dtypes, both compare modes, both mask modes, with and without the row-major
+    copy, both launch forms, random launch shapes.  Lists equal, outputs within the fp32-output bound."""
+    rng = np.random.default_rng(1234 + seed)
+    for case in range(8):
+        d_in = 8 * int(rng.integers(1, 150))
+        d_out = 8 * int(rng.integers(1, 200))
+        rank = 8 * int(rng.integers(0, min(d_in, d_out) // 8 + 1))
+        if rng.random() < 0.5:
+            rank = min(rank, 8 * int(rng.integers(0, 9)))
+        dt = int(rng.integers(0, 2))
+        B = int(rng.choice([1, 1, 2, 3, 4, 5, 7, 8, 9, 16, 17, 31, 32]))
+        cmp_mode, mask_mode, rowmajor = int(rng.integers(0, 2)), int(rng.integers(0, 2)), int(rng.integers(0, 2))
+        L = synth.random_layer(d_in, d_out, rank, dt, seed=9000 + 100 * seed + case)
+        src = synth.DModelInput(d_in, config=88, linear=10 * seed + case)
+        X16 = synth.encode16(src.tokens(B), dt)
+        s_level = float(rng.choice([0.0, 0.3, 0.5, 0.5, 0.8, 1.0]))
+        tau = gu.calibrated_tau(L, src, s_level) if 0.0 < s_level < 1.0 else (-INF if s_level == 0.0 else INF)
+        tuning = {"launches": int(rng.integers(1, 3))}
+        if rng.random() < 0.5:
+            tuning.update(splits=int(rng.integers(1, 40)), waves=int(rng.choice([1, 2, 4, 8])))
+        if rng.random() < 0.3:
+            tuning.update(lowrank_rows=int(rng.integers(1, 33)))
+        label = dict(d_in=d_in, d_out=d_out, rank=rank, dt=dt, B=B, cmp=cmp_mode, mask=mask_mode, rowmajor=rowmajor,
+                     s=s_level, **tuning)
+        print("case", label, flush=True)
+        _parity(L, X16, tau, out_dtype=rs.F32, tuning=tuning, cmp_mode=cmp_mode, batch_mask_mode=mask_mode,
+                dense_rowmajor=rowmajor)
