@@ -5,8 +5,9 @@
 // 1 KiB row segment per 64-lane wave, many rows in flight, fp32 accumulation on the
 // vector ALU.  Storage:
 //
-//   M    [d_in][d_out]   W column-major (row c = all outputs of input channel c; Sec. 3.4 asks
-//                        for this layout so that a kept channel is one contiguous run)
+//   M    [d_in + r][d_out]  W column-major (row c = all outputs of input channel c; Sec. 3.4 asks
+//                        for this layout so that a kept channel is one contiguous run), followed by
+//                        U_r^T (row d_in + j = U_r[:, j]) for the one-launch kernel
 //   SVt  [r][d_in]       S_r V_r^T, one singular component per row
 //   U    [d_out][r]      U_r row-major
 //
@@ -31,7 +32,8 @@
 // cache write-back or invalidate is needed; a workgroup waits for its own atomics to be acknowledged
 // (s_waitcnt) before it bumps a counter.  The last workgroup to arrive at a column tile swaps the
 // tile's sums out of yacc (which re-zeroes them), rounds once and stores Y; the last tile of the
-// layer puts t_pub and the counters back.
+// layer puts t_pub and the counters back.  For the gate / up pair of an MLP (Sec. 3.1) the two layers
+// share one set of counters and the finisher stores H = round(silu(g) * u) instead of g and u.
 #include "kernels.h"
 #include "device_common.h"
 
@@ -180,9 +182,10 @@ __device__ __forceinline__ void stream_rest(const uint16_t *__restrict__ M, size
     }
 }
 
-// Cross-wave reduction of a column tile through LDS, then fp32 atomics into yacc.  No fences and no
-// arrival counters: the kernel boundary before k_finish orders the atomics (an agent-scope fence
-// per workgroup costs an L2 write-back + invalidate on this chip and dominated the run time).
+// Cross-wave reduction of a column tile through LDS, then fp32 atomics into yacc.  No fences: in the
+// two-launch form the kernel boundary before k_finish orders the atomics, in the one-launch form the
+// caller waits for their acknowledgement (an agent-scope fence per workgroup costs an L2 write-back +
+// invalidate on this chip and dominated the run time).
 template <int BT>
 __device__ __forceinline__ void reduce_to_yacc(float (&acc)[BT][8], float *s_red, float *yacc, int b0, int nb,
                                                int d_out, int tile)
