@@ -206,6 +206,8 @@ rsparse_status rsparse_synchronize(rsparse_layer *layer);
 /* Stored 16-bit factors, host buffers U16 [d_out][rank] and SV16 [rank][d_in] (either may be NULL). */
 rsparse_status rsparse_get_factors(const rsparse_layer *layer, void *U16_host, void *SV16_host);
 
+/* Threshold and launch-shape changes apply to calls made afterwards; a call already captured into a HIP
+ * graph replays with the threshold, tuning and pointers it was captured with. */
 rsparse_status rsparse_set_tau(rsparse_layer *layer, float tau);
 rsparse_status rsparse_set_tuning(rsparse_layer *layer, const rsparse_tuning *tuning);
 rsparse_status rsparse_get_config(const rsparse_layer *layer, rsparse_config *cfg_out);
