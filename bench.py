@@ -454,6 +454,29 @@ def main():
         extras["sparsity_sweep"] = sweep
         extras["us_per_linear_separate_calls"] = round(timed(pass_rsparse_separate, args.steps, args.warmup) * 1000 / 3, 3)
 
+    # ------------------------------------------------------------------ hot-cache and single-call latency (labelled as such)
+    if not args.no_extras:
+        g0, u0, d0 = blocks[0]
+
+        def pass_hot(sptr):              # the same three layers every step: weights partly served by the Infinity Cache
+            for _ in range(RING_BLOCKS):
+                rs.rsparse_linear_group([g0[1], u0[1]], g0[2].data_ptr(), 1, [g0[3].data_ptr(), u0[3].data_ptr()], sptr)
+                rs.rsparse_linear(d0[1], d0[2].data_ptr(), 1, d0[3].data_ptr(), sptr)
+
+        extras["us_per_linear_hot_cache_same_layers"] = round(
+            min(timed(pass_hot, args.steps, args.warmup, eager=e) for e in (False, True)) * 1000.0 / 3.0, 3)
+        lat = []
+        for i in range(60):              # one call at a time: host launch + kernel + synchronize, wall clock
+            _, layer, xd, yd, *_ = ring[(3 * i + 2) % len(ring)]
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            rs.rsparse_linear(layer, xd.data_ptr(), 1, yd.data_ptr(), stream.cuda_stream)
+            torch.cuda.synchronize()
+            lat.append((time.perf_counter() - t1) * 1e6)
+        lat.sort()
+        extras["us_single_call_latency_incl_launch_and_sync"] = {"median": round(lat[len(lat) // 2], 1), "min": round(lat[0], 1),
+                                                                 "layer": "down 11008 -> 4096, one call, host wall clock"}
+
     # ------------------------------------------------------------------ down projection on the gated MLP input
     if not args.no_extras:
         downs = [d for (_, _, d) in blocks]
