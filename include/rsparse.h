@@ -80,7 +80,8 @@ typedef struct {
     int32_t waves;           /* waves (of 64 lanes) per workgroup in those kernels: 1, 2, 4 or 8 */
     int32_t lowrank_rows;    /* rows of S_r V_r^T per stage-1 workgroup */
     int32_t dense_kernel;    /* rsparse_dense_ref: 0 auto, 1 axpy over column-major W, 2 row-dot */
-    int32_t nontemporal;     /* 1: stream weights with non-temporal loads */
+    int32_t nontemporal;     /* weight loads of the vector-path kernels: 0 default (non-temporal), 1 non-temporal,
+                                2 ordinary (temporal) loads */
     int32_t stages;          /* rsparse_linear, two-launch form: 0 the whole layer, 1 first launch only, 2 second
                                 only -- for timing one kernel in isolation; results are only valid with 0 */
     int32_t tile_map;        /* workgroup -> (column tile, split) mapping: 0 default, 1 tile-fastest (plain),

@@ -371,7 +371,7 @@ __device__ __forceinline__ void lowrank_rows(const GatherArgs &a, unsigned char 
 #pragma unroll
                     for (int u = 0; u < LU; ++u) {
                         const int q = q0 + u * 64;
-                        v[u] = (q < nq) ? ldg16<false>(row + q * 8) : u32x4{0, 0, 0, 0};
+                        v[u] = (q < nq) ? ldg16<true>(row + q * 8) : u32x4{0, 0, 0, 0};       // streamed once
                     }
 #pragma unroll
                     for (int u = 0; u < LU; ++u) {
@@ -764,7 +764,7 @@ __global__ __launch_bounds__(256) void k_finish(const FinishGroupArgs ga)
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
             const int i = (p * lpr + sub) * 8;
-            v[g][p] = (PASSES > 0 && o < d_out && i < r) ? ldg16<false>(L.U + (size_t)o * r + i) : u32x4{0, 0, 0, 0};
+            v[g][p] = (PASSES > 0 && o < d_out && i < r) ? ldg16<true>(L.U + (size_t)o * r + i) : u32x4{0, 0, 0, 0};
         }
 #pragma unroll
         for (int b = 0; b < BT; ++b)
@@ -821,7 +821,7 @@ __global__ __launch_bounds__(256) void k_finish(const FinishGroupArgs ga)
                 const int i = (p * lpr + sub) * 8;
                 if (i < r) {
                     float f[8];
-                    unpack8<DT>(ldg16<false>(L.U + (size_t)o * r + i), f);
+                    unpack8<DT>(ldg16<true>(L.U + (size_t)o * r + i), f);
 #pragma unroll
                     for (int b = 0; b < BT; ++b)
 #pragma unroll
