@@ -87,7 +87,7 @@ typedef struct {
     int32_t tile_map;        /* workgroup -> (column tile, split) mapping: 0 default, 1 tile-fastest (plain),
                                 2 XCD-aware (all splits of a tile on ids congruent mod 8) */
     int32_t mfma_min_batch;  /* smallest batch that takes the matrix-core path (needs dense_rowmajor = 1):
-                                0 = default (5 for rsparse_linear, 2 for rsparse_dense_ref), 33 = never (all batches
+                                0 = default (5 for rsparse_linear; 2 for rsparse_dense_ref, 4 on layers of 2^25 weights or more), 33 = never (all batches
                                 then run in tiles of up to 8 tokens on the vector ALU) */
     int32_t mfma_rows;       /* output rows per workgroup of the matrix-core kernels: 0 default, or 64, 128, 256 */
     int32_t launches;        /* rsparse_linear up to 8 tokens (and beyond without the row-major copy): 0 default

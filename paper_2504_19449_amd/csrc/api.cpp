@@ -547,7 +547,11 @@ rsparse_status rsparse_dense_ref_group(rsparse_layer *const *layers, int32_t n_l
         lc[i] = resolve_launch(layers[i], batch, true, n_layers, i ? lc[0].waves : 0);
         can_rowdot = can_rowdot && layers[i]->Wrow != nullptr && rowdot_supported(layers[i]->cfg.d_in, batch);
     }
-    bool mfma = batch >= (layers[0]->tuning.mfma_min_batch > 0 ? layers[0]->tuning.mfma_min_batch : kMfmaDefaultMinBatchDense);
+    // the dense baseline moves to the matrix cores from 2 tokens on small layers and from 4 on large ones
+    // (measured: 4096 x 11008 and 8192 x 8192 are still faster on the vector path at 2-3 tokens)
+    const bool large = (size_t)layers[0]->cfg.d_in * layers[0]->cfg.d_out >= ((size_t)1 << 25);
+    bool mfma = batch >= (layers[0]->tuning.mfma_min_batch > 0 ? layers[0]->tuning.mfma_min_batch
+                                                                 : (large ? 4 : kMfmaDefaultMinBatchDense));
     for (int i = 0; i < n_layers; ++i) mfma = mfma && mfma_path_supported(v[i], batch);
     if (mfma) {
         for (int i = 0; i < n_layers; ++i)
