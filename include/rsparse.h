@@ -101,7 +101,7 @@ typedef struct {
 } rsparse_tuning;
 
 /*
- * Offline preparation (Sec. 3.4: "computed offline through a single SVD").
+ * Offline preparation (Sec. 3.4: the low-rank factors come from one SVD of W, done ahead of time).
  * W_host: host, [d_out][d_in] 16-bit of cfg->dtype.  The library computes the top-`rank`
  * singular triplets on the host, forms U_r and S_r V_r^T, rounds each once to cfg->dtype,
  * packs W column-major and uploads everything.  *out receives a new handle.
