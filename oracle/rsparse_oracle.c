@@ -321,6 +321,33 @@ void orc_silu32_array(const float *g, size_t n, float *out)
     for (size_t i = 0; i < n; ++i) out[i] = orc_silu32(g[i]);
 }
 
+/* ---- 4-bit weights ------------------------------------------------------- */
+
+/* The combination with weight quantisation (Sec. 4.4, the answer on quantisation and Table 2:
+ * 4-bit GPTQ weights, groups of 128).  GPTQ's storage format: every output row o is cut into groups
+ * of `group` consecutive input channels, each with a 16-bit scale s and a 4-bit zero point z; the
+ * weight the layer multiplies by is the real number
+ *
+ *     W~[o][c] = s[o][c / group] * (q[o][c] - z[o][c / group]),      q, z in 0..15
+ *
+ * which a double holds exactly.  The R-Sparse layer on 4-bit weights is orc_rsparse_linear with this
+ * W~ as its (double) W; the low-rank factors stay 16-bit inputs of their own.
+ * q: [d_out][d_in] one code per byte;  s16: [d_out][d_in / group];  z: [d_out][d_in / group]. */
+int orc_dequant_q4(const uint8_t *q, const void *s16, int s_kind, const uint8_t *z, int d_out, int d_in,
+                   int group, double *W)
+{
+    if (!q || !s16 || !z || !W || d_out < 1 || d_in < 1 || group < 1 || d_in % group) return 1;
+    if (s_kind != ORC_F16 && s_kind != ORC_BF16) return 1;
+    const size_t G = (size_t)d_in / group;
+    for (size_t o = 0; o < (size_t)d_out; ++o)
+        for (size_t c = 0; c < (size_t)d_in; ++c) {
+            const size_t g = c / group;
+            if (q[o * d_in + c] > 15 || z[o * G + g] > 15) return 1;
+            W[o * d_in + c] = ld(s16, o * G + g, s_kind) * ((double)q[o * d_in + c] - (double)z[o * G + g]);
+        }
+    return 0;
+}
+
 int orc_max_threads(void)
 {
 #ifdef _OPENMP

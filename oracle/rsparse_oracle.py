@@ -39,6 +39,8 @@ def _load():
         lib.orc_gated_input.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_size_t, C.c_void_p]
         lib.orc_silu32_array.restype = None
         lib.orc_silu32_array.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.orc_dequant_q4.restype = C.c_int
+        lib.orc_dequant_q4.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
         _lib = lib
     return _lib
 
@@ -141,3 +143,24 @@ def dense_linear(W, X, kind_w, kind_x, nthreads=1) -> np.ndarray:
 def quantile_tau(x, x_kind, s) -> float:
     x = _arr(x, x_kind).reshape(-1)
     return float(_load().orc_quantile_tau(_ptr(x), x_kind, x.size, float(s)))
+
+
+def dequant_q4(Q, S16, Z, dtype, group=128) -> np.ndarray:
+    """W~ = s * (q - z) as float64 [d_out, d_in] (Sec. 4.4, 4-bit weights in GPTQ's group format)."""
+    Q = np.ascontiguousarray(Q, dtype=np.uint8)
+    d_out, d_in = Q.shape
+    S16 = _arr(S16, dtype)
+    Z = np.ascontiguousarray(Z, dtype=np.uint8)
+    assert S16.shape == Z.shape == (d_out, d_in // group)
+    W = np.empty((d_out, d_in), dtype=np.float64)
+    if _load().orc_dequant_q4(_ptr(Q), _ptr(S16), dtype, _ptr(Z), d_out, d_in, group, _ptr(W)) != 0:
+        raise ValueError("oracle rejected its arguments")
+    return W
+
+
+def rsparse_linear_q4(Q, S16, Z, U16, SV16, X, dtype, tau, *, group=128, **kw):
+    """The R-Sparse layer on 4-bit weights: the plain layer with W~ in place of W; factors 16-bit."""
+    W = dequant_q4(Q, S16, Z, dtype, group)
+    U = None if U16 is None else decode16(U16, dtype)
+    SV = None if SV16 is None else decode16(SV16, dtype)
+    return rsparse_linear(W, U, SV, X, F64, dtype, tau, **kw)

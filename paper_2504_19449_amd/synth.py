@@ -201,3 +201,29 @@ def random_layer(d_in: int, d_out: int, rank: int, dtype: int, seed: int) -> Lay
     sv = g.standard_normal((rank, d_in), dtype=np.float32) * (sig[:rank, None] / np.sqrt(d_in)).astype(np.float32)
     out.SV16 = encode16(sv, dtype)
     return out
+
+
+def quantize_q4(W, dtype: int, group: int = 128):
+    """Synthetic 4-bit weights in GPTQ's storage format (Sec. 4.4 combines R-Sparse with GPTQ, group
+    128): per output row and group of `group` input channels a 16-bit scale and a 4-bit zero point,
+    codes in 0..15.  GPTQ itself needs calibration activations; this input generator rounds to nearest
+    on the same asymmetric min/max grid, which fills the format with realistic code, scale and
+    zero-point statistics.  Returns (Q uint8 [d_out, d_in], S16 bits [d_out, G], Z uint8 [d_out, G]).
+    What the codes mean as weights is the method's business and is not computed here."""
+    W = np.asarray(W, dtype=np.float64)
+    d_out, d_in = W.shape
+    if d_in % group:
+        raise ValueError("d_in must be a multiple of the group size")
+    G = d_in // group
+    Wg = W.reshape(d_out, G, group)
+    lo = np.minimum(Wg.min(axis=2), 0.0)
+    hi = np.maximum(Wg.max(axis=2), 0.0)
+    scale = (hi - lo) / 15.0
+    scale[scale == 0.0] = 1.0
+    S16 = encode16(scale, dtype)
+    s = decode16(S16, dtype)                   # the grid is laid on the scale as stored
+    s[s == 0.0] = 1.0
+    Z = np.clip(np.rint(-lo / s), 0, 15)
+    Q = np.clip(np.rint(Wg / s[:, :, None]) + Z[:, :, None], 0, 15)
+    return (np.ascontiguousarray(Q.reshape(d_out, d_in).astype(np.uint8)), S16,
+            np.ascontiguousarray(Z.astype(np.uint8)))

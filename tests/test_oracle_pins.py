@@ -421,3 +421,105 @@ def test_recipe_search_uniform_stream():
     u = _Uniform(123)
     xs = np.array([u() for _ in range(20000)])
     assert xs.min() >= 0.0 and xs.max() < 1.0 and abs(xs.mean() - 0.5) < 0.01
+
+
+# --------------------------------------------------------------------------- 4-bit weights (Sec. 4.4)
+
+def test_q4_hand_worked_golden():
+    """Dequantisation and the layer on it, against numbers worked by hand from the format's definition."""
+    path = os.path.join(os.path.dirname(__file__), "golden", "hand_worked_q4.txt")
+    item = {}
+    with open(path) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#") or line.startswith("case:"):
+                continue
+            key, val = line.split(":", 1)
+            item[key.strip()] = [[float(v) for v in row.split()] for row in val.split(";")]
+    group = int(item["group"][0][0])
+    Q = np.array(item["Q"], dtype=np.uint8)
+    Z = np.array(item["Z"], dtype=np.uint8)
+    for dt in (oracle.F16, oracle.BF16):
+        S16 = synth.encode16(np.array(item["S"]), dt)
+        assert oracle.dequant_q4(Q, S16, Z, dt, group).tolist() == item["expect W"]
+        X16 = synth.encode16(np.array(item["X"]), dt)
+        tau = item["tau"][0][0]
+        out0 = oracle.rsparse_linear_q4(Q, S16, Z, None, None, X16, dt, tau, group=group)
+        assert out0["act"][0].tolist() == [int(v) for v in item["expect rank=0 kept"][0]]
+        assert out0["Y"].tolist() == item["expect rank=0 Y"]
+        U16 = synth.encode16(np.array(item["U"]), dt)
+        SV16 = synth.encode16(np.array(item["SV"]), dt)
+        out1 = oracle.rsparse_linear_q4(Q, S16, Z, U16, SV16, X16, dt, tau, group=group)
+        assert out1["Y"].tolist() == item["expect rank=1 Y"]
+
+
+def test_q4_single_code_lands_on_its_own_row_channel_and_group():
+    """One non-zero (q - z) at a time: the value must appear at exactly [o][c] with the scale of group
+    c / group of row o -- a transposed operand or a group taken along the wrong axis fails here."""
+    d_out, d_in, group = 3, 8, 4
+    G = d_in // group
+    scales = np.array([[1.0, 2.0], [4.0, 8.0], [16.0, 32.0]])
+    S16 = synth.encode16(scales, oracle.F16)
+    Z = np.full((d_out, G), 5, dtype=np.uint8)
+    for o in range(d_out):
+        for c in range(d_in):
+            Q = np.full((d_out, d_in), 5, dtype=np.uint8)
+            Q[o, c] = 7
+            W = oracle.dequant_q4(Q, S16, Z, oracle.F16, group)
+            want = np.zeros((d_out, d_in))
+            want[o, c] = 2.0 * scales[o, c // group]
+            assert np.array_equal(W, want), (o, c)
+
+
+def test_q4_grid_round_trip_and_rounding_bound():
+    """Two properties that tie the oracle's dequantisation to the (independent) synthetic quantiser.
+    Weights built on a known grid (power-of-two scale, codes 0 and 15 present in every group) are
+    recovered exactly, codes included; arbitrary weights come back within half a step of the stored
+    scale, plus what the 16-bit rounding of the scale can shift the top of the range."""
+    rng = np.random.default_rng(11)
+    d_out, d_in, group = 16, 256, 128
+    G = d_in // group
+    for dt in (oracle.F16, oracle.BF16):
+        s_true = 2.0 ** rng.integers(-9, -3, size=(d_out, G)).astype(np.float64)
+        z_true = rng.integers(0, 16, size=(d_out, G))
+        q_true = rng.integers(0, 16, size=(d_out, d_in))
+        q_true[:, 0::group] = 0
+        q_true[:, 1::group] = 15
+        W = np.repeat(s_true, group, axis=1) * (q_true - np.repeat(z_true, group, axis=1))
+        Q, S16, Z = synth.quantize_q4(W, dt, group)
+        assert np.array_equal(Q, q_true) and np.array_equal(Z, z_true)
+        assert np.array_equal(oracle.dequant_q4(Q, S16, Z, dt, group), W)
+
+        W = rng.standard_normal((d_out, d_in)) * 0.02
+        Q, S16, Z = synth.quantize_q4(W, dt, group)
+        assert Q.max() <= 15 and Z.max() <= 15
+        Wq = oracle.dequant_q4(Q, S16, Z, dt, group)
+        s = np.repeat(synth.decode16(S16, dt), group, axis=1)
+        eps = 2.0 ** (-8 if dt == oracle.BF16 else -11)
+        assert np.all(np.abs(W - Wq) <= 0.5 * s + 16.0 * s * eps + 0.5 * s)   # zero-point rounding: another half step
+        assert np.mean(np.abs(W - Wq) <= 0.5 * s * (1 + 1e-12)) > 0.9
+
+
+def test_q4_all_channels_kept_is_the_dense_product_with_the_dequantised_weights():
+    rng = np.random.default_rng(5)
+    d_out, d_in, group = 24, 256, 128
+    W = rng.standard_normal((d_out, d_in)) * 0.05
+    Q, S16, Z = synth.quantize_q4(W, oracle.BF16, group)
+    X16 = synth.encode16(rng.standard_normal((2, d_in)), oracle.BF16)
+    out = oracle.rsparse_linear_q4(Q, S16, Z, None, None, X16, oracle.BF16, -math.inf, group=group)
+    Wq = oracle.dequant_q4(Q, S16, Z, oracle.BF16, group)
+    want = oracle.dense_linear(Wq, X16, oracle.F64, oracle.BF16)
+    assert np.array_equal(out["Y"], want)
+    # and the dequantised matrix is what numpy's integer arithmetic gives
+    s = np.repeat(synth.decode16(S16, oracle.BF16), group, axis=1)
+    z = np.repeat(Z.astype(np.int64), group, axis=1)
+    assert np.array_equal(Wq, s * (Q.astype(np.int64) - z))
+
+
+def test_q4_rejects_codes_out_of_range():
+    Q = np.zeros((1, 4), dtype=np.uint8)
+    Q[0, 1] = 16
+    S16 = synth.encode16(np.ones((1, 2)), oracle.F16)
+    Z = np.zeros((1, 2), dtype=np.uint8)
+    with pytest.raises(ValueError):
+        oracle.dequant_q4(Q, S16, Z, oracle.F16, 2)
