@@ -127,6 +127,24 @@ rsparse_status rsparse_prepare_factors(const rsparse_config *cfg, const void *W_
                                        rsparse_layer **out);
 
 /*
+ * The same layer on 4-bit weights (Sec. 4.4 combines R-Sparse with 4-bit GPTQ weights in groups of 128 and
+ * names a kernel that fuses sparsity and dequantisation as the open efficiency gain).  The weights arrive in
+ * GPTQ's storage format, all host: Q_host [d_out][d_in] codes 0..15, one per byte; S16_host
+ * [d_out][d_in / group_size] scales, 16-bit of cfg->dtype; Z_host [d_out][d_in / group_size] zero points
+ * 0..15, one per byte.  The weight they stand for is W~[o][c] = s[o][g] * (q[o][c] - z[o][g]),
+ * g = c / group_size, and the layer computes Sec. 3.4's formula with W~ in place of W; the factors
+ * U16_host / SV16_host stay 16-bit and are the caller's (of the unquantised W, or of W~).  group_size: a power
+ * of two in [32, 1024] that divides d_in.  The library packs the codes channel-major (one kept channel = one
+ * contiguous run of d_out / 2 bytes) and dequantises in registers: per quantisation group it accumulates
+ * sum x_c q_c and sum x_c and applies scale and zero point once.  Limits of this path: max_batch <= 4,
+ * dense_rowmajor = 0; rsparse_linear and friends run it as two launches per layer (grouped calls and
+ * rsparse_mlp_gate_up take such layers one at a time); rsparse_dense_ref gives the dense product with W~.
+ */
+rsparse_status rsparse_prepare_q4(const rsparse_config *cfg, const uint8_t *Q_host, const void *S16_host,
+                                  const uint8_t *Z_host, int32_t group_size, const void *U16_host,
+                                  const void *SV16_host, rsparse_layer **out);
+
+/*
  * The hot path (Sec. 3.4): threshold X, build the kept-channel lists, gather-multiply the
  * kept columns of W, run the other channels through the rank-r factors, sum, round once.
  * X_dev: device, [batch][d_in] 16-bit, 16-byte aligned.  Y_dev: device, [batch][d_out] of

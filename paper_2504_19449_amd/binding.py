@@ -12,7 +12,7 @@ OK, EINVAL, ENOMEM, EHIP, EBATCH, EALIGN, ESVD = range(7)
 _STATUS = {1: "EINVAL", 2: "ENOMEM", 3: "EHIP", 4: "EBATCH", 5: "EALIGN", 6: "ESVD"}
 
 EXPORTED_SYMBOLS = [
-    "rsparse_prepare", "rsparse_compute_factors", "rsparse_prepare_factors", "rsparse_linear",
+    "rsparse_prepare", "rsparse_compute_factors", "rsparse_prepare_factors", "rsparse_prepare_q4", "rsparse_linear",
     "rsparse_linear_gated", "rsparse_gated_input", "rsparse_mlp_gate_up", "rsparse_dense_ref", "rsparse_linear_group", "rsparse_dense_ref_group", "rsparse_last_active", "rsparse_synchronize",
     "rsparse_get_factors", "rsparse_set_tau", "rsparse_set_tuning",
     "rsparse_get_config", "rsparse_calibrate_tau", "rsparse_required_bytes", "rsparse_dense_bytes",
@@ -70,6 +70,7 @@ def load_library():
     lib.rsparse_prepare.argtypes = [C.POINTER(Config), vp, C.POINTER(vp)]
     lib.rsparse_compute_factors.argtypes = [C.POINTER(Config), vp, vp, vp, vp]
     lib.rsparse_prepare_factors.argtypes = [C.POINTER(Config), vp, vp, vp, C.POINTER(vp)]
+    lib.rsparse_prepare_q4.argtypes = [C.POINTER(Config), vp, vp, vp, i32, vp, vp, C.POINTER(vp)]
     lib.rsparse_linear.argtypes = [vp, vp, i32, vp, vp]
     lib.rsparse_dense_ref.argtypes = [vp, vp, i32, vp, vp]
     lib.rsparse_linear_gated.argtypes = [vp, vp, vp, i32, vp, vp]
@@ -100,7 +101,7 @@ def load_library():
     for name in ("rsparse_linear_group", "rsparse_dense_ref_group", "rsparse_prepare", "rsparse_compute_factors",
                  "rsparse_prepare_factors", "rsparse_linear", "rsparse_dense_ref",
                  "rsparse_last_active", "rsparse_get_factors", "rsparse_set_tau", "rsparse_set_tuning",
-                 "rsparse_get_config", "rsparse_calibrate_tau", "rsparse_synchronize", "rsparse_linear_gated", "rsparse_gated_input", "rsparse_mlp_gate_up"):
+                 "rsparse_get_config", "rsparse_calibrate_tau", "rsparse_synchronize", "rsparse_linear_gated", "rsparse_gated_input", "rsparse_mlp_gate_up", "rsparse_prepare_q4"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -180,6 +181,28 @@ def rsparse_prepare_factors(cfg: Config, W16, U16, SV16) -> Layer:
         raise ValueError("U must be [d_out, rank] and SV [rank, d_in]")
     h = C.c_void_p()
     _check(load_library().rsparse_prepare_factors(C.byref(cfg), _hp(W16), _hp(U16), _hp(SV16), C.byref(h)))
+    return Layer(h, cfg)
+
+
+def rsparse_prepare_q4(cfg: Config, Q, S16, Z, group_size: int, U16=None, SV16=None) -> Layer:
+    """Layer on 4-bit weights: Q [d_out, d_in] uint8 codes, S16 / Z [d_out, d_in / group_size]."""
+    Q = np.ascontiguousarray(Q)
+    Z = np.ascontiguousarray(Z)
+    S16 = _host16(S16, "S")
+    if Q.dtype != np.uint8 or Z.dtype != np.uint8:
+        raise TypeError("Q and Z must be uint8")
+    if group_size < 1 or cfg.d_in % group_size:
+        raise ValueError("group_size must divide d_in")
+    G = cfg.d_in // group_size
+    if Q.shape != (cfg.d_out, cfg.d_in) or S16.shape != (cfg.d_out, G) or Z.shape != (cfg.d_out, G):
+        raise ValueError("Q must be [d_out, d_in], S and Z [d_out, d_in / group_size]")
+    U16, SV16 = _host16(U16, "U"), _host16(SV16, "SV")
+    if cfg.rank > 0 and (U16 is None or SV16 is None or U16.shape != (cfg.d_out, cfg.rank)
+                         or SV16.shape != (cfg.rank, cfg.d_in)):
+        raise ValueError("U must be [d_out, rank] and SV [rank, d_in]")
+    h = C.c_void_p()
+    _check(load_library().rsparse_prepare_q4(C.byref(cfg), _hp(Q), _hp(S16), _hp(Z), group_size, _hp(U16), _hp(SV16),
+                                             C.byref(h)))
     return Layer(h, cfg)
 
 

@@ -134,6 +134,11 @@ struct rsparse_layer {
     uint16_t *xg = nullptr;                // [max_batch][d_in] gated input x = round16(silu(g) * u), written out per call
     size_t n_t = 0, n_y = 0;
     bool last_fused = false;
+    // 4-bit weights (rsparse_prepare_q4): codes, group scales, group zero points; M and Wrow stay null
+    uint8_t *Mq = nullptr, *qz = nullptr;
+    uint16_t *qs = nullptr;
+    int qshift = 0, qtiles = 0;
+    bool q4() const { return Mq != nullptr; }
     int tiles = 0, nz_max = 1;
     std::vector<uint16_t> U16, SV16;       // host copies of the stored factors
     hipStream_t last_stream = nullptr;
@@ -147,6 +152,7 @@ struct rsparse_layer {
         v.d_in = cfg.d_in; v.d_out = cfg.d_out; v.rank = cfg.rank;
         v.dtype = cfg.dtype; v.out_dtype = cfg.out_dtype; v.cmp_mode = cfg.cmp_mode;
         v.batch_mask_mode = cfg.batch_mask_mode; v.tau = cfg.tau;
+        v.Mq = Mq; v.qs = qs; v.qz = qz; v.qshift = qshift; v.qtiles = qtiles;
         return v;
     }
 };
@@ -247,11 +253,20 @@ void free_layer(rsparse_layer *L)
     (void)hipFree(L->M); (void)hipFree(L->SVt); (void)hipFree(L->U); (void)hipFree(L->Wrow); (void)hipFree(L->t);
     (void)hipFree(L->yacc); (void)hipFree(L->act_bits); (void)hipFree(L->chan_bits);
     (void)hipFree(L->act_list); (void)hipFree(L->act_count); (void)hipFree(L->sync); (void)hipFree(L->t_pub); (void)hipFree(L->xg); (void)hipFree(L->hy);
+    (void)hipFree(L->Mq); (void)hipFree(L->qs); (void)hipFree(L->qz);
     delete L;
 }
 
+// 4-bit weights as the caller hands them over (rsparse_prepare_q4); all host pointers.
+struct Q4Host {
+    const uint8_t *Q;        // [d_out][d_in] codes
+    const uint16_t *S16;     // [d_out][d_in / group]
+    const uint8_t *Z;        // [d_out][d_in / group]
+    int group;
+};
+
 rsparse_status build_layer(const rsparse_config *cfg, const uint16_t *W, const uint16_t *U16, const uint16_t *SV16,
-                           rsparse_layer **out)
+                           rsparse_layer **out, const Q4Host *q4 = nullptr)
 {
     rsparse_layer *L = new (std::nothrow) rsparse_layer();
     if (!L) return fail(RSPARSE_ENOMEM, "host allocation failed");
@@ -271,21 +286,54 @@ rsparse_status build_layer(const rsparse_config *cfg, const uint16_t *W, const u
         // one-launch kernel streams as r more channels
         std::vector<uint16_t> host;
         try {
-            host.resize((d_in + r) * d_out);
+            if (!q4) host.resize((d_in + r) * d_out);
             if (r) { L->U16.assign(U16, U16 + d_out * r); L->SV16.assign(SV16, SV16 + r * d_in); }
         } catch (const std::bad_alloc &) { return fail(RSPARSE_ENOMEM, "host allocation failed"); }
-        transpose16(W, d_out, d_in, host.data());
-        if (r) transpose16(U16, d_out, r, host.data() + d_in * d_out);
-
-        RS_HIP(hipMalloc((void **)&L->M, host.size() * 2));
-        RS_HIP(hipMemcpy(L->M, host.data(), host.size() * 2, hipMemcpyHostToDevice));
+        if (!q4) {
+            transpose16(W, d_out, d_in, host.data());
+            if (r) transpose16(U16, d_out, r, host.data() + d_in * d_out);
+            RS_HIP(hipMalloc((void **)&L->M, host.size() * 2));
+            RS_HIP(hipMemcpy(L->M, host.data(), host.size() * 2, hipMemcpyHostToDevice));
+        } else {
+            // codes channel-major in the lane order of the 4-bit kernel (layout: kernels.h), scales and zero
+            // points group-major in plain column order; rows padded to whole 1024-column tiles with zeros
+            L->qtiles = (int)((d_out + kQ4Tile - 1) / kQ4Tile);
+            L->qshift = 0;
+            while ((1 << L->qshift) < q4->group) ++L->qshift;
+            const size_t G = d_in >> L->qshift, ldq = (size_t)L->qtiles * (kQ4Tile / 2), lds = (size_t)L->qtiles * kQ4Tile;
+            std::vector<uint8_t> mq, zq;
+            std::vector<uint16_t> sq;
+            try {
+                mq.assign(d_in * ldq, 0); zq.assign(G * lds, 0); sq.assign(G * lds, 0);
+            } catch (const std::bad_alloc &) { return fail(RSPARSE_ENOMEM, "host allocation failed"); }
+            parallel_for(d_in, [&](size_t c) {
+                for (size_t o = 0; o < d_out; ++o) {
+                    const size_t T = o / kQ4Tile, within = o % kQ4Tile;
+                    const size_t h = within / 512, l = (within % 512) / 8, e = within % 8;
+                    const size_t byte = c * ldq + T * (kQ4Tile / 2) + l * 8 + h * 4 + (e & 3);
+                    const uint8_t code = q4->Q[o * d_in + c] & 15u;
+                    mq[byte] |= (uint8_t)(e < 4 ? code : code << 4);
+                }
+            });
+            for (size_t o = 0; o < d_out; ++o)
+                for (size_t g = 0; g < G; ++g) {
+                    sq[g * lds + o] = q4->S16[o * G + g];
+                    zq[g * lds + o] = q4->Z[o * G + g];
+                }
+            RS_HIP(hipMalloc((void **)&L->Mq, mq.size()));
+            RS_HIP(hipMemcpy(L->Mq, mq.data(), mq.size(), hipMemcpyHostToDevice));
+            RS_HIP(hipMalloc((void **)&L->qs, sq.size() * 2));
+            RS_HIP(hipMemcpy(L->qs, sq.data(), sq.size() * 2, hipMemcpyHostToDevice));
+            RS_HIP(hipMalloc((void **)&L->qz, zq.size()));
+            RS_HIP(hipMemcpy(L->qz, zq.data(), zq.size(), hipMemcpyHostToDevice));
+        }
         if (r) {
             RS_HIP(hipMalloc((void **)&L->SVt, r * d_in * 2));
             RS_HIP(hipMemcpy(L->SVt, SV16, r * d_in * 2, hipMemcpyHostToDevice));
             RS_HIP(hipMalloc((void **)&L->U, d_out * r * 2));
             RS_HIP(hipMemcpy(L->U, U16, d_out * r * 2, hipMemcpyHostToDevice));
         }
-        if (cfg->dense_rowmajor) {
+        if (cfg->dense_rowmajor && !q4) {
             RS_HIP(hipMalloc((void **)&L->Wrow, d_in * d_out * 2));
             RS_HIP(hipMemcpy(L->Wrow, W, d_in * d_out * 2, hipMemcpyHostToDevice));
         }
@@ -395,7 +443,74 @@ rsparse_status rsparse_prepare(const rsparse_config *cfg, const void *W_host, rs
     return build_layer(cfg, (const uint16_t *)W_host, U16.data(), SV16.data(), out);
 }
 
+rsparse_status rsparse_prepare_q4(const rsparse_config *cfg, const uint8_t *Q_host, const void *S16_host,
+                                  const uint8_t *Z_host, int32_t group_size, const void *U16_host,
+                                  const void *SV16_host, rsparse_layer **out)
+{
+    if (!out) return fail(RSPARSE_EINVAL, "out is NULL");
+    *out = nullptr;
+    rsparse_status st = check_config(cfg);
+    if (st != RSPARSE_OK) return st;
+    if (!Q_host || !S16_host || !Z_host) return fail(RSPARSE_EINVAL, "Q_host, S16_host and Z_host must be non-NULL");
+    if (cfg->rank > 0 && (!U16_host || !SV16_host)) return fail(RSPARSE_EINVAL, "factors are NULL but rank > 0");
+    if (group_size < 32 || group_size > 1024 || (group_size & (group_size - 1)) || cfg->d_in % group_size)
+        return fail(RSPARSE_EINVAL, "group_size must be a power of two in [32, 1024] that divides d_in (got %d)", group_size);
+    if (cfg->max_batch > 4) return fail(RSPARSE_EINVAL, "layers with 4-bit weights take at most 4 tokens (max_batch %d)", cfg->max_batch);
+    if (cfg->dense_rowmajor) return fail(RSPARSE_EINVAL, "dense_rowmajor is not available with 4-bit weights");
+    const size_t n = (size_t)cfg->d_in * cfg->d_out, ng = n / group_size;
+    for (size_t i = 0; i < n; ++i)
+        if (Q_host[i] > 15) return fail(RSPARSE_EINVAL, "code %u at %zu is not a 4-bit value", (unsigned)Q_host[i], i);
+    for (size_t i = 0; i < ng; ++i)
+        if (Z_host[i] > 15) return fail(RSPARSE_EINVAL, "zero point %u at %zu is not a 4-bit value", (unsigned)Z_host[i], i);
+    const Q4Host q4{Q_host, (const uint16_t *)S16_host, Z_host, group_size};
+    return build_layer(cfg, nullptr, (const uint16_t *)U16_host, (const uint16_t *)SV16_host, out, &q4);
+}
+
 namespace {
+
+// Launch shape of the 4-bit kernel: the weight stream is a quarter of the 16-bit one, so fewer, 4-wave
+// workgroups with longer contiguous runs (a wave folds scale and zero point once per quantisation group it meets).
+Launch resolve_launch_q4(const rsparse_layer *L, int batch, bool dense)
+{
+    Launch c{};
+    const rsparse_tuning &t = L->tuning;
+    const int bt = batch_tile_of(batch);
+    c.waves = (t.waves == 1 || t.waves == 2 || t.waves == 4 || t.waves == 8) ? t.waves : 4;
+    c.nontemporal = t.nontemporal == 2 ? 0 : 1;
+    c.tile_map = 1;
+    const int rows = dense ? L->cfg.d_in : std::max(8, L->cfg.d_in / 2);
+    int splits = t.splits;
+    if (splits <= 0) {
+        const int target_wgs = std::max(L->qtiles, 2 * L->cus);
+        splits = (target_wgs + L->qtiles - 1) / L->qtiles;
+        splits = std::max(1, std::min(splits, std::max(1, rows / (c.waves * 8))));      // >= 8 rows per wave
+    }
+    splits = std::min(splits, 4096);
+    while (gather_lds_bytes(L->cfg.d_in, splits, c.waves, bt) > 60 * 1024) splits *= 2;
+    c.splits = splits;
+    int lr = t.lowrank_rows;
+    if (lr <= 0) {
+        const double wg_bytes = (double)rows / splits * (kQ4Tile / 2);
+        lr = (int)(wg_bytes / (2.0 * L->cfg.d_in) + 0.5);
+        lr = std::max(lr, c.waves);                                                      // a row for every wave
+    }
+    c.lowrank_rows = std::max(1, std::min(lr, 4 * c.waves));
+    return c;
+}
+
+// One layer with 4-bit weights: first launch (codes dequantised in registers), then the common finish.
+rsparse_status linear_q4(rsparse_layer *L, const void *X_dev, int32_t batch, void *Y_dev, bool dense, hipStream_t s)
+{
+    const LayerView v = L->view();
+    const Launch lc = resolve_launch_q4(L, batch, dense);
+    const int stages = L->tuning.stages;
+    if (stages != 2) RS_HIP(launch_q4_sparse_and_t(v, lc, X_dev, batch, true, dense, s));
+    if (stages != 1) RS_HIP(launch_finish(&v, 1, batch, &Y_dev, !dense, s));
+    if (!dense) {
+        L->last_stream = s; L->last_batch = batch; L->last_mfma = false; L->last_fused = false;
+    }
+    return RSPARSE_OK;
+}
 
 rsparse_status check_group(rsparse_layer *const *layers, int32_t n, const void *X, int32_t batch, void *const *Y)
 {
@@ -452,6 +567,21 @@ rsparse_status linear_group_impl(rsparse_layer *const *layers, int32_t n_layers,
     rsparse_status st = check_group(layers, n_layers, X_dev, batch, Y_devs);
     if (st != RSPARSE_OK) return st;
     hipStream_t s = (hipStream_t)stream;
+    bool any_q4 = false;
+    for (int i = 0; i < n_layers; ++i) any_q4 = any_q4 || layers[i]->q4();
+    if (any_q4) {
+        // layers with 4-bit weights run one at a time, each in its own pair of launches
+        if (G_dev) {
+            RS_HIP(launch_gated_input(G_dev, X_dev, layers[0]->xg, (size_t)batch * layers[0]->cfg.d_in, layers[0]->cfg.dtype, s));
+            X_dev = layers[0]->xg;
+        }
+        for (int i = 0; i < n_layers; ++i) {
+            rsparse_status qs = layers[i]->q4() ? linear_q4(layers[i], X_dev, batch, Y_devs[i], false, s)
+                                                : linear_group_impl(&layers[i], 1, X_dev, nullptr, batch, &Y_devs[i], stream);
+            if (qs != RSPARSE_OK) return qs;
+        }
+        return RSPARSE_OK;
+    }
     LayerView v[RSPARSE_MAX_GROUP];
     Launch lc[RSPARSE_MAX_GROUP];
     const int stages = layers[0]->tuning.stages;
@@ -511,7 +641,7 @@ rsparse_status rsparse_mlp_gate_up(rsparse_layer *gate, rsparse_layer *up, const
     for (int i = 0; i < 2; ++i) mfma = mfma && mfma_path_supported(v[i], batch);
     const int bt = batch_tile_of(batch);
     const bool one_tile = (batch + bt - 1) / bt == 1;
-    if (fused && !mfma && one_tile && lc[0].tile_map != 2 && lc[1].tile_map != 2) {
+    if (fused && !mfma && one_tile && lc[0].tile_map != 2 && lc[1].tile_map != 2 && !gate->q4() && !up->q4()) {
         // both projections and the activation in one launch: the last workgroup of a column tile
         // rounds g and u, applies silu(g) * u and stores H
         RS_HIP(launch_fused(v, lc, 2, X_dev, batch, outs, s, true));
@@ -539,6 +669,16 @@ rsparse_status rsparse_dense_ref_group(rsparse_layer *const *layers, int32_t n_l
     rsparse_status st = check_group(layers, n_layers, X_dev, batch, Y_devs);
     if (st != RSPARSE_OK) return st;
     hipStream_t s = (hipStream_t)stream;
+    bool any_q4 = false;
+    for (int i = 0; i < n_layers; ++i) any_q4 = any_q4 || layers[i]->q4();
+    if (any_q4) {
+        for (int i = 0; i < n_layers; ++i) {
+            rsparse_status qs = layers[i]->q4() ? linear_q4(layers[i], X_dev, batch, Y_devs[i], true, s)
+                                                : rsparse_dense_ref_group(&layers[i], 1, X_dev, batch, &Y_devs[i], stream);
+            if (qs != RSPARSE_OK) return qs;
+        }
+        return RSPARSE_OK;
+    }
     LayerView v[RSPARSE_MAX_GROUP];
     Launch lc[RSPARSE_MAX_GROUP];
     bool can_rowdot = true;
@@ -716,6 +856,11 @@ size_t rsparse_required_bytes(const rsparse_layer *L, int32_t batch, int32_t k_u
     if (!L || batch < 1 || k_union < 0) return 0;
     const size_t e = 2, d_in = L->cfg.d_in, d_out = L->cfg.d_out, r = L->cfg.rank, B = batch, k = k_union;
     const size_t eo = L->cfg.out_dtype == RSPARSE_F32 ? 4 : 2;
+    if (L->q4()) {
+        // half a byte per kept weight; scale (2 bytes) and zero point (half a byte) of every group that holds a kept channel (at most all)
+        const size_t groups = std::min<size_t>(d_in >> L->qshift, k);
+        return k * d_out / 2 + groups * d_out * 5 / 2 + e * (r * d_out + r * d_in + B * d_in) + eo * B * d_out;
+    }
     return e * (k * d_out + r * d_out + r * d_in + B * d_in) + eo * B * d_out;
 }
 
@@ -724,6 +869,7 @@ size_t rsparse_dense_bytes(const rsparse_layer *L, int32_t batch)
     if (!L || batch < 1) return 0;
     const size_t e = 2, d_in = L->cfg.d_in, d_out = L->cfg.d_out, B = batch;
     const size_t eo = L->cfg.out_dtype == RSPARSE_F32 ? 4 : 2;
+    if (L->q4()) return d_in * d_out / 2 + (d_in >> L->qshift) * d_out * 5 / 2 + e * B * d_in + eo * B * d_out;
     return e * (d_in * d_out + B * d_in) + eo * B * d_out;
 }
 

@@ -27,6 +27,13 @@ struct LayerView {
     int32_t *act_count;     // [nz]
     int *sync;              // arrival counters of the one-launch path (layout: kSync* below); zero between calls
     uint32_t *t_pub;        // [nz][BT][rank] one-launch path: t as fp32 bits; all-ones (not ready) between calls
+    // 4-bit weights (Mq != nullptr; then M and Wrow are null).  A column tile is kQ4Tile = 1024 outputs: lane l
+    // of a wave owns the 8 bytes T * 512 + l * 8 .. of a row, two words h = 0, 1; byte k of word h holds the
+    // code of column T * 1024 + h * 512 + l * 8 + k in its low nibble and of column ... + 4 + k in its high one.
+    const uint8_t *Mq;      // [d_in][qtiles * 512] bytes, row c = the codes of W[:, c]
+    const uint16_t *qs;     // [d_in >> qshift][qtiles * 1024] group scales, 16-bit of dtype, plain column order
+    const uint8_t *qz;      // [d_in >> qshift][qtiles * 1024] group zero points, one per byte
+    int qshift, qtiles;     // log2(group size); column tiles of 1024
     int d_in, d_out, rank;
     int dtype, out_dtype, cmp_mode, batch_mask_mode;
     float tau;
@@ -65,6 +72,13 @@ hipError_t launch_sparse_and_t(const LayerView *L, const Launch *cfg, int n, con
 // stores H = round(silu(round(g)) * round(u)) to Y[0] instead of the two outputs (Y[1] is not written).
 hipError_t launch_fused(const LayerView *L, const Launch *cfg, int n, const void *X, int batch, void *const *Y,
                         hipStream_t stream, bool gate_up = false);
+// First launch of a layer with 4-bit weights (at most 4 tokens): as launch_sparse_and_t, with the codes
+// dequantised in registers -- per quantisation group the kernel accumulates sum_c x_c q_c and sum_c x_c and
+// applies scale and zero point once, when the group ends.  dense: every channel is kept (the dense baseline
+// on the same weights).  launch_finish completes the layer.
+constexpr int kQ4Tile = 1024;
+hipError_t launch_q4_sparse_and_t(const LayerView &L, const Launch &cfg, const void *X, int batch, bool with_t,
+                                  bool dense, hipStream_t stream);
 // Second launch: Y = round(yacc + U_r t) (use_rank) or round(yacc); re-zeroes yacc.
 hipError_t launch_finish(const LayerView *L, int n, int batch, void *const *Y, bool use_rank, hipStream_t stream);
 // Dense baselines.

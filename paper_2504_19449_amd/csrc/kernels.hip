@@ -231,6 +231,7 @@ struct GatherArgs {
     int nz;                            // one-launch path only: batch tiles in the grid
     int wait_polls;                    // one-launch path only: bound on re-reads of a t entry that is not ready
     int skip_stage1;                   // test hook: the stage-1 workgroups publish nothing (exercises the bound)
+    int dense;                         // 4-bit kernel only: keep every channel (the dense baseline)
 };
 
 // t_pub entries hold this pattern until the stage-1 workgroups have written them.  No computed
@@ -414,6 +415,125 @@ __device__ __forceinline__ void lowrank_rows(const GatherArgs &a, unsigned char 
 }
 
 // ---------------------------------------------------------------------------------------------
+// 4-bit weights (Sec. 4.4: R-Sparse on GPTQ weights, groups of 128 input channels): W~[o][c] =
+// s[o][g] (q[o][c] - z[o][g]).  A wave streams a CONTIGUOUS run of its workgroup's kept-channel list, so
+// the channels of one quantisation group arrive together: it accumulates grp = sum_c x_c q_c and
+// sumx = sum_c x_c while the group lasts and folds acc += s (grp - z sumx) once when it ends -- the
+// codes go from nibble to float and into one FMA per token, nothing else per weight.  Scale and zero
+// point of a group are requested when the group opens and used when it closes.
+// A lane owns 16 output columns of a 1024-column tile: 8 bytes per row, words h = 0, 1 (layout: kernels.h).
+// ---------------------------------------------------------------------------------------------
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+template <bool NT>
+__device__ __forceinline__ u32x2 ldg8(const uint8_t *p)
+{
+    const u32x2 *q = reinterpret_cast<const u32x2 *>(p);
+    return NT ? __builtin_nontemporal_load(q) : *q;
+}
+
+template <bool NT>
+__device__ __forceinline__ void load_batch_q4(const uint8_t *__restrict__ Mq, size_t ld, int off, bool ok,
+                                              const int *s_idx, int j_hi, int j0, u32x2 (&v)[kUnroll])
+{
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        v[u] = u32x2{0u, 0u};
+        if (j0 + u < j_hi) {
+            const int idx = uniform(s_idx[j0 + u]);
+            if (ok) v[u] = ldg8<NT>(Mq + (size_t)idx * ld + off);
+        }
+    }
+}
+
+// The eight codes of one word as floats: element e < 4 is the low nibble of byte e, element 4 + e its high nibble.
+__device__ __forceinline__ void codes8(uint32_t w, float (&f)[8])
+{
+    const uint32_t lo = w & 0x0f0f0f0fu, hi = (w >> 4) & 0x0f0f0f0fu;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        f[k] = (float)((lo >> (8 * k)) & 0xffu);
+        f[4 + k] = (float)((hi >> (8 * k)) & 0xffu);
+    }
+}
+
+template <int BT>
+struct Q4State {
+    float acc[2][BT][8];    // finished groups, scaled
+    float grp[2][BT][8];    // sum_c x_c q_c of the open group
+    float sumx[BT];         // sum_c x_c of the open group
+    u32x4 sv[2];            // scales of the open group, 8 columns per word h
+    u32x2 zv[2];            // its zero points, one byte per column
+    int g;                  // the open group, -1 = none
+};
+
+template <int BT>
+__device__ __forceinline__ void q4_open(Q4State<BT> &st, const LayerView &L, int g, int colq, bool ok)
+{
+    st.g = g;
+    const size_t at = (size_t)g * ((size_t)L.qtiles * kQ4Tile) + colq;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        st.sv[h] = ok ? *reinterpret_cast<const u32x4 *>(L.qs + at + h * 512) : u32x4{0, 0, 0, 0};
+        st.zv[h] = ok ? *reinterpret_cast<const u32x2 *>(L.qz + at + h * 512) : u32x2{0, 0};
+    }
+}
+
+template <int DT, int BT>
+__device__ __forceinline__ void q4_close(Q4State<BT> &st)
+{
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        float sf[8];
+        unpack8<DT>(st.sv[h], sf);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t zw = st.zv[h][e >> 2];
+            const float zf = (float)((zw >> (8 * (e & 3))) & 0xffu);
+#pragma unroll
+            for (int b = 0; b < BT; ++b) {
+                const float d = __builtin_fmaf(-zf, st.sumx[b], st.grp[h][b][e]);
+                st.acc[h][b][e] = __builtin_fmaf(sf[e], d, st.acc[h][b][e]);
+                st.grp[h][b][e] = 0.f;
+            }
+        }
+    }
+#pragma unroll
+    for (int b = 0; b < BT; ++b) st.sumx[b] = 0.f;
+}
+
+template <int DT, int BT>
+__device__ __forceinline__ void q4_consume(Q4State<BT> &st, const LayerView &L, const u32x2 (&v)[kUnroll],
+                                           const int *s_idx, const float *s_coef, int j_hi, int j0, int colq, bool ok)
+{
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        if (j0 + u < j_hi) {
+            const int g = uniform(s_idx[j0 + u]) >> L.qshift;
+            if (g != st.g) {
+                if (st.g >= 0) q4_close<DT, BT>(st);
+                q4_open<BT>(st, L, g, colq, ok);
+            }
+            float cf[BT];
+#pragma unroll
+            for (int b = 0; b < BT; ++b) {
+                cf[b] = uniform(s_coef[(j0 + u) * BT + b]);
+                st.sumx[b] += cf[b];
+            }
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                float f[8];
+                codes8(v[u][h], f);
+#pragma unroll
+                for (int b = 0; b < BT; ++b)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) st.grp[h][b][e] = __builtin_fmaf(cf[b], f[e], st.grp[h][b][e]);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // First launch of the layer.  Workgroups [0, lr_wgs) compute stage 1 of the low-rank part; the
 // others do steps 1-2 of the sparse part: sparsification mask and ascending kept-channel list
 // (Sec. 3.4, sigma_t) -- every workgroup scans the whole token and keeps its balanced share --
@@ -421,7 +541,7 @@ __device__ __forceinline__ void lowrank_rows(const GatherArgs &a, unsigned char 
 // The two groups are independent, so they share one launch.
 // grid.x = lr_wgs + tiles * splits, grid.z = batch tiles of BT tokens, block = 64 * waves.
 // ---------------------------------------------------------------------------------------------
-template <int DT, int BT, bool NT, bool FUSED>
+template <int DT, int BT, bool NT, bool FUSED, bool Q4 = false>
 __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *smem)
 {
     const int z = blockIdx.z;
@@ -458,7 +578,8 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
             const int q = q0 + p * nthr;
             if (q < nq) {
                 uint32_t m[BT];
-                s_u[q] = (uint8_t)masks_of8<DT, BT>(a.X, a.batch, b0, nb, d_in, q * 8, L.tau, L.cmp_mode, union_all, raw[p], m);
+                const uint32_t kept = masks_of8<DT, BT>(a.X, a.batch, b0, nb, d_in, q * 8, L.tau, L.cmp_mode, union_all, raw[p], m);
+                s_u[q] = (Q4 && a.dense) ? (uint8_t)0xffu : (uint8_t)kept;
             }
         }
     }
@@ -506,7 +627,15 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
         for (int e = 0; e < 8; ++e) acc[b][e] = 0.f;
     u32x4 va[kUnroll];
     const int j_first = w * kUnroll, step = nw * kUnroll;
-    load_batch<NT>(L.M, (size_t)d_out, col, colok, s.idx, n_all, j_first, va);
+    // 4-bit weights: this wave's contiguous run [jq_lo, jq_hi) of the list, 8 bytes per lane and row
+    const int jq_lo = (int)(((long long)w * n) / nw), jq_hi = (int)(((long long)(w + 1) * n) / nw);
+    const int colq = tile * kQ4Tile + lane * 8;
+    const bool okq = colq < d_out;
+    const size_t ldq = (size_t)L.qtiles * (kQ4Tile / 2);
+    const int offq = tile * (kQ4Tile / 2) + lane * 8;
+    u32x2 qa[kUnroll];
+    if constexpr (Q4) load_batch_q4<NT>(L.Mq, ldq, offq, okq, s.idx, jq_hi, jq_lo, qa);
+    else load_batch<NT>(L.M, (size_t)d_out, col, colok, s.idx, n_all, j_first, va);
 
     // ---- ... and fetch the coefficients x[b, c] * m[b, c] of my rows while those loads fly
     for (int j = tid; j < n; j += nthr) {
@@ -519,7 +648,7 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
             if (b < nb) {
                 const uint16_t h = a.X[(size_t)(b0 + b) * d_in + c];
                 xf = (DT == F16) ? (float)__builtin_bit_cast(_Float16, h) : as_f((uint32_t)h << 16);
-                kb = union_all ? true : keep(xf, L.tau, L.cmp_mode);
+                kb = (union_all || (Q4 && a.dense)) ? true : keep(xf, L.tau, L.cmp_mode);
             }
             s.coef[j * BT + b] = kb ? xf : 0.f;
             bits |= (uint32_t)kb << b;
@@ -530,6 +659,36 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
         }
     }
     __syncthreads();
+
+    if constexpr (Q4) {
+        Q4State<BT> st;
+        st.g = -1;
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int b = 0; b < BT; ++b)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) { st.acc[h][b][e] = 0.f; st.grp[h][b][e] = 0.f; }
+#pragma unroll
+        for (int b = 0; b < BT; ++b) st.sumx[b] = 0.f;
+        u32x2 qb[kUnroll];
+        int j0 = jq_lo;
+        while (j0 < jq_hi) {
+            load_batch_q4<NT>(L.Mq, ldq, offq, okq, s.idx, jq_hi, j0 + kUnroll, qb);
+            q4_consume<DT, BT>(st, L, qa, s.idx, s.coef, jq_hi, j0, colq, okq);
+            j0 += kUnroll;
+            if (j0 >= jq_hi) break;
+            load_batch_q4<NT>(L.Mq, ldq, offq, okq, s.idx, jq_hi, j0 + kUnroll, qa);
+            q4_consume<DT, BT>(st, L, qb, s.idx, s.coef, jq_hi, j0, colq, okq);
+            j0 += kUnroll;
+        }
+        if (st.g >= 0) q4_close<DT, BT>(st);
+        // the two 512-column halves of the tile go through the 16-bit path's reduction one after the other
+        reduce_to_yacc<BT>(st.acc[0], s.red, L.yacc, b0, nb, d_out, tile * 2);
+        __syncthreads();
+        reduce_to_yacc<BT>(st.acc[1], s.red, L.yacc, b0, nb, d_out, tile * 2 + 1);
+        return;
+    }
 
     if (!FUSED) {
         stream_rest<DT, BT, NT>(L.M, (size_t)d_out, col, colok, s.idx, s.coef, n, j_first, step, va, acc, [](int) {});
@@ -647,6 +806,14 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
             reset_t(L.t_pub, L.rank);
         }
     }
+}
+
+// 4-bit weights, up to 4 tokens: the same scan, list and stage-1 workgroups, the weight stream as above.
+template <int DT, int BT, bool NT>
+__global__ __launch_bounds__(512) void k_q4_sparse_and_t(const GroupArgs ga)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    sparse_body<DT, BT, NT, false, true>(ga, smem);
 }
 
 // Eight tokens of accumulators need the full register file: 4 waves per workgroup, one per SIMD.
@@ -1019,6 +1186,48 @@ hipError_t launch_sparse_and_t(const LayerView *L, const Launch *cfg, int n, con
     })
     if (L[0].dtype == F16) { RS_G(F16) } else { RS_G(BF16) }
 #undef RS_G
+    return hipGetLastError();
+}
+
+hipError_t launch_q4_sparse_and_t(const LayerView &L, const Launch &cfg, const void *X, int batch, bool with_t,
+                                  bool dense, hipStream_t stream)
+{
+    if (!L.Mq || !L.qs || !L.qz || batch < 1 || batch > 4 || L.qshift < 3 || (L.d_in >> L.qshift) < 1 ||
+        ((L.d_in >> L.qshift) << L.qshift) != L.d_in || L.qtiles != (L.d_out + kQ4Tile - 1) / kQ4Tile ||
+        cfg.splits < 1 || cfg.lowrank_rows < 1 || cfg.lowrank_rows > kRowsPerWave * cfg.waves)
+        return hipErrorInvalidValue;
+    const int bt = batch_tile(batch);
+    GroupArgs ga{};
+    ga.n = 1;
+    GatherArgs &a = ga.job[0];
+    a.L = L; a.X = (const uint16_t *)X; a.batch = batch; a.splits = cfg.splits; a.tiles = L.qtiles;
+    a.cap = gather_cap(L.d_in, cfg.splits);
+    a.lr_rows = cfg.lowrank_rows;
+    a.lr_wgs = (with_t && !dense && L.rank > 0) ? (L.rank + cfg.lowrank_rows - 1) / cfg.lowrank_rows : 0;
+    a.lr_chunk = lowrank_chunk(L.d_in, bt);
+    a.tile_map = 1;
+    a.dense = dense ? 1 : 0;
+    const int total = a.lr_wgs + L.qtiles * cfg.splits;
+    for (int i = 0; i < kMaxGroup; ++i) ga.wg_end[i] = total;
+    size_t lds = gather_lds_bytes(L.d_in, cfg.splits, cfg.waves, bt);
+    if (a.lr_wgs > 0) lds = std::max(lds, lowrank_lds_bytes(L.d_in, bt));
+    if (lds > 64 * 1024) return hipErrorInvalidValue;
+    dim3 grid(total, 1, 1), block(kWave * cfg.waves);
+    const bool nt = cfg.nontemporal != 0;
+#define RS_Q(DT)                                                                                         \
+    switch (bt) {                                                                                        \
+    case 1: if (nt) hipLaunchKernelGGL((k_q4_sparse_and_t<DT, 1, true>), grid, block, lds, stream, ga);  \
+            else hipLaunchKernelGGL((k_q4_sparse_and_t<DT, 1, false>), grid, block, lds, stream, ga);    \
+            break;                                                                                       \
+    case 2: if (nt) hipLaunchKernelGGL((k_q4_sparse_and_t<DT, 2, true>), grid, block, lds, stream, ga);  \
+            else hipLaunchKernelGGL((k_q4_sparse_and_t<DT, 2, false>), grid, block, lds, stream, ga);    \
+            break;                                                                                       \
+    default: if (nt) hipLaunchKernelGGL((k_q4_sparse_and_t<DT, 4, true>), grid, block, lds, stream, ga); \
+             else hipLaunchKernelGGL((k_q4_sparse_and_t<DT, 4, false>), grid, block, lds, stream, ga);   \
+             break;                                                                                      \
+    }
+    if (L.dtype == F16) { RS_Q(F16) } else { RS_Q(BF16) }
+#undef RS_Q
     return hipGetLastError();
 }
 

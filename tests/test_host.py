@@ -16,7 +16,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "rsparse.h")).read()
-    declared = sorted(set(re.findall(r"\b(rsparse_[a-z_]+)\s*\(", header)))
+    declared = sorted(set(re.findall(r"\b(rsparse_[a-z0-9_]+)\s*\(", header)))
     lib = rs.load_library()
     assert declared, "no declarations found"
     for name in declared:
@@ -157,3 +157,30 @@ def test_recipe_search_matches_the_oracle_bit_for_bit():
     assert got[0].tolist() == want[0] and got[2].tolist() == want[2]
     with pytest.raises(rs.RSparseError):
         rs.rsparse_search_recipe(lambda r: 0.0, 0)
+
+
+@pytest.mark.parametrize("bad", [
+    dict(group=48), dict(group=16), dict(group=2048), dict(group=256, d_in=384), dict(max_batch=5),
+    dict(dense_rowmajor=1), dict(code=16), dict(zero=16), dict(null="Q"), dict(null="S"), dict(null="Z"),
+])
+def test_q4_argument_validation(bad):
+    """Every check of rsparse_prepare_q4 happens before the first device call, so it is testable here."""
+    import ctypes as C
+    d_in, d_out, group = bad.get("d_in", 256), 16, bad.get("group", 128)
+    cfg = rs.make_config(d_in, d_out, 0, 0.5, rs.F16, max_batch=bad.get("max_batch", 1),
+                         dense_rowmajor=bad.get("dense_rowmajor", 0))
+    G = max(1, d_in // group)
+    Q = np.zeros((d_out, d_in), dtype=np.uint8)
+    S = np.zeros((d_out, G), dtype=np.uint16)
+    Z = np.zeros((d_out, G), dtype=np.uint8)
+    if "code" in bad:
+        Q[3, 5] = bad["code"]
+    if "zero" in bad:
+        Z[2, 0] = bad["zero"]
+    ptr = {k: v.ctypes.data_as(C.c_void_p) for k, v in (("Q", Q), ("S", S), ("Z", Z))}
+    if "null" in bad:
+        ptr[bad["null"]] = None
+    h = C.c_void_p()
+    st = rs.load_library().rsparse_prepare_q4(C.byref(cfg), ptr["Q"], ptr["S"], ptr["Z"], group, None, None, C.byref(h))
+    assert st == 1 and h.value is None
+    assert rs.rsparse_last_error()
