@@ -476,6 +476,7 @@ Launch resolve_launch_q4(const rsparse_layer *L, int batch, bool dense)
     const rsparse_tuning &t = L->tuning;
     const int bt = batch_tile_of(batch);
     c.waves = (t.waves == 1 || t.waves == 2 || t.waves == 4 || t.waves == 8) ? t.waves : 4;
+    if (bt >= 4 && c.waves > 4) c.waves = 4;         // the 4-token kernel is built for at most 256 lanes
     c.nontemporal = t.nontemporal == 2 ? 0 : 1;
     c.tile_map = 1;
     const int rows = dense ? L->cfg.d_in : std::max(8, L->cfg.d_in / 2);

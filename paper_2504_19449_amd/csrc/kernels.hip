@@ -289,6 +289,17 @@ __device__ __forceinline__ int find_job(const int (&wg_end)[kMaxGroup], int n, i
     return li;
 }
 
+// Balanced share [lo, hi) of n items for part p of `parts`: the first n % parts shares hold one item more.
+// 32-bit arithmetic on wave-uniform values -- a 64-bit division is some 200 emulated instructions here,
+// and it sat on every workgroup's path to its first weight load.
+__device__ __forceinline__ void balanced_share(int n, int parts, int p, int &lo, int &hi)
+{
+    const unsigned un = (unsigned)uniform(n), up = (unsigned)uniform(parts), pp = (unsigned)uniform(p);
+    const unsigned base = un / up, rem = un - base * up;
+    lo = (int)(pp * base + min(pp, rem));
+    hi = lo + (int)base + (pp < rem ? 1 : 0);
+}
+
 // LDS carve-up of the gather part.
 struct GatherLds {
     int *idx;
@@ -424,6 +435,11 @@ __device__ __forceinline__ void lowrank_rows(const GatherArgs &a, unsigned char 
 // A lane owns 16 output columns of a 1024-column tile: 8 bytes per row, words h = 0, 1 (layout: kernels.h).
 // ---------------------------------------------------------------------------------------------
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+// A batch of kUnroll rows as one register vector (word 2u + h = word h of row u): the rolled loop below
+// picks a row by a run-time index, which the compiler serves with relative register addressing on a
+// vector type (an array would go to scratch memory).
+typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+static_assert(kUnroll == 8, "u32x16 holds 8 rows of two words");
 
 template <bool NT>
 __device__ __forceinline__ u32x2 ldg8(const uint8_t *p)
@@ -432,17 +448,21 @@ __device__ __forceinline__ u32x2 ldg8(const uint8_t *p)
     return NT ? __builtin_nontemporal_load(q) : *q;
 }
 
+// kUnroll rows starting at list position j0 of a non-empty run that ends at j_hi.  Positions past the end
+// re-read the run's last row (a cache hit) and are given a zero coefficient by the consumer, so that a batch
+// is always eight unconditional loads: the compiler can then count outstanding loads exactly and lets the
+// next batch stay in flight while this one is consumed.  Rows and the scale / zero-point rows are padded
+// to whole tiles, so lanes past d_out read zeros instead of being masked off.
 template <bool NT>
-__device__ __forceinline__ void load_batch_q4(const uint8_t *__restrict__ Mq, size_t ld, int off, bool ok,
-                                              const int *s_idx, int j_hi, int j0, u32x2 (&v)[kUnroll])
+__device__ __forceinline__ void load_batch_q4(const uint8_t *__restrict__ Mq, size_t ld, int off, const int *s_idx,
+                                              int j_hi, int j0, u32x16 &v)
 {
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
-        v[u] = u32x2{0u, 0u};
-        if (j0 + u < j_hi) {
-            const int idx = uniform(s_idx[j0 + u]);
-            if (ok) v[u] = ldg8<NT>(Mq + (size_t)idx * ld + off);
-        }
+        const int idx = uniform(s_idx[min(j0 + u, j_hi - 1)]);
+        const u32x2 w = ldg8<NT>(Mq + (size_t)idx * ld + off);
+        v[2 * u] = w[0];
+        v[2 * u + 1] = w[1];
     }
 }
 
@@ -468,14 +488,14 @@ struct Q4State {
 };
 
 template <int BT>
-__device__ __forceinline__ void q4_open(Q4State<BT> &st, const LayerView &L, int g, int colq, bool ok)
+__device__ __forceinline__ void q4_open(Q4State<BT> &st, const LayerView &L, int g, int colq)
 {
     st.g = g;
     const size_t at = (size_t)g * ((size_t)L.qtiles * kQ4Tile) + colq;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-        st.sv[h] = ok ? *reinterpret_cast<const u32x4 *>(L.qs + at + h * 512) : u32x4{0, 0, 0, 0};
-        st.zv[h] = ok ? *reinterpret_cast<const u32x2 *>(L.qz + at + h * 512) : u32x2{0, 0};
+        st.sv[h] = *reinterpret_cast<const u32x4 *>(L.qs + at + h * 512);
+        st.zv[h] = *reinterpret_cast<const u32x2 *>(L.qz + at + h * 512);
     }
 }
 
@@ -502,33 +522,50 @@ __device__ __forceinline__ void q4_close(Q4State<BT> &st)
     for (int b = 0; b < BT; ++b) st.sumx[b] = 0.f;
 }
 
-template <int DT, int BT>
-__device__ __forceinline__ void q4_consume(Q4State<BT> &st, const LayerView &L, const u32x2 (&v)[kUnroll],
-                                           const int *s_idx, const float *s_coef, int j_hi, int j0, int colq, bool ok)
+// One row: its 16 codes times the token coefficients, into the open group's sums.
+template <int BT>
+__device__ __forceinline__ void q4_row(Q4State<BT> &st, const u32x2 w, const float *s_coef, int j, int j_hi)
 {
+    float cf[BT];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-        if (j0 + u < j_hi) {
+    for (int b = 0; b < BT; ++b) {
+        cf[b] = uniform(s_coef[min(j, j_hi - 1) * BT + b]);
+        cf[b] = j < j_hi ? cf[b] : 0.f;
+        st.sumx[b] += cf[b];
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        float f[8];
+        codes8(w[h], f);
+#pragma unroll
+        for (int b = 0; b < BT; ++b)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) st.grp[h][b][e] = __builtin_fmaf(cf[b], f[e], st.grp[h][b][e]);
+    }
+}
+
+// A batch of up to kUnroll rows.  The list is ascending, so when its first and last row lie in the open
+// group all of them do: that common case is straight-line code.  A batch that crosses a group boundary
+// takes the rolled loop, which holds the only copy of the fold (close) and of the scale request (open).
+template <int DT, int BT>
+__device__ __forceinline__ void q4_consume(Q4State<BT> &st, const LayerView &L, const u32x16 &v,
+                                           const int *s_idx, const float *s_coef, int j_hi, int j0, int colq)
+{
+    const int j_last = min(j0 + kUnroll, j_hi) - 1;
+    const int g_first = uniform(s_idx[j0]) >> L.qshift, g_last = uniform(s_idx[j_last]) >> L.qshift;
+    if (g_first == st.g && g_last == st.g) {
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) q4_row<BT>(st, u32x2{v[2 * u], v[2 * u + 1]}, s_coef, j0 + u, j_hi);
+    } else {
+#pragma unroll 1
+        for (int u = 0; u < kUnroll; ++u) {
+            if (j0 + u >= j_hi) break;
             const int g = uniform(s_idx[j0 + u]) >> L.qshift;
             if (g != st.g) {
                 if (st.g >= 0) q4_close<DT, BT>(st);
-                q4_open<BT>(st, L, g, colq, ok);
+                q4_open<BT>(st, L, g, colq);
             }
-            float cf[BT];
-#pragma unroll
-            for (int b = 0; b < BT; ++b) {
-                cf[b] = uniform(s_coef[(j0 + u) * BT + b]);
-                st.sumx[b] += cf[b];
-            }
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                float f[8];
-                codes8(v[u][h], f);
-#pragma unroll
-                for (int b = 0; b < BT; ++b)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) st.grp[h][b][e] = __builtin_fmaf(cf[b], f[e], st.grp[h][b][e]);
-            }
+            q4_row<BT>(st, u32x2{v[2 * u], v[2 * u + 1]}, s_coef, j0 + u, j_hi);
         }
     }
 }
@@ -594,8 +631,8 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
     int pos = block_exclusive_scan(cnt, s.misc, k);
 
     // ---- my balanced share [lo, hi) of the ascending kept list
-    const int lo = (int)(((long long)split * k) / a.splits);
-    const int hi = (int)(((long long)(split + 1) * k) / a.splits);
+    int lo, hi;
+    balanced_share(k, a.splits, split, lo, hi);
     const int n = hi - lo;
     if (cnt > 0 && pos < hi && pos + cnt > lo) {
         for (int q = q_begin; q < q_end; ++q) {
@@ -611,8 +648,8 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
     // ---- one launch: my share of the rows of U_r^T follows the kept channels as rows d_in + j of M
     int n_all = n;
     if (FUSED) {
-        const int r_lo = (int)(((long long)split * L.rank) / a.splits);
-        const int r_hi = (int)(((long long)(split + 1) * L.rank) / a.splits);
+        int r_lo, r_hi;
+        balanced_share(L.rank, a.splits, split, r_lo, r_hi);
         for (int i = tid; i < r_hi - r_lo; i += nthr) s.idx[n + i] = d_in + r_lo + i;
         n_all = n + (r_hi - r_lo);
     }
@@ -628,14 +665,28 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
     u32x4 va[kUnroll];
     const int j_first = w * kUnroll, step = nw * kUnroll;
     // 4-bit weights: this wave's contiguous run [jq_lo, jq_hi) of the list, 8 bytes per lane and row
-    const int jq_lo = (int)(((long long)w * n) / nw), jq_hi = (int)(((long long)(w + 1) * n) / nw);
+    // (wave index and row count go through readfirstlane: the compiler cannot know they are wave-uniform, and
+    //  would otherwise run the row loop and the group tests under execution masks)
+    const int wq = uniform(w), nq_rows = uniform(n);
+    int jq_lo, jq_hi;
+    balanced_share(nq_rows, nw, wq, jq_lo, jq_hi);
     const int colq = tile * kQ4Tile + lane * 8;
-    const bool okq = colq < d_out;
     const size_t ldq = (size_t)L.qtiles * (kQ4Tile / 2);
     const int offq = tile * (kQ4Tile / 2) + lane * 8;
-    u32x2 qa[kUnroll];
-    if constexpr (Q4) load_batch_q4<NT>(L.Mq, ldq, offq, okq, s.idx, jq_hi, jq_lo, qa);
-    else load_batch<NT>(L.M, (size_t)d_out, col, colok, s.idx, n_all, j_first, va);
+    u32x16 qa, qb;
+    Q4State<Q4 ? BT : 1> st;
+    if constexpr (Q4) {
+        st.g = -1;
+        if (jq_lo < jq_hi) {
+            // two batches of rows and the first group's scale and zero point are requested before the
+            // coefficients are fetched: a wave with up to 16 rows has everything in flight at once
+            load_batch_q4<NT>(L.Mq, ldq, offq, s.idx, jq_hi, jq_lo, qa);
+            load_batch_q4<NT>(L.Mq, ldq, offq, s.idx, jq_hi, jq_lo + kUnroll, qb);
+            q4_open<BT>(st, L, uniform(s.idx[jq_lo]) >> L.qshift, colq);
+        }
+    } else {
+        load_batch<NT>(L.M, (size_t)d_out, col, colok, s.idx, n_all, j_first, va);
+    }
 
     // ---- ... and fetch the coefficients x[b, c] * m[b, c] of my rows while those loads fly
     for (int j = tid; j < n; j += nthr) {
@@ -661,8 +712,6 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
     __syncthreads();
 
     if constexpr (Q4) {
-        Q4State<BT> st;
-        st.g = -1;
 #pragma unroll
         for (int h = 0; h < 2; ++h)
 #pragma unroll
@@ -671,16 +720,13 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
                 for (int e = 0; e < 8; ++e) { st.acc[h][b][e] = 0.f; st.grp[h][b][e] = 0.f; }
 #pragma unroll
         for (int b = 0; b < BT; ++b) st.sumx[b] = 0.f;
-        u32x2 qb[kUnroll];
-        int j0 = jq_lo;
-        while (j0 < jq_hi) {
-            load_batch_q4<NT>(L.Mq, ldq, offq, okq, s.idx, jq_hi, j0 + kUnroll, qb);
-            q4_consume<DT, BT>(st, L, qa, s.idx, s.coef, jq_hi, j0, colq, okq);
-            j0 += kUnroll;
-            if (j0 >= jq_hi) break;
-            load_batch_q4<NT>(L.Mq, ldq, offq, okq, s.idx, jq_hi, j0 + kUnroll, qa);
-            q4_consume<DT, BT>(st, L, qb, s.idx, s.coef, jq_hi, j0, colq, okq);
-            j0 += kUnroll;
+        for (int j0 = jq_lo; j0 < jq_hi; j0 += 2 * kUnroll) {
+            q4_consume<DT, BT>(st, L, qa, s.idx, s.coef, jq_hi, j0, colq);
+            if (j0 + kUnroll >= jq_hi) break;
+            load_batch_q4<NT>(L.Mq, ldq, offq, s.idx, jq_hi, j0 + 2 * kUnroll, qa);
+            q4_consume<DT, BT>(st, L, qb, s.idx, s.coef, jq_hi, j0 + kUnroll, colq);
+            if (j0 + 2 * kUnroll >= jq_hi) break;
+            load_batch_q4<NT>(L.Mq, ldq, offq, s.idx, jq_hi, j0 + 3 * kUnroll, qb);
         }
         if (st.g >= 0) q4_close<DT, BT>(st);
         // the two 512-column halves of the tile go through the 16-bit path's reduction one after the other
@@ -809,8 +855,10 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
 }
 
 // 4-bit weights, up to 4 tokens: the same scan, list and stage-1 workgroups, the weight stream as above.
+// (four tokens need two sets of 16 x 4 accumulators: at most 4 waves per workgroup, one per SIMD, so that a
+//  wave may use the whole register file)
 template <int DT, int BT, bool NT>
-__global__ __launch_bounds__(512) void k_q4_sparse_and_t(const GroupArgs ga)
+__global__ __launch_bounds__(BT >= 4 ? 256 : 512) void k_q4_sparse_and_t(const GroupArgs ga)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     sparse_body<DT, BT, NT, false, true>(ga, smem);
@@ -852,8 +900,8 @@ __global__ __launch_bounds__(BT >= 8 ? 256 : 512) void k_dense_axpy(const GroupA
     const int nb = min(BT, a.batch - b0);
     const GatherLds s = carve(smem, a.cap, BT, nw);
 
-    const int lo = (int)(((long long)split * d_in) / a.splits);
-    const int hi = (int)(((long long)(split + 1) * d_in) / a.splits);
+    int lo, hi;
+    balanced_share(d_in, a.splits, split, lo, hi);
     const int n = hi - lo;
     for (int j = tid; j < n; j += nthr) {
         s.idx[j] = lo + j;
@@ -1197,6 +1245,7 @@ hipError_t launch_q4_sparse_and_t(const LayerView &L, const Launch &cfg, const v
         cfg.splits < 1 || cfg.lowrank_rows < 1 || cfg.lowrank_rows > kRowsPerWave * cfg.waves)
         return hipErrorInvalidValue;
     const int bt = batch_tile(batch);
+    if (bt >= 4 && cfg.waves > 4) return hipErrorInvalidValue;
     GroupArgs ga{};
     ga.n = 1;
     GatherArgs &a = ga.job[0];
