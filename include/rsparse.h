@@ -57,7 +57,7 @@ typedef enum {
 #define RSPARSE_MAX_BATCH 32
 
 typedef struct {
-    int32_t d_in;            /* input channels; multiple of 8 */
+    int32_t d_in;            /* input channels; multiple of 8, at most 65536 */
     int32_t d_out;           /* output features; multiple of 8 */
     int32_t rank;            /* r in [0, min(d_in, d_out)], multiple of 8; 0 = sparse part only */
     int32_t max_batch;       /* 1..RSPARSE_MAX_BATCH; scratch is sized for it */

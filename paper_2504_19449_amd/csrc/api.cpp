@@ -166,7 +166,8 @@ rsparse_status check_config(const rsparse_config *c)
     if (!c) return fail(RSPARSE_EINVAL, "config is NULL");
     if (c->d_in < 8 || c->d_out < 8 || (c->d_in % 8) || (c->d_out % 8))
         return fail(RSPARSE_EINVAL, "d_in and d_out must be positive multiples of 8 (got %d, %d)", c->d_in, c->d_out);
-    if (c->d_in > (1 << 20) || c->d_out > (1 << 20)) return fail(RSPARSE_EINVAL, "dimension too large");
+    // the gather kernels keep 5 bytes of LDS per 8 input channels for the scan of the token
+    if (c->d_in > 65536 || c->d_out > (1 << 20)) return fail(RSPARSE_EINVAL, "dimension too large (d_in <= 65536, d_out <= 2^20)");
     if (c->rank < 0 || c->rank > std::min(c->d_in, c->d_out) || (c->rank % 8))
         return fail(RSPARSE_EINVAL, "rank %d must be a multiple of 8 in [0, min(d_in, d_out)]", c->rank);
     if (c->max_batch < 1 || c->max_batch > RSPARSE_MAX_BATCH)
@@ -216,7 +217,7 @@ Launch resolve_launch(const rsparse_layer *L, int batch, bool dense, int group, 
         if (fused) splits = std::min(splits, std::max(32, (L->cus + L->tiles - 1) / L->tiles));
     }
     splits = std::min(splits, 4096);
-    while (gather_lds_bytes(L->cfg.d_in, splits, c.waves, bt, fused ? L->cfg.rank : 0) > 60 * 1024) splits *= 2;
+    while (gather_lds_bytes(L->cfg.d_in, splits, c.waves, bt, fused ? L->cfg.rank : 0) > 60 * 1024 && splits < 65536) splits *= 2;
     c.splits = splits;
     int lr = t.lowrank_rows;
     if (lr <= 0) {
@@ -487,7 +488,7 @@ Launch resolve_launch_q4(const rsparse_layer *L, int batch, bool dense)
         splits = std::max(1, std::min(splits, std::max(1, rows / (c.waves * 8))));      // >= 8 rows per wave
     }
     splits = std::min(splits, 4096);
-    while (gather_lds_bytes(L->cfg.d_in, splits, c.waves, bt) > 60 * 1024) splits *= 2;
+    while (gather_lds_bytes(L->cfg.d_in, splits, c.waves, bt) > 60 * 1024 && splits < 65536) splits *= 2;
     c.splits = splits;
     int lr = t.lowrank_rows;
     if (lr <= 0) {

@@ -469,7 +469,10 @@ __device__ __forceinline__ void load_batch_q4(const uint8_t *__restrict__ Mq, si
 // The eight codes of one word as floats: element e < 4 is the low nibble of byte e, element 4 + e its high nibble.
 __device__ __forceinline__ void codes8(uint32_t w, float (&f)[8])
 {
-    const uint32_t lo = w & 0x0f0f0f0fu, hi = (w >> 4) & 0x0f0f0f0fu;
+    uint32_t lo = w & 0x0f0f0f0fu, hi = (w >> 4) & 0x0f0f0f0fu;
+    // keep the two masked words as they are: each byte then converts with one byte-select instruction,
+    // where the compiler would otherwise extract every nibble with a bit-field op first
+    __asm__ volatile("" : "+v"(lo), "+v"(hi));
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         f[k] = (float)((lo >> (8 * k)) & 0xffu);
@@ -622,26 +625,35 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
     }
     __syncthreads();
 
-    // ---- pass 2: each thread owns a contiguous run of those bytes; block scan gives list positions
+    // ---- pass 2: each thread owns a contiguous run of those bytes; a block scan gives the list position
+    //      of every byte's first kept channel
     const int QC = (nq + nthr - 1) / nthr;
     const int q_begin = min(nq, tid * QC), q_end = min(nq, q_begin + QC);
     int cnt = 0;
     for (int q = q_begin; q < q_end; ++q) cnt += __popc((uint32_t)s_u[q]);
     int k;
     int pos = block_exclusive_scan(cnt, s.misc, k);
+    int *s_P = reinterpret_cast<int *>(s_u + ((nq + 3) & ~3));
+    for (int q = q_begin; q < q_end; ++q) {
+        s_P[q] = pos;
+        pos += __popc((uint32_t)s_u[q]);
+    }
 
-    // ---- my balanced share [lo, hi) of the ascending kept list
+    // ---- my balanced share [lo, hi) of the ascending kept list.  Only a few dozen bytes hold it; they are
+    //      dealt out one per thread (a thread that wrote all of its own run serially held the barrier for
+    //      up to a microsecond on wide inputs)
     int lo, hi;
     balanced_share(k, a.splits, split, lo, hi);
     const int n = hi - lo;
-    if (cnt > 0 && pos < hi && pos + cnt > lo) {
-        for (int q = q_begin; q < q_end; ++q) {
-            uint32_t u = s_u[q];
-            while (u) {
-                const int e = __builtin_ctz(u);
-                u &= u - 1;
-                const int p = pos++;
-                if (p >= lo && p < hi) s.idx[p - lo] = q * 8 + e;
+    __syncthreads();
+    for (int q = tid; q < nq; q += nthr) {
+        const uint32_t u = s_u[q];
+        const int P = s_P[q];
+        if (u != 0u && P < hi && P + __popc(u) > lo) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int p = P + __popc(u & ((1u << e) - 1u));
+                if (((u >> e) & 1u) && p >= lo && p < hi) s.idx[p - lo] = q * 8 + e;
             }
         }
     }
@@ -1169,7 +1181,8 @@ int lowrank_chunk(int d_in, int bt)
 size_t gather_lds_bytes(int d_in, int splits, int waves, int bt, int fused_rank)
 {
     const size_t cap = gather_cap(d_in, splits, fused_rank);
-    return (waves > 1 ? (size_t)waves * kTile * 4 : 0) + cap * bt * 4 + cap * 4 + 16 * 4 + (size_t)d_in / 8 + 16;
+    return (waves > 1 ? (size_t)waves * kTile * 4 : 0) + cap * bt * 4 + cap * 4 + 16 * 4 + (size_t)d_in / 8 + 16 +
+           (size_t)d_in / 2 + 4;      // ... + keep-bits of every 8 channels + their list positions
 }
 
 size_t lowrank_lds_bytes(int d_in, int bt)
@@ -1225,6 +1238,7 @@ hipError_t launch_sparse_and_t(const LayerView *L, const Launch *cfg, int n, con
     }
     for (int i = n; i < kMaxGroup; ++i) ga.wg_end[i] = total;
     if (total == 0) return hipSuccess;
+    if (lds > 64 * 1024) return hipErrorInvalidValue;
     dim3 grid(total, 1, nz), block(kWave * cfg[0].waves);
     const bool nt = cfg[0].nontemporal != 0;
 #define RS_G(DT)                                                                                       \
