@@ -197,6 +197,8 @@ def main():
                          "R-Sparse vs dense per linear; prints one JSON line with key 'sweep'")
     ap.add_argument("--pmc-pass", action="store_true",
                     help="for rocprofv3 --pmc: one 256 MiB device copy of known size, then 3 eager ring passes; no timing")
+    ap.add_argument("--q4-pass", action="store_true",
+                    help="only the leg on 4-bit weights (for rocprofv3 --kernel-trace): prints one JSON line with key 'weights_4bit'")
     ap.add_argument("--pmc-mfma", action="store_true",
                     help="with --pmc-pass: also 2 eager passes of the matrix-core kernels at 8192 -> 28672, r = 1024, 32 tokens, "
                          "and 3 of the vector path at 4096 -> 11008, r = 512, 4 tokens")
@@ -318,6 +320,55 @@ def main():
             samples.append(e0.elapsed_time(e1) / steps)
         samples.sort()
         return samples[len(samples) // 2]
+
+    # ------------------------------------------------------------------ the same block on 4-bit weights (Sec. 4.4)
+    def leg_weights_4bit():
+        q4 = {}
+        q_specs = [("gate", D_MODEL, D_FF, "dmodel"), ("up", D_MODEL, D_FF, "dmodel"), ("down", D_FF, D_MODEL, "down")]
+        for q_rank in (RANK, 64):
+            q_ring = []
+            for li, (name, d_in, d_out, kind) in enumerate(q_specs):
+                Lq = synth.random_layer(d_in, d_out, q_rank, dt, seed=7000 + 10 * li + q_rank)
+                Qc, Sc, Zc = synth.quantize_q4(synth.decode16(Lq.W16, dt), dt, 128)
+                for blk in range(RING_BLOCKS):
+                    cfg = rs.make_config(d_in, d_out, q_rank, taus[name][args.sparsity], dt, max_batch=1)
+                    q_ring.append((li, blk, rs.rsparse_prepare_q4(cfg, Qc, Sc, Zc, 128, Lq.U16, Lq.SV16)))
+            q_ring.sort(key=lambda e: (e[1], e[0]))            # block-major: gate, up, down of block 0, then block 1 ...
+            xs = {0: blocks[0][0][2], 1: blocks[0][0][2], 2: blocks[0][2][2]}
+            ys = {0: blocks[0][0][3], 1: blocks[0][1][3], 2: blocks[0][2][3]}
+
+            def pass_q4(sptr):
+                for li, _, layer in q_ring:
+                    rs.rsparse_linear(layer, xs[li].data_ptr(), 1, ys[li].data_ptr(), sptr)
+
+            def pass_q4_dense(sptr):
+                for li, _, layer in q_ring:
+                    rs.rsparse_dense_ref(layer, xs[li].data_ptr(), 1, ys[li].data_ptr(), sptr)
+
+            pass_q4(stream.cuda_stream)
+            torch.cuda.synchronize()
+            kq = [len(rs.rsparse_last_active(layer, -1)) for _, _, layer in q_ring]
+            rbq = sum(rs.rsparse_required_bytes(layer, 1, k) for (_, _, layer), k in zip(q_ring, kq)) / len(q_ring)
+            dbq = sum(rs.rsparse_dense_bytes(layer, 1) for _, _, layer in q_ring) / len(q_ring)
+            us_q = min(timed(pass_q4, args.steps, args.warmup, eager=e) for e in (False, True)) * 1000.0 / 3.0
+            entry = {"us_per_linear": round(us_q, 3), "required_bytes_per_linear": int(rbq),
+                     "gbs_required": round(rbq / (us_q * 1e-6) / 1e9, 1)}
+            if q_rank == RANK:
+                us_qd = min(timed(pass_q4_dense, args.steps, args.warmup, eager=e) for e in (False, True)) * 1000.0 / 3.0
+                q4["dense_4bit"] = {"us_per_linear": round(us_qd, 3), "bytes_per_linear": int(dbq),
+                                    "gbs": round(dbq / (us_qd * 1e-6) / 1e9, 1)}
+            q4[f"rsparse_rank{q_rank}"] = entry
+            for _, _, layer in q_ring:
+                layer.destroy()
+        q4["note"] = ("the benchmark's three linears with 4-bit weights (GPTQ format, groups of 128; i.i.d. operands), batch 1, "
+                      "same thresholds, two launches per linear; rank 512 is the headline recipe, rank 64 a sparse-heavy one "
+                      "(rho ~ 0.96); compare us_per_linear with the 16-bit value above")
+        return q4
+
+
+    if args.q4_pass:
+        print(json.dumps({"weights_4bit": leg_weights_4bit()}), flush=True)
+        return
 
     if args.pmc_pass:
         a = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")     # 256 MiB
@@ -525,50 +576,9 @@ def main():
             "note": "11008 -> 4096, batch 1: rsparse_linear_gated (x = round(silu(g) * u) by one small launch, then the "
                     "layer) vs rsparse_linear on a ready input"}
 
-    # ------------------------------------------------------------------ the same block on 4-bit weights (Sec. 4.4)
     if not args.no_extras:
-        q4 = {}
-        q_specs = [("gate", D_MODEL, D_FF, "dmodel"), ("up", D_MODEL, D_FF, "dmodel"), ("down", D_FF, D_MODEL, "down")]
-        for q_rank in (RANK, 64):
-            q_ring = []
-            for li, (name, d_in, d_out, kind) in enumerate(q_specs):
-                Lq = synth.random_layer(d_in, d_out, q_rank, dt, seed=7000 + 10 * li + q_rank)
-                Qc, Sc, Zc = synth.quantize_q4(synth.decode16(Lq.W16, dt), dt, 128)
-                for blk in range(RING_BLOCKS):
-                    cfg = rs.make_config(d_in, d_out, q_rank, taus[name][args.sparsity], dt, max_batch=1)
-                    q_ring.append((li, blk, rs.rsparse_prepare_q4(cfg, Qc, Sc, Zc, 128, Lq.U16, Lq.SV16)))
-            q_ring.sort(key=lambda e: (e[1], e[0]))            # block-major: gate, up, down of block 0, then block 1 ...
-            xs = {0: blocks[0][0][2], 1: blocks[0][0][2], 2: blocks[0][2][2]}
-            ys = {0: blocks[0][0][3], 1: blocks[0][1][3], 2: blocks[0][2][3]}
-
-            def pass_q4(sptr):
-                for li, _, layer in q_ring:
-                    rs.rsparse_linear(layer, xs[li].data_ptr(), 1, ys[li].data_ptr(), sptr)
-
-            def pass_q4_dense(sptr):
-                for li, _, layer in q_ring:
-                    rs.rsparse_dense_ref(layer, xs[li].data_ptr(), 1, ys[li].data_ptr(), sptr)
-
-            pass_q4(stream.cuda_stream)
-            torch.cuda.synchronize()
-            kq = [len(rs.rsparse_last_active(layer, -1)) for _, _, layer in q_ring]
-            rbq = sum(rs.rsparse_required_bytes(layer, 1, k) for (_, _, layer), k in zip(q_ring, kq)) / len(q_ring)
-            dbq = sum(rs.rsparse_dense_bytes(layer, 1) for _, _, layer in q_ring) / len(q_ring)
-            us_q = min(timed(pass_q4, args.steps, args.warmup, eager=e) for e in (False, True)) * 1000.0 / 3.0
-            entry = {"us_per_linear": round(us_q, 3), "required_bytes_per_linear": int(rbq),
-                     "gbs_required": round(rbq / (us_q * 1e-6) / 1e9, 1)}
-            if q_rank == RANK:
-                us_qd = min(timed(pass_q4_dense, args.steps, args.warmup, eager=e) for e in (False, True)) * 1000.0 / 3.0
-                q4["dense_4bit"] = {"us_per_linear": round(us_qd, 3), "bytes_per_linear": int(dbq),
-                                    "gbs": round(dbq / (us_qd * 1e-6) / 1e9, 1)}
-            q4[f"rsparse_rank{q_rank}"] = entry
-            for _, _, layer in q_ring:
-                layer.destroy()
-        q4["note"] = ("the benchmark's three linears with 4-bit weights (GPTQ format, groups of 128; i.i.d. operands), batch 1, "
-                      "same thresholds, two launches per linear; rank 512 is the headline recipe, rank 64 a sparse-heavy one "
-                      "(rho ~ 0.96); compare us_per_linear with the 16-bit value above")
-        extras["weights_4bit"] = q4
-        log(f"4-bit weights: {q4}")
+        extras["weights_4bit"] = leg_weights_4bit()
+        log(f"4-bit weights: {extras['weights_4bit']}")
 
     # ------------------------------------------------------------------ what this card streams at this size
     if not args.no_extras:
