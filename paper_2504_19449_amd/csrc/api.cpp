@@ -136,7 +136,7 @@ struct rsparse_layer {
     bool last_fused = false;
     // 4-bit weights (rsparse_prepare_q4): codes, group scales, group zero points; M and Wrow stay null
     uint8_t *Mq = nullptr, *qz = nullptr;
-    uint16_t *qs = nullptr;
+    uint16_t *qs = nullptr, *Ut = nullptr;
     int qshift = 0, qtiles = 0;
     bool q4() const { return Mq != nullptr; }
     int tiles = 0, nz_max = 1;
@@ -152,7 +152,7 @@ struct rsparse_layer {
         v.d_in = cfg.d_in; v.d_out = cfg.d_out; v.rank = cfg.rank;
         v.dtype = cfg.dtype; v.out_dtype = cfg.out_dtype; v.cmp_mode = cfg.cmp_mode;
         v.batch_mask_mode = cfg.batch_mask_mode; v.tau = cfg.tau;
-        v.Mq = Mq; v.qs = qs; v.qz = qz; v.qshift = qshift; v.qtiles = qtiles;
+        v.Mq = Mq; v.qs = qs; v.qz = qz; v.Ut = Ut; v.qshift = qshift; v.qtiles = qtiles;
         return v;
     }
 };
@@ -254,7 +254,7 @@ void free_layer(rsparse_layer *L)
     (void)hipFree(L->M); (void)hipFree(L->SVt); (void)hipFree(L->U); (void)hipFree(L->Wrow); (void)hipFree(L->t);
     (void)hipFree(L->yacc); (void)hipFree(L->act_bits); (void)hipFree(L->chan_bits);
     (void)hipFree(L->act_list); (void)hipFree(L->act_count); (void)hipFree(L->sync); (void)hipFree(L->t_pub); (void)hipFree(L->xg); (void)hipFree(L->hy);
-    (void)hipFree(L->Mq); (void)hipFree(L->qs); (void)hipFree(L->qz);
+    (void)hipFree(L->Mq); (void)hipFree(L->qs); (void)hipFree(L->qz); (void)hipFree(L->Ut);
     delete L;
 }
 
@@ -327,6 +327,15 @@ rsparse_status build_layer(const rsparse_config *cfg, const uint16_t *W, const u
             RS_HIP(hipMemcpy(L->qs, sq.data(), sq.size() * 2, hipMemcpyHostToDevice));
             RS_HIP(hipMalloc((void **)&L->qz, zq.size()));
             RS_HIP(hipMemcpy(L->qz, zq.data(), zq.size(), hipMemcpyHostToDevice));
+            if (r) {
+                // U_r^T with rows padded to whole tiles, for the one-launch kernel
+                std::vector<uint16_t> ut;
+                try { ut.assign(r * lds, 0); } catch (const std::bad_alloc &) { return fail(RSPARSE_ENOMEM, "host allocation failed"); }
+                for (size_t o = 0; o < d_out; ++o)
+                    for (size_t j = 0; j < r; ++j) ut[j * lds + o] = U16[o * r + j];
+                RS_HIP(hipMalloc((void **)&L->Ut, ut.size() * 2));
+                RS_HIP(hipMemcpy(L->Ut, ut.data(), ut.size() * 2, hipMemcpyHostToDevice));
+            }
         }
         if (r) {
             RS_HIP(hipMalloc((void **)&L->SVt, r * d_in * 2));
@@ -471,7 +480,7 @@ namespace {
 
 // Launch shape of the 4-bit kernel: the weight stream is a quarter of the 16-bit one, so fewer, 4-wave
 // workgroups with longer contiguous runs (a wave folds scale and zero point once per quantisation group it meets).
-Launch resolve_launch_q4(const rsparse_layer *L, int batch, bool dense)
+Launch resolve_launch_q4(const rsparse_layer *L, int batch, bool dense, bool fused)
 {
     Launch c{};
     const rsparse_tuning &t = L->tuning;
@@ -488,8 +497,10 @@ Launch resolve_launch_q4(const rsparse_layer *L, int batch, bool dense)
         splits = std::max(1, std::min(splits, std::max(1, rows / (c.waves * 8))));      // >= 8 rows per wave
     }
     splits = std::min(splits, 4096);
-    while (gather_lds_bytes(L->cfg.d_in, splits, c.waves, bt) > 60 * 1024 && splits < 65536) splits *= 2;
+    while (gather_lds_bytes(L->cfg.d_in, splits, c.waves, bt, fused ? L->cfg.rank : 0) > 60 * 1024 && splits < 65536) splits *= 2;
     c.splits = splits;
+    c.wait_polls = t.debug_wait_polls;
+    c.skip_stage1 = t.debug_skip_stage1 ? 1 : 0;
     int lr = t.lowrank_rows;
     if (lr <= 0) {
         const double wg_bytes = (double)rows / splits * (kQ4Tile / 2);
@@ -497,6 +508,13 @@ Launch resolve_launch_q4(const rsparse_layer *L, int batch, bool dense)
         lr = std::max(lr, c.waves);                                                      // a row for every wave
     }
     c.lowrank_rows = std::max(1, std::min(lr, 4 * c.waves));
+    // one launch: stage 1 is cut as fine as the resident slots that the gather workgroups leave free allow
+    // (the rule of the 16-bit kernel), so that t is there when the rows of U_r^T come up
+    if (fused && t.lowrank_rows <= 0) {
+        const int free_slots = 2 * L->cus - L->qtiles * splits;
+        const int need = free_slots > 0 ? (L->cfg.rank + free_slots - 1) / free_slots : 4 * c.waves;
+        c.lowrank_rows = std::max(std::max(1, c.waves / 2), std::min(4 * c.waves, need));
+    }
     return c;
 }
 
@@ -504,12 +522,18 @@ Launch resolve_launch_q4(const rsparse_layer *L, int batch, bool dense)
 rsparse_status linear_q4(rsparse_layer *L, const void *X_dev, int32_t batch, void *Y_dev, bool dense, hipStream_t s)
 {
     const LayerView v = L->view();
-    const Launch lc = resolve_launch_q4(L, batch, dense);
     const int stages = L->tuning.stages;
-    if (stages != 2) RS_HIP(launch_q4_sparse_and_t(v, lc, X_dev, batch, true, dense, s));
-    if (stages != 1) RS_HIP(launch_finish(&v, 1, batch, &Y_dev, !dense, s));
+    // one launch unless asked otherwise; the dense baseline keeps the two-launch form
+    const bool fused = !dense && L->tuning.launches != 2 && stages == 0;
+    const Launch lc = resolve_launch_q4(L, batch, dense, fused);
+    if (fused) {
+        RS_HIP(launch_q4(v, lc, X_dev, batch, true, false, Y_dev, s));
+    } else {
+        if (stages != 2) RS_HIP(launch_q4(v, lc, X_dev, batch, true, dense, nullptr, s));
+        if (stages != 1) RS_HIP(launch_finish(&v, 1, batch, &Y_dev, !dense, s));
+    }
     if (!dense) {
-        L->last_stream = s; L->last_batch = batch; L->last_mfma = false; L->last_fused = false;
+        L->last_stream = s; L->last_batch = batch; L->last_mfma = false; L->last_fused = fused;
     }
     return RSPARSE_OK;
 }

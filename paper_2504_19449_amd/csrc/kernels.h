@@ -33,6 +33,7 @@ struct LayerView {
     const uint8_t *Mq;      // [d_in][qtiles * 512] bytes, row c = the codes of W[:, c]
     const uint16_t *qs;     // [d_in >> qshift][qtiles * 1024] group scales, 16-bit of dtype, plain column order
     const uint8_t *qz;      // [d_in >> qshift][qtiles * 1024] group zero points, one per byte
+    const uint16_t *Ut;     // [rank][qtiles * 1024] = U_r^T, zero-padded rows (the one-launch 4-bit kernel streams it)
     int qshift, qtiles;     // log2(group size); column tiles of 1024
     int d_in, d_out, rank;
     int dtype, out_dtype, cmp_mode, batch_mask_mode;
@@ -75,10 +76,11 @@ hipError_t launch_fused(const LayerView *L, const Launch *cfg, int n, const void
 // First launch of a layer with 4-bit weights (at most 4 tokens): as launch_sparse_and_t, with the codes
 // dequantised in registers -- per quantisation group the kernel accumulates sum_c x_c q_c and sum_c x_c and
 // applies scale and zero point once, when the group ends.  dense: every channel is kept (the dense baseline
-// on the same weights).  launch_finish completes the layer.
+// on the same weights).  Y_fused == nullptr: launch_finish completes the layer.  Y_fused != nullptr: the whole
+// layer in this one launch, as launch_fused (not with dense).
 constexpr int kQ4Tile = 1024;
-hipError_t launch_q4_sparse_and_t(const LayerView &L, const Launch &cfg, const void *X, int batch, bool with_t,
-                                  bool dense, hipStream_t stream);
+hipError_t launch_q4(const LayerView &L, const Launch &cfg, const void *X, int batch, bool with_t, bool dense,
+                     void *Y_fused, hipStream_t stream);
 // Second launch: Y = round(yacc + U_r t) (use_rank) or round(yacc); re-zeroes yacc.
 hipError_t launch_finish(const LayerView *L, int n, int batch, void *const *Y, bool use_rank, hipStream_t stream);
 // Dense baselines.

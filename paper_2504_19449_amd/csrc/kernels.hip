@@ -723,37 +723,6 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
     }
     __syncthreads();
 
-    if constexpr (Q4) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int b = 0; b < BT; ++b)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) { st.acc[h][b][e] = 0.f; st.grp[h][b][e] = 0.f; }
-#pragma unroll
-        for (int b = 0; b < BT; ++b) st.sumx[b] = 0.f;
-        for (int j0 = jq_lo; j0 < jq_hi; j0 += 2 * kUnroll) {
-            q4_consume<DT, BT>(st, L, qa, s.idx, s.coef, jq_hi, j0, colq);
-            if (j0 + kUnroll >= jq_hi) break;
-            load_batch_q4<NT>(L.Mq, ldq, offq, s.idx, jq_hi, j0 + 2 * kUnroll, qa);
-            q4_consume<DT, BT>(st, L, qb, s.idx, s.coef, jq_hi, j0 + kUnroll, colq);
-            if (j0 + 2 * kUnroll >= jq_hi) break;
-            load_batch_q4<NT>(L.Mq, ldq, offq, s.idx, jq_hi, j0 + 3 * kUnroll, qb);
-        }
-        if (st.g >= 0) q4_close<DT, BT>(st);
-        // the two 512-column halves of the tile go through the 16-bit path's reduction one after the other
-        reduce_to_yacc<BT>(st.acc[0], s.red, L.yacc, b0, nb, d_out, tile * 2);
-        __syncthreads();
-        reduce_to_yacc<BT>(st.acc[1], s.red, L.yacc, b0, nb, d_out, tile * 2 + 1);
-        return;
-    }
-
-    if (!FUSED) {
-        stream_rest<DT, BT, NT>(L.M, (size_t)d_out, col, colok, s.idx, s.coef, n, j_first, step, va, acc, [](int) {});
-        reduce_to_yacc<BT>(acc, s.red, L.yacc, b0, nb, d_out, tile);
-        return;
-    }
-
     // ---- one launch.  The coefficients of the U_r^T rows are t.  Lane l of a wave looks after row
     //      l / BT, token l % BT of a batch; the entries of a batch are requested while the batch
     //      before it is consumed, and written to this wave's own coefficient slots when it is due.
@@ -782,7 +751,6 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
         }
         if (!ok && lane == 0) __hip_atomic_store(L.sync + kSyncError, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     };
-    request_t(j_first);
     auto need_t = [&](int j0) {
         if (j0 + kUnroll > n) {                      // this batch holds rows of U_r^T
             settle_t();
@@ -792,8 +760,55 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
         }
         request_t(j0 + step);
     };
-    stream_rest<DT, BT, NT>(L.M, (size_t)d_out, col, colok, s.idx, s.coef, n_all, j_first, step, va, acc, need_t);
-    reduce_to_yacc<BT>(acc, s.red, L.yacc, b0, nb, d_out, tile);
+
+    if constexpr (Q4) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int b = 0; b < BT; ++b)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) { st.acc[h][b][e] = 0.f; st.grp[h][b][e] = 0.f; }
+#pragma unroll
+        for (int b = 0; b < BT; ++b) st.sumx[b] = 0.f;
+        for (int j0 = jq_lo; j0 < jq_hi; j0 += 2 * kUnroll) {
+            q4_consume<DT, BT>(st, L, qa, s.idx, s.coef, jq_hi, j0, colq);
+            if (j0 + kUnroll >= jq_hi) break;
+            load_batch_q4<NT>(L.Mq, ldq, offq, s.idx, jq_hi, j0 + 2 * kUnroll, qa);
+            q4_consume<DT, BT>(st, L, qb, s.idx, s.coef, jq_hi, j0 + kUnroll, colq);
+            if (j0 + 2 * kUnroll >= jq_hi) break;
+            load_batch_q4<NT>(L.Mq, ldq, offq, s.idx, jq_hi, j0 + 3 * kUnroll, qb);
+        }
+        if (st.g >= 0) q4_close<DT, BT>(st);
+        if constexpr (FUSED) {
+            // one launch: my share of the rows of U_r^T (16-bit, row j = U_r[:, j], padded to whole tiles)
+            // with coefficients t, through the 16-bit path's stream, once per 512-column half of the tile.
+            // The list holds them as rows d_in + j, so the base is moved back by d_in rows.
+            const size_t ldu = (size_t)L.qtiles * kQ4Tile;
+            const uint16_t *Uv = reinterpret_cast<const uint16_t *>(reinterpret_cast<uintptr_t>(L.Ut) -
+                                                                    (uintptr_t)d_in * ldu * sizeof(uint16_t));
+            const int ju = n + j_first;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                u32x4 ua[kUnroll];
+                load_batch<NT>(Uv, ldu, colq + h * 512, true, s.idx, n_all, ju, ua);
+                request_t(ju);
+                stream_rest<DT, BT, NT>(Uv, ldu, colq + h * 512, true, s.idx, s.coef, n_all, ju, step, ua, st.acc[h], need_t);
+            }
+        }
+        // the two 512-column halves of the tile go through the 16-bit path's reduction one after the other
+        reduce_to_yacc<BT>(st.acc[0], s.red, L.yacc, b0, nb, d_out, tile * 2);
+        __syncthreads();
+        reduce_to_yacc<BT>(st.acc[1], s.red, L.yacc, b0, nb, d_out, tile * 2 + 1);
+        if constexpr (!FUSED) return;
+    } else if (!FUSED) {
+        stream_rest<DT, BT, NT>(L.M, (size_t)d_out, col, colok, s.idx, s.coef, n, j_first, step, va, acc, [](int) {});
+        reduce_to_yacc<BT>(acc, s.red, L.yacc, b0, nb, d_out, tile);
+        return;
+    } else {
+        request_t(j_first);
+        stream_rest<DT, BT, NT>(L.M, (size_t)d_out, col, colok, s.idx, s.coef, n_all, j_first, step, va, acc, need_t);
+        reduce_to_yacc<BT>(acc, s.red, L.yacc, b0, nb, d_out, tile);
+    }
 
     // ---- arrive at the tile; the last of its `splits` workgroups owns the finish.  For a gate/up pair
     //      the two layers share the gate layer's counters and the tile is finished once, by the last
@@ -824,8 +839,9 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
     if (s.misc[12] != arrivals - 1) return;
 
     // ---- Y = round(Y_s + Y_r): swap the sums out (this re-zeroes yacc for the next call), round once
-    for (int c = tid; c < kTile; c += nthr) {
-        const int o = tile * kTile + c;
+    constexpr int TW = Q4 ? kQ4Tile : kTile;
+    for (int c = tid; c < TW; c += nthr) {
+        const int o = tile * TW + c;
         if (o < d_out) {
             float v[BT], vu[BT];
 #pragma unroll
@@ -874,6 +890,15 @@ __global__ __launch_bounds__(BT >= 4 ? 256 : 512) void k_q4_sparse_and_t(const G
 {
     extern __shared__ __align__(16) unsigned char smem[];
     sparse_body<DT, BT, NT, false, true>(ga, smem);
+}
+
+// The whole layer on 4-bit weights in one launch (as k_rsparse_fused: stage-1 workgroups publish t, the gather
+// workgroups add their share of U_r^T t, the last workgroup of a column tile rounds and stores).
+template <int DT, int BT, bool NT>
+__global__ __launch_bounds__(BT >= 4 ? 256 : 512) void k_q4_fused(const GroupArgs ga)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    sparse_body<DT, BT, NT, true, true>(ga, smem);
 }
 
 // Eight tokens of accumulators need the full register file: 4 waves per workgroup, one per SIMD.
@@ -1251,9 +1276,11 @@ hipError_t launch_sparse_and_t(const LayerView *L, const Launch *cfg, int n, con
     return hipGetLastError();
 }
 
-hipError_t launch_q4_sparse_and_t(const LayerView &L, const Launch &cfg, const void *X, int batch, bool with_t,
-                                  bool dense, hipStream_t stream)
+hipError_t launch_q4(const LayerView &L, const Launch &cfg, const void *X, int batch, bool with_t, bool dense,
+                     void *Y_fused, hipStream_t stream)
 {
+    const bool fused = Y_fused != nullptr;
+    if (fused && (dense || !with_t || !L.sync || !L.t_pub || (L.rank > 0 && !L.Ut))) return hipErrorInvalidValue;
     if (!L.Mq || !L.qs || !L.qz || batch < 1 || batch > 4 || L.qshift < 3 || (L.d_in >> L.qshift) < 1 ||
         ((L.d_in >> L.qshift) << L.qshift) != L.d_in || L.qtiles != (L.d_out + kQ4Tile - 1) / kQ4Tile ||
         cfg.splits < 1 || cfg.lowrank_rows < 1 || cfg.lowrank_rows > kRowsPerWave * cfg.waves)
@@ -1264,32 +1291,41 @@ hipError_t launch_q4_sparse_and_t(const LayerView &L, const Launch &cfg, const v
     ga.n = 1;
     GatherArgs &a = ga.job[0];
     a.L = L; a.X = (const uint16_t *)X; a.batch = batch; a.splits = cfg.splits; a.tiles = L.qtiles;
-    a.cap = gather_cap(L.d_in, cfg.splits);
+    a.cap = gather_cap(L.d_in, cfg.splits, fused ? L.rank : 0);
     a.lr_rows = cfg.lowrank_rows;
     a.lr_wgs = (with_t && !dense && L.rank > 0) ? (L.rank + cfg.lowrank_rows - 1) / cfg.lowrank_rows : 0;
     a.lr_chunk = lowrank_chunk(L.d_in, bt);
     a.tile_map = 1;
     a.dense = dense ? 1 : 0;
+    a.Y = Y_fused;
+    a.nz = 1;
+    a.wait_polls = cfg.wait_polls > 0 ? cfg.wait_polls : kWaitLimitPolls;
+    a.skip_stage1 = cfg.skip_stage1;
     const int total = a.lr_wgs + L.qtiles * cfg.splits;
     for (int i = 0; i < kMaxGroup; ++i) ga.wg_end[i] = total;
-    size_t lds = gather_lds_bytes(L.d_in, cfg.splits, cfg.waves, bt);
+    size_t lds = gather_lds_bytes(L.d_in, cfg.splits, cfg.waves, bt, fused ? L.rank : 0);
     if (a.lr_wgs > 0) lds = std::max(lds, lowrank_lds_bytes(L.d_in, bt));
     if (lds > 64 * 1024) return hipErrorInvalidValue;
     dim3 grid(total, 1, 1), block(kWave * cfg.waves);
     const bool nt = cfg.nontemporal != 0;
-#define RS_Q(DT)                                                                                         \
-    switch (bt) {                                                                                        \
-    case 1: if (nt) hipLaunchKernelGGL((k_q4_sparse_and_t<DT, 1, true>), grid, block, lds, stream, ga);  \
-            else hipLaunchKernelGGL((k_q4_sparse_and_t<DT, 1, false>), grid, block, lds, stream, ga);    \
-            break;                                                                                       \
-    case 2: if (nt) hipLaunchKernelGGL((k_q4_sparse_and_t<DT, 2, true>), grid, block, lds, stream, ga);  \
-            else hipLaunchKernelGGL((k_q4_sparse_and_t<DT, 2, false>), grid, block, lds, stream, ga);    \
-            break;                                                                                       \
-    default: if (nt) hipLaunchKernelGGL((k_q4_sparse_and_t<DT, 4, true>), grid, block, lds, stream, ga); \
-             else hipLaunchKernelGGL((k_q4_sparse_and_t<DT, 4, false>), grid, block, lds, stream, ga);   \
-             break;                                                                                      \
+#define RS_Q1(DT, BTV)                                                                                  \
+    do {                                                                                                \
+        if (fused) {                                                                                    \
+            if (nt) hipLaunchKernelGGL((k_q4_fused<DT, BTV, true>), grid, block, lds, stream, ga);      \
+            else hipLaunchKernelGGL((k_q4_fused<DT, BTV, false>), grid, block, lds, stream, ga);        \
+        } else {                                                                                        \
+            if (nt) hipLaunchKernelGGL((k_q4_sparse_and_t<DT, BTV, true>), grid, block, lds, stream, ga);  \
+            else hipLaunchKernelGGL((k_q4_sparse_and_t<DT, BTV, false>), grid, block, lds, stream, ga);    \
+        }                                                                                               \
+    } while (0)
+#define RS_Q(DT)                     \
+    switch (bt) {                    \
+    case 1: RS_Q1(DT, 1); break;     \
+    case 2: RS_Q1(DT, 2); break;     \
+    default: RS_Q1(DT, 4); break;    \
     }
     if (L.dtype == F16) { RS_Q(F16) } else { RS_Q(BF16) }
+#undef RS_Q1
 #undef RS_Q
     return hipGetLastError();
 }

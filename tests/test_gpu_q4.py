@@ -97,7 +97,8 @@ def test_q4_launch_shapes(ragged_q4, tuning):
     q = ragged_q4[synth.BF16]
     X16, src = gu.tokens_for(q.L, 3, linear=7)
     tau = gu.calibrated_tau(q.L, src, 0.5)
-    _parity(q, X16, tau, out_dtype=rs.F32, tuning=tuning)
+    _parity(q, X16, tau, out_dtype=rs.F32, tuning=tuning)                       # one launch (the default)
+    _parity(q, X16[:1], tau, out_dtype=rs.F32, tuning=dict(tuning, launches=2))  # stage 2 in a second kernel
 
 
 @pytest.mark.parametrize("group,d_in", [(32, 1056), (64, 1088), (256, 1280), (1024, 2048)])
@@ -127,6 +128,50 @@ def test_q4_extreme_codes_and_zero_points():
     q.Z = np.where(rng.random(q.Z.shape) < 0.5, 0, 15).astype(np.uint8)
     X16, src = gu.tokens_for(L, 2)
     _parity(q, X16, gu.calibrated_tau(L, src, 0.5), out_dtype=rs.F32)
+
+
+@pytest.mark.parametrize("launches", [1, 2])
+@pytest.mark.parametrize("B", [1, 4])
+def test_q4_both_launch_forms_on_a_reused_handle(ragged_q4, launches, B):
+    """Back-to-back calls with different kept sets on one handle, in either form: the one-launch form's arrival
+    counters, published intermediates and accumulators must be back in their idle state after every call."""
+    q = ragged_q4[synth.F16]
+    X16, src = gu.tokens_for(q.L, B, linear=60 + B)
+    tau = gu.calibrated_tau(q.L, src, 0.5)
+    layer = q.prepare(tau, max_batch=B, out_dtype=rs.F32)
+    rs.rsparse_set_tuning(layer, launches=launches)
+    for t in (tau, -INF, gu.calibrated_tau(q.L, src, 0.8), INF, tau):
+        rs.rsparse_set_tau(layer, t)
+        got = gu.run_linear(layer, X16)
+        rs.rsparse_synchronize(layer)
+        want = q.oracle(X16, t)
+        gu.check_lists(got, want)
+        gu.check_outputs(got["Y"], want["Y"], rs.F32)
+    layer.destroy()
+
+
+def test_q4_bounded_wait_runs_out_and_the_handle_recovers(ragged_q4):
+    """The error path of the one-launch form, forced from the host (stage 1 publishes nothing, the wait bound is
+    a few polls): every kernel still ends, the call is reported invalid, the next call is correct again."""
+    q = ragged_q4[synth.BF16]
+    X16, src = gu.tokens_for(q.L, 2, linear=78)
+    tau = gu.calibrated_tau(q.L, src, 0.5)
+    layer = q.prepare(tau, max_batch=2, out_dtype=rs.F32)
+    rs.rsparse_set_tuning(layer, launches=1, debug_skip_stage1=1, debug_wait_polls=4)
+    Xd = gu.to_dev16(X16)
+    Y = gu._alloc_out(layer, 2)
+    rs.rsparse_linear(layer, Xd.data_ptr(), 2, Y.data_ptr(), gu.stream_ptr())
+    with pytest.raises(rs.RSparseError) as e:
+        rs.rsparse_synchronize(layer)
+    assert e.value.status == rs.binding.EHIP
+    rs.rsparse_set_tuning(layer, launches=1)
+    for _ in range(2):
+        got = gu.run_linear(layer, X16)
+        rs.rsparse_synchronize(layer)
+        want = q.oracle(X16, tau)
+        gu.check_lists(got, want)
+        gu.check_outputs(got["Y"], want["Y"], rs.F32)
+    layer.destroy()
 
 
 def test_q4_dense_baseline_and_reuse(ragged_q4):
@@ -206,18 +251,33 @@ def test_q4_mixed_group_call(ragged_q4):
 
 
 def test_q4_config1_shapes_as_benchmarked():
-    """The MLP shapes of the benchmark workload (4096 -> 14336 and 14336 -> 4096, bf16, r = 512 and the small
-    rank of a sparse-heavy recipe) at the default launch shape, all outputs against the oracle."""
+    """The MLP shapes of the benchmark workload (4096 -> 11008 and 11008 -> 4096, bf16, r = 512 and the small
+    rank of a sparse-heavy recipe) at the default launch shape, captured into a HIP graph and replayed, both
+    launch forms; every output of every replay against the oracle."""
+    torch = gu.torch_mod()
     dt = synth.BF16
-    for d_in, d_out, rank, kind in ((4096, 14336, 512, "dmodel"), (14336, 4096, 64, "down")):
+    for d_in, d_out, rank, kind in ((4096, 11008, 512, "dmodel"), (11008, 4096, 64, "down")):
         L = synth.random_layer(d_in, d_out, rank, dt, seed=4100 + rank)
         q = Q4Layer(L, 128)
         X16, src = gu.tokens_for(L, 1, kind=kind, linear=rank)
         tau = gu.calibrated_tau(L, src, 0.5)
         layer = q.prepare(tau, max_batch=1)
-        got = gu.run_linear(layer, X16)
         want = q.oracle(X16, tau)
-        gu.check_lists(got, want)
-        gu.check_outputs(got["Y"], want["Y"], dt)
+        Xd = gu.to_dev16(X16)
+        Y = gu._alloc_out(layer, 1)
+        for launches in (1, 2):
+            rs.rsparse_set_tuning(layer, launches=launches)
+            got = gu.run_linear(layer, X16)
+            gu.check_lists(got, want)
+            gu.check_outputs(got["Y"], want["Y"], dt)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                rs.rsparse_linear(layer, Xd.data_ptr(), 1, Y.data_ptr(), torch.cuda.current_stream().cuda_stream)
+            for rep in range(3):
+                Y.fill_(0x7FFF)
+                graph.replay()
+                torch.cuda.synchronize()
+                rs.rsparse_synchronize(layer)
+                gu.check_outputs(gu._read_out(layer, Y), want["Y"], dt)
         gu.check_outputs(gu.run_dense(layer, X16), q.dense(X16), dt)
         layer.destroy()
