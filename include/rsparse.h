@@ -91,8 +91,8 @@ typedef struct {
                                 then run in tiles of up to 8 tokens on the vector ALU) */
     int32_t mfma_rows;       /* output rows per workgroup of the matrix-core kernels: 0 default, or 64, 128, 256 */
     int32_t launches;        /* rsparse_linear up to 8 tokens (and beyond without the row-major copy): 0 default
-                                (one launch), 1 one launch, 2 two launches (stage 2 and the rounding in a second
-                                kernel).  stages != 0 implies two launches */
+                                (one launch; two on 4-bit weights), 1 one launch, 2 two launches (stage 2 and the
+                                rounding in a second kernel).  stages != 0 implies two launches */
     int32_t debug_wait_polls;   /* one-launch kernel: bound on the re-reads of a low-rank intermediate that stage 1 has
                                    not published yet; 0 = default (2^20, or 0.5 s) */
     int32_t debug_skip_stage1;  /* test hook for the error path, needs debug_wait_polls in [1, 64]: stage 1 publishes
@@ -137,8 +137,9 @@ rsparse_status rsparse_prepare_factors(const rsparse_config *cfg, const void *W_
  * of two in [32, 1024] that divides d_in.  The library packs the codes channel-major (one kept channel = one
  * contiguous run of d_out / 2 bytes) and dequantises in registers: per quantisation group it accumulates
  * sum x_c q_c and sum x_c and applies scale and zero point once.  Limits of this path: max_batch <= 4,
- * dense_rowmajor = 0; rsparse_linear and friends run it as two launches per layer (grouped calls and
- * rsparse_mlp_gate_up take such layers one at a time); rsparse_dense_ref gives the dense product with W~.
+ * dense_rowmajor = 0; rsparse_linear and friends run it as two launches per layer by default (tuning
+ * launches = 1 selects a one-launch form, measured no faster); grouped calls and rsparse_mlp_gate_up take
+ * such layers one at a time; rsparse_dense_ref gives the dense product with W~.
  */
 rsparse_status rsparse_prepare_q4(const rsparse_config *cfg, const uint8_t *Q_host, const void *S16_host,
                                   const uint8_t *Z_host, int32_t group_size, const void *U16_host,

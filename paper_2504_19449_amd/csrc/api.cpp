@@ -523,8 +523,9 @@ rsparse_status linear_q4(rsparse_layer *L, const void *X_dev, int32_t batch, voi
 {
     const LayerView v = L->view();
     const int stages = L->tuning.stages;
-    // one launch unless asked otherwise; the dense baseline keeps the two-launch form
-    const bool fused = !dense && L->tuning.launches != 2 && stages == 0;
+    // two launches by default: the one-launch form (launches = 1) measured no faster on these weights --
+    // its tail waits for up to `splits` same-address atomics that the two-launch form never waits for
+    const bool fused = !dense && L->tuning.launches == 1 && stages == 0;
     const Launch lc = resolve_launch_q4(L, batch, dense, fused);
     if (fused) {
         RS_HIP(launch_q4(v, lc, X_dev, batch, true, false, Y_dev, s));

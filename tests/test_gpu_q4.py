@@ -97,8 +97,8 @@ def test_q4_launch_shapes(ragged_q4, tuning):
     q = ragged_q4[synth.BF16]
     X16, src = gu.tokens_for(q.L, 3, linear=7)
     tau = gu.calibrated_tau(q.L, src, 0.5)
-    _parity(q, X16, tau, out_dtype=rs.F32, tuning=tuning)                       # one launch (the default)
-    _parity(q, X16[:1], tau, out_dtype=rs.F32, tuning=dict(tuning, launches=2))  # stage 2 in a second kernel
+    _parity(q, X16, tau, out_dtype=rs.F32, tuning=tuning)                       # two launches (the default)
+    _parity(q, X16, tau, out_dtype=rs.F32, tuning=dict(tuning, launches=1))     # the whole layer in one launch
 
 
 @pytest.mark.parametrize("group,d_in", [(32, 1056), (64, 1088), (256, 1280), (1024, 2048)])
