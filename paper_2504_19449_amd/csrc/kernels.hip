@@ -251,18 +251,22 @@ __device__ __forceinline__ void wait_own_writes()
 // handed to the 8 XCDs round-robin by index, and fp32 atomics from different XCDs to one line move
 // it between their L2s; giving every split of a tile an index congruent to (tile mod 8) keeps a
 // tile's accumulators in one L2.  Indices past the last real pair are idle.
-__device__ __forceinline__ bool map_tile(const GatherArgs &a, int g, int &tile, int &split)
+__device__ __forceinline__ bool map_tile(int tile_map, int tiles, int splits, int g, int &tile, int &split)
 {
-    if (a.tile_map != 2) {
-        tile = g % a.tiles;
-        split = g / a.tiles;
+    if (tile_map != 2) {
+        tile = g % tiles;
+        split = g / tiles;
         return true;
     }
     const int x = g & 7, slot = g >> 3;              // slot enumerates (tile / 8, split)
-    const int tgroup = slot / a.splits;
-    split = slot % a.splits;
+    const int tgroup = slot / splits;
+    split = slot % splits;
     tile = tgroup * 8 + x;
-    return tile < a.tiles;
+    return tile < tiles;
+}
+__device__ __forceinline__ bool map_tile(const GatherArgs &a, int g, int &tile, int &split)
+{
+    return map_tile(a.tile_map, a.tiles, a.splits, g, tile, split);
 }
 
 // Several layers that read the same input share one launch: job i owns workgroups
@@ -283,6 +287,22 @@ __device__ __forceinline__ int find_job(const int (&wg_end)[kMaxGroup], int n, i
         if (i + 1 < n && wg >= wg_end[i]) { li = i + 1; begin = wg_end[i]; }
     local = wg - begin;
     return li;
+}
+
+// Keep a wave-uniform kernel argument in scalar registers from here on.  Left alone, the compiler re-reads
+// kernel arguments at their uses -- a scalar-cache round trip and a wait each time, e.g. in front of every
+// single load of the token (six dependent waits before the first token load became three; the scalar cache
+// hits are cheap, so this measured neutral on the benchmark).
+__device__ __forceinline__ int pin(int v) { __asm__ volatile("" : "+s"(v)); return v; }
+__device__ __forceinline__ float pin(float v) { __asm__ volatile("" : "+s"(v)); return v; }
+template <typename T>
+__device__ __forceinline__ const T *pin(const T *p)
+{
+    uintptr_t u = reinterpret_cast<uintptr_t>(p);
+    __asm__ volatile("" : "+s"(u));
+    // back through a global-memory pointer type, so that loads stay global loads (not generic ones)
+    typedef const T __attribute__((address_space(1))) *global_ptr;
+    return (const T *)reinterpret_cast<global_ptr>(u);
 }
 
 // Balanced share [lo, hi) of n items for part p of `parts`: the first n % parts shares hold one item more.
@@ -583,19 +603,24 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
     const int z = blockIdx.z;
     int wg;
     const GatherArgs &a = ga.job[find_job(ga.wg_end, ga.n, blockIdx.x, wg)];
-    if (wg < a.lr_wgs) {
+    const LayerView &L = a.L;
+    // everything the path to the first weight load needs, fetched in one go
+    const int lr_wgs = pin(a.lr_wgs), tile_map = pin(a.tile_map), n_tiles = pin(a.tiles), n_splits = pin(a.splits);
+    const uint16_t *const X = pin(a.X);
+    const int d_in = pin(L.d_in), d_out = pin(L.d_out), batch = pin(a.batch), cap = pin(a.cap);
+    const float tau = pin(L.tau);
+    const int cmp_mode = pin(L.cmp_mode);
+    const bool union_all = pin(L.batch_mask_mode) == 1;
+    if (wg < lr_wgs) {
         lowrank_rows<DT, BT, FUSED>(a, smem, wg, z);
         return;
     }
     const int tid = threadIdx.x, nthr = blockDim.x, lane = tid & 63, w = tid >> 6, nw = nthr >> 6;
     int tile, split;
-    if (!map_tile(a, wg - a.lr_wgs, tile, split)) return;
-    const LayerView &L = a.L;
-    const int d_in = L.d_in, d_out = L.d_out;
+    if (!map_tile(tile_map, n_tiles, n_splits, wg - lr_wgs, tile, split)) return;
     const int b0 = z * BT;
-    const int nb = min(BT, a.batch - b0);
-    const bool union_all = L.batch_mask_mode == 1;
-    const GatherLds s = carve(smem, a.cap, BT, nw);
+    const int nb = min(BT, batch - b0);
+    const GatherLds s = carve(smem, cap, BT, nw);
     const int col = tile * kTile + lane * 8;
     const bool colok = col < d_out;
 
@@ -611,12 +636,12 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
     int *s_tot = s_P + nq, *s_base = s_tot + E;
     constexpr int PB = TokenBatch<BT>::kGroups;
     // every list slot starts as a valid channel, so that no later arithmetic slip can turn LDS leftovers into addresses
-    for (int i = tid; i < a.cap; i += nthr) s.idx[i] = 0;
+    for (int i = tid; i < cap; i += nthr) s.idx[i] = 0;
     for (int qb = w * 64; qb < nq; qb += nthr * PB) {
         u32x4 raw[PB][BT];
 #pragma unroll
         for (int p = 0; p < PB; ++p)
-            if (qb + p * nthr + lane < nq) load_raw8<BT>(a.X, b0, nb, d_in, (qb + p * nthr + lane) * 8, raw[p]);
+            if (qb + p * nthr + lane < nq) load_raw8<BT>(X, b0, nb, d_in, (qb + p * nthr + lane) * 8, raw[p]);
 #pragma unroll
         for (int p = 0; p < PB; ++p) {
             const int qrow = qb + p * nthr;            // first chunk of this wave's block: the same for all its lanes
@@ -625,7 +650,7 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
                 uint32_t kept = 0u;
                 if (q < nq) {
                     uint32_t m[BT];
-                    kept = masks_of8<DT, BT>(a.X, a.batch, b0, nb, d_in, q * 8, L.tau, L.cmp_mode, union_all, raw[p], m);
+                    kept = masks_of8<DT, BT>(X, batch, b0, nb, d_in, q * 8, tau, cmp_mode, union_all, raw[p], m);
                     if (Q4 && a.dense) kept = 0xffu;
                 }
                 const int c = __popc(kept);
@@ -655,7 +680,7 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
     // ---- my balanced share [lo, hi) of the ascending kept list: each thread writes out the entries of its
     //      own chunks that fall into it
     int lo, hi;
-    balanced_share(k, a.splits, split, lo, hi);
+    balanced_share(k, n_splits, split, lo, hi);
     const int n = hi - lo;
     for (int qrow = w * 64; qrow < nq; qrow += nthr) {
         const int q = qrow + lane;
@@ -675,7 +700,7 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
     int n_all = n;
     if (FUSED) {
         int r_lo, r_hi;
-        balanced_share(L.rank, a.splits, split, r_lo, r_hi);
+        balanced_share(L.rank, n_splits, split, r_lo, r_hi);
         for (int i = tid; i < r_hi - r_lo; i += nthr) s.idx[n + i] = d_in + r_lo + i;
         n_all = n + (r_hi - r_lo);
     }
@@ -723,9 +748,9 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
             float xf = 0.f;
             bool kb = false;
             if (b < nb) {
-                const uint16_t h = a.X[(size_t)(b0 + b) * d_in + c];
+                const uint16_t h = X[(size_t)(b0 + b) * d_in + c];
                 xf = (DT == F16) ? (float)__builtin_bit_cast(_Float16, h) : as_f((uint32_t)h << 16);
-                kb = (union_all || (Q4 && a.dense)) ? true : keep(xf, L.tau, L.cmp_mode);
+                kb = (union_all || (Q4 && a.dense)) ? true : keep(xf, tau, cmp_mode);
             }
             s.coef[j * BT + b] = kb ? xf : 0.f;
             bits |= (uint32_t)kb << b;
