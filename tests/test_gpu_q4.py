@@ -281,3 +281,32 @@ def test_q4_config1_shapes_as_benchmarked():
                 gu.check_outputs(gu._read_out(layer, Y), want["Y"], dt)
         gu.check_outputs(gu.run_dense(layer, X16), q.dense(X16), dt)
         layer.destroy()
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_q4_random_shapes_and_settings(seed):
+    """Seeded sweep over small random layers on 4-bit weights: group sizes 32-256, d_in any multiple of the
+    group, d_out any multiple of 8 (1-3 column tiles, ragged), ranks from 0 up, 1-4 tokens, both dtypes, compare
+    modes, mask modes and launch forms, random launch shapes.  Lists equal, outputs within the fp32-output bound."""
+    rng = np.random.default_rng(4321 + seed)
+    for case in range(8):
+        group = int(rng.choice([32, 64, 128, 256]))
+        d_in = group * int(rng.integers(1, max(2, 1400 // group)))
+        d_out = 8 * int(rng.integers(1, 330))
+        rank = 8 * int(rng.integers(0, min(min(d_in, d_out) // 8, 12) + 1))
+        dt = int(rng.integers(0, 2))
+        B = int(rng.integers(1, 5))
+        cmp_mode, mask_mode = int(rng.integers(0, 2)), int(rng.integers(0, 2))
+        q = Q4Layer(synth.random_layer(d_in, d_out, rank, dt, seed=9500 + 100 * seed + case), group)
+        src = synth.DModelInput(d_in, config=89, linear=10 * seed + case)
+        X16 = synth.encode16(src.tokens(B), dt)
+        s_level = float(rng.choice([0.0, 0.3, 0.5, 0.5, 0.8, 0.97, 1.0]))
+        tau = gu.calibrated_tau(q.L, src, s_level) if 0.0 < s_level < 1.0 else (-INF if s_level == 0.0 else INF)
+        tuning = {"launches": int(rng.integers(1, 3))}
+        if rng.random() < 0.5:
+            tuning.update(splits=int(rng.integers(1, 40)), waves=int(rng.choice([1, 2, 4, 8])))
+        if rng.random() < 0.3:
+            tuning.update(lowrank_rows=int(rng.integers(1, 33)))
+        print("case", dict(group=group, d_in=d_in, d_out=d_out, rank=rank, dt=dt, B=B, cmp=cmp_mode, mask=mask_mode,
+                           s=s_level, **tuning), flush=True)
+        _parity(q, X16, tau, out_dtype=rs.F32, tuning=tuning, cmp_mode=cmp_mode, batch_mask_mode=mask_mode)
