@@ -134,10 +134,10 @@ def decoder_layer_sweep(torch, np, rs, synth):
         fn_group([b["gate"][0], b["up"][0]], b["gate"][1].data_ptr(), B, [b["gate"][2].data_ptr(), b["up"][2].data_ptr()], sptr)
         fn_one(b["down"][0], b["down"][1].data_ptr(), B, b["down"][2].data_ptr(), sptr)
 
-    def timed(B, fn_group, fn_one, reps=60):
+    def timed(B, fn_group, fn_one, reps=60, layer_fn=None):
         def one_pass(sptr):
             for b in ring:
-                one_layer(b, B, sptr, fn_group, fn_one)
+                (layer_fn or one_layer)(b, B, sptr, fn_group, fn_one)
         one_pass(stream.cuda_stream)
         torch.cuda.synchronize()
         g = torch.cuda.CUDAGraph()
@@ -171,6 +171,25 @@ def decoder_layer_sweep(torch, np, rs, synth):
         set_all()
         row["us_dense"] = round(timed(B, rs.rsparse_dense_ref_group, rs.rsparse_dense_ref), 2)
         row["speedup"] = round(row["us_dense"] / min(row["us_rsparse_one_launch"], row["us_rsparse_two_launches"]), 3)
+        if B == 1:
+            # per call, what rsparse_plan_layer picks for single-token decode (byte model + fixed launch costs)
+            plan = {"qkv": rs.rsparse_plan_layer(4096, 4096, r, 0.5, 3)[2], "o": rs.rsparse_plan_layer(4096, 4096, r, 0.5, 1)[2],
+                    "gate_up": rs.rsparse_plan_layer(4096, 11008, r, 0.5, 2)[2], "down": rs.rsparse_plan_layer(11008, 4096, r, 0.5, 1)[2]}
+
+            def planned_layer(b, Bn, sptr, _g, _o):
+                grp = lambda use: rs.rsparse_linear_group if use else rs.rsparse_dense_ref_group
+                one = lambda use: rs.rsparse_linear if use else rs.rsparse_dense_ref
+                grp(plan["qkv"])([b[n][0] for n in "qkv"], b["q"][1].data_ptr(), Bn, [b[n][2].data_ptr() for n in "qkv"], sptr)
+                one(plan["o"])(b["o"][0], b["o"][1].data_ptr(), Bn, b["o"][2].data_ptr(), sptr)
+                grp(plan["gate_up"])([b["gate"][0], b["up"][0]], b["gate"][1].data_ptr(), Bn,
+                                     [b["gate"][2].data_ptr(), b["up"][2].data_ptr()], sptr)
+                one(plan["down"])(b["down"][0], b["down"][1].data_ptr(), Bn, b["down"][2].data_ptr(), sptr)
+
+            set_all(launches=1)
+            row["plan"] = {k: ("rsparse" if v else "dense") for k, v in plan.items()}
+            row["us_planned"] = round(timed(B, None, None, layer_fn=planned_layer), 2)
+            row["speedup_planned"] = round(row["us_dense"] / row["us_planned"], 3)
+            set_all()
         out.append(row)
         log(str(row))
     for b in ring:

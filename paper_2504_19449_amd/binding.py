@@ -16,7 +16,7 @@ EXPORTED_SYMBOLS = [
     "rsparse_linear_gated", "rsparse_gated_input", "rsparse_mlp_gate_up", "rsparse_dense_ref", "rsparse_linear_group", "rsparse_dense_ref_group", "rsparse_last_active", "rsparse_synchronize",
     "rsparse_get_factors", "rsparse_set_tau", "rsparse_set_tuning",
     "rsparse_get_config", "rsparse_calibrate_tau", "rsparse_required_bytes", "rsparse_dense_bytes",
-    "rsparse_recipe", "rsparse_search_recipe", "rsparse_destroy", "rsparse_last_error",
+    "rsparse_recipe", "rsparse_plan_layer", "rsparse_search_recipe", "rsparse_destroy", "rsparse_last_error",
 ]
 
 
@@ -92,6 +92,9 @@ def load_library():
     lib.rsparse_recipe.argtypes = [i32, i32, C.c_double, C.c_double, C.POINTER(C.c_double), C.POINTER(i32),
                                    C.POINTER(C.c_double)]
     lib.rsparse_recipe.restype = C.c_int
+    lib.rsparse_plan_layer.argtypes = [i32, i32, i32, C.c_double, i32, C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                       C.POINTER(i32)]
+    lib.rsparse_plan_layer.restype = C.c_int
     lib.rsparse_search_recipe.argtypes = [LOSS_FN, vp, i32, i32, i32, C.c_double, C.c_double, i32, C.c_uint64,
                                           C.c_double, C.c_double, vp, vp, vp, vp]
     lib.rsparse_search_recipe.restype = C.c_int
@@ -305,6 +308,14 @@ def rsparse_recipe(d_in: int, d_out: int, budget_c: float, rho: float):
     s, r, io = C.c_double(0), C.c_int32(0), C.c_double(0)
     _check(load_library().rsparse_recipe(d_in, d_out, float(budget_c), float(rho), C.byref(s), C.byref(r), C.byref(io)))
     return s.value, r.value, io.value
+
+
+def rsparse_plan_layer(d_in: int, d_out: int, rank: int, keep_fraction: float, group: int = 1):
+    """(estimated us with R-Sparse, estimated us dense, use R-Sparse?) for one layer at one token; host code."""
+    a, b, use = C.c_double(), C.c_double(), C.c_int32()
+    _check(load_library().rsparse_plan_layer(d_in, d_out, rank, keep_fraction, group, C.byref(a), C.byref(b),
+                                             C.byref(use)))
+    return a.value, b.value, bool(use.value)
 
 
 def rsparse_destroy(layer: Layer):

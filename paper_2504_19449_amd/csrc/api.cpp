@@ -919,6 +919,26 @@ rsparse_status rsparse_recipe(int32_t d_in, int32_t d_out, double budget_c, doub
     return RSPARSE_OK;
 }
 
+rsparse_status rsparse_plan_layer(int32_t d_in, int32_t d_out, int32_t rank, double keep_fraction, int32_t group,
+                                  double *us_rsparse_out, double *us_dense_out, int32_t *use_rsparse_out)
+{
+    if (d_in < 1 || d_out < 1 || rank < 0 || rank > std::min(d_in, d_out)) return fail(RSPARSE_EINVAL, "bad layer shape");
+    if (!(keep_fraction >= 0.0) || keep_fraction > 1.0) return fail(RSPARSE_EINVAL, "keep_fraction must be in [0, 1]");
+    if (group < 1 || group > RSPARSE_MAX_GROUP) return fail(RSPARSE_EINVAL, "group %d outside [1, %d]", group, RSPARSE_MAX_GROUP);
+    // measured on MI355X with this library's kernels (16-bit weights, one token)
+    constexpr double kBytesPerUs = 6.5e6, kFixedRsparseUs = 8.5, kFixedDenseUs = 3.6;
+    const double m = d_out, n = d_in, r = rank, e = 2.0;
+    const double io = e * (n + m);
+    const double bytes_rs = e * (keep_fraction * n * m + r * (n + m)) + io;
+    const double bytes_dense = e * n * m + io;
+    const double us_rs = kFixedRsparseUs / group + bytes_rs / kBytesPerUs;
+    const double us_dense = kFixedDenseUs / group + bytes_dense / kBytesPerUs;
+    if (us_rsparse_out) *us_rsparse_out = us_rs;
+    if (us_dense_out) *us_dense_out = us_dense;
+    if (use_rsparse_out) *use_rsparse_out = us_rs < us_dense ? 1 : 0;
+    return RSPARSE_OK;
+}
+
 void rsparse_destroy(rsparse_layer *L) { free_layer(L); }
 
 }  // extern "C"

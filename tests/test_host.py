@@ -184,3 +184,31 @@ def test_q4_argument_validation(bad):
     st = rs.load_library().rsparse_prepare_q4(C.byref(cfg), ptr["Q"], ptr["S"], ptr["Z"], group, None, None, C.byref(h))
     assert st == 1 and h.value is None
     assert rs.rsparse_last_error()
+
+
+def test_plan_layer_byte_model_and_decisions():
+    """rsparse_plan_layer: the estimate is Sec. 3.4's byte model over a fixed rate plus a fixed cost per launch,
+    so it must be monotone in everything that adds bytes, and must reproduce the clear-cut decisions: small
+    attention projections dense, the large MLP layers with R-Sparse, nothing with R-Sparse when every channel
+    is kept."""
+    rs_small, d_small, use_small = rs.rsparse_plan_layer(4096, 4096, 256, 0.5)
+    assert not use_small and rs_small > d_small
+    rs_big, d_big, use_big = rs.rsparse_plan_layer(8192, 28672, 1024, 0.5)
+    assert use_big and 1.2 < d_big / rs_big < 1.6
+    assert not rs.rsparse_plan_layer(8192, 28672, 1024, 1.0)[2]
+    # exact arithmetic of the model on one case: bytes / 6.5e6 + fixed / group
+    us_rs, us_d, _ = rs.rsparse_plan_layer(4096, 11008, 512, 0.5, group=2)
+    io = 2.0 * (4096 + 11008)
+    want_rs = 8.5 / 2 + (2.0 * (0.5 * 4096 * 11008 + 512 * (4096 + 11008)) + io) / 6.5e6
+    want_d = 3.6 / 2 + (2.0 * 4096 * 11008 + io) / 6.5e6
+    assert abs(us_rs - want_rs) < 1e-9 and abs(us_d - want_d) < 1e-9
+    # monotone: more kept channels and more rank never make R-Sparse cheaper; sharing a launch never dearer
+    base = rs.rsparse_plan_layer(4096, 11008, 256, 0.4)[0]
+    assert rs.rsparse_plan_layer(4096, 11008, 256, 0.6)[0] > base
+    assert rs.rsparse_plan_layer(4096, 11008, 512, 0.4)[0] > base
+    assert rs.rsparse_plan_layer(4096, 11008, 256, 0.4, group=2)[0] < base
+    for bad in (dict(d_in=0), dict(rank=5000), dict(keep_fraction=1.5), dict(group=0), dict(group=5)):
+        kw = dict(d_in=4096, d_out=4096, rank=256, keep_fraction=0.5, group=1)
+        kw.update(bad)
+        with pytest.raises(rs.RSparseError):
+            rs.rsparse_plan_layer(**kw)
