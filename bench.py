@@ -27,7 +27,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-TRAFFIC_BYTES_PER_LAUNCH = 92.1e6   # rocprofv3 PMC: (120.9 + 61.6) / 2 MB fetched + 0.8 MB written per launch; see profiles/
+TRAFFIC_BYTES_PER_LAUNCH = 92.0e6   # rocprofv3 PMC: (120.8 + 61.5) / 2 MB fetched + 0.8 MB written per launch; see profiles/
 REPEATS = 5                # timed brackets of `steps` steps each; the median is reported
 RING_BLOCKS = 4            # MLP blocks in the ring: 12 layers, ~1.2 GiB of column-major weights
 RANK = 512
