@@ -136,8 +136,8 @@ rsparse_status rsparse_prepare_factors(const rsparse_config *cfg, const void *W_
  * U16_host / SV16_host stay 16-bit and are the caller's (of the unquantised W, or of W~).  group_size: a power
  * of two in [32, 1024] that divides d_in.  The library packs the codes channel-major (one kept channel = one
  * contiguous run of d_out / 2 bytes) and dequantises in registers: per quantisation group it accumulates
- * sum x_c q_c and sum x_c and applies scale and zero point once.  Limits of this path: max_batch <= 4,
- * dense_rowmajor = 0; rsparse_linear and friends run it as two launches per layer by default (tuning
+ * sum x_c q_c and sum x_c and applies scale and zero point once.  Limits of this path: dense_rowmajor = 0
+ * (no matrix-core path: batches above 4 tokens run as tiles of 4, the codes streamed once per tile); rsparse_linear and friends run it as two launches per layer by default (tuning
  * launches = 1 selects a one-launch form, measured no faster); grouped calls and rsparse_mlp_gate_up take
  * such layers one at a time; rsparse_dense_ref gives the dense product with W~.
  */

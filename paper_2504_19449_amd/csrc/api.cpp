@@ -143,6 +143,7 @@ struct rsparse_layer {
     std::vector<uint16_t> U16, SV16;       // host copies of the stored factors
     hipStream_t last_stream = nullptr;
     int last_batch = 0;
+    int last_bt = 0;                       // tokens per batch tile of the last call's kept lists (0 = batch_tile_of(last_batch))
 
     LayerView view() const
     {
@@ -274,7 +275,8 @@ rsparse_status build_layer(const rsparse_config *cfg, const uint16_t *W, const u
     L->cfg = *cfg;
     const size_t d_in = cfg->d_in, d_out = cfg->d_out, r = cfg->rank;
     L->tiles = (int)((d_out + kTile - 1) / kTile);
-    L->nz_max = std::max(1, (cfg->max_batch + kMaxBT - 1) / kMaxBT);
+    // (the 4-bit kernels hold at most 4 tokens per batch tile)
+    L->nz_max = std::max(1, q4 ? (cfg->max_batch + 3) / 4 : (cfg->max_batch + kMaxBT - 1) / kMaxBT);
 
     rsparse_status st = RSPARSE_OK;
     auto body = [&]() -> rsparse_status {
@@ -465,7 +467,6 @@ rsparse_status rsparse_prepare_q4(const rsparse_config *cfg, const uint8_t *Q_ho
     if (cfg->rank > 0 && (!U16_host || !SV16_host)) return fail(RSPARSE_EINVAL, "factors are NULL but rank > 0");
     if (group_size < 32 || group_size > 1024 || (group_size & (group_size - 1)) || cfg->d_in % group_size)
         return fail(RSPARSE_EINVAL, "group_size must be a power of two in [32, 1024] that divides d_in (got %d)", group_size);
-    if (cfg->max_batch > 4) return fail(RSPARSE_EINVAL, "layers with 4-bit weights take at most 4 tokens (max_batch %d)", cfg->max_batch);
     if (cfg->dense_rowmajor) return fail(RSPARSE_EINVAL, "dense_rowmajor is not available with 4-bit weights");
     const size_t n = (size_t)cfg->d_in * cfg->d_out, ng = n / group_size;
     for (size_t i = 0; i < n; ++i)
@@ -484,7 +485,7 @@ Launch resolve_launch_q4(const rsparse_layer *L, int batch, bool dense, bool fus
 {
     Launch c{};
     const rsparse_tuning &t = L->tuning;
-    const int bt = batch_tile_of(batch);
+    const int bt = std::min(4, batch_tile_of(batch));
     c.waves = (t.waves == 1 || t.waves == 2 || t.waves == 4 || t.waves == 8) ? t.waves : 4;
     if (bt >= 4 && c.waves > 4) c.waves = 4;         // the 4-token kernel is built for at most 256 lanes
     c.nontemporal = t.nontemporal == 2 ? 0 : 1;
@@ -525,7 +526,8 @@ rsparse_status linear_q4(rsparse_layer *L, const void *X_dev, int32_t batch, voi
     const int stages = L->tuning.stages;
     // two launches by default: the one-launch form (launches = 1) measured no faster on these weights --
     // its tail waits for up to `splits` same-address atomics that the two-launch form never waits for
-    const bool fused = !dense && L->tuning.launches == 1 && stages == 0;
+    // (its arrival counters cover up to kSyncMaxZ batch tiles of 4 tokens)
+    const bool fused = !dense && L->tuning.launches == 1 && stages == 0 && (batch + 3) / 4 <= kSyncMaxZ;
     const Launch lc = resolve_launch_q4(L, batch, dense, fused);
     if (fused) {
         RS_HIP(launch_q4(v, lc, X_dev, batch, true, false, Y_dev, s));
@@ -535,6 +537,7 @@ rsparse_status linear_q4(rsparse_layer *L, const void *X_dev, int32_t batch, voi
     }
     if (!dense) {
         L->last_stream = s; L->last_batch = batch; L->last_mfma = false; L->last_fused = fused;
+        L->last_bt = std::min(4, batch_tile_of(batch));
     }
     return RSPARSE_OK;
 }
@@ -640,6 +643,7 @@ rsparse_status linear_group_impl(rsparse_layer *const *layers, int32_t n_layers,
         layers[i]->last_batch = batch;
         layers[i]->last_mfma = mfma;
         layers[i]->last_fused = !mfma && fused;
+        layers[i]->last_bt = 0;
     }
     return RSPARSE_OK;
 }
@@ -673,7 +677,7 @@ rsparse_status rsparse_mlp_gate_up(rsparse_layer *gate, rsparse_layer *up, const
         // rounds g and u, applies silu(g) * u and stores H
         RS_HIP(launch_fused(v, lc, 2, X_dev, batch, outs, s, true));
         for (int i = 0; i < 2; ++i) {
-            pair[i]->last_stream = s; pair[i]->last_batch = batch; pair[i]->last_mfma = false; pair[i]->last_fused = true;
+            pair[i]->last_stream = s; pair[i]->last_batch = batch; pair[i]->last_mfma = false; pair[i]->last_fused = true; pair[i]->last_bt = 0;
         }
         return RSPARSE_OK;
     }
@@ -776,7 +780,7 @@ rsparse_status rsparse_last_active(rsparse_layer *L, int32_t token, int32_t *idx
         *count = n;
         return RSPARSE_OK;
     }
-    const int bt = batch_tile_of(L->last_batch);
+    const int bt = L->last_bt > 0 ? L->last_bt : batch_tile_of(L->last_batch);
     const int nz = (L->last_batch + bt - 1) / bt;
     const size_t d_in = L->cfg.d_in;
     std::vector<int32_t> cnt(nz), list;

@@ -73,7 +73,7 @@ hipError_t launch_sparse_and_t(const LayerView *L, const Launch *cfg, int n, con
 // stores H = round(silu(round(g)) * round(u)) to Y[0] instead of the two outputs (Y[1] is not written).
 hipError_t launch_fused(const LayerView *L, const Launch *cfg, int n, const void *X, int batch, void *const *Y,
                         hipStream_t stream, bool gate_up = false);
-// First launch of a layer with 4-bit weights (at most 4 tokens): as launch_sparse_and_t, with the codes
+// First launch of a layer with 4-bit weights (batch tiles of at most 4 tokens): as launch_sparse_and_t, with the codes
 // dequantised in registers -- per quantisation group the kernel accumulates sum_c x_c q_c and sum_c x_c and
 // applies scale and zero point once, when the group ends.  dense: every channel is kept (the dense baseline
 // on the same weights).  Y_fused == nullptr: launch_finish completes the layer.  Y_fused != nullptr: the whole

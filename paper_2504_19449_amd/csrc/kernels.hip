@@ -1323,12 +1323,15 @@ hipError_t launch_q4(const LayerView &L, const Launch &cfg, const void *X, int b
 {
     const bool fused = Y_fused != nullptr;
     if (fused && (dense || !with_t || !L.sync || !L.t_pub || (L.rank > 0 && !L.Ut))) return hipErrorInvalidValue;
-    if (!L.Mq || !L.qs || !L.qz || batch < 1 || batch > 4 || L.qshift < 3 || (L.d_in >> L.qshift) < 1 ||
+    if (!L.Mq || !L.qs || !L.qz || batch < 1 || batch > 32 || L.qshift < 3 || (L.d_in >> L.qshift) < 1 ||
         ((L.d_in >> L.qshift) << L.qshift) != L.d_in || L.qtiles != (L.d_out + kQ4Tile - 1) / kQ4Tile ||
         cfg.splits < 1 || cfg.lowrank_rows < 1 || cfg.lowrank_rows > kRowsPerWave * cfg.waves)
         return hipErrorInvalidValue;
-    const int bt = batch_tile(batch);
+    // batches above 4 tokens run as batch tiles of 4 in the grid's z dimension (the codes are streamed once per tile)
+    const int bt = std::min(4, batch_tile(batch));
+    const int nz = (batch + bt - 1) / bt;
     if (bt >= 4 && cfg.waves > 4) return hipErrorInvalidValue;
+    if (fused && nz > kSyncMaxZ) return hipErrorInvalidValue;
     GroupArgs ga{};
     ga.n = 1;
     GatherArgs &a = ga.job[0];
@@ -1340,7 +1343,7 @@ hipError_t launch_q4(const LayerView &L, const Launch &cfg, const void *X, int b
     a.tile_map = 1;
     a.dense = dense ? 1 : 0;
     a.Y = Y_fused;
-    a.nz = 1;
+    a.nz = nz;
     a.wait_polls = cfg.wait_polls > 0 ? cfg.wait_polls : kWaitLimitPolls;
     a.skip_stage1 = cfg.skip_stage1;
     const int total = a.lr_wgs + L.qtiles * cfg.splits;
@@ -1348,7 +1351,7 @@ hipError_t launch_q4(const LayerView &L, const Launch &cfg, const void *X, int b
     size_t lds = gather_lds_bytes(L.d_in, cfg.splits, cfg.waves, bt, fused ? L.rank : 0);
     if (a.lr_wgs > 0) lds = std::max(lds, lowrank_lds_bytes(L.d_in, bt));
     if (lds > 64 * 1024) return hipErrorInvalidValue;
-    dim3 grid(total, 1, 1), block(kWave * cfg.waves);
+    dim3 grid(total, 1, nz), block(kWave * cfg.waves);
     const bool nt = cfg.nontemporal != 0;
 #define RS_Q1(DT, BTV)                                                                                  \
     do {                                                                                                \

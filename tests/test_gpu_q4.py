@@ -68,14 +68,17 @@ def test_q4_ragged_batch1(ragged_q4, dt, out):
         assert 0.3 * q.L.d_in < len(got["act"][0]) < 0.7 * q.L.d_in
 
 
-@pytest.mark.parametrize("B", [2, 3, 4])
+@pytest.mark.parametrize("B", [2, 3, 4, 5, 8, 9, 16, 17, 32])
 @pytest.mark.parametrize("mask_mode", [0, 1])
 def test_q4_batches(ragged_q4, B, mask_mode):
+    """Up to 4 tokens share one pass over the codes; larger batches run as batch tiles of 4.  Both launch
+    forms (the one-launch form covers up to 16 tokens and falls back to two launches beyond)."""
     q = ragged_q4[synth.BF16]
     X16, src = gu.tokens_for(q.L, B, linear=B)
     tau = gu.calibrated_tau(q.L, src, 0.5)
     _parity(q, X16, tau, out_dtype=rs.F32, batch_mask_mode=mask_mode)
     _parity(q, X16, tau, batch_mask_mode=mask_mode)
+    _parity(q, X16, tau, out_dtype=rs.F32, batch_mask_mode=mask_mode, tuning=dict(launches=1))
 
 
 def test_q4_edge_thresholds_and_sparsities(ragged_q4):
@@ -286,7 +289,7 @@ def test_q4_config1_shapes_as_benchmarked():
 @pytest.mark.parametrize("seed", range(4))
 def test_q4_random_shapes_and_settings(seed):
     """Seeded sweep over small random layers on 4-bit weights: group sizes 32-256, d_in any multiple of the
-    group, d_out any multiple of 8 (1-3 column tiles, ragged), ranks from 0 up, 1-4 tokens, both dtypes, compare
+    group, d_out any multiple of 8 (1-3 column tiles, ragged), ranks from 0 up, 1-32 tokens, both dtypes, compare
     modes, mask modes and launch forms, random launch shapes.  Lists equal, outputs within the fp32-output bound."""
     rng = np.random.default_rng(4321 + seed)
     for case in range(8):
@@ -295,7 +298,7 @@ def test_q4_random_shapes_and_settings(seed):
         d_out = 8 * int(rng.integers(1, 330))
         rank = 8 * int(rng.integers(0, min(min(d_in, d_out) // 8, 12) + 1))
         dt = int(rng.integers(0, 2))
-        B = int(rng.integers(1, 5))
+        B = int(rng.choice([1, 1, 2, 3, 4, 4, 5, 7, 12, 16, 17, 32]))
         cmp_mode, mask_mode = int(rng.integers(0, 2)), int(rng.integers(0, 2))
         q = Q4Layer(synth.random_layer(d_in, d_out, rank, dt, seed=9500 + 100 * seed + case), group)
         src = synth.DModelInput(d_in, config=89, linear=10 * seed + case)
