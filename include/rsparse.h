@@ -103,7 +103,7 @@ typedef struct {
 /*
  * Offline preparation (Sec. 3.4: the low-rank factors come from one SVD of W, done ahead of time).
  * W_host: host, [d_out][d_in] 16-bit of cfg->dtype.  The library computes the top-`rank`
- * singular triplets on the host, forms U_r and S_r V_r^T, rounds each once to cfg->dtype,
+ * singular triplets on the host in fp64, forms U_r and S_r V_r^T, rounds each entry once (fp64 to cfg->dtype, nearest even),
  * packs W column-major and uploads everything.  *out receives a new handle.
  */
 rsparse_status rsparse_prepare(const rsparse_config *cfg, const void *W_host, rsparse_layer **out);
@@ -162,7 +162,7 @@ rsparse_status rsparse_linear(rsparse_layer *layer, const void *X_dev, int32_t b
  * the layer's own.  G_dev, Up_dev: device, [batch][d_in] 16-bit of cfg.dtype, 16-byte aligned (the
  * outputs of the gate and up projections).  silu is evaluated by a fixed fp32 recipe (range
  * reduction x = -g = n ln2 + r, degree-7 polynomial for exp(r), one division) so that the 16-bit x,
- * and with it the kept-channel sets, are reproducible bit for bit; it is within 2.2 ulp of
+ * and with it the kept-channel sets, are reproducible bit for bit; it is within 3 ulp (fp32; measured 2.4) of
  * g / (1 + exp(-g)).  Everything else as rsparse_linear (rsparse_last_active reports the kept
  * channels of x).
  */
@@ -246,6 +246,22 @@ rsparse_status rsparse_calibrate_tau(const void *X_host, int32_t dtype, size_t n
  */
 size_t rsparse_required_bytes(const rsparse_layer *layer, int32_t batch, int32_t k_union);
 size_t rsparse_dense_bytes(const rsparse_layer *layer, int32_t batch);
+
+/*
+ * The same byte model from the layer's shape alone (host code, no handle, no device): Sec. 3.4 gives the
+ * memory I/O of the layer relative to the full one as r (m + n) / (m n) + s, s the share of weight columns
+ * loaded; in bytes, with e = 2 per 16-bit value, k_union kept channels, B = batch:
+ *   *required_out = e (k d_out + r d_out + r d_in + B d_in) + e_out B d_out
+ *   *dense_out    = e (d_in d_out + B d_in) + e_out B d_out
+ *   *required_inactive_only_out = the same as required with r (d_in - k) for r d_in: what a layout of
+ *                   S_r V_r^T that reads only the dropped channels' entries would move
+ * (e_out = 4 for fp32 output).  q4_group = 0: 16-bit weights; otherwise the group size of 4-bit weights
+ * (rsparse_prepare_q4): half a byte per weight plus 2.5 bytes per output and group that holds a kept channel.
+ * Only d_in, d_out, rank, dtype and out_dtype of cfg matter (the rest must still be valid).  Any output
+ * pointer may be NULL.
+ */
+rsparse_status rsparse_io_model(const rsparse_config *cfg, int32_t q4_group, int32_t batch, int32_t k_union,
+                                size_t *required_out, size_t *dense_out, size_t *required_inactive_only_out);
 
 /*
  * Sparsification recipe of one layer (Sec. 3.5): a budget C (memory I/O relative to the full layer)

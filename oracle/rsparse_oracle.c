@@ -250,8 +250,9 @@ double orc_quantile_tau(const void *x, int x_kind, size_t n, double s)
  *   p = exp(r) by the degree-7 Taylor polynomial (Horner, fused multiply-adds)
  *   e = p * 2^n (exponent-field addition);  silu = g / (1 + e);  h = round16(silu * u)
  *
- * Pins: silu32 against the fp64 value g / (1 + exp(-g)) to a few ulp; the rounding step against
- * numpy's fp16 / bf16 conversions.
+ * Pins: silu32 against the fp64 value g / (1 + exp(-g)): within 3 ulp (measured 2.4); the rounding step
+ * against torch's fp16 / bf16 conversions; the whole recipe against orc_gated_input_plain below (the plain
+ * fp64 definition): equal bits except next to a rounding flip point.
  */
 static inline uint32_t f32_bits(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
 static inline float f32_from(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }
@@ -319,6 +320,86 @@ int orc_gated_input(const uint16_t *g16, const uint16_t *u16, int kind, size_t n
 void orc_silu32_array(const float *g, size_t n, float *out)
 {
     for (size_t i = 0; i < n; ++i) out[i] = orc_silu32(g[i]);
+}
+
+/* The two fp32 -> 16-bit roundings above, exposed so that the tests can pin them against an independent
+ * implementation (torch's CPU conversions). */
+void orc_round16_array(const float *f, size_t n, int kind, uint16_t *out16)
+{
+    for (size_t i = 0; i < n; ++i) out16[i] = kind == ORC_F16 ? f32_to_f16_rne(f[i]) : f32_to_bf16_rne(f[i]);
+}
+
+/* ---- the gated input by its plain definition (Sec. 3.1) -----------------------------------------
+ *
+ * h = u * g / (1 + exp(-g)) evaluated in fp64 with the C library's exp, then ONE rounding (nearest, ties to
+ * even) of that double to the 16-bit storage type.  No recipe, no fp32 intermediate: this is the definition
+ * the fp32 recipe above approximates, and the cross-check of that recipe and of the device's copy of it.
+ *
+ * The rounding is written from the formats' definitions (p significand bits, smallest normal exponent
+ * emin, largest finite value), not from bit manipulation: scale the magnitude so that one unit in the
+ * last place becomes 1.0, round with rint (the default rounding mode is nearest-even), scale back.
+ *   fp16:  p = 11, emin = -14, max = 65504         bf16:  p = 8, emin = -126, max = (2 - 2^-7) 2^127
+ * out16[i]: the rounded bits.  margin[i] (may be NULL): how far the fp64 value is from the nearest point
+ * where the rounding flips (a midpoint between two neighbouring 16-bit values), as a fraction of the
+ * spacing of the 16-bit values there -- 0 = exactly on a midpoint, 0.5 = exactly representable.  A result
+ * whose margin exceeds the error of an approximate evaluation cannot differ from that evaluation's.
+ */
+static uint16_t round_double_to16(double v, int kind, double *margin)
+{
+    const int p = kind == ORC_F16 ? 11 : 8, emin = kind == ORC_F16 ? -14 : -126;
+    const int emax = kind == ORC_F16 ? 15 : 127, ebits = kind == ORC_F16 ? 5 : 8, bias = emax;
+    const uint16_t sign = signbit(v) ? 0x8000u : 0u;
+    const uint16_t inf = (uint16_t)(((1u << ebits) - 1u) << (p - 1));
+    if (margin) *margin = 0.5;
+    if (isnan(v)) return (uint16_t)(inf | (1u << (p - 2)));          /* quiet NaN, sign dropped */
+    double a = fabs(v);
+    if (isinf(a)) return (uint16_t)(sign | inf);
+    if (a == 0.0) return sign;
+    int e;
+    (void)frexp(a, &e);                    /* a = m 2^e, 0.5 <= m < 1, i.e. 2^(e-1) <= a < 2^e */
+    int ex = e - 1;                        /* exponent of the leading bit */
+    if (ex < emin) ex = emin;              /* subnormal range: fixed spacing 2^(emin - p + 1) */
+    const double q = ldexp(a, -(ex - (p - 1)));      /* a in units of the spacing: exact (power of two) */
+    const double n = rint(q);                         /* nearest, ties to even */
+    if (margin) {
+        const double f = q - floor(q);                /* position between two neighbours */
+        *margin = fabs(f - 0.5);
+    }
+    double r = ldexp(n, ex - (p - 1));
+    /* the largest finite value is (2 - 2^(1-p)) 2^emax; rounding reached 2^(emax+1) -> infinity */
+    if (r >= ldexp(1.0, emax + 1)) return (uint16_t)(sign | inf);
+    if (r == 0.0) return sign;
+    int e2;
+    const double m2 = frexp(r, &e2);       /* r = m2 2^e2 */
+    int ex2 = e2 - 1;
+    uint32_t bits;
+    if (ex2 < emin) {
+        bits = (uint32_t)ldexp(r, -(emin - (p - 1)));                  /* subnormal: the count of spacings */
+    } else {
+        const uint32_t frac = (uint32_t)(ldexp(m2, p) - ldexp(1.0, p - 1));   /* significand without the leading bit */
+        bits = ((uint32_t)(ex2 + bias) << (p - 1)) | frac;
+    }
+    return (uint16_t)(sign | bits);
+}
+
+int orc_gated_input_plain(const uint16_t *g16, const uint16_t *u16, int kind, size_t n, uint16_t *out16,
+                          double *margin)
+{
+    if (kind != ORC_F16 && kind != ORC_BF16) return 1;
+    for (size_t i = 0; i < n; ++i) {
+        const double g = kind == ORC_F16 ? orc_half_to_double(g16[i]) : orc_bf16_to_double(g16[i]);
+        const double u = kind == ORC_F16 ? orc_half_to_double(u16[i]) : orc_bf16_to_double(u16[i]);
+        /* g = -inf: the quotient reads inf / inf; the function's limit there is 0 from below */
+        const double silu = (isinf(g) && g < 0) ? -0.0 : g / (1.0 + exp(-g));
+        out16[i] = round_double_to16(silu * u, kind, margin ? margin + i : NULL);
+    }
+    return 0;
+}
+
+/* One rounding of doubles to the 16-bit type, by the definition above (test hook). */
+void orc_round16_from_double(const double *v, size_t n, int kind, uint16_t *out16)
+{
+    for (size_t i = 0; i < n; ++i) out16[i] = round_double_to16(v[i], kind, NULL);
 }
 
 /* ---- 4-bit weights ------------------------------------------------------- */

@@ -12,13 +12,21 @@ from . import build as _build
 
 F16, BF16, F64 = 0, 1, 2
 
+# How close (in units of the local spacing of the 16-bit values) the exact gated input u * silu(g) must be to a
+# rounding flip point before an evaluation within 3 fp32 ulp of silu, followed by one fp32 product rounding,
+# may round the other way: 3.5 ulp <= 7 * 2^-24 relative, times 2^p spacings per unit of relative error
+# (p = 11 significand bits for fp16, 8 for bf16).
+RECIPE_BAND = {F16: 7.0 * 2.0 ** -24 * 2.0 ** 11, BF16: 7.0 * 2.0 ** -24 * 2.0 ** 8}
+
 _lib = None
 
 
 def _load():
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
+        # RSPARSE_ORACLE_LIB: a library built from a (deliberately altered) copy of the source, for the
+        # test that plants mistakes in the oracle and expects the pins to catch them
+        path = os.environ.get("RSPARSE_ORACLE_LIB") or _build.build(force=False)
         lib = C.CDLL(path)
         lib.orc_rsparse_linear.restype = C.c_int
         lib.orc_rsparse_linear.argtypes = [
@@ -39,6 +47,12 @@ def _load():
         lib.orc_gated_input.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_size_t, C.c_void_p]
         lib.orc_silu32_array.restype = None
         lib.orc_silu32_array.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.orc_round16_array.restype = None
+        lib.orc_round16_array.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_void_p]
+        lib.orc_gated_input_plain.restype = C.c_int
+        lib.orc_gated_input_plain.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_size_t, C.c_void_p, C.c_void_p]
+        lib.orc_round16_from_double.restype = None
+        lib.orc_round16_from_double.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_void_p]
         lib.orc_dequant_q4.restype = C.c_int
         lib.orc_dequant_q4.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
         _lib = lib
@@ -82,6 +96,36 @@ def gated_input(G16, U16, dtype) -> np.ndarray:
     out = np.empty(G16.shape, dtype=np.uint16)
     rc = _load().orc_gated_input(_ptr(G16), _ptr(U16), dtype, G16.size, _ptr(out))
     assert rc == 0
+    return out
+
+
+def gated_input_plain(G16, U16, dtype):
+    """h = round16(u * g / (1 + exp(-g))) from the plain fp64 definition (Sec. 3.1), one rounding.
+    Returns (bits, margin): margin = distance of the fp64 value from the nearest rounding flip point, in
+    units of the local spacing of the 16-bit values (0 .. 0.5)."""
+    G16 = _arr(G16, dtype)
+    U16 = _arr(U16, dtype)
+    assert G16.shape == U16.shape
+    out = np.empty(G16.shape, dtype=np.uint16)
+    margin = np.empty(G16.shape, dtype=np.float64)
+    rc = _load().orc_gated_input_plain(_ptr(G16), _ptr(U16), dtype, G16.size, _ptr(out), _ptr(margin))
+    assert rc == 0
+    return out, margin
+
+
+def round16(f32, dtype) -> np.ndarray:
+    """The oracle's fp32 -> fp16 / bf16 rounding (nearest even), as uint16 bits."""
+    f = np.ascontiguousarray(f32, dtype=np.float32)
+    out = np.empty(f.shape, dtype=np.uint16)
+    _load().orc_round16_array(_ptr(f), f.size, dtype, _ptr(out))
+    return out
+
+
+def round16_from_double(v, dtype) -> np.ndarray:
+    """One rounding of fp64 values to fp16 / bf16 by the formats' definition, as uint16 bits."""
+    v = np.ascontiguousarray(v, dtype=np.float64)
+    out = np.empty(v.shape, dtype=np.uint16)
+    _load().orc_round16_from_double(_ptr(v), v.size, dtype, _ptr(out))
     return out
 
 

@@ -15,7 +15,7 @@ EXPORTED_SYMBOLS = [
     "rsparse_prepare", "rsparse_compute_factors", "rsparse_prepare_factors", "rsparse_prepare_q4", "rsparse_linear",
     "rsparse_linear_gated", "rsparse_gated_input", "rsparse_mlp_gate_up", "rsparse_dense_ref", "rsparse_linear_group", "rsparse_dense_ref_group", "rsparse_last_active", "rsparse_synchronize",
     "rsparse_get_factors", "rsparse_set_tau", "rsparse_set_tuning",
-    "rsparse_get_config", "rsparse_calibrate_tau", "rsparse_required_bytes", "rsparse_dense_bytes",
+    "rsparse_get_config", "rsparse_calibrate_tau", "rsparse_required_bytes", "rsparse_dense_bytes", "rsparse_io_model",
     "rsparse_recipe", "rsparse_plan_layer", "rsparse_search_recipe", "rsparse_destroy", "rsparse_last_error",
 ]
 
@@ -89,6 +89,9 @@ def load_library():
     lib.rsparse_required_bytes.restype = C.c_size_t
     lib.rsparse_dense_bytes.argtypes = [vp, i32]
     lib.rsparse_dense_bytes.restype = C.c_size_t
+    lib.rsparse_io_model.argtypes = [C.POINTER(Config), i32, i32, i32, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t),
+                                     C.POINTER(C.c_size_t)]
+    lib.rsparse_io_model.restype = C.c_int
     lib.rsparse_recipe.argtypes = [i32, i32, C.c_double, C.c_double, C.POINTER(C.c_double), C.POINTER(i32),
                                    C.POINTER(C.c_double)]
     lib.rsparse_recipe.restype = C.c_int
@@ -301,6 +304,13 @@ def rsparse_required_bytes(layer: Layer, batch: int, k_union: int) -> int:
 
 def rsparse_dense_bytes(layer: Layer, batch: int) -> int:
     return int(load_library().rsparse_dense_bytes(layer.handle, batch))
+
+
+def rsparse_io_model(cfg: Config, batch: int, k_union: int, q4_group: int = 0):
+    """(required, dense, required with inactive-only factor reads) bytes of Sec. 3.4's I/O model; host code."""
+    a, b, c = C.c_size_t(0), C.c_size_t(0), C.c_size_t(0)
+    _check(load_library().rsparse_io_model(C.byref(cfg), q4_group, batch, k_union, C.byref(a), C.byref(b), C.byref(c)))
+    return a.value, b.value, c.value
 
 
 def rsparse_recipe(d_in: int, d_out: int, budget_c: float, rho: float):

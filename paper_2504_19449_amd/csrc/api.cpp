@@ -70,10 +70,15 @@ float widen16(uint16_t h, int dtype) { return dtype == RSPARSE_F16 ? half_bits_t
 
 uint16_t double_to_bf16(double d)
 {
-    float f = (float)d;   // double -> float -> bf16; the first step is exact enough for factor storage
+    // One rounding, double -> bf16.  Going through fp32 rounds twice; the only way that can differ is when
+    // the first rounding lands exactly on a bf16 tie (low half 0x8000) that d itself was not on: move the
+    // fp32 value one step towards d, so that the second rounding goes to d's side of the tie.
+    float f = (float)d;
     uint32_t u;
     memcpy(&u, &f, 4);
     if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    if ((u & 0xffffu) == 0x8000u && (u & 0x7f800000u) != 0x7f800000u && (double)f != d)
+        u += std::fabs(d) > std::fabs((double)f) ? 1u : 0xffffffffu;
     u += 0x7fffu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
 }
@@ -882,26 +887,47 @@ rsparse_status rsparse_calibrate_tau(const void *X_host, int32_t dtype, size_t n
     return RSPARSE_OK;
 }
 
+rsparse_status rsparse_io_model(const rsparse_config *cfg, int32_t q4_group, int32_t batch, int32_t k_union,
+                                size_t *required_out, size_t *dense_out, size_t *required_inactive_only_out)
+{
+    rsparse_status st = check_config(cfg);
+    if (st != RSPARSE_OK) return st;
+    if (batch < 1 || batch > RSPARSE_MAX_BATCH) return fail(RSPARSE_EBATCH, "batch %d outside [1, %d]", batch, RSPARSE_MAX_BATCH);
+    if (k_union < 0 || k_union > cfg->d_in) return fail(RSPARSE_EINVAL, "k_union %d outside [0, d_in]", k_union);
+    if (q4_group != 0 && (q4_group < 32 || q4_group > 1024 || (q4_group & (q4_group - 1)) || cfg->d_in % q4_group))
+        return fail(RSPARSE_EINVAL, "q4_group must be 0 or a power of two in [32, 1024] that divides d_in");
+    const size_t e = 2, d_in = cfg->d_in, d_out = cfg->d_out, r = cfg->rank, B = batch, k = k_union;
+    const size_t eo = cfg->out_dtype == RSPARSE_F32 ? 4 : 2;
+    const size_t io = e * B * d_in + eo * B * d_out;
+    size_t w_kept, w_all;
+    if (q4_group) {
+        // half a byte per weight; scale (2 bytes) and zero point (half a byte) per output and group -- of every
+        // group that holds a kept channel (at most min(groups, k))
+        const size_t groups = d_in / (size_t)q4_group;
+        w_kept = k * d_out / 2 + std::min(groups, k) * d_out * 5 / 2;
+        w_all = d_in * d_out / 2 + groups * d_out * 5 / 2;
+    } else {
+        w_kept = e * k * d_out;
+        w_all = e * d_in * d_out;
+    }
+    if (required_out) *required_out = w_kept + e * (r * d_out + r * d_in) + io;
+    if (dense_out) *dense_out = w_all + io;
+    if (required_inactive_only_out) *required_inactive_only_out = w_kept + e * (r * d_out + r * (d_in - k)) + io;
+    return RSPARSE_OK;
+}
+
 size_t rsparse_required_bytes(const rsparse_layer *L, int32_t batch, int32_t k_union)
 {
-    if (!L || batch < 1 || k_union < 0) return 0;
-    const size_t e = 2, d_in = L->cfg.d_in, d_out = L->cfg.d_out, r = L->cfg.rank, B = batch, k = k_union;
-    const size_t eo = L->cfg.out_dtype == RSPARSE_F32 ? 4 : 2;
-    if (L->q4()) {
-        // half a byte per kept weight; scale (2 bytes) and zero point (half a byte) of every group that holds a kept channel (at most all)
-        const size_t groups = std::min<size_t>(d_in >> L->qshift, k);
-        return k * d_out / 2 + groups * d_out * 5 / 2 + e * (r * d_out + r * d_in + B * d_in) + eo * B * d_out;
-    }
-    return e * (k * d_out + r * d_out + r * d_in + B * d_in) + eo * B * d_out;
+    size_t v = 0;
+    if (!L || rsparse_io_model(&L->cfg, L->q4() ? 1 << L->qshift : 0, batch, k_union, &v, nullptr, nullptr) != RSPARSE_OK) return 0;
+    return v;
 }
 
 size_t rsparse_dense_bytes(const rsparse_layer *L, int32_t batch)
 {
-    if (!L || batch < 1) return 0;
-    const size_t e = 2, d_in = L->cfg.d_in, d_out = L->cfg.d_out, B = batch;
-    const size_t eo = L->cfg.out_dtype == RSPARSE_F32 ? 4 : 2;
-    if (L->q4()) return d_in * d_out / 2 + (d_in >> L->qshift) * d_out * 5 / 2 + e * B * d_in + eo * B * d_out;
-    return e * (d_in * d_out + B * d_in) + eo * B * d_out;
+    size_t v = 0;
+    if (!L || rsparse_io_model(&L->cfg, L->q4() ? 1 << L->qshift : 0, batch, 0, nullptr, &v, nullptr) != RSPARSE_OK) return 0;
+    return v;
 }
 
 rsparse_status rsparse_recipe(int32_t d_in, int32_t d_out, double budget_c, double rho, double *keep_fraction_out,

@@ -57,9 +57,18 @@ def encode16(a, dtype: int) -> np.ndarray:
         with np.errstate(over="ignore"):
             return np.ascontiguousarray(a.astype(np.float16)).view(np.uint16)
     if dtype == BF16:
-        f = np.ascontiguousarray(a.astype(np.float32))
+        with np.errstate(over="ignore"):
+            f = np.ascontiguousarray(a.astype(np.float32))
         u = f.view(np.uint32).astype(np.uint64)
         nan = np.isnan(f)
+        if a.dtype == np.float64:
+            # one rounding from fp64: if the fp32 step landed exactly on a bf16 tie that `a` was not on, move one
+            # fp32 step towards `a` so that the second rounding falls on a's side
+            with np.errstate(invalid="ignore"):
+                fd = f.astype(np.float64)
+                tie = ((u & 0xFFFF) == 0x8000) & np.isfinite(f) & (fd != a)
+                up = np.abs(a) > np.abs(fd)
+            u = np.where(tie & up, u + 1, np.where(tie & ~up, u - 1, u))
         rounded = (u + 0x7FFF + ((u >> 16) & 1)) >> 16
         out = rounded.astype(np.uint16)
         out[nan] = 0x7FC0

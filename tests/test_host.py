@@ -212,3 +212,61 @@ def test_plan_layer_byte_model_and_decisions():
         kw.update(bad)
         with pytest.raises(rs.RSparseError):
             rs.rsparse_plan_layer(**kw)
+
+
+def test_io_model_is_the_byte_form_of_sec_3_4():
+    """rsparse_io_model (which rsparse_required_bytes / rsparse_dense_bytes evaluate for a handle) against
+    the paper's own cost model: relative memory I/O r (m + n) / (m n) + s with s the share of columns loaded
+    (Sec. 3.4), here in bytes with the token and the output added, for every benchmark shape; numbers that
+    the survey tabulates for configs[0] and configs[1] are reproduced to the byte."""
+    shapes = [(4096, 4096, 256, rs.F16), (4096, 11008, 512, rs.BF16), (11008, 4096, 512, rs.BF16),
+              (4096, 14336, 256, rs.BF16), (4096, 1024, 128, rs.BF16), (8192, 28672, 1024, rs.BF16),
+              (28672, 8192, 1024, rs.BF16), (8192, 1024, 1024, rs.BF16), (1032, 1096, 40, rs.F16)]
+    for d_in, d_out, r, dt in shapes:
+        for B in (1, 2, 8, 32):
+            for k in (0, d_in // 2, (d_in * 3) // 10, d_in):
+                for out in (dt, rs.F32):
+                    cfg = rs.make_config(d_in, d_out, r, 0.0, dt, max_batch=32, out_dtype=out)
+                    req, dense, req_in = rs.rsparse_io_model(cfg, B, k)
+                    eo = 4 if out == rs.F32 else 2
+                    io = 2 * B * d_in + eo * B * d_out
+                    assert dense == 2 * d_in * d_out + io
+                    assert req == 2 * (k * d_out + r * d_out + r * d_in) + io
+                    assert req_in == 2 * (k * d_out + r * d_out + r * (d_in - k)) + io
+                    # the paper's relative form: (required - token - output) / W bytes = r (m + n) / (m n) + s
+                    m, n, s = d_out, d_in, k / d_in
+                    assert math.isclose((req - io) / (2 * d_in * d_out), r * (m + n) / (m * n) + s, rel_tol=1e-12)
+    # tabulated values: 4096 x 4096, r = 256, half the channels -> 20.99 MB against 33.57 MB (ratio 0.625);
+    # 4096 -> 11008, r = 512: 60.59 MB against 90.21 MB
+    req, dense, req_in = rs.rsparse_io_model(rs.make_config(4096, 4096, 256, 0.0, rs.F16), 1, 2048)
+    assert (req, dense) == (20987904, 33570816) and abs(req / dense - 0.625) < 3e-4
+    assert abs(dense / req_in - 1.68) < 0.005
+    req, dense, _ = rs.rsparse_io_model(rs.make_config(4096, 11008, 512, 0.0, rs.BF16), 1, 2048)
+    assert round(req / 1e6, 2) == 60.59 and round(dense / 1e6, 2) == 90.21
+    # 4-bit weights, groups of 128: half a byte per weight, 2.5 bytes per output and touched group
+    cfg = rs.make_config(4096, 11008, 512, 0.0, rs.BF16)
+    req, dense, _ = rs.rsparse_io_model(cfg, 1, 2048, q4_group=128)
+    fac = 2 * (512 * 11008 + 512 * 4096)
+    assert dense == 4096 * 11008 // 2 + 32 * 11008 * 5 // 2 + 2 * 4096 + 2 * 11008
+    assert req == 2048 * 11008 // 2 + 32 * 11008 * 5 // 2 + fac + 2 * 4096 + 2 * 11008
+    assert rs.rsparse_io_model(cfg, 1, 3, q4_group=128)[0] == 3 * 11008 // 2 + 3 * 11008 * 5 // 2 + fac + 2 * 4096 + 2 * 11008
+    for bad in (dict(batch=0), dict(batch=33), dict(k_union=-1), dict(k_union=4097), dict(q4_group=100), dict(q4_group=16)):
+        kw = dict(batch=1, k_union=10, q4_group=0)
+        kw.update(bad)
+        with pytest.raises(rs.RSparseError):
+            rs.rsparse_io_model(cfg, **kw)
+
+
+def test_bf16_encodings_round_fp64_once():
+    """The generator's bf16 encoder and the library's factor rounding (through rsparse_compute_factors' stored
+    factors) round a double ONCE: equal to the oracle's rounding-by-definition, also on doubles that a detour
+    through fp32 would first push onto a tie."""
+    rng = np.random.default_rng(17)
+    v = rng.standard_normal(200000) * np.exp(rng.uniform(-30, 30, 200000))
+    base = synth.decode16(rng.integers(0x0080, 0x7F00, 50000).astype(np.uint16), synth.BF16)      # bf16 values
+    nxt = synth.decode16((synth.encode16(base, synth.BF16).astype(np.uint32) + 1).astype(np.uint16), synth.BF16)
+    mid = 0.5 * (base + nxt)                                                                       # exact ties
+    near = np.concatenate([mid * (1 + 2.0 ** -40), mid * (1 - 2.0 ** -40), mid, -mid * (1 + 2.0 ** -45)])
+    allv = np.concatenate([v, near, [0.0, -0.0, np.inf, -np.inf, 1e39, -1e39, 1e-45]])
+    assert np.array_equal(synth.encode16(allv, synth.BF16), oracle.round16_from_double(allv, synth.BF16))
+    assert np.array_equal(synth.encode16(allv, synth.F16), oracle.round16_from_double(allv, synth.F16))

@@ -325,7 +325,7 @@ def test_silu32_recipe_against_fp64():
     g64 = g.astype(np.float64)
     want = g64 / (1.0 + np.exp(-g64))
     ulp = np.spacing(np.abs(want).astype(np.float32)).astype(np.float64)
-    assert np.max(np.abs(got - want) / ulp) <= 4.0
+    assert np.max(np.abs(got - want) / ulp) <= 3.0          # measured: 2.4
     # special values
     sp = oracle.silu32(np.array([np.nan, np.inf, -np.inf, -88.0, -1e30, 0.0], dtype=np.float32))
     assert np.isnan(sp[0]) and sp[1] == np.inf
@@ -356,6 +356,146 @@ def test_gated_input_is_one_rounding_of_the_fp32_product(dt):
     assert np.array_equal(np.isnan(synth.decode16(got, dt)), nan)
     assert np.array_equal(got[~nan], want[~nan])
     assert nan[:2].all() and np.isinf(synth.decode16(got[2:3], dt))[0]
+
+
+def _boundary_words():
+    """fp32 bit patterns that exercise a 16-bit rounding: every high half with the low half at 0, just below
+    half, exactly half and just above half (ties, carries into the exponent, overflow to infinity, NaN and
+    infinity included), plus a million random words."""
+    hi = np.arange(65536, dtype=np.uint32) << 16
+    lows = np.array([0x0000, 0x7FFF, 0x8000, 0x8001, 0x0001, 0xFFFF, 0x1000, 0x0FFF, 0x1001, 0x2FFF, 0x3000], dtype=np.uint32)
+    words = (hi[:, None] | lows[None, :]).reshape(-1)
+    rnd = np.random.default_rng(5).integers(0, 2 ** 32, size=1_000_000, dtype=np.uint64).astype(np.uint32)
+    return np.concatenate([words, rnd])
+
+
+@pytest.mark.parametrize("dt", [synth.F16, synth.BF16])
+def test_fp32_to_16bit_rounding_against_torch(dt):
+    """The oracle's fp32 -> bf16 / fp16 roundings against torch's CPU conversions (an implementation of its
+    own: neither the add-0x7FFF formula of the generators nor the device's), bit for bit on every non-NaN
+    input; NaN must stay NaN."""
+    import torch
+    f = _boundary_words().view(np.float32)
+    got = oracle.round16(f, dt)
+    tdt = torch.float16 if dt == synth.F16 else torch.bfloat16
+    want = torch.from_numpy(f.copy()).to(tdt).view(torch.int16).numpy().view(np.uint16)
+    nan = np.isnan(f)
+    assert np.array_equal(got[~nan], want[~nan])
+    dec = synth.decode16(got[nan], dt)
+    assert np.isnan(dec).all()
+    # the overflow edge in words: the largest fp32 values below the rounding point stay finite, the rest become inf
+    if dt == synth.BF16:
+        assert oracle.round16(np.array([0x7F7F7FFF], dtype=np.uint32).view(np.float32), dt)[0] == 0x7F7F
+        assert oracle.round16(np.array([0x7F7F8000], dtype=np.uint32).view(np.float32), dt)[0] == 0x7F80
+    else:
+        assert oracle.round16(np.array([65519.996], dtype=np.float32), dt)[0] == 0x7BFF
+        assert oracle.round16(np.array([65520.0], dtype=np.float32), dt)[0] == 0x7C00
+
+
+@pytest.mark.parametrize("dt", [synth.F16, synth.BF16])
+def test_fp64_to_16bit_rounding_by_definition(dt):
+    """round16_from_double (used by the plain-definition gated input) against (a) torch on doubles that are
+    exact fp32 values, (b) exact rational arithmetic on random doubles: the result is a nearest representable
+    neighbour, ties to the even one, (c) doubles a hair above / below a tie, which a double rounding through
+    fp32 would get wrong."""
+    import torch
+    from fractions import Fraction
+    f = _boundary_words()[:65536 * 11:7].view(np.float32)
+    tdt = torch.float16 if dt == synth.F16 else torch.bfloat16
+    want = torch.from_numpy(f.copy()).to(tdt).view(torch.int16).numpy().view(np.uint16)
+    got = oracle.round16_from_double(f.astype(np.float64), dt)
+    ok = ~np.isnan(f)
+    assert np.array_equal(got[ok], want[ok])
+    # (b) exact check on random doubles over the whole finite range of the format
+    rng = np.random.default_rng(8)
+    top = 17.0 if dt == synth.F16 else 128.5
+    low = -26.0 if dt == synth.F16 else -136.0
+    v = np.ldexp(rng.uniform(1.0, 2.0, 3000), rng.integers(int(low), int(top), 3000)) * rng.choice([-1.0, 1.0], 3000)
+    bits = oracle.round16_from_double(v, dt)
+    dec = synth.decode16(bits, dt)
+    allv = np.sort(synth.decode16(np.arange(65536, dtype=np.uint16), dt))
+    allv = allv[np.isfinite(allv)]
+    for x, b, d in zip(v, bits, dec):
+        i = np.searchsorted(allv, x)
+        cands = [allv[j] for j in (i - 1, i) if 0 <= j < len(allv)]
+        if np.isinf(d):
+            # overflow: x is at least half a spacing past the largest finite value
+            big = Fraction(float(allv[-1]))
+            sp = big - Fraction(float(allv[-2]))
+            assert abs(Fraction(float(x))) >= big + sp / 2
+            continue
+        err = abs(Fraction(float(d)) - Fraction(float(x)))
+        best = min(abs(Fraction(float(c)) - Fraction(float(x))) for c in cands)
+        assert err == best, (x, d, cands)
+        if len(cands) == 2 and abs(Fraction(float(cands[0])) - Fraction(float(x))) == abs(Fraction(float(cands[1])) - Fraction(float(x))):
+            assert (int(b) & 1) == 0
+    # (c) ties and near-ties
+    one = 1.0
+    sp = 2.0 ** -10 if dt == synth.F16 else 2.0 ** -7
+    up_bits = oracle.round16_from_double(np.array([one + sp]), dt)[0]
+    one_bits = oracle.round16_from_double(np.array([one]), dt)[0]
+    two_bits = oracle.round16_from_double(np.array([one + 2 * sp]), dt)[0]
+    mid = one + sp / 2
+    assert oracle.round16_from_double(np.array([mid]), dt)[0] == one_bits                  # tie -> even (1.0)
+    assert oracle.round16_from_double(np.array([np.nextafter(mid, 2.0)]), dt)[0] == up_bits
+    assert oracle.round16_from_double(np.array([one + 1.5 * sp]), dt)[0] == two_bits       # tie -> even (1 + 2 sp)
+    assert oracle.round16_from_double(np.array([np.nextafter(one + 1.5 * sp, 0.0)]), dt)[0] == up_bits
+    # a value that rounds to the tie in fp32 first and then the wrong way: mid + 2^-30 must go up
+    assert oracle.round16_from_double(np.array([mid + 2.0 ** -30]), dt)[0] == up_bits
+    # signed zero, infinities, subnormal spacing
+    z = oracle.round16_from_double(np.array([0.0, -0.0, np.inf, -np.inf]), dt)
+    assert list(z) == ([0x0000, 0x8000, 0x7C00, 0xFC00] if dt == synth.F16 else [0x0000, 0x8000, 0x7F80, 0xFF80])
+    tiny = 2.0 ** -24 if dt == synth.F16 else 2.0 ** -133
+    assert list(oracle.round16_from_double(np.array([tiny, 0.5 * tiny, 0.5000001 * tiny, 1.5 * tiny, 2.5 * tiny]), dt)) == [1, 0, 1, 2, 2]
+
+
+@pytest.mark.parametrize("dt", [synth.F16, synth.BF16])
+def test_gated_input_plain_definition(dt):
+    """The gated input by its definition (Sec. 3.1: the up projection times SiLU of the gate projection)
+    against numpy's fp64 evaluation, a closed-form identity and special values; and the fp32 recipe that
+    the index sets are built from differs from it only where the exact product sits next to a rounding flip
+    point."""
+    rng = np.random.default_rng(21)
+    n = 200000
+    g = rng.standard_normal(n) * 3.0
+    u = rng.standard_normal(n) * np.exp(rng.uniform(-6, 4, n))
+    G16, U16 = synth.encode16(g, dt), synth.encode16(u, dt)
+    bits, margin = oracle.gated_input_plain(G16, U16, dt)
+    gd, ud = synth.decode16(G16, dt), synth.decode16(U16, dt)
+    # numpy: g * sigmoid(g) with the logistic written the other way round (1 / (1 + e^-g) = e^g / (1 + e^g))
+    with np.errstate(over="ignore"):
+        ref = ud * gd * np.where(gd >= 0, 1.0 / (1.0 + np.exp(-gd)), np.exp(gd) / (1.0 + np.exp(gd)))
+    want = oracle.round16_from_double(ref, dt)
+    differ = bits != want
+    assert differ.mean() < 1e-6 and (margin[differ] < 1e-9).all()      # only exact-tie hair-splitting between the two fp64 forms
+    # identity silu(g) - silu(-g) = g  (from sigmoid(g) + sigmoid(-g) = 1), checked on the unrounded path via u = 1
+    ones = synth.encode16(np.ones(1000), dt)
+    gp = synth.encode16(np.linspace(0.01, 8.0, 1000), dt)
+    gm = synth.encode16(-synth.decode16(gp, dt), dt)
+    sp_ = synth.decode16(oracle.gated_input_plain(gp, ones, dt)[0], dt)
+    sm_ = synth.decode16(oracle.gated_input_plain(gm, ones, dt)[0], dt)
+    spacing = 2.0 ** (-10 if dt == synth.F16 else -7)
+    assert np.all(np.abs((sp_ - sm_) - synth.decode16(gp, dt)) <= 1.01 * spacing * np.maximum(np.abs(sp_), 0.28))
+    # special values: silu(0) = 0, silu(-inf) u = -0 * u, silu(+inf) = +inf, NaN propagates
+    sv = oracle.gated_input_plain(synth.encode16(np.array([0.0, -np.inf, np.inf, np.nan, 2.0]), dt),
+                                  synth.encode16(np.array([3.0, 2.0, 2.0, 1.0, np.nan]), dt), dt)[0]
+    d = synth.decode16(sv, dt)
+    assert d[0] == 0.0 and d[1] == 0.0 and np.signbit(d[1]) and d[2] == np.inf and np.isnan(d[3]) and np.isnan(d[4])
+    # the fp32 recipe against the definition: equal bits wherever the exact product is not within the
+    # recipe's error of a flip point.  The recipe is within 3 ulp (fp32) of silu and adds one fp32 rounding of
+    # the product: <= 3.5 ulp <= 7 * 2^-24 relative, i.e. at most 7 * 2^-24 * 2^p of the 16-bit spacing
+    # (p significand bits: the spacing is at least 2^-p of the value).
+    recipe = oracle.gated_input(G16, U16, dt)
+    p_bits = 11 if dt == synth.F16 else 8
+    band = oracle.RECIPE_BAND[dt]
+    finite = np.isfinite(synth.decode16(bits, dt))
+    outside = finite & (margin > band)
+    assert np.array_equal(recipe[outside], bits[outside])
+    inside = finite & ~outside
+    assert inside.mean() < 4 * band + 1e-3          # the band is a sliver of the number line
+    # inside the band the two may differ by at most one step of the 16-bit grid
+    a, b = synth.decode16(recipe[inside], dt), synth.decode16(bits[inside], dt)
+    assert np.all(np.abs(a - b) <= 2.0 ** (1 - p_bits) * np.maximum(np.abs(a), np.abs(b)) + 1e-45)
 
 
 # --------------------------------------------------------------------------- recipe search (Sec. 3.5)
