@@ -72,6 +72,13 @@ typedef struct {
                                 the row-dot kernel of rsparse_dense_ref and by the matrix-core path that
                                 rsparse_linear takes from 5 tokens on (see mfma_min_batch); without it those
                                 batches run in tiles of up to 8 tokens on the vector ALU */
+    int32_t strip_cols;      /* layout of W on the device for the vector path (up to 8 tokens per batch tile).  0: column-major
+                                (Sec. 3.4), run by the column-tile kernel: tiles of 512 outputs x channel splits whose partial
+                                sums meet in fp32 atomics.  32, 64, 128, 256 or 512: the columns are cut into strips of that
+                                many outputs, stored strip after strip, and run by the strip kernel: one workgroup (or a few,
+                                tuning `splits`) per strip, every wave on a fixed range of input channels; with one workgroup
+                                per strip no sums cross workgroups and Y is bit-reproducible from run to run.  Same results
+                                within the stated tolerance; see rsparse_tuning.splits.  Not with 4-bit weights. */
 } rsparse_config;
 
 /* Launch-shape overrides for measurements; 0 = library default. */
@@ -307,6 +314,16 @@ rsparse_status rsparse_search_recipe(rsparse_loss_fn loss, void *user, int32_t n
                                      int32_t generations, double p_m, double p_c, int32_t group_size,
                                      uint64_t seed, double lo, double hi, const double *rho_start,
                                      double *rho_out, double *loss_out, double *history_out);
+
+/*
+ * Measurement aid, only in libraries built with RSPARSE_STAMPS=1 (python -m paper_2504_19449_amd.build --stamps; any other
+ * build returns RSPARSE_EINVAL): from now on every wave of the strip kernel's launches writes one record of 16
+ * 64-bit words into buf_dev (device, room for capacity_waves records; record i belongs to wave i of the launch,
+ * workgroups in grid order) -- word 0: kind (0 strip wave, 1 stage-1 wave, 2 strip wave that finished a split
+ * strip) | workgroup << 8 | wave << 40; words 1..14: the 100 MHz wall clock at the wave's phase boundaries (0 = phase
+ * not reached); word 15: rows streamed.  NULL / 0 switches it off.  Launches overwrite each other's records.
+ */
+rsparse_status rsparse_debug_stamps(void *buf_dev, int32_t capacity_waves);
 
 void rsparse_destroy(rsparse_layer *layer);
 

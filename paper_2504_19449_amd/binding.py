@@ -16,14 +16,14 @@ EXPORTED_SYMBOLS = [
     "rsparse_linear_gated", "rsparse_gated_input", "rsparse_mlp_gate_up", "rsparse_dense_ref", "rsparse_linear_group", "rsparse_dense_ref_group", "rsparse_last_active", "rsparse_synchronize",
     "rsparse_get_factors", "rsparse_set_tau", "rsparse_set_tuning",
     "rsparse_get_config", "rsparse_calibrate_tau", "rsparse_required_bytes", "rsparse_dense_bytes", "rsparse_io_model",
-    "rsparse_recipe", "rsparse_plan_layer", "rsparse_search_recipe", "rsparse_destroy", "rsparse_last_error",
+    "rsparse_recipe", "rsparse_plan_layer", "rsparse_search_recipe", "rsparse_debug_stamps", "rsparse_destroy", "rsparse_last_error",
 ]
 
 
 class Config(C.Structure):
     _fields_ = [("d_in", C.c_int32), ("d_out", C.c_int32), ("rank", C.c_int32), ("max_batch", C.c_int32),
                 ("tau", C.c_float), ("dtype", C.c_int32), ("out_dtype", C.c_int32), ("cmp_mode", C.c_int32),
-                ("batch_mask_mode", C.c_int32), ("dense_rowmajor", C.c_int32)]
+                ("batch_mask_mode", C.c_int32), ("dense_rowmajor", C.c_int32), ("strip_cols", C.c_int32)]
 
 
 class Tuning(C.Structure):
@@ -101,6 +101,8 @@ def load_library():
     lib.rsparse_search_recipe.argtypes = [LOSS_FN, vp, i32, i32, i32, C.c_double, C.c_double, i32, C.c_uint64,
                                           C.c_double, C.c_double, vp, vp, vp, vp]
     lib.rsparse_search_recipe.restype = C.c_int
+    lib.rsparse_debug_stamps.argtypes = [vp, i32]
+    lib.rsparse_debug_stamps.restype = C.c_int
     lib.rsparse_destroy.argtypes = [vp]
     lib.rsparse_destroy.restype = None
     lib.rsparse_last_error.restype = C.c_char_p
@@ -151,9 +153,9 @@ class Layer:
 
 
 def _make_config(d_in, d_out, rank, tau, dtype, max_batch=1, out_dtype=None, cmp_mode=0,
-                 batch_mask_mode=0, dense_rowmajor=0) -> Config:
+                 batch_mask_mode=0, dense_rowmajor=0, strip_cols=0) -> Config:
     return Config(d_in, d_out, rank, max_batch, float(tau), dtype, dtype if out_dtype is None else out_dtype,
-                  cmp_mode, batch_mask_mode, dense_rowmajor)
+                  cmp_mode, batch_mask_mode, dense_rowmajor, strip_cols)
 
 
 def rsparse_prepare(cfg: Config, W16) -> Layer:
@@ -326,6 +328,11 @@ def rsparse_plan_layer(d_in: int, d_out: int, rank: int, keep_fraction: float, g
     _check(load_library().rsparse_plan_layer(d_in, d_out, rank, keep_fraction, group, C.byref(a), C.byref(b),
                                              C.byref(use)))
     return a.value, b.value, bool(use.value)
+
+
+def rsparse_debug_stamps(buf_dev: int, capacity_waves: int):
+    """Stamps builds only: where the strip kernel's waves write their phase time stamps (0, 0 = off)."""
+    _check(load_library().rsparse_debug_stamps(buf_dev, capacity_waves))
 
 
 def rsparse_destroy(layer: Layer):

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librsparse.so")
-SOURCES = ["kernels.hip", "kernels_mfma.hip", "api.cpp", "svd_host.cpp", "recipe_search.cpp"]
+SOURCES = ["kernels.hip", "kernels_strip.hip", "kernels_mfma.hip", "api.cpp", "svd_host.cpp", "recipe_search.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
          # keep the compiler from forming packed-fp32 instructions on its own
@@ -22,7 +22,10 @@ def is_current() -> bool:
     return all(os.path.getmtime(d) <= t for d in deps)
 
 
-def build(force: bool = True) -> str:
+def build(force: bool = True, stamps: bool = False) -> str:
+    """stamps=True (or RSPARSE_STAMPS=1 in the environment): a measurement build whose strip kernel records per-wave
+    phase time stamps (rsparse_debug_stamps); same file name, never what tests or the benchmark's timed legs should load."""
+    stamps = stamps or os.environ.get("RSPARSE_STAMPS") == "1"
     if not force and is_current():
         return LIB
     objs = []
@@ -31,7 +34,8 @@ def build(force: bool = True) -> str:
     for src in SOURCES:
         obj = os.path.join(HERE, "_build", src + ".o")
         objs.append(obj)
-        procs.append((src, subprocess.Popen([HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj],
+        procs.append((src, subprocess.Popen([HIPCC, *FLAGS, *(["-DRSPARSE_STAMPS=1"] if stamps else []), "-c",
+                                             os.path.join(CSRC, src), "-o", obj],
                                             stderr=subprocess.PIPE, text=True)))
     for src, p in procs:
         _, err = p.communicate()
@@ -45,4 +49,4 @@ def build(force: bool = True) -> str:
 
 
 if __name__ == "__main__":
-    print(build(force=True))
+    print(build(force=True, stamps="--stamps" in sys.argv))

@@ -129,6 +129,14 @@ struct rsparse_layer {
     int device = 0;
     int cus = 256;
     uint16_t *M = nullptr, *SVt = nullptr, *U = nullptr, *Wrow = nullptr;
+    uint16_t *Ms = nullptr;                // strip-major W + U_r^T: [strips][d_in + rank][strip_w]
+    int strip_w = 0, strips = 0;
+    long long strip_stride = 0;
+    unsigned long long *t_tag = nullptr;   // [t_slots][rank] {generation, t} of the strip kernel
+    int t_slots = 0;
+    int32_t *act_seg = nullptr;            // [nz_max][d_in / 8] kept channels per channel range (strip kernel)
+    bool last_strip = false;               // the last call went through the strip kernel ...
+    int last_ranges = 0;                   // ... with this many channel ranges (splits x waves)
     float *t = nullptr, *yacc = nullptr;
     uint32_t *act_bits = nullptr, *chan_bits = nullptr;
     bool last_mfma = false;
@@ -137,7 +145,7 @@ struct rsparse_layer {
     uint32_t *t_pub = nullptr;
     uint16_t *hy = nullptr;                // [max_batch][d_out] 16-bit output scratch (gate / up results of rsparse_mlp_gate_up's fallback)
     uint16_t *xg = nullptr;                // [max_batch][d_in] gated input x = round16(silu(g) * u), written out per call
-    size_t n_t = 0, n_y = 0;
+    size_t n_t = 0, n_y = 0, sync_n = 0;
     bool last_fused = false;
     // 4-bit weights (rsparse_prepare_q4): codes, group scales, group zero points; M and Wrow stay null
     uint8_t *Mq = nullptr, *qz = nullptr;
@@ -159,6 +167,7 @@ struct rsparse_layer {
         v.dtype = cfg.dtype; v.out_dtype = cfg.out_dtype; v.cmp_mode = cfg.cmp_mode;
         v.batch_mask_mode = cfg.batch_mask_mode; v.tau = cfg.tau;
         v.Mq = Mq; v.qs = qs; v.qz = qz; v.Ut = Ut; v.qshift = qshift; v.qtiles = qtiles;
+        v.Ms = Ms; v.strip_w = strip_w; v.strip_stride = strip_stride; v.t_tag = t_tag; v.t_slots = t_slots; v.act_seg = act_seg;
         return v;
     }
 };
@@ -185,6 +194,7 @@ rsparse_status check_config(const rsparse_config *c)
     if (c->cmp_mode != 0 && c->cmp_mode != 1) return fail(RSPARSE_EINVAL, "cmp_mode must be 0 or 1");
     if (c->batch_mask_mode != 0 && c->batch_mask_mode != 1) return fail(RSPARSE_EINVAL, "batch_mask_mode must be 0 or 1");
     if (c->dense_rowmajor != 0 && c->dense_rowmajor != 1) return fail(RSPARSE_EINVAL, "dense_rowmajor must be 0 or 1");
+    if (c->strip_cols != 0 && !strip_width_ok(c->strip_cols)) return fail(RSPARSE_EINVAL, "strip_cols must be 0, 32, 64, 128, 256 or 512");
     return RSPARSE_OK;
 }
 
@@ -244,6 +254,43 @@ Launch resolve_launch(const rsparse_layer *L, int batch, bool dense, int group, 
     return c;
 }
 
+// Launch shape of the strip kernel: one workgroup per strip when the launch then still has a workgroup for at
+// least half of the compute units; layers with fewer strips split the channels over several workgroups per strip.
+Launch resolve_strip(const rsparse_layer *L, int batch, bool dense, int group, bool fused)
+{
+    Launch c{};
+    const rsparse_tuning &t = L->tuning;
+    const int bt = batch_tile_of(batch);
+    c.waves = strip_waves(batch);
+    c.nontemporal = 1;
+    c.tile_map = 1;
+    c.wait_polls = t.debug_wait_polls;
+    c.skip_stage1 = t.debug_skip_stage1 ? 1 : 0;
+    const int rank = dense ? 0 : L->cfg.rank;
+    int splits = t.splits;
+    if (splits <= 0) {
+        const int target = std::max(1, L->cus / std::max(1, group));
+        splits = L->strips * 2 >= target ? 1 : (target + L->strips - 1) / L->strips;
+    }
+    splits = std::max(1, std::min(splits, 4096));
+    while (strip_list_cap(L->cfg.d_in, rank, splits, c.waves, bt, L->strip_w) <= 0 && splits < 4096) ++splits;
+    c.splits = splits;
+    // stage 1: a row of S_r V_r^T is shared by enough waves that a wave's part is one batch of loads (8 KiB), as long
+    // as that leaves at most about one stage-1 workgroup per compute unit
+    const int chunk = std::min(L->cfg.d_in, (24576 / bt) & ~7);
+    int ws = 1;
+    while (ws < c.waves && chunk * 2 / ws > 8192) ws *= 2;
+    int rpw = c.waves / ws;
+    while (rpw < c.waves && (L->cfg.rank + rpw - 1) / rpw > L->cus / std::max(1, group)) rpw *= 2;
+    if (t.lowrank_rows > 0) {
+        rpw = 1;
+        while (rpw * 2 <= std::min(t.lowrank_rows, c.waves)) rpw *= 2;
+    }
+    c.lowrank_rows = rpw;
+    (void)fused;
+    return c;
+}
+
 rsparse_status check_call(rsparse_layer *L, const void *X, int32_t batch, void *Y)
 {
     if (!L) return fail(RSPARSE_EINVAL, "layer is NULL");
@@ -260,6 +307,7 @@ void free_layer(rsparse_layer *L)
     (void)hipFree(L->M); (void)hipFree(L->SVt); (void)hipFree(L->U); (void)hipFree(L->Wrow); (void)hipFree(L->t);
     (void)hipFree(L->yacc); (void)hipFree(L->act_bits); (void)hipFree(L->chan_bits);
     (void)hipFree(L->act_list); (void)hipFree(L->act_count); (void)hipFree(L->sync); (void)hipFree(L->t_pub); (void)hipFree(L->xg); (void)hipFree(L->hy);
+    (void)hipFree(L->Ms); (void)hipFree(L->t_tag); (void)hipFree(L->act_seg);
     (void)hipFree(L->Mq); (void)hipFree(L->qs); (void)hipFree(L->qz); (void)hipFree(L->Ut);
     delete L;
 }
@@ -300,8 +348,26 @@ rsparse_status build_layer(const rsparse_config *cfg, const uint16_t *W, const u
         if (!q4) {
             transpose16(W, d_out, d_in, host.data());
             if (r) transpose16(U16, d_out, r, host.data() + d_in * d_out);
-            RS_HIP(hipMalloc((void **)&L->M, host.size() * 2));
-            RS_HIP(hipMemcpy(L->M, host.data(), host.size() * 2, hipMemcpyHostToDevice));
+            if (cfg->strip_cols == 0) {
+                RS_HIP(hipMalloc((void **)&L->M, host.size() * 2));
+                RS_HIP(hipMemcpy(L->M, host.data(), host.size() * 2, hipMemcpyHostToDevice));
+            } else {
+            // strip layout: the same rows cut into strips of strip_cols columns, strip after strip (columns past
+            // d_out are zero); the strip kernel gives each strip to one workgroup (or to a few that split the channels)
+            const int sw = cfg->strip_cols;
+            L->strip_w = sw;
+            L->strips = (int)((d_out + sw - 1) / sw);
+            const size_t rows = d_in + r, W = sw;
+            L->strip_stride = (long long)(rows * W);
+            std::vector<uint16_t> ms;
+            try { ms.assign((size_t)L->strips * rows * W, 0); } catch (const std::bad_alloc &) { return fail(RSPARSE_ENOMEM, "host allocation failed"); }
+            parallel_for(rows, [&](size_t c) {
+                const uint16_t *src = host.data() + c * d_out;
+                for (size_t o = 0; o < d_out; ++o) ms[((o / W) * rows + c) * W + (o % W)] = src[o];
+            });
+            RS_HIP(hipMalloc((void **)&L->Ms, ms.size() * 2));
+            RS_HIP(hipMemcpy(L->Ms, ms.data(), ms.size() * 2, hipMemcpyHostToDevice));
+            }
         } else {
             // codes channel-major in the lane order of the 4-bit kernel (layout: kernels.h), scales and zero
             // points group-major in plain column order; rows padded to whole 1024-column tiles with zeros
@@ -369,8 +435,18 @@ rsparse_status build_layer(const rsparse_config *cfg, const uint16_t *W, const u
         RS_HIP(hipMalloc((void **)&L->act_bits, n_list * 4));
         RS_HIP(hipMalloc((void **)&L->act_count, (size_t)L->nz_max * 4));
         RS_HIP(hipMalloc((void **)&L->chan_bits, d_in * 4));
-        RS_HIP(hipMalloc((void **)&L->sync, sync_words(L->tiles) * 4));
-        RS_HIP(hipMemset(L->sync, 0, sync_words(L->tiles) * 4));
+        L->sync_n = sync_words(std::max(L->tiles, L->strips));
+        RS_HIP(hipMalloc((void **)&L->sync, L->sync_n * 4));
+        RS_HIP(hipMemset(L->sync, 0, L->sync_n * 4));
+        {
+            const int one = 1;                        // generation 1: no entry of t_tag (all zero) carries it
+            RS_HIP(hipMemcpy(L->sync + kSyncGen, &one, 4, hipMemcpyHostToDevice));
+        }
+        L->t_slots = (int)bpad;
+        RS_HIP(hipMalloc((void **)&L->t_tag, n_t * 8));
+        RS_HIP(hipMemset(L->t_tag, 0, n_t * 8));
+        RS_HIP(hipMalloc((void **)&L->act_seg, (size_t)L->nz_max * (d_in / 8) * 4));
+        RS_HIP(hipMemset(L->act_seg, 0, (size_t)L->nz_max * (d_in / 8) * 4));
         L->n_t = n_t;
         RS_HIP(hipMalloc((void **)&L->t_pub, n_t * 4));
         RS_HIP(hipMemset(L->t_pub, 0xff, n_t * 4));          // every entry "not ready"
@@ -473,6 +549,7 @@ rsparse_status rsparse_prepare_q4(const rsparse_config *cfg, const uint8_t *Q_ho
     if (group_size < 32 || group_size > 1024 || (group_size & (group_size - 1)) || cfg->d_in % group_size)
         return fail(RSPARSE_EINVAL, "group_size must be a power of two in [32, 1024] that divides d_in (got %d)", group_size);
     if (cfg->dense_rowmajor) return fail(RSPARSE_EINVAL, "dense_rowmajor is not available with 4-bit weights");
+    if (cfg->strip_cols) return fail(RSPARSE_EINVAL, "strip_cols is not available with 4-bit weights");
     const size_t n = (size_t)cfg->d_in * cfg->d_out, ng = n / group_size;
     for (size_t i = 0; i < n; ++i)
         if (Q_host[i] > 15) return fail(RSPARSE_EINVAL, "code %u at %zu is not a 4-bit value", (unsigned)Q_host[i], i);
@@ -543,6 +620,7 @@ rsparse_status linear_q4(rsparse_layer *L, const void *X_dev, int32_t batch, voi
     if (!dense) {
         L->last_stream = s; L->last_batch = batch; L->last_mfma = false; L->last_fused = fused;
         L->last_bt = std::min(4, batch_tile_of(batch));
+        L->last_strip = false;
     }
     return RSPARSE_OK;
 }
@@ -633,6 +711,40 @@ rsparse_status linear_group_impl(rsparse_layer *const *layers, int32_t n_layers,
         RS_HIP(launch_gated_input(G_dev, X_dev, layers[0]->xg, (size_t)batch * layers[0]->cfg.d_in, layers[0]->cfg.dtype, s));
         X_dev = layers[0]->xg;
     }
+    // layers packed in strips go through the strip kernel; a group must share one layout (and one strip width),
+    // otherwise its layers run one at a time
+    if (!mfma && n_layers > 1) {
+        bool same = true;
+        for (int i = 1; i < n_layers; ++i) same = same && layers[i]->strip_w == layers[0]->strip_w;
+        if (!same) {
+            for (int i = 0; i < n_layers; ++i) {
+                rsparse_status one = linear_group_impl(&layers[i], 1, X_dev, nullptr, batch, &Y_devs[i], stream);
+                if (one != RSPARSE_OK) return one;
+            }
+            return RSPARSE_OK;
+        }
+    }
+    const bool strip = !mfma && layers[0]->Ms != nullptr;
+    if (strip) {
+        Launch sc[RSPARSE_MAX_GROUP];
+        for (int i = 0; i < n_layers; ++i) sc[i] = resolve_strip(layers[i], batch, false, n_layers, fused);
+        if (fused) {
+            RS_HIP(launch_strip(v, sc, n_layers, X_dev, batch, Y_devs, true, false, layers[0]->cus, s));
+        } else {
+            if (stages != 2) RS_HIP(launch_sparse_and_t(v, lc, n_layers, X_dev, batch, true, false, s));
+            if (stages != 1) RS_HIP(launch_strip(v, sc, n_layers, X_dev, batch, Y_devs, false, false, layers[0]->cus, s));
+        }
+        for (int i = 0; i < n_layers; ++i) {
+            layers[i]->last_stream = s;
+            layers[i]->last_batch = batch;
+            layers[i]->last_mfma = false;
+            layers[i]->last_fused = true;           // rsparse_synchronize looks at the device-side error word
+            layers[i]->last_bt = 0;
+            layers[i]->last_strip = true;
+            layers[i]->last_ranges = sc[i].splits * sc[i].waves;
+        }
+        return RSPARSE_OK;
+    }
     if (mfma) {
         // matrix-core path, one layer at a time (each is already a full-chip launch)
         for (int i = 0; i < n_layers; ++i)
@@ -649,6 +761,7 @@ rsparse_status linear_group_impl(rsparse_layer *const *layers, int32_t n_layers,
         layers[i]->last_mfma = mfma;
         layers[i]->last_fused = !mfma && fused;
         layers[i]->last_bt = 0;
+        layers[i]->last_strip = false;
     }
     return RSPARSE_OK;
 }
@@ -677,12 +790,12 @@ rsparse_status rsparse_mlp_gate_up(rsparse_layer *gate, rsparse_layer *up, const
     for (int i = 0; i < 2; ++i) mfma = mfma && mfma_path_supported(v[i], batch);
     const int bt = batch_tile_of(batch);
     const bool one_tile = (batch + bt - 1) / bt == 1;
-    if (fused && !mfma && one_tile && lc[0].tile_map != 2 && lc[1].tile_map != 2 && !gate->q4() && !up->q4()) {
+    if (fused && !mfma && one_tile && lc[0].tile_map != 2 && lc[1].tile_map != 2 && gate->M && up->M) {
         // both projections and the activation in one launch: the last workgroup of a column tile
         // rounds g and u, applies silu(g) * u and stores H
         RS_HIP(launch_fused(v, lc, 2, X_dev, batch, outs, s, true));
         for (int i = 0; i < 2; ++i) {
-            pair[i]->last_stream = s; pair[i]->last_batch = batch; pair[i]->last_mfma = false; pair[i]->last_fused = true; pair[i]->last_bt = 0;
+            pair[i]->last_stream = s; pair[i]->last_batch = batch; pair[i]->last_mfma = false; pair[i]->last_fused = true; pair[i]->last_bt = 0; pair[i]->last_strip = false;
         }
         return RSPARSE_OK;
     }
@@ -739,8 +852,29 @@ rsparse_status rsparse_dense_ref_group(rsparse_layer *const *layers, int32_t n_l
         return fail(RSPARSE_EINVAL, "row-dot dense kernel needs dense_rowmajor=1 and batch_tile*d_in*2 <= 64 KiB");
     // row dots win for short rows; for long rows (and for more than one token) the axpy form streams better
     if (kernel == 0) kernel = (can_rowdot && layers[0]->cfg.d_in <= 8192 && batch == 1) ? 2 : 1;
-    if (kernel == 2) RS_HIP(launch_dense_rowdot(v, lc, n_layers, X_dev, batch, Y_devs, s));
-    else RS_HIP(launch_dense_axpy(v, lc, n_layers, X_dev, batch, Y_devs, s));
+    bool strip = true, colmajor = true;
+    for (int i = 0; i < n_layers; ++i) {
+        strip = strip && layers[i]->Ms != nullptr && layers[i]->strip_w == layers[0]->strip_w;
+        colmajor = colmajor && layers[i]->M != nullptr;
+    }
+    if (kernel != 2 && !strip && !colmajor) {
+        // mixed layouts: one layer at a time
+        for (int i = 0; i < n_layers; ++i) {
+            rsparse_status one = rsparse_dense_ref_group(&layers[i], 1, X_dev, batch, &Y_devs[i], stream);
+            if (one != RSPARSE_OK) return one;
+        }
+        return RSPARSE_OK;
+    }
+    if (kernel == 2) {
+        RS_HIP(launch_dense_rowdot(v, lc, n_layers, X_dev, batch, Y_devs, s));
+    } else if (strip) {
+        // the strip kernel with every channel kept and no low-rank part
+        Launch sc[RSPARSE_MAX_GROUP];
+        for (int i = 0; i < n_layers; ++i) sc[i] = resolve_strip(layers[i], batch, true, n_layers, false);
+        RS_HIP(launch_strip(v, sc, n_layers, X_dev, batch, Y_devs, false, true, layers[0]->cus, s));
+    } else {
+        RS_HIP(launch_dense_axpy(v, lc, n_layers, X_dev, batch, Y_devs, s));
+    }
     return RSPARSE_OK;
 }
 
@@ -759,7 +893,10 @@ rsparse_status rsparse_synchronize(rsparse_layer *L)
         RS_HIP(hipMemcpy(&flag, L->sync + kSyncError, 4, hipMemcpyDeviceToHost));
         if (flag != 0) {
             // leave the counters usable for the next call
-            RS_HIP(hipMemset(L->sync, 0, sync_words(L->tiles) * 4));
+            int gen = 0;                              // the generation of the strip kernel's hand-off survives the reset
+            RS_HIP(hipMemcpy(&gen, L->sync + kSyncGen, 4, hipMemcpyDeviceToHost));
+            RS_HIP(hipMemset(L->sync, 0, L->sync_n * 4));
+            RS_HIP(hipMemcpy(L->sync + kSyncGen, &gen, 4, hipMemcpyHostToDevice));
             RS_HIP(hipMemset(L->t_pub, 0xff, L->n_t * 4));
             RS_HIP(hipMemset(L->yacc, 0, L->n_y * 4));
             return fail(RSPARSE_EHIP, "a cross-workgroup wait of the one-launch kernel ran out; the last result is invalid");
@@ -791,7 +928,28 @@ rsparse_status rsparse_last_active(rsparse_layer *L, int32_t token, int32_t *idx
     std::vector<int32_t> cnt(nz), list;
     std::vector<uint32_t> bits;
     RS_HIP(hipMemcpy(cnt.data(), L->act_count, nz * 4, hipMemcpyDeviceToHost));
+    std::vector<int32_t> seg, seg_list;
+    std::vector<uint32_t> seg_bits;
     auto fetch = [&](int z) -> rsparse_status {
+        if (L->last_strip) {
+            // the strip kernel leaves one ascending list per channel range, at the range's first channel; the
+            // ranges in order are the ascending list of the batch tile
+            const size_t nq = d_in / 8;
+            const size_t R = std::min<size_t>((size_t)L->last_ranges, nq);
+            seg.resize(R); seg_list.resize(d_in); seg_bits.resize(d_in);
+            RS_HIP(hipMemcpy(seg.data(), L->act_seg + z * nq, R * 4, hipMemcpyDeviceToHost));
+            RS_HIP(hipMemcpy(seg_list.data(), L->act_list + z * d_in, d_in * 4, hipMemcpyDeviceToHost));
+            RS_HIP(hipMemcpy(seg_bits.data(), L->act_bits + z * d_in, d_in * 4, hipMemcpyDeviceToHost));
+            list.clear(); bits.clear();
+            const size_t parts = (size_t)L->last_ranges, base = nq / parts, rem = nq - base * parts;
+            for (size_t rho = 0; rho < R; ++rho) {
+                const size_t lo = (rho * base + std::min(rho, rem)) * 8, len = (base + (rho < rem ? 1 : 0)) * 8;
+                if (seg[rho] < 0 || (size_t)seg[rho] > len) return fail(RSPARSE_EHIP, "corrupt list count %d", seg[rho]);
+                list.insert(list.end(), seg_list.begin() + lo, seg_list.begin() + lo + seg[rho]);
+                bits.insert(bits.end(), seg_bits.begin() + lo, seg_bits.begin() + lo + seg[rho]);
+            }
+            return RSPARSE_OK;
+        }
         if (cnt[z] < 0 || (size_t)cnt[z] > d_in) return fail(RSPARSE_EHIP, "corrupt list count %d", cnt[z]);
         list.resize(cnt[z]); bits.resize(cnt[z]);
         if (cnt[z]) {
@@ -966,6 +1124,15 @@ rsparse_status rsparse_plan_layer(int32_t d_in, int32_t d_out, int32_t rank, dou
     if (us_rsparse_out) *us_rsparse_out = us_rs;
     if (us_dense_out) *us_dense_out = us_dense;
     if (use_rsparse_out) *use_rsparse_out = us_rs < us_dense ? 1 : 0;
+    return RSPARSE_OK;
+}
+
+rsparse_status rsparse_debug_stamps(void *buf_dev, int32_t capacity_waves)
+{
+    if (capacity_waves < 0 || (buf_dev == nullptr) != (capacity_waves == 0)) return fail(RSPARSE_EINVAL, "buffer and capacity must both be set or both be zero");
+    hipError_t e = set_stamp_buffer(buf_dev, capacity_waves);
+    if (e == hipErrorNotSupported) return fail(RSPARSE_EINVAL, "this library was built without RSPARSE_STAMPS");
+    RS_HIP(e);
     return RSPARSE_OK;
 }
 

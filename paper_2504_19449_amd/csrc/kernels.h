@@ -27,6 +27,15 @@ struct LayerView {
     int32_t *act_count;     // [nz]
     int *sync;              // arrival counters of the one-launch path (layout: kSync* below); zero between calls
     uint32_t *t_pub;        // [nz][BT][rank] one-launch path: t as fp32 bits; all-ones (not ready) between calls
+    unsigned long long *t_tag;  // [t_slots][rank] strip kernel: {generation of the launch that wrote it, t as fp32 bits}
+    int t_slots;            // token slots of t_tag (max_batch rounded up to whole batch tiles)
+    // strip-major W for the strip kernel: strip s holds columns [s * strip_w, (s + 1) * strip_w) of all d_in + rank
+    // rows (row c = W[:, c], row d_in + j = U_r[:, j]) contiguously, [strips][d_in + rank][strip_w]; columns past
+    // d_out are zero
+    const uint16_t *Ms;
+    int strip_w;
+    long long strip_stride; // 16-bit elements from one strip to the next: (d_in + rank + padding rows) * strip_w
+    int32_t *act_seg;       // [nz][d_in / 8] strip kernel: kept channels found in each channel range of batch tile z
     // 4-bit weights (Mq != nullptr; then M and Wrow are null).  A column tile is kQ4Tile = 1024 outputs: lane l
     // of a wave owns the 8 bytes T * 512 + l * 8 .. of a row, two words h = 0, 1; byte k of word h holds the
     // code of column T * 1024 + h * 512 + l * 8 + k in its low nibble and of column ... + 4 + k in its high one.
@@ -53,8 +62,11 @@ struct Launch {
 // Arrival counters of the one-launch path, as offsets into LayerView::sync (32-bit words).
 constexpr int kSyncTilesDone = 0;   // column tiles (over all batch tiles) whose outputs have been stored
 constexpr int kSyncError = 1;       // set when a bounded wait ran out (results of that call are invalid)
+constexpr int kSyncGen = 2;         // strip kernel: generation number of the next launch (bumped once per launch)
+constexpr int kSyncStarted = 8;     // strip kernel: [kSyncStartedN] how many waves of the launch have read the generation
+constexpr int kSyncStartedN = 256;
 constexpr int kSyncMaxZ = 4;        // batch tiles per launch
-constexpr int kSyncTile = 8;        // [nz][tiles] channel splits of the tile that have added their sums
+constexpr int kSyncTile = kSyncStarted + kSyncStartedN;   // [nz][tiles] channel splits of the tile that have added their sums
 inline size_t sync_words(int tiles) { return (size_t)kSyncTile + (size_t)kSyncMaxZ * tiles; }
 
 // All launchers take a group of n <= kMaxGroupLayers layers that read the same input X (same d_in and
@@ -95,6 +107,21 @@ hipError_t launch_dense_rowdot(const LayerView *L, const Launch *cfg, int n, con
 bool mfma_path_supported(const LayerView &L, int batch);
 hipError_t launch_mfma_linear(const LayerView &L, const void *X, int batch, void *Y, uint32_t *chan_bits, int cus,
                               int stages, bool dense, int rows_per_wg_hint, hipStream_t stream);
+// The whole layer over strip-major weights (LayerView::Ms), up to 8 tokens per batch tile: one workgroup per strip
+// of strip_w output columns streams all kept rows of the strip and stores its slice of Y (cfg[i].splits == 1), or
+// `splits` workgroups per strip meet in yacc.  fused: stage 1 runs in the same launch and hands t over through
+// LayerView::t_tag; otherwise t must have been stored to LayerView::t by an earlier launch
+// (launch_sparse_and_t with with_gather = false).  dense: the dense product Y = X W^T through the same kernel
+// (every channel kept, no low-rank part).  Layers of a group share d_in, dtype and strip_w.
+hipError_t launch_strip(const LayerView *L, const Launch *cfg, int n, const void *X, int batch, void *const *Y,
+                        bool fused, bool dense, int cus, hipStream_t stream);
+// Stamps builds only (see device_stage1.h): where the strip kernel's waves write their phase time stamps;
+// hipErrorNotSupported in product builds.
+hipError_t set_stamp_buffer(void *buf_dev, int capacity_waves);
+int strip_waves(int batch);                       // waves per workgroup the strip kernel runs with
+// list entries per wave that fit in LDS for this launch shape; 0 = the shape does not fit (more splits needed)
+int strip_list_cap(int d_in, int rank, int splits, int waves, int bt, int strip_w);
+bool strip_width_ok(int w);
 // out[0:n) = round16(silu(G) * Up), n a multiple of 8, all 16-byte aligned.
 hipError_t launch_gated_input(const void *G, const void *Up, void *out, size_t n, int dtype, hipStream_t stream);
 // Zero `n` 32-bit words (a fill kernel, safe to record into a HIP graph).
