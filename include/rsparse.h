@@ -163,6 +163,23 @@ rsparse_status rsparse_linear(rsparse_layer *layer, const void *X_dev, int32_t b
                               void *Y_dev, void *stream);
 
 /*
+ * rsparse_linear for callers that cannot allocate device memory while they run -- code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc: same arguments, same result, but the call's scratch
+ * (partial sums, arrival counters, the hand-off of the low-rank intermediate, the kept-channel lists) lies in a
+ * file-scope device array of 2 MiB inside the library instead of in buffers the handle allocated, and the call
+ * itself allocates and frees nothing (no hipMalloc / hipFree, no allocating library routine; the array's device
+ * address is looked up once per device, on the first call there).  Each GPU the library runs on holds its copy of
+ * the array until the process ends.  Limits: 16-bit weights, batch <= 8, d_in and d_out <= 32768, rank <= 2048;
+ * anything larger is rejected with RSPARSE_EBATCH / RSPARSE_EINVAL before anything is launched.  Runs the vector
+ * path (never the matrix cores) preceded by one small fill launch that clears the part of the array the call uses,
+ * all on `stream` and capturable.  Every call on a GPU shares that GPU's array: calls that overlap on one GPU
+ * (different streams, different handles) race -- order them.  rsparse_last_active and rsparse_synchronize work
+ * afterwards as long as no other rsparse_linear_static call has run on that GPU in between.
+ */
+rsparse_status rsparse_linear_static(rsparse_layer *layer, const void *X_dev, int32_t batch,
+                                     void *Y_dev, void *stream);
+
+/*
  * The same layer applied to the gated MLP input (Sec. 3.1: H = X W_up^T (.) sigma(X W_gate^T) feeds the
  * down projection; Sec. 3.4 sparsifies that input like any other): x = round(silu(g) * u), rounded
  * once to the layer's 16-bit type and written to the handle's scratch by one small launch ahead of

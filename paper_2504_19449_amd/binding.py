@@ -12,7 +12,7 @@ OK, EINVAL, ENOMEM, EHIP, EBATCH, EALIGN, ESVD = range(7)
 _STATUS = {1: "EINVAL", 2: "ENOMEM", 3: "EHIP", 4: "EBATCH", 5: "EALIGN", 6: "ESVD"}
 
 EXPORTED_SYMBOLS = [
-    "rsparse_prepare", "rsparse_compute_factors", "rsparse_prepare_factors", "rsparse_prepare_q4", "rsparse_linear",
+    "rsparse_prepare", "rsparse_compute_factors", "rsparse_prepare_factors", "rsparse_prepare_q4", "rsparse_linear", "rsparse_linear_static",
     "rsparse_linear_gated", "rsparse_gated_input", "rsparse_mlp_gate_up", "rsparse_dense_ref", "rsparse_linear_group", "rsparse_dense_ref_group", "rsparse_last_active", "rsparse_synchronize",
     "rsparse_get_factors", "rsparse_set_tau", "rsparse_set_tuning",
     "rsparse_get_config", "rsparse_calibrate_tau", "rsparse_required_bytes", "rsparse_dense_bytes", "rsparse_io_model",
@@ -72,6 +72,8 @@ def load_library():
     lib.rsparse_prepare_factors.argtypes = [C.POINTER(Config), vp, vp, vp, C.POINTER(vp)]
     lib.rsparse_prepare_q4.argtypes = [C.POINTER(Config), vp, vp, vp, i32, vp, vp, C.POINTER(vp)]
     lib.rsparse_linear.argtypes = [vp, vp, i32, vp, vp]
+    lib.rsparse_linear_static.argtypes = [vp, vp, i32, vp, vp]
+    lib.rsparse_linear_static.restype = C.c_int
     lib.rsparse_dense_ref.argtypes = [vp, vp, i32, vp, vp]
     lib.rsparse_linear_gated.argtypes = [vp, vp, vp, i32, vp, vp]
     lib.rsparse_gated_input.argtypes = [vp, vp, vp, C.c_size_t, i32, vp]
@@ -217,6 +219,11 @@ def rsparse_prepare_q4(cfg: Config, Q, S16, Z, group_size: int, U16=None, SV16=N
 def rsparse_linear(layer: Layer, X_dev: int, batch: int, Y_dev: int, stream: int = 0):
     """X_dev / Y_dev / stream are raw device pointers / a hipStream_t as integers."""
     _check(load_library().rsparse_linear(layer.handle, X_dev, batch, Y_dev, stream))
+
+
+def rsparse_linear_static(layer: Layer, X_dev: int, batch: int, Y_dev: int, stream: int = 0):
+    """rsparse_linear with its scratch in the library's static device array (allocates nothing)."""
+    _check(load_library().rsparse_linear_static(layer.handle, X_dev, batch, Y_dev, stream))
 
 
 def rsparse_linear_gated(layer: Layer, G_dev: int, Up_dev: int, batch: int, Y_dev: int, stream: int = 0):

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librsparse.so")
-SOURCES = ["kernels.hip", "kernels_strip.hip", "kernels_mfma.hip", "api.cpp", "svd_host.cpp", "recipe_search.cpp"]
+SOURCES = ["kernels.hip", "kernels_strip.hip", "kernels_mfma.hip", "static_scratch.hip", "api.cpp", "svd_host.cpp", "recipe_search.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
          # keep the compiler from forming packed-fp32 instructions on its own

@@ -143,6 +143,7 @@ struct rsparse_layer {
     int32_t *act_list = nullptr, *act_count = nullptr;
     int *sync = nullptr;
     uint32_t *t_pub = nullptr;
+    ScratchView last_scratch{};            // the per-call scratch the last call used: the handle's own, or the static one
     uint16_t *hy = nullptr;                // [max_batch][d_out] 16-bit output scratch (gate / up results of rsparse_mlp_gate_up's fallback)
     uint16_t *xg = nullptr;                // [max_batch][d_in] gated input x = round16(silu(g) * u), written out per call
     size_t n_t = 0, n_y = 0, sync_n = 0;
@@ -158,16 +159,26 @@ struct rsparse_layer {
     int last_batch = 0;
     int last_bt = 0;                       // tokens per batch tile of the last call's kept lists (0 = batch_tile_of(last_batch))
 
-    LayerView view() const
+    ScratchView own_scratch() const
     {
+        ScratchView sp{};
+        sp.t = t; sp.yacc = yacc; sp.act_list = act_list; sp.act_bits = act_bits; sp.act_count = act_count;
+        sp.act_seg = act_seg; sp.sync = sync; sp.t_pub = t_pub; sp.t_tag = t_tag; sp.t_slots = t_slots;
+        sp.n_t = n_t; sp.n_y = n_y; sp.sync_n = sync_n;
+        return sp;
+    }
+
+    LayerView view(const ScratchView *ov = nullptr) const
+    {
+        const ScratchView sp = ov ? *ov : own_scratch();
         LayerView v{};
-        v.M = M; v.SVt = SVt; v.U = U; v.Wrow = Wrow; v.t = t; v.yacc = yacc;
-        v.act_list = act_list; v.act_bits = act_bits; v.act_count = act_count; v.sync = sync; v.t_pub = t_pub;
+        v.M = M; v.SVt = SVt; v.U = U; v.Wrow = Wrow; v.t = sp.t; v.yacc = sp.yacc;
+        v.act_list = sp.act_list; v.act_bits = sp.act_bits; v.act_count = sp.act_count; v.sync = sp.sync; v.t_pub = sp.t_pub;
         v.d_in = cfg.d_in; v.d_out = cfg.d_out; v.rank = cfg.rank;
         v.dtype = cfg.dtype; v.out_dtype = cfg.out_dtype; v.cmp_mode = cfg.cmp_mode;
         v.batch_mask_mode = cfg.batch_mask_mode; v.tau = cfg.tau;
         v.Mq = Mq; v.qs = qs; v.qz = qz; v.Ut = Ut; v.qshift = qshift; v.qtiles = qtiles;
-        v.Ms = Ms; v.strip_w = strip_w; v.strip_stride = strip_stride; v.t_tag = t_tag; v.t_slots = t_slots; v.act_seg = act_seg;
+        v.Ms = Ms; v.strip_w = strip_w; v.strip_stride = strip_stride; v.t_tag = sp.t_tag; v.t_slots = sp.t_slots; v.act_seg = sp.act_seg;
         return v;
     }
 };
@@ -619,6 +630,7 @@ rsparse_status linear_q4(rsparse_layer *L, const void *X_dev, int32_t batch, voi
     }
     if (!dense) {
         L->last_stream = s; L->last_batch = batch; L->last_mfma = false; L->last_fused = fused;
+        L->last_scratch = L->own_scratch();
         L->last_bt = std::min(4, batch_tile_of(batch));
         L->last_strip = false;
     }
@@ -644,7 +656,7 @@ rsparse_status check_group(rsparse_layer *const *layers, int32_t n, const void *
 
 namespace {
 rsparse_status linear_group_impl(rsparse_layer *const *layers, int32_t n_layers, const void *X_dev, const void *G_dev,
-                                 int32_t batch, void *const *Y_devs, void *stream);
+                                 int32_t batch, void *const *Y_devs, void *stream, const ScratchView *ov = nullptr);
 }
 
 rsparse_status rsparse_linear_group(rsparse_layer *const *layers, int32_t n_layers, const void *X_dev, int32_t batch,
@@ -674,8 +686,9 @@ rsparse_status rsparse_linear_gated(rsparse_layer *L, const void *G_dev, const v
 }
 
 namespace {
+// ov: per-call scratch to use instead of the handles' own (rsparse_linear_static; one layer, vector path only)
 rsparse_status linear_group_impl(rsparse_layer *const *layers, int32_t n_layers, const void *X_dev, const void *G_dev,
-                                 int32_t batch, void *const *Y_devs, void *stream)
+                                 int32_t batch, void *const *Y_devs, void *stream, const ScratchView *ov)
 {
     rsparse_status st = check_group(layers, n_layers, X_dev, batch, Y_devs);
     if (st != RSPARSE_OK) return st;
@@ -701,10 +714,11 @@ rsparse_status linear_group_impl(rsparse_layer *const *layers, int32_t n_layers,
     // one launch unless asked otherwise (timing a stage alone needs the two-launch form)
     const bool fused = layers[0]->tuning.launches != 2 && stages == 0;
     for (int i = 0; i < n_layers; ++i) {
-        v[i] = layers[i]->view();
+        v[i] = layers[i]->view(ov);
         lc[i] = resolve_launch(layers[i], batch, false, n_layers, i ? lc[0].waves : 0, fused);
+        layers[i]->last_scratch = ov ? *ov : layers[i]->own_scratch();
     }
-    bool mfma = batch >= (layers[0]->tuning.mfma_min_batch > 0 ? layers[0]->tuning.mfma_min_batch : kMfmaDefaultMinBatch);
+    bool mfma = !ov && batch >= (layers[0]->tuning.mfma_min_batch > 0 ? layers[0]->tuning.mfma_min_batch : kMfmaDefaultMinBatch);
     for (int i = 0; i < n_layers; ++i) mfma = mfma && mfma_path_supported(v[i], batch);
     // a gated input is written out once first (one small launch), then the layer runs on it
     if (G_dev) {
@@ -796,6 +810,7 @@ rsparse_status rsparse_mlp_gate_up(rsparse_layer *gate, rsparse_layer *up, const
         RS_HIP(launch_fused(v, lc, 2, X_dev, batch, outs, s, true));
         for (int i = 0; i < 2; ++i) {
             pair[i]->last_stream = s; pair[i]->last_batch = batch; pair[i]->last_mfma = false; pair[i]->last_fused = true; pair[i]->last_bt = 0; pair[i]->last_strip = false;
+            pair[i]->last_scratch = pair[i]->own_scratch();
         }
         return RSPARSE_OK;
     }
@@ -810,6 +825,24 @@ rsparse_status rsparse_mlp_gate_up(rsparse_layer *gate, rsparse_layer *up, const
 rsparse_status rsparse_linear(rsparse_layer *L, const void *X_dev, int32_t batch, void *Y_dev, void *stream)
 {
     return rsparse_linear_group(&L, 1, X_dev, batch, &Y_dev, stream);
+}
+
+rsparse_status rsparse_linear_static(rsparse_layer *L, const void *X_dev, int32_t batch, void *Y_dev, void *stream)
+{
+    rsparse_status st = check_call(L, X_dev, batch, Y_dev);
+    if (st != RSPARSE_OK) return st;
+    if (L->q4()) return fail(RSPARSE_EINVAL, "rsparse_linear_static runs 16-bit weights only");
+    if (batch > kStaticMaxBatch)
+        return fail(RSPARSE_EBATCH, "rsparse_linear_static: batch %d exceeds the static scratch's %d tokens", batch, kStaticMaxBatch);
+    if (L->cfg.d_in > kStaticMaxDim || L->cfg.d_out > kStaticMaxDim || L->cfg.rank > kStaticMaxRank)
+        return fail(RSPARSE_EINVAL, "rsparse_linear_static: layer %d -> %d, rank %d exceeds the static scratch (d_in, d_out <= %d, rank <= %d)",
+                    L->cfg.d_in, L->cfg.d_out, L->cfg.rank, kStaticMaxDim, kStaticMaxRank);
+    int dev = -1;
+    RS_HIP(hipGetDevice(&dev));
+    if (dev != L->device) return fail(RSPARSE_EINVAL, "the layer lives on device %d, the current device is %d", L->device, dev);
+    ScratchView sp{};
+    RS_HIP(static_scratch_for_call(dev, L->cfg.d_out, L->cfg.rank, batch, (hipStream_t)stream, &sp));
+    return linear_group_impl(&L, 1, X_dev, nullptr, batch, &Y_dev, stream, &sp);
 }
 
 rsparse_status rsparse_dense_ref_group(rsparse_layer *const *layers, int32_t n_layers, const void *X_dev,
@@ -889,16 +922,17 @@ rsparse_status rsparse_synchronize(rsparse_layer *L)
     if (L->last_batch == 0) return RSPARSE_OK;
     RS_HIP(hipStreamSynchronize(L->last_stream));
     if (L->last_fused) {
+        const ScratchView &sp = L->last_scratch;
         int flag = 0;
-        RS_HIP(hipMemcpy(&flag, L->sync + kSyncError, 4, hipMemcpyDeviceToHost));
+        RS_HIP(hipMemcpy(&flag, sp.sync + kSyncError, 4, hipMemcpyDeviceToHost));
         if (flag != 0) {
             // leave the counters usable for the next call
             int gen = 0;                              // the generation of the strip kernel's hand-off survives the reset
-            RS_HIP(hipMemcpy(&gen, L->sync + kSyncGen, 4, hipMemcpyDeviceToHost));
-            RS_HIP(hipMemset(L->sync, 0, L->sync_n * 4));
-            RS_HIP(hipMemcpy(L->sync + kSyncGen, &gen, 4, hipMemcpyHostToDevice));
-            RS_HIP(hipMemset(L->t_pub, 0xff, L->n_t * 4));
-            RS_HIP(hipMemset(L->yacc, 0, L->n_y * 4));
+            RS_HIP(hipMemcpy(&gen, sp.sync + kSyncGen, 4, hipMemcpyDeviceToHost));
+            RS_HIP(hipMemset(sp.sync, 0, sp.sync_n * 4));
+            RS_HIP(hipMemcpy(sp.sync + kSyncGen, &gen, 4, hipMemcpyHostToDevice));
+            RS_HIP(hipMemset(sp.t_pub, 0xff, sp.n_t * 4));
+            RS_HIP(hipMemset(sp.yacc, 0, sp.n_y * 4));
             return fail(RSPARSE_EHIP, "a cross-workgroup wait of the one-launch kernel ran out; the last result is invalid");
         }
     }
@@ -927,7 +961,8 @@ rsparse_status rsparse_last_active(rsparse_layer *L, int32_t token, int32_t *idx
     const size_t d_in = L->cfg.d_in;
     std::vector<int32_t> cnt(nz), list;
     std::vector<uint32_t> bits;
-    RS_HIP(hipMemcpy(cnt.data(), L->act_count, nz * 4, hipMemcpyDeviceToHost));
+    const ScratchView &sp = L->last_scratch;
+    RS_HIP(hipMemcpy(cnt.data(), sp.act_count, nz * 4, hipMemcpyDeviceToHost));
     std::vector<int32_t> seg, seg_list;
     std::vector<uint32_t> seg_bits;
     auto fetch = [&](int z) -> rsparse_status {
@@ -937,9 +972,9 @@ rsparse_status rsparse_last_active(rsparse_layer *L, int32_t token, int32_t *idx
             const size_t nq = d_in / 8;
             const size_t R = std::min<size_t>((size_t)L->last_ranges, nq);
             seg.resize(R); seg_list.resize(d_in); seg_bits.resize(d_in);
-            RS_HIP(hipMemcpy(seg.data(), L->act_seg + z * nq, R * 4, hipMemcpyDeviceToHost));
-            RS_HIP(hipMemcpy(seg_list.data(), L->act_list + z * d_in, d_in * 4, hipMemcpyDeviceToHost));
-            RS_HIP(hipMemcpy(seg_bits.data(), L->act_bits + z * d_in, d_in * 4, hipMemcpyDeviceToHost));
+            RS_HIP(hipMemcpy(seg.data(), sp.act_seg + z * nq, R * 4, hipMemcpyDeviceToHost));
+            RS_HIP(hipMemcpy(seg_list.data(), sp.act_list + z * d_in, d_in * 4, hipMemcpyDeviceToHost));
+            RS_HIP(hipMemcpy(seg_bits.data(), sp.act_bits + z * d_in, d_in * 4, hipMemcpyDeviceToHost));
             list.clear(); bits.clear();
             const size_t parts = (size_t)L->last_ranges, base = nq / parts, rem = nq - base * parts;
             for (size_t rho = 0; rho < R; ++rho) {
@@ -953,8 +988,8 @@ rsparse_status rsparse_last_active(rsparse_layer *L, int32_t token, int32_t *idx
         if (cnt[z] < 0 || (size_t)cnt[z] > d_in) return fail(RSPARSE_EHIP, "corrupt list count %d", cnt[z]);
         list.resize(cnt[z]); bits.resize(cnt[z]);
         if (cnt[z]) {
-            RS_HIP(hipMemcpy(list.data(), L->act_list + z * d_in, (size_t)cnt[z] * 4, hipMemcpyDeviceToHost));
-            RS_HIP(hipMemcpy(bits.data(), L->act_bits + z * d_in, (size_t)cnt[z] * 4, hipMemcpyDeviceToHost));
+            RS_HIP(hipMemcpy(list.data(), sp.act_list + z * d_in, (size_t)cnt[z] * 4, hipMemcpyDeviceToHost));
+            RS_HIP(hipMemcpy(bits.data(), sp.act_bits + z * d_in, (size_t)cnt[z] * 4, hipMemcpyDeviceToHost));
         }
         return RSPARSE_OK;
     };

@@ -49,6 +49,28 @@ struct LayerView {
     float tau;
 };
 
+// Per-call scratch of a layer: what the kernels write besides Y.  Normally owned by the handle (allocated when the
+// layer is prepared); rsparse_linear_static points it into a file-scope device array instead.
+struct ScratchView {
+    float *t, *yacc;
+    int32_t *act_list;
+    uint32_t *act_bits;
+    int32_t *act_count, *act_seg;
+    int *sync;
+    uint32_t *t_pub;
+    unsigned long long *t_tag;
+    int t_slots;
+    size_t n_t, n_y, sync_n;       // 32-bit words of t / t_pub (and 64-bit words of t_tag), of yacc, of sync
+};
+
+// Limits of the static scratch (static_scratch.hip): one batch tile of up to 8 tokens, dimensions up to 32768,
+// rank up to 2048 -- 1.6 MB carved out of a 2 MiB array.
+constexpr int kStaticMaxBatch = 8, kStaticMaxDim = 32768, kStaticMaxRank = 2048;
+// The scratch of one call in the calling device's static array (its address is looked up once per device), cleared
+// for this call by one fill launch on `stream`: accumulators and counters zero, hand-off entries "not written".
+// Allocates nothing.
+hipError_t static_scratch_for_call(int device, int d_out, int rank, int batch, hipStream_t stream, ScratchView *out);
+
 struct Launch {
     int splits;        // channel splits per column tile
     int waves;         // waves per workgroup (first launch / dense axpy)
