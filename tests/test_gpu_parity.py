@@ -651,3 +651,89 @@ def test_random_shapes_and_settings(seed):
         print("case", label, flush=True)
         _parity(L, X16, tau, out_dtype=rs.F32, tuning=tuning, cmp_mode=cmp_mode, batch_mask_mode=mask_mode,
                 dense_rowmajor=rowmajor)
+
+
+def test_prepare_with_the_host_svd_end_to_end():
+    """rsparse_prepare (the first call of the path: host SVD -> stored 16-bit factors -> pack -> upload) followed by
+    rsparse_get_factors / rsparse_get_config: the oracle consumes exactly the factor bits the library stored, and
+    the layer must match it; the factors themselves are checked against the generator's closed form through the
+    product they stand for (Eckart-Young: the best rank-r approximation), not vector by vector."""
+    for d_in, d_out, r, dt in ((520, 264, 24, synth.BF16), (264, 520, 16, synth.F16)):
+        L = synth.make_layer(d_in, d_out, r, dt, config=89, linear=dt)
+        src = synth.DModelInput(d_in, config=89, linear=dt)
+        tau = gu.calibrated_tau(L, src, 0.5)
+        cfg = rs.make_config(d_in, d_out, r, tau, dt, max_batch=2, out_dtype=rs.F32, cmp_mode=1)
+        layer = rs.rsparse_prepare(cfg, L.W16)
+        back = rs.rsparse_get_config(layer)
+        for f in ("d_in", "d_out", "rank", "max_batch", "dtype", "out_dtype", "cmp_mode", "batch_mask_mode", "dense_rowmajor", "strip_cols"):
+            assert getattr(back, f) == getattr(cfg, f), f
+        assert back.tau == np.float32(tau)
+        U16, SV16 = rs.rsparse_get_factors(layer)
+        assert U16.shape == (d_out, r) and SV16.shape == (r, d_in)
+        # the stored factors reproduce the top-r part of W: || U (S V^T) - U_r diag(s_r) V_r^T ||_F is at the level of
+        # 16-bit rounding of the factors
+        prod = synth.decode16(U16, dt) @ synth.decode16(SV16, dt)
+        best = (L.U[:, :r] * L.sigma[:r]) @ L.V[:, :r].T
+        assert np.linalg.norm(prod - best) <= (2e-2 if dt == synth.BF16 else 4e-3) * np.linalg.norm(best)
+        X16 = synth.encode16(src.tokens(2), dt)
+        got = gu.run_linear(layer, X16)
+        import oracle
+        want = oracle.rsparse_linear(L.W16, U16, SV16, X16, dt, dt, tau, cmp_mode=1, nthreads=8)
+        gu.check_lists(got, want)
+        gu.check_outputs(got["Y"], want["Y"], rs.F32)
+        rs.rsparse_set_tau(layer, 2.0 * tau)
+        assert rs.rsparse_get_config(layer).tau == np.float32(2.0 * tau)
+        # the byte model of the handle equals the shape-only model
+        assert rs.rsparse_required_bytes(layer, 2, 100) == rs.rsparse_io_model(cfg, 2, 100)[0]
+        assert rs.rsparse_dense_bytes(layer, 2) == rs.rsparse_io_model(cfg, 2, 0)[1]
+        layer.destroy()
+
+
+def test_prepare_with_the_host_svd_on_a_4096_layer(config0):
+    """The same on configs[0]'s 4096 x 4096 layer (power-law spectrum; r = 64 keeps the host SVD to seconds)."""
+    import oracle
+    dt = synth.F16
+    L = config0
+    src = synth.DModelInput(4096, config=89, linear=3)
+    tau = gu.calibrated_tau(L, src, 0.5)
+    cfg = rs.make_config(4096, 4096, 64, tau, dt)
+    layer = rs.rsparse_prepare(cfg, L.W16)
+    U16, SV16 = rs.rsparse_get_factors(layer)
+    # the top 64 components of the generator's closed form, up to fp16 rounding of W and of the factors
+    best = (L.U[:, :64] * L.sigma[:64]) @ L.V[:, :64].T
+    assert np.linalg.norm(synth.decode16(U16, dt) @ synth.decode16(SV16, dt) - best) <= 2e-2 * np.linalg.norm(best)
+    X16 = synth.encode16(src.tokens(1), dt)
+    got = gu.run_linear(layer, X16)
+    want = oracle.rsparse_linear(L.W16, U16, SV16, X16, dt, dt, tau, nthreads=8)
+    gu.check_lists(got, want)
+    gu.check_outputs(got["Y"], want["Y"], dt)
+    layer.destroy()
+
+
+def test_nothing_is_written_past_the_end_of_the_outputs(ragged):
+    """Canaries around Y: the output buffer sits inside a larger allocation filled with a pattern; after calls
+    through every path (one and two launches, 8-token tiles, matrix cores, strips, dense baselines) only the
+    batch x d_out outputs may have changed."""
+    torch = gu.torch_mod()
+    L = ragged[synth.BF16]
+    X16, src = gu.tokens_for(L, 9, linear=12)
+    tau = gu.calibrated_tau(L, src, 0.5)
+    pad = 4096                                                   # 16-bit words of canary on each side
+    for kw, tuning, B in ((dict(), dict(), 1), (dict(), dict(launches=2), 3), (dict(), dict(), 8),
+                          (dict(dense_rowmajor=1), dict(), 9), (dict(strip_cols=32), dict(), 1),
+                          (dict(strip_cols=64), dict(splits=3), 9), (dict(out_dtype=rs.F32), dict(), 2)):
+        layer = gu.prepare(L, tau, max_batch=B, **kw)
+        rs.rsparse_set_tuning(layer, **tuning)
+        words = (2 if layer.cfg.out_dtype == rs.F32 else 1) * B * L.d_out
+        buf = torch.full((pad + words + pad,), 0x5A5A, dtype=torch.int16, device="cuda")
+        Y = buf[pad:pad + words]
+        assert Y.data_ptr() % 16 == 0
+        Xd = gu.to_dev16(X16[:B])
+        for fn in (rs.rsparse_linear, rs.rsparse_dense_ref, rs.rsparse_linear_static if B <= 8 else rs.rsparse_linear):
+            buf.fill_(0x5A5A)
+            fn(layer, Xd.data_ptr(), B, Y.data_ptr(), gu.stream_ptr())
+            torch.cuda.synchronize()
+            host = buf.cpu().numpy()
+            assert np.all(host[:pad] == 0x5A5A) and np.all(host[pad + words:] == 0x5A5A), (kw, tuning, B, fn.__name__)
+            assert np.any(host[pad:pad + words] != 0x5A5A)
+        layer.destroy()
