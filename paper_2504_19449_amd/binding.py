@@ -46,6 +46,9 @@ _lib = None
 
 
 def library_path() -> str:
+    """The in-tree library, or the file RSPARSE_LIB names (a measurement build of the same sources)."""
+    if os.environ.get("RSPARSE_LIB"):
+        return os.environ["RSPARSE_LIB"]
     return os.path.join(os.path.dirname(os.path.abspath(__file__)), "librsparse.so")
 
 

@@ -6,6 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librsparse.so")
+LIB_STAMPS = os.path.join(HERE, "librsparse_stamps.so")     # measurement build, loaded only on request (RSPARSE_LIB)
 SOURCES = ["kernels.hip", "kernels_strip.hip", "kernels_mfma.hip", "static_scratch.hip", "api.cpp", "svd_host.cpp", "recipe_search.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
@@ -24,15 +25,17 @@ def is_current() -> bool:
 
 def build(force: bool = True, stamps: bool = False) -> str:
     """stamps=True (or RSPARSE_STAMPS=1 in the environment): a measurement build whose strip kernel records per-wave
-    phase time stamps (rsparse_debug_stamps); same file name, never what tests or the benchmark's timed legs should load."""
+    phase time stamps (rsparse_debug_stamps).  It goes to librsparse_stamps.so, which nothing loads unless the
+    environment names it in RSPARSE_LIB (`bench.py --stamps` does)."""
     stamps = stamps or os.environ.get("RSPARSE_STAMPS") == "1"
-    if not force and is_current():
+    if not stamps and not force and is_current():
         return LIB
+    lib = LIB_STAMPS if stamps else LIB
     objs = []
     procs = []
     os.makedirs(os.path.join(HERE, "_build"), exist_ok=True)
     for src in SOURCES:
-        obj = os.path.join(HERE, "_build", src + ".o")
+        obj = os.path.join(HERE, "_build", src + (".stamps.o" if stamps else ".o"))
         objs.append(obj)
         procs.append((src, subprocess.Popen([HIPCC, *FLAGS, *(["-DRSPARSE_STAMPS=1"] if stamps else []), "-c",
                                              os.path.join(CSRC, src), "-o", obj],
@@ -44,8 +47,8 @@ def build(force: bool = True, stamps: bool = False) -> str:
             raise RuntimeError(f"hipcc failed on {src}:\n{err}")
         if err.strip():
             sys.stderr.write(err + "\n")
-    subprocess.run([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *objs], check=True)
-    return LIB
+    subprocess.run([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", lib, *objs], check=True)
+    return lib
 
 
 if __name__ == "__main__":

@@ -280,8 +280,11 @@ Launch resolve_strip(const rsparse_layer *L, int batch, bool dense, int group, b
     const int rank = dense ? 0 : L->cfg.rank;
     int splits = t.splits;
     if (splits <= 0) {
-        const int target = std::max(1, L->cus / std::max(1, group));
-        splits = L->strips * 2 >= target ? 1 : (target + L->strips - 1) / L->strips;
+        // measured: small layers (under 2^26 weights) run best at about one workgroup per two compute units, large
+        // ones at one per compute unit, the linears of a grouped call sharing that number
+        const bool large = (size_t)L->cfg.d_in * L->cfg.d_out >= ((size_t)1 << 26);
+        const int target = std::max(1, (large ? L->cus : L->cus / 2) / std::max(1, group));
+        splits = std::max(1, (target + L->strips / 2) / L->strips);
     }
     splits = std::max(1, std::min(splits, 4096));
     while (strip_list_cap(L->cfg.d_in, rank, splits, c.waves, bt, L->strip_w) <= 0 && splits < 4096) ++splits;
