@@ -21,8 +21,11 @@
  * product; r = 0 and tau = +inf give the "Sparse" and "Low-Rank" ablations of
  * Sec. 4.4; the (singular component, channel) double sum of Sec. 3.3 restricted
  * to the kept block, brute-forced over all masks of 8x8 layers; closed-form
- * factors; the Eckart-Young bound; numpy's matvec.  No function here is
- * "parity unpinned".
+ * factors; the Eckart-Young bound; numpy's matvec.  Variants (fixed-count
+ * activation, signed threshold, output bias, the multi-phase activation and
+ * residual biases of Sec. 3.2) are pinned in tests/test_oracle_variants.py:
+ * numpy's stable sort, literal loops, a hand-worked example, the identity
+ * Y_s + Y_r = sigma_T(H) W^T.  No function here is "parity unpinned".
  *
  * W is [d_out][d_in] row-major (nn.Linear orientation, Y = X W^T); "columns of
  * W" are input channels.  X is [B][d_in], Y is [B][d_out].
@@ -81,8 +84,11 @@ void orc_decode16(const uint16_t *in, size_t n, int dtype, double *out)
 
 /* Keep-predicate of sigma_t: |x| >= t (the paper's definition, cmp_mode 0) or the
  * strict variant |x| > t (cmp_mode 1).  A NaN compares false: it is not kept. */
+/* cmp_mode 0: |x| >= t (the printed sigma_t of Sec. 3.4); 1: |x| > t; 2: x >= t, signed -- the sparse components of
+ * the multi-phase activation of Sec. 3.2 are the values at or above T_0, whatever their magnitude. */
 static inline int keep(double x, float tau, int cmp_mode)
 {
+    if (cmp_mode == 2) return x >= (double)tau;
     double a = fabs(x);
     return cmp_mode == 0 ? (a >= (double)tau) : (a > (double)tau);
 }
@@ -109,49 +115,27 @@ static int list_of(const uint8_t *mask, int d_in, int want, int32_t *out)
 
 /* ---- the R-Sparse linear layer ------------------------------------------ */
 
-/*
- * kind_w / kind_x: ORC_F16, ORC_BF16 (W, U, SV, X are uint16 bit patterns) or ORC_F64.
- * batch_mask_mode 0: every token uses its own mask (the paper's elementwise sigma_t).
- * batch_mask_mode 1: every token uses the union of the batch's masks.
- * Optional outputs (may be NULL): act [B][d_in] ascending kept channels per token (first
- * cnt[b] entries valid), cnt [B], uni [d_in] ascending union of kept channels, ucnt [1].
- * Returns 0, or -1 on allocation failure / bad arguments.
- */
-int orc_rsparse_linear(const void *W, const void *U, const void *SV, int kind_w,
-                       const void *X, int kind_x,
-                       int B, int d_in, int d_out, int r,
-                       float tau, int cmp_mode, int batch_mask_mode,
-                       double *Y, int32_t *act, int32_t *cnt, int32_t *uni, int32_t *ucnt,
-                       int nthreads)
+/* Steps 2-4 for given masks: mask [B][d_in], 1 = the channel is kept (sigma(X) != 0 there).  bias: NULL, or [d_out]
+ * added to every token's output (the static form of the residual biases of Sec. 3.2). */
+int orc_rsparse_linear_masked(const void *W, const void *U, const void *SV, int kind_w,
+                              const void *X, int kind_x,
+                              int B, int d_in, int d_out, int r,
+                              const uint8_t *mask, const double *bias, double *Y, int nthreads)
 {
-    if (B < 1 || d_in < 1 || d_out < 1 || r < 0 || tau != tau) return -1;
+    if (B < 1 || d_in < 1 || d_out < 1 || r < 0 || !mask) return -1;
     if (nthreads < 1) nthreads = 1;
-    size_t esz = (kind_x == ORC_F64) ? 8 : 2;
-    uint8_t *mask = malloc((size_t)B * d_in);
-    uint8_t *umask = calloc((size_t)d_in, 1);
     int32_t *a_list = malloc(sizeof(int32_t) * (size_t)d_in);
     int32_t *i_list = malloc(sizeof(int32_t) * (size_t)d_in);
     double *xs = malloc(sizeof(double) * (size_t)d_in);
     double *t = malloc(sizeof(double) * (size_t)(r > 0 ? r : 1));
-    if (!mask || !umask || !a_list || !i_list || !xs || !t) {
-        free(mask); free(umask); free(a_list); free(i_list); free(xs); free(t);
+    if (!a_list || !i_list || !xs || !t) {
+        free(a_list); free(i_list); free(xs); free(t);
         return -1;
     }
-
-    /* step 1 for every token, and the union over the batch */
     for (int b = 0; b < B; ++b) {
-        const void *xb = (const char *)X + (size_t)b * d_in * esz;
-        orc_mask(xb, kind_x, d_in, tau, cmp_mode, mask + (size_t)b * d_in);
-        for (int c = 0; c < d_in; ++c) umask[c] |= mask[(size_t)b * d_in + c];
-    }
-    if (uni && ucnt) *ucnt = list_of(umask, d_in, 1, uni);
-
-    for (int b = 0; b < B; ++b) {
-        const uint8_t *mb = batch_mask_mode == 1 ? umask : mask + (size_t)b * d_in;
+        const uint8_t *mb = mask + (size_t)b * d_in;
         int k = list_of(mb, d_in, 1, a_list);         /* kept channels:  sigma_t(X) != 0      */
         int z = list_of(mb, d_in, 0, i_list);         /* the rest:       X - sigma_t(X) != 0  */
-        if (act) memcpy(act + (size_t)b * d_in, a_list, sizeof(int32_t) * (size_t)k);
-        if (cnt) cnt[b] = k;
         for (int c = 0; c < d_in; ++c) xs[c] = ld(X, (size_t)b * d_in + c, kind_x);
 
         /* step 3a: t = (S_r V_r^T) (x - sigma_t(x)), only the channels that were zeroed */
@@ -178,10 +162,162 @@ int orc_rsparse_linear(const void *W, const void *U, const void *SV, int kind_w,
             for (int i = 0; i < r; ++i)
                 yr += ld(U, (size_t)o * r + i, kind_w) * t[i];
             /* step 4 */
-            Y[(size_t)b * d_out + o] = ys + yr;
+            Y[(size_t)b * d_out + o] = bias ? ys + yr + bias[o] : ys + yr;
         }
     }
-    free(mask); free(umask); free(a_list); free(i_list); free(xs); free(t);
+    free(a_list); free(i_list); free(xs); free(t);
+    return 0;
+}
+
+/* Fixed-count activation: keep the k channels of largest magnitude of one token (a variant of the thresholding of
+ * Sec. 3.4 in which the sparsity is exact per token instead of in expectation).  Among equal magnitudes the lower
+ * channel index is kept first; NaN is never kept (as under a threshold, where it compares false); with fewer than k
+ * non-NaN channels all of them are kept.  Returns the number kept. */
+typedef struct { double a; int c; } orc_mag;
+static int cmp_mag(const void *p, const void *q)
+{
+    const orc_mag *x = p, *y = q;
+    if (x->a != y->a) return x->a > y->a ? -1 : 1;     /* larger magnitude first */
+    return x->c < y->c ? -1 : (x->c > y->c ? 1 : 0);   /* then lower channel */
+}
+int orc_topk_mask(const void *x, int x_kind, int d_in, int k, uint8_t *mask)
+{
+    if (d_in < 1 || k < 0) return -1;
+    orc_mag *m = malloc(sizeof(orc_mag) * (size_t)d_in);
+    if (!m) return -1;
+    int n = 0;
+    for (int c = 0; c < d_in; ++c) {
+        double v = ld(x, (size_t)c, x_kind);
+        mask[c] = 0;
+        if (v == v) { m[n].a = fabs(v); m[n].c = c; ++n; }
+    }
+    qsort(m, (size_t)n, sizeof(orc_mag), cmp_mag);
+    int kept = k < n ? k : n;
+    for (int i = 0; i < kept; ++i) mask[m[i].c] = 1;
+    free(m);
+    return kept;
+}
+
+/*
+ * kind_w / kind_x: ORC_F16, ORC_BF16 (W, U, SV, X are uint16 bit patterns) or ORC_F64.
+ * topk 0: masks from the threshold tau under cmp_mode; topk > 0: fixed-count masks (tau, cmp_mode unused).
+ * batch_mask_mode 0: every token uses its own mask (the paper's elementwise sigma_t).
+ * batch_mask_mode 1: every token uses the union of the batch's masks.
+ * bias: NULL or [d_out].
+ * Optional outputs (may be NULL): act [B][d_in] ascending kept channels per token (first
+ * cnt[b] entries valid), cnt [B], uni [d_in] ascending union of kept channels, ucnt [1].
+ * Returns 0, or -1 on allocation failure / bad arguments.
+ */
+int orc_rsparse_linear_ex(const void *W, const void *U, const void *SV, int kind_w,
+                          const void *X, int kind_x,
+                          int B, int d_in, int d_out, int r,
+                          float tau, int cmp_mode, int topk, int batch_mask_mode, const double *bias,
+                          double *Y, int32_t *act, int32_t *cnt, int32_t *uni, int32_t *ucnt,
+                          int nthreads)
+{
+    if (B < 1 || d_in < 1 || d_out < 1 || r < 0 || tau != tau || topk < 0) return -1;
+    size_t esz = (kind_x == ORC_F64) ? 8 : 2;
+    uint8_t *mask = malloc((size_t)B * d_in);
+    uint8_t *umask = calloc((size_t)d_in, 1);
+    if (!mask || !umask) { free(mask); free(umask); return -1; }
+
+    /* step 1 for every token, and the union over the batch */
+    for (int b = 0; b < B; ++b) {
+        const void *xb = (const char *)X + (size_t)b * d_in * esz;
+        if (topk > 0) orc_topk_mask(xb, kind_x, d_in, topk, mask + (size_t)b * d_in);
+        else orc_mask(xb, kind_x, d_in, tau, cmp_mode, mask + (size_t)b * d_in);
+        for (int c = 0; c < d_in; ++c) umask[c] |= mask[(size_t)b * d_in + c];
+    }
+    if (uni && ucnt) *ucnt = list_of(umask, d_in, 1, uni);
+    if (batch_mask_mode == 1)
+        for (int b = 0; b < B; ++b) memcpy(mask + (size_t)b * d_in, umask, (size_t)d_in);
+    for (int b = 0; b < B; ++b) {
+        int k = 0;
+        for (int c = 0; c < d_in; ++c)
+            if (mask[(size_t)b * d_in + c]) { if (act) act[(size_t)b * d_in + k] = c; ++k; }
+        if (cnt) cnt[b] = k;
+    }
+    int rc = orc_rsparse_linear_masked(W, U, SV, kind_w, X, kind_x, B, d_in, d_out, r, mask, bias, Y, nthreads);
+    free(mask); free(umask);
+    return rc;
+}
+
+int orc_rsparse_linear(const void *W, const void *U, const void *SV, int kind_w,
+                       const void *X, int kind_x,
+                       int B, int d_in, int d_out, int r,
+                       float tau, int cmp_mode, int batch_mask_mode,
+                       double *Y, int32_t *act, int32_t *cnt, int32_t *uni, int32_t *ucnt,
+                       int nthreads)
+{
+    return orc_rsparse_linear_ex(W, U, SV, kind_w, X, kind_x, B, d_in, d_out, r, tau, cmp_mode, 0, batch_mask_mode, NULL,
+                                 Y, act, cnt, uni, ucnt, nthreads);
+}
+
+/* ---- Sec. 3.2: the multi-phase activation and its residual biases ----------------------------------------------
+ *
+ * sigma_T(x) = x                      if x >= T_0
+ *            = (T_i + T_{i+1}) / 2    if T_{i+1} <= x < T_i,   i = 0 .. l-2,     T_0 > T_1 > ... > T_{l-1}.
+ * The paper takes T_{l-1} as the minimum of the input, so nothing lies below it; for thresholds fixed in advance a
+ * value below T_{l-1} is put into the last interval (reading).  l = 1: everything below T_0 becomes 0 (with T_0 = 0
+ * this is ReLU, as Sec. 3.2 notes).
+ */
+static int phase_of(double x, const double *T, int l)   /* x < T_0, l >= 2: the i with T_{i+1} <= x < T_i */
+{
+    for (int i = 0; i + 1 < l; ++i)
+        if (x >= T[i + 1]) return i;
+    return l - 2;                                        /* below T_{l-1}: the last interval */
+}
+double orc_multiphase(double x, const double *T, int l)
+{
+    if (x != x) return x;
+    if (x >= T[0]) return x;
+    if (l < 2) return 0.0;
+    int i = phase_of(x, T, l);
+    return 0.5 * (T[i] + T[i + 1]);
+}
+
+/* The data-dependent residual of one token h (Sec. 3.2):
+ *   Y_r = sum_{j=0}^{l-2} (T_j + T_{j+1})/2 * ( sum_{k in U_j} W^T[:, k] ),   U_j = { k : T_{j+1} <= h_k < T_j }.
+ * Yr [d_out].  Each inner sum is the bias B_j of the paper; Bj (optional, [l-1][d_out]) receives them. */
+int orc_multiphase_residual(const void *W, int kind_w, const void *h, int kind_h, int d_in, int d_out,
+                            const double *T, int l, double *Yr, double *Bj)
+{
+    if (d_in < 1 || d_out < 1 || l < 1) return -1;
+    for (int i = 0; i + 1 < l; ++i) if (!(T[i] > T[i + 1])) return -1;
+    for (int o = 0; o < d_out; ++o) Yr[o] = 0.0;
+    for (int j = 0; j + 1 < l; ++j) {
+        for (int o = 0; o < d_out; ++o) {
+            double bsum = 0.0;                                   /* B_j[o] = sum over the channels of U_j of W[o][k] */
+            for (int k = 0; k < d_in; ++k) {
+                double v = ld(h, (size_t)k, kind_h);
+                if (v < T[0] && phase_of(v, T, l) == j) bsum += ld(W, (size_t)o * d_in + k, kind_w);
+            }
+            if (Bj) Bj[(size_t)j * d_out + o] = bsum;
+            Yr[o] += 0.5 * (T[j] + T[j + 1]) * bsum;
+        }
+    }
+    return 0;
+}
+
+/* Static bias: the data-dependent residual averaged over N calibration tokens (reading: Sec. 3.2 says the biases can
+ * be made static and pre-computed but not how; the mean over calibration data is the least-squares constant). */
+int orc_static_bias(const void *W, int kind_w, const void *H, int kind_h, int N, int d_in, int d_out,
+                    const double *T, int l, double *bias)
+{
+    if (N < 1) return -1;
+    size_t esz = (kind_h == ORC_F64) ? 8 : 2;
+    double *yr = malloc(sizeof(double) * (size_t)d_out);
+    if (!yr) return -1;
+    for (int o = 0; o < d_out; ++o) bias[o] = 0.0;
+    for (int n = 0; n < N; ++n) {
+        if (orc_multiphase_residual(W, kind_w, (const char *)H + (size_t)n * d_in * esz, kind_h, d_in, d_out, T, l, yr, NULL)) {
+            free(yr);
+            return -1;
+        }
+        for (int o = 0; o < d_out; ++o) bias[o] += yr[o];
+    }
+    for (int o = 0; o < d_out; ++o) bias[o] /= (double)N;
+    free(yr);
     return 0;
 }
 

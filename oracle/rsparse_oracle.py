@@ -33,6 +33,25 @@ def _load():
             C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int,
             C.c_int, C.c_int, C.c_int, C.c_int, C.c_float, C.c_int, C.c_int,
             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]
+        lib.orc_rsparse_linear_ex.restype = C.c_int
+        lib.orc_rsparse_linear_ex.argtypes = [
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int,
+            C.c_int, C.c_int, C.c_int, C.c_int, C.c_float, C.c_int, C.c_int, C.c_int, C.c_void_p,
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]
+        lib.orc_rsparse_linear_masked.restype = C.c_int
+        lib.orc_rsparse_linear_masked.argtypes = [
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int,
+            C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]
+        lib.orc_topk_mask.restype = C.c_int
+        lib.orc_topk_mask.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
+        lib.orc_multiphase.restype = C.c_double
+        lib.orc_multiphase.argtypes = [C.c_double, C.c_void_p, C.c_int]
+        lib.orc_multiphase_residual.restype = C.c_int
+        lib.orc_multiphase_residual.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int,
+                                                C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+        lib.orc_static_bias.restype = C.c_int
+        lib.orc_static_bias.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
+                                        C.c_void_p, C.c_int, C.c_void_p]
         lib.orc_dense_linear.restype = C.c_int
         lib.orc_dense_linear.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int,
                                          C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int]
@@ -137,9 +156,9 @@ def mask(x, x_kind, tau, cmp_mode=0) -> np.ndarray:
 
 
 def rsparse_linear(W, U, SV, X, kind_w, kind_x, tau, *, cmp_mode=0, batch_mask_mode=0,
-                   nthreads=1):
+                   nthreads=1, topk=0, bias=None):
     """Returns dict(Y [B,d_out] float64, act: list of ascending int32 arrays per token,
-    union: ascending int32 array)."""
+    union: ascending int32 array).  topk > 0: fixed-count masks instead of the threshold; bias: [d_out] added."""
     W = _arr(W, kind_w)
     d_out, d_in = W.shape
     X = _arr(X, kind_x)
@@ -160,14 +179,85 @@ def rsparse_linear(W, U, SV, X, kind_w, kind_x, tau, *, cmp_mode=0, batch_mask_m
     cnt = np.zeros(B, dtype=np.int32)
     uni = np.full(d_in, -1, dtype=np.int32)
     ucnt = np.zeros(1, dtype=np.int32)
-    rc = _load().orc_rsparse_linear(_ptr(W), _ptr(U), _ptr(SV), kind_w, _ptr(X), kind_x,
-                                    B, d_in, d_out, r, float(np.float32(tau)), cmp_mode,
-                                    batch_mask_mode, _ptr(Y), _ptr(act), _ptr(cnt), _ptr(uni),
-                                    _ptr(ucnt), nthreads)
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float64)
+        assert bias.shape == (d_out,)
+    rc = _load().orc_rsparse_linear_ex(_ptr(W), _ptr(U), _ptr(SV), kind_w, _ptr(X), kind_x,
+                                       B, d_in, d_out, r, float(np.float32(tau)), cmp_mode, int(topk),
+                                       batch_mask_mode, _ptr(bias) if bias is not None else None,
+                                       _ptr(Y), _ptr(act), _ptr(cnt), _ptr(uni), _ptr(ucnt), nthreads)
     if rc != 0:
         raise ValueError("oracle rejected its arguments")
     return {"Y": Y, "act": [act[b, :cnt[b]].copy() for b in range(B)],
             "union": uni[:ucnt[0]].copy()}
+
+
+def rsparse_linear_masked(W, U, SV, X, kind_w, kind_x, mask, *, bias=None, nthreads=1) -> np.ndarray:
+    """Steps 2-4 for given masks [B][d_in] (1 = kept)."""
+    W = _arr(W, kind_w)
+    d_out, d_in = W.shape
+    X = _arr(X, kind_x)
+    if X.ndim == 1:
+        X = X[None, :]
+    B = X.shape[0]
+    if U is None:
+        U = np.zeros((d_out, 0), dtype=W.dtype)
+        SV = np.zeros((0, d_in), dtype=W.dtype)
+    U = _arr(U, kind_w)
+    SV = _arr(SV, kind_w)
+    r = U.shape[1]
+    mask = np.ascontiguousarray(mask, dtype=np.uint8).reshape(B, d_in)
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float64)
+    Y = np.empty((B, d_out), dtype=np.float64)
+    rc = _load().orc_rsparse_linear_masked(_ptr(W), _ptr(U), _ptr(SV), kind_w, _ptr(X), kind_x, B, d_in, d_out, r,
+                                           _ptr(mask), _ptr(bias) if bias is not None else None, _ptr(Y), nthreads)
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments")
+    return Y
+
+
+def topk_mask(x, x_kind, k) -> np.ndarray:
+    """uint8 [d_in]: 1 on the k channels of largest magnitude (lower channel first among equals, NaN never)."""
+    x = _arr(x, x_kind).reshape(-1)
+    m = np.zeros(x.shape[0], dtype=np.uint8)
+    if _load().orc_topk_mask(_ptr(x), x_kind, x.shape[0], int(k), _ptr(m)) < 0:
+        raise ValueError("oracle rejected its arguments")
+    return m
+
+
+def multiphase(x, T) -> np.ndarray:
+    """sigma_T of Sec. 3.2, elementwise, float64 in and out."""
+    T = np.ascontiguousarray(T, dtype=np.float64)
+    x = np.asarray(x, dtype=np.float64)
+    lib = _load()
+    return np.array([lib.orc_multiphase(float(v), _ptr(T), len(T)) for v in x.reshape(-1)]).reshape(x.shape)
+
+
+def multiphase_residual(W, kind_w, h, kind_h, T):
+    """(Y_r [d_out], B [l-1][d_out]): the data-dependent residual of one token and its biases (Sec. 3.2)."""
+    W = _arr(W, kind_w)
+    d_out, d_in = W.shape
+    h = _arr(h, kind_h).reshape(-1)
+    T = np.ascontiguousarray(T, dtype=np.float64)
+    Yr = np.empty(d_out)
+    Bj = np.empty((max(len(T) - 1, 0), d_out))
+    if _load().orc_multiphase_residual(_ptr(W), kind_w, _ptr(h), kind_h, d_in, d_out, _ptr(T), len(T), _ptr(Yr),
+                                       _ptr(Bj) if Bj.size else None) != 0:
+        raise ValueError("oracle rejected its arguments")
+    return Yr, Bj
+
+
+def static_bias(W, kind_w, H, kind_h, T) -> np.ndarray:
+    """Mean over the calibration tokens H [N][d_in] of the data-dependent residual."""
+    W = _arr(W, kind_w)
+    d_out, d_in = W.shape
+    H = _arr(H, kind_h).reshape(-1, d_in)
+    T = np.ascontiguousarray(T, dtype=np.float64)
+    b = np.empty(d_out)
+    if _load().orc_static_bias(_ptr(W), kind_w, _ptr(H), kind_h, H.shape[0], d_in, d_out, _ptr(T), len(T), _ptr(b)) != 0:
+        raise ValueError("oracle rejected its arguments")
+    return b
 
 
 def dense_linear(W, X, kind_w, kind_x, nthreads=1) -> np.ndarray:
