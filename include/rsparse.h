@@ -65,9 +65,14 @@ typedef struct {
                                 -INFINITY keeps every channel, +INFINITY none; NaN is rejected */
     int32_t dtype;           /* of W, X and the factors: RSPARSE_F16 or RSPARSE_BF16 */
     int32_t out_dtype;       /* of Y: equal to dtype, or RSPARSE_F32 */
-    int32_t cmp_mode;        /* 0: keep |x| >= tau (the paper's definition)   1: keep |x| > tau */
+    int32_t cmp_mode;        /* 0: keep |x| >= tau (the paper's definition)   1: keep |x| > tau
+                                2: keep x >= tau, signed -- the sparse components of the multi-phase activation of
+                                Sec. 3.2 are the values at or above T_0 (see rsparse_set_bias) */
     int32_t batch_mask_mode; /* 0: every token uses its own mask (sigma_t is elementwise)
-                                1: every token uses the union of the batch's masks */
+                                1: every token uses the union of the batch's masks
+                                2: own masks up to 3 tokens, the union from 4 tokens on (there the union is ~90 % of the
+                                channels anyway, its columns are loaded either way, and using them for every token is
+                                strictly more accurate at the same bytes) */
     int32_t dense_rowmajor;  /* 1: also keep W row-major on the device (doubles the weight footprint).  Needed by
                                 the row-dot kernel of rsparse_dense_ref and by the matrix-core path that
                                 rsparse_linear takes from 5 tokens on (see mfma_min_batch); without it those
@@ -79,6 +84,12 @@ typedef struct {
                                 tuning `splits`) per strip, every wave on a fixed range of input channels; with one workgroup
                                 per strip no sums cross workgroups and Y is bit-reproducible from run to run.  Same results
                                 within the stated tolerance; see rsparse_tuning.splits.  Not with 4-bit weights. */
+    int32_t topk;            /* 0: channels are kept by the threshold tau.  k > 0: fixed-count activation -- every token keeps
+                                exactly its min(k, non-NaN channels) channels of largest magnitude (among equal magnitudes
+                                the lower channel first; NaN never), so the sparsity is exact per token instead of holding
+                                in expectation; tau is ignored, cmp_mode must be 0.  One small extra launch per call finds
+                                each token's k-th magnitude.  Vector path only (batches above 8 run in tiles of 8); not with
+                                4-bit weights.  k <= d_in. */
 } rsparse_config;
 
 /* Launch-shape overrides for measurements; 0 = library default. */
@@ -249,6 +260,28 @@ rsparse_status rsparse_synchronize(rsparse_layer *layer);
 
 /* Stored 16-bit factors, host buffers U16 [d_out][rank] and SV16 [rank][d_in] (either may be NULL). */
 rsparse_status rsparse_get_factors(const rsparse_layer *layer, void *U16_host, void *SV16_host);
+
+/*
+ * Static output bias (R-Sparse, Sec. 3.2: the part of the input below the sparse components can be approximated by a
+ * few biases, which can be made static and pre-computed).  bias_host: [d_out] fp32 on the host, copied to the device
+ * (owned by the handle), or NULL to remove it.  From then on rsparse_linear and its variants compute
+ * Y = round(Y_s + Y_r + bias); rsparse_dense_ref does not add it.  Works with any rank (rank = 0 with cmp_mode = 2 is the
+ * pure multi-phase form of Sec. 3.2).  Synchronises the device.  Errors: RSPARSE_EINVAL (NULL layer), RSPARSE_EHIP.
+ */
+rsparse_status rsparse_set_bias(rsparse_layer *layer, const float *bias_host);
+
+/*
+ * The static bias of the multi-phase activation of Sec. 3.2, host code (prepare time).  T[0] > T[1] > ... > T[l-1] are the
+ * thresholds; a value h >= T[0] is a sparse component (kept as it is), a value in [T[i+1], T[i]) becomes the midpoint
+ * (T[i] + T[i+1]) / 2 (values below T[l-1] count into the last interval; l = 1: everything below T[0] becomes 0).  For one
+ * token the residual output is  sum_i midpoint_i * sum_{k in U_i} W[:, k]  with U_i the channels in interval i; the
+ * static bias is its mean over the n_tokens calibration tokens H_host [n_tokens][d_in] (16-bit of `dtype`, host):
+ *   bias[o] = sum_k W[o][k] * mean_tokens( midpoint of h_k's interval, or 0 if h_k >= T[0] ),  accumulated in fp64.
+ * W_host [d_out][d_in] row-major 16-bit of `dtype`.  bias_out: [d_out] fp32, host, caller-owned.
+ * Errors: RSPARSE_EINVAL (NULL pointers, sizes < 1, T not strictly decreasing or not finite).
+ */
+rsparse_status rsparse_multiphase_bias(const void *W_host, int32_t dtype, int32_t d_in, int32_t d_out, const void *H_host,
+                                       int32_t n_tokens, const float *T, int32_t l, float *bias_out);
 
 /* Threshold and launch-shape changes apply to calls made afterwards; a call already captured into a HIP
  * graph replays with the threshold, tuning and pointers it was captured with. */

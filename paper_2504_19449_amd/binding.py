@@ -14,7 +14,7 @@ _STATUS = {1: "EINVAL", 2: "ENOMEM", 3: "EHIP", 4: "EBATCH", 5: "EALIGN", 6: "ES
 EXPORTED_SYMBOLS = [
     "rsparse_prepare", "rsparse_compute_factors", "rsparse_prepare_factors", "rsparse_prepare_q4", "rsparse_linear", "rsparse_linear_static",
     "rsparse_linear_gated", "rsparse_gated_input", "rsparse_mlp_gate_up", "rsparse_dense_ref", "rsparse_linear_group", "rsparse_dense_ref_group", "rsparse_last_active", "rsparse_synchronize",
-    "rsparse_get_factors", "rsparse_set_tau", "rsparse_set_tuning",
+    "rsparse_get_factors", "rsparse_set_tau", "rsparse_set_bias", "rsparse_multiphase_bias", "rsparse_set_tuning",
     "rsparse_get_config", "rsparse_calibrate_tau", "rsparse_required_bytes", "rsparse_dense_bytes", "rsparse_io_model",
     "rsparse_recipe", "rsparse_plan_layer", "rsparse_search_recipe", "rsparse_debug_stamps", "rsparse_destroy", "rsparse_last_error",
 ]
@@ -23,7 +23,7 @@ EXPORTED_SYMBOLS = [
 class Config(C.Structure):
     _fields_ = [("d_in", C.c_int32), ("d_out", C.c_int32), ("rank", C.c_int32), ("max_batch", C.c_int32),
                 ("tau", C.c_float), ("dtype", C.c_int32), ("out_dtype", C.c_int32), ("cmp_mode", C.c_int32),
-                ("batch_mask_mode", C.c_int32), ("dense_rowmajor", C.c_int32), ("strip_cols", C.c_int32)]
+                ("batch_mask_mode", C.c_int32), ("dense_rowmajor", C.c_int32), ("strip_cols", C.c_int32), ("topk", C.c_int32)]
 
 
 class Tuning(C.Structure):
@@ -87,6 +87,10 @@ def load_library():
     lib.rsparse_synchronize.argtypes = [vp]
     lib.rsparse_get_factors.argtypes = [vp, vp, vp]
     lib.rsparse_set_tau.argtypes = [vp, C.c_float]
+    lib.rsparse_set_bias.argtypes = [vp, vp]
+    lib.rsparse_set_bias.restype = C.c_int
+    lib.rsparse_multiphase_bias.argtypes = [vp, i32, i32, i32, vp, i32, vp, i32, vp]
+    lib.rsparse_multiphase_bias.restype = C.c_int
     lib.rsparse_set_tuning.argtypes = [vp, C.POINTER(Tuning)]
     lib.rsparse_get_config.argtypes = [vp, C.POINTER(Config)]
     lib.rsparse_calibrate_tau.argtypes = [vp, i32, C.c_size_t, C.c_double, C.POINTER(C.c_float)]
@@ -113,7 +117,7 @@ def load_library():
     lib.rsparse_last_error.restype = C.c_char_p
     for name in ("rsparse_linear_group", "rsparse_dense_ref_group", "rsparse_prepare", "rsparse_compute_factors",
                  "rsparse_prepare_factors", "rsparse_linear", "rsparse_dense_ref",
-                 "rsparse_last_active", "rsparse_get_factors", "rsparse_set_tau", "rsparse_set_tuning",
+                 "rsparse_last_active", "rsparse_get_factors", "rsparse_set_tau", "rsparse_set_bias", "rsparse_multiphase_bias", "rsparse_set_tuning",
                  "rsparse_get_config", "rsparse_calibrate_tau", "rsparse_synchronize", "rsparse_linear_gated", "rsparse_gated_input", "rsparse_mlp_gate_up", "rsparse_prepare_q4"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
@@ -158,9 +162,9 @@ class Layer:
 
 
 def _make_config(d_in, d_out, rank, tau, dtype, max_batch=1, out_dtype=None, cmp_mode=0,
-                 batch_mask_mode=0, dense_rowmajor=0, strip_cols=0) -> Config:
+                 batch_mask_mode=0, dense_rowmajor=0, strip_cols=0, topk=0) -> Config:
     return Config(d_in, d_out, rank, max_batch, float(tau), dtype, dtype if out_dtype is None else out_dtype,
-                  cmp_mode, batch_mask_mode, dense_rowmajor, strip_cols)
+                  cmp_mode, batch_mask_mode, dense_rowmajor, strip_cols, topk)
 
 
 def rsparse_prepare(cfg: Config, W16) -> Layer:
@@ -288,6 +292,30 @@ def rsparse_get_factors(layer: Layer):
 def rsparse_set_tau(layer: Layer, tau: float):
     _check(load_library().rsparse_set_tau(layer.handle, float(tau)))
     layer.cfg.tau = float(tau)
+
+
+def rsparse_set_bias(layer: Layer, bias):
+    """bias: float32 [d_out] on the host, or None to remove it."""
+    if bias is None:
+        _check(load_library().rsparse_set_bias(layer.handle, None))
+        return
+    b = np.ascontiguousarray(bias, dtype=np.float32)
+    if b.shape != (layer.cfg.d_out,):
+        raise ValueError("bias must be [d_out]")
+    _check(load_library().rsparse_set_bias(layer.handle, _hp(b)))
+
+
+def rsparse_multiphase_bias(W16, dtype: int, H16, T) -> np.ndarray:
+    """Static bias of the multi-phase activation (Sec. 3.2) from calibration tokens H16 [n][d_in]; float32 [d_out]."""
+    W16 = _host16(W16, "W")
+    H16 = _host16(H16, "H")
+    d_out, d_in = W16.shape
+    if H16.ndim != 2 or H16.shape[1] != d_in:
+        raise ValueError("H must be [n_tokens, d_in]")
+    T = np.ascontiguousarray(T, dtype=np.float32)
+    out = np.empty(d_out, dtype=np.float32)
+    _check(load_library().rsparse_multiphase_bias(_hp(W16), dtype, d_in, d_out, _hp(H16), H16.shape[0], _hp(T), len(T), _hp(out)))
+    return out
 
 
 def rsparse_set_tuning(layer: Layer, **kw):

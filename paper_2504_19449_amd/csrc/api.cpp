@@ -145,6 +145,8 @@ struct rsparse_layer {
     uint32_t *t_pub = nullptr;
     ScratchView last_scratch{};            // the per-call scratch the last call used: the handle's own, or the static one
     uint16_t *hy = nullptr;                // [max_batch][d_out] 16-bit output scratch (gate / up results of rsparse_mlp_gate_up's fallback)
+    float *bias = nullptr;                 // [d_out] fp32 static bias (rsparse_set_bias), or null
+    KeepRule *rules = nullptr;             // [max_batch] per-token rules of the fixed-count activation (cfg.topk > 0)
     uint16_t *xg = nullptr;                // [max_batch][d_in] gated input x = round16(silu(g) * u), written out per call
     size_t n_t = 0, n_y = 0, sync_n = 0;
     bool last_fused = false;
@@ -163,12 +165,14 @@ struct rsparse_layer {
     {
         ScratchView sp{};
         sp.t = t; sp.yacc = yacc; sp.act_list = act_list; sp.act_bits = act_bits; sp.act_count = act_count;
-        sp.act_seg = act_seg; sp.sync = sync; sp.t_pub = t_pub; sp.t_tag = t_tag; sp.t_slots = t_slots;
+        sp.act_seg = act_seg; sp.sync = sync; sp.t_pub = t_pub; sp.t_tag = t_tag; sp.t_slots = t_slots; sp.rules = rules;
         sp.n_t = n_t; sp.n_y = n_y; sp.sync_n = sync_n;
         return sp;
     }
 
-    LayerView view(const ScratchView *ov = nullptr) const
+    // The view of one call: `batch` decides the mask mode when the configuration leaves it to the library; the dense
+    // baseline gets no bias and no fixed-count rules.
+    LayerView view(const ScratchView *ov = nullptr, int batch = 1, bool dense = false) const
     {
         const ScratchView sp = ov ? *ov : own_scratch();
         LayerView v{};
@@ -176,7 +180,15 @@ struct rsparse_layer {
         v.act_list = sp.act_list; v.act_bits = sp.act_bits; v.act_count = sp.act_count; v.sync = sp.sync; v.t_pub = sp.t_pub;
         v.d_in = cfg.d_in; v.d_out = cfg.d_out; v.rank = cfg.rank;
         v.dtype = cfg.dtype; v.out_dtype = cfg.out_dtype; v.cmp_mode = cfg.cmp_mode;
-        v.batch_mask_mode = cfg.batch_mask_mode; v.tau = cfg.tau;
+        v.batch_mask_mode = cfg.batch_mask_mode == 2 ? (batch >= 4 ? 1 : 0) : cfg.batch_mask_mode;
+        v.tau = cfg.tau;
+        // |x| > tau is |x| >= the next fp32 above tau; nothing is above +inf (a NaN bound keeps nothing)
+        v.tau_ge = cfg.tau;
+        if (cfg.cmp_mode == 1)
+            v.tau_ge = cfg.tau == INFINITY ? NAN : std::nextafterf(cfg.tau, INFINITY);
+        v.keep_signed = cfg.cmp_mode == 2 ? 1 : 0;
+        v.rules = (cfg.topk > 0 && !dense) ? sp.rules : nullptr;
+        v.bias = dense ? nullptr : bias;
         v.Mq = Mq; v.qs = qs; v.qz = qz; v.Ut = Ut; v.qshift = qshift; v.qtiles = qtiles;
         v.Ms = Ms; v.strip_w = strip_w; v.strip_stride = strip_stride; v.t_tag = sp.t_tag; v.t_slots = sp.t_slots; v.act_seg = sp.act_seg;
         return v;
@@ -202,8 +214,10 @@ rsparse_status check_config(const rsparse_config *c)
     if (c->dtype != RSPARSE_F16 && c->dtype != RSPARSE_BF16) return fail(RSPARSE_EINVAL, "dtype must be F16 or BF16");
     if (c->out_dtype != c->dtype && c->out_dtype != RSPARSE_F32)
         return fail(RSPARSE_EINVAL, "out_dtype must equal dtype or be F32");
-    if (c->cmp_mode != 0 && c->cmp_mode != 1) return fail(RSPARSE_EINVAL, "cmp_mode must be 0 or 1");
-    if (c->batch_mask_mode != 0 && c->batch_mask_mode != 1) return fail(RSPARSE_EINVAL, "batch_mask_mode must be 0 or 1");
+    if (c->cmp_mode < 0 || c->cmp_mode > 2) return fail(RSPARSE_EINVAL, "cmp_mode must be 0, 1 or 2");
+    if (c->batch_mask_mode < 0 || c->batch_mask_mode > 2) return fail(RSPARSE_EINVAL, "batch_mask_mode must be 0, 1 or 2");
+    if (c->topk < 0 || c->topk > c->d_in) return fail(RSPARSE_EINVAL, "topk %d outside [0, d_in]", c->topk);
+    if (c->topk > 0 && c->cmp_mode != 0) return fail(RSPARSE_EINVAL, "the fixed-count activation (topk > 0) needs cmp_mode 0");
     if (c->dense_rowmajor != 0 && c->dense_rowmajor != 1) return fail(RSPARSE_EINVAL, "dense_rowmajor must be 0 or 1");
     if (c->strip_cols != 0 && !strip_width_ok(c->strip_cols)) return fail(RSPARSE_EINVAL, "strip_cols must be 0, 32, 64, 128, 256 or 512");
     return RSPARSE_OK;
@@ -321,7 +335,7 @@ void free_layer(rsparse_layer *L)
     (void)hipFree(L->M); (void)hipFree(L->SVt); (void)hipFree(L->U); (void)hipFree(L->Wrow); (void)hipFree(L->t);
     (void)hipFree(L->yacc); (void)hipFree(L->act_bits); (void)hipFree(L->chan_bits);
     (void)hipFree(L->act_list); (void)hipFree(L->act_count); (void)hipFree(L->sync); (void)hipFree(L->t_pub); (void)hipFree(L->xg); (void)hipFree(L->hy);
-    (void)hipFree(L->Ms); (void)hipFree(L->t_tag); (void)hipFree(L->act_seg);
+    (void)hipFree(L->Ms); (void)hipFree(L->t_tag); (void)hipFree(L->act_seg); (void)hipFree(L->bias); (void)hipFree(L->rules);
     (void)hipFree(L->Mq); (void)hipFree(L->qs); (void)hipFree(L->qz); (void)hipFree(L->Ut);
     delete L;
 }
@@ -449,6 +463,8 @@ rsparse_status build_layer(const rsparse_config *cfg, const uint16_t *W, const u
         RS_HIP(hipMalloc((void **)&L->act_bits, n_list * 4));
         RS_HIP(hipMalloc((void **)&L->act_count, (size_t)L->nz_max * 4));
         RS_HIP(hipMalloc((void **)&L->chan_bits, d_in * 4));
+        RS_HIP(hipMalloc((void **)&L->rules, (size_t)cfg->max_batch * sizeof(KeepRule)));
+        RS_HIP(hipMemset(L->rules, 0, (size_t)cfg->max_batch * sizeof(KeepRule)));
         L->sync_n = sync_words(std::max(L->tiles, L->strips));
         RS_HIP(hipMalloc((void **)&L->sync, L->sync_n * 4));
         RS_HIP(hipMemset(L->sync, 0, L->sync_n * 4));
@@ -564,6 +580,7 @@ rsparse_status rsparse_prepare_q4(const rsparse_config *cfg, const uint8_t *Q_ho
         return fail(RSPARSE_EINVAL, "group_size must be a power of two in [32, 1024] that divides d_in (got %d)", group_size);
     if (cfg->dense_rowmajor) return fail(RSPARSE_EINVAL, "dense_rowmajor is not available with 4-bit weights");
     if (cfg->strip_cols) return fail(RSPARSE_EINVAL, "strip_cols is not available with 4-bit weights");
+    if (cfg->topk) return fail(RSPARSE_EINVAL, "the fixed-count activation (topk > 0) is not available with 4-bit weights");
     const size_t n = (size_t)cfg->d_in * cfg->d_out, ng = n / group_size;
     for (size_t i = 0; i < n; ++i)
         if (Q_host[i] > 15) return fail(RSPARSE_EINVAL, "code %u at %zu is not a 4-bit value", (unsigned)Q_host[i], i);
@@ -618,7 +635,7 @@ Launch resolve_launch_q4(const rsparse_layer *L, int batch, bool dense, bool fus
 // One layer with 4-bit weights: first launch (codes dequantised in registers), then the common finish.
 rsparse_status linear_q4(rsparse_layer *L, const void *X_dev, int32_t batch, void *Y_dev, bool dense, hipStream_t s)
 {
-    const LayerView v = L->view();
+    const LayerView v = L->view(nullptr, batch, dense);
     const int stages = L->tuning.stages;
     // two launches by default: the one-launch form (launches = 1) measured no faster on these weights --
     // its tail waits for up to `splits` same-address atomics that the two-launch form never waits for
@@ -717,17 +734,22 @@ rsparse_status linear_group_impl(rsparse_layer *const *layers, int32_t n_layers,
     // one launch unless asked otherwise (timing a stage alone needs the two-launch form)
     const bool fused = layers[0]->tuning.launches != 2 && stages == 0;
     for (int i = 0; i < n_layers; ++i) {
-        v[i] = layers[i]->view(ov);
+        v[i] = layers[i]->view(ov, batch);
         lc[i] = resolve_launch(layers[i], batch, false, n_layers, i ? lc[0].waves : 0, fused);
         layers[i]->last_scratch = ov ? *ov : layers[i]->own_scratch();
     }
     bool mfma = !ov && batch >= (layers[0]->tuning.mfma_min_batch > 0 ? layers[0]->tuning.mfma_min_batch : kMfmaDefaultMinBatch);
-    for (int i = 0; i < n_layers; ++i) mfma = mfma && mfma_path_supported(v[i], batch);
+    for (int i = 0; i < n_layers; ++i) mfma = mfma && mfma_path_supported(v[i], batch) && layers[i]->cfg.topk == 0;
     // a gated input is written out once first (one small launch), then the layer runs on it
     if (G_dev) {
         RS_HIP(launch_gated_input(G_dev, X_dev, layers[0]->xg, (size_t)batch * layers[0]->cfg.d_in, layers[0]->cfg.dtype, s));
         X_dev = layers[0]->xg;
     }
+    // fixed-count activation: each token's rule (its k-th magnitude and tie cut) first, one small launch per layer
+    for (int i = 0; i < n_layers; ++i)
+        if (layers[i]->cfg.topk > 0 && v[i].rules)
+            RS_HIP(launch_topk_rules(X_dev, layers[i]->cfg.dtype, batch, layers[i]->cfg.d_in, layers[i]->cfg.topk,
+                                     const_cast<KeepRule *>(v[i].rules), s));
     // layers packed in strips go through the strip kernel; a group must share one layout (and one strip width),
     // otherwise its layers run one at a time
     if (!mfma && n_layers > 1) {
@@ -800,16 +822,20 @@ rsparse_status rsparse_mlp_gate_up(rsparse_layer *gate, rsparse_layer *up, const
     LayerView v[2];
     Launch lc[2];
     for (int i = 0; i < 2; ++i) {
-        v[i] = pair[i]->view();
+        v[i] = pair[i]->view(nullptr, batch);
         lc[i] = resolve_launch(pair[i], batch, false, 2, i ? lc[0].waves : 0, fused);
     }
     bool mfma = batch >= (gate->tuning.mfma_min_batch > 0 ? gate->tuning.mfma_min_batch : kMfmaDefaultMinBatch);
-    for (int i = 0; i < 2; ++i) mfma = mfma && mfma_path_supported(v[i], batch);
+    for (int i = 0; i < 2; ++i) mfma = mfma && mfma_path_supported(v[i], batch) && pair[i]->cfg.topk == 0;
     const int bt = batch_tile_of(batch);
     const bool one_tile = (batch + bt - 1) / bt == 1;
     if (fused && !mfma && one_tile && lc[0].tile_map != 2 && lc[1].tile_map != 2 && gate->M && up->M) {
         // both projections and the activation in one launch: the last workgroup of a column tile
         // rounds g and u, applies silu(g) * u and stores H
+        for (int i = 0; i < 2; ++i)
+            if (pair[i]->cfg.topk > 0)
+                RS_HIP(launch_topk_rules(X_dev, pair[i]->cfg.dtype, batch, pair[i]->cfg.d_in, pair[i]->cfg.topk,
+                                         const_cast<KeepRule *>(v[i].rules), s));
         RS_HIP(launch_fused(v, lc, 2, X_dev, batch, outs, s, true));
         for (int i = 0; i < 2; ++i) {
             pair[i]->last_stream = s; pair[i]->last_batch = batch; pair[i]->last_mfma = false; pair[i]->last_fused = true; pair[i]->last_bt = 0; pair[i]->last_strip = false;
@@ -868,7 +894,7 @@ rsparse_status rsparse_dense_ref_group(rsparse_layer *const *layers, int32_t n_l
     Launch lc[RSPARSE_MAX_GROUP];
     bool can_rowdot = true;
     for (int i = 0; i < n_layers; ++i) {
-        v[i] = layers[i]->view();
+        v[i] = layers[i]->view(nullptr, batch, true);
         lc[i] = resolve_launch(layers[i], batch, true, n_layers, i ? lc[0].waves : 0);
         can_rowdot = can_rowdot && layers[i]->Wrow != nullptr && rowdot_supported(layers[i]->cfg.d_in, batch);
     }
@@ -1034,6 +1060,52 @@ rsparse_status rsparse_set_tau(rsparse_layer *L, float tau)
     if (!L) return fail(RSPARSE_EINVAL, "layer is NULL");
     if (std::isnan(tau)) return fail(RSPARSE_EINVAL, "tau is NaN");
     L->cfg.tau = tau;
+    return RSPARSE_OK;
+}
+
+rsparse_status rsparse_set_bias(rsparse_layer *L, const float *bias_host)
+{
+    if (!L) return fail(RSPARSE_EINVAL, "layer is NULL");
+    RS_HIP(hipSetDevice(L->device));
+    RS_HIP(hipDeviceSynchronize());                 // no call may still be reading the old bias
+    if (!bias_host) {
+        (void)hipFree(L->bias);
+        L->bias = nullptr;
+        return RSPARSE_OK;
+    }
+    if (!L->bias) RS_HIP(hipMalloc((void **)&L->bias, (size_t)L->cfg.d_out * 4));
+    RS_HIP(hipMemcpy(L->bias, bias_host, (size_t)L->cfg.d_out * 4, hipMemcpyHostToDevice));
+    return RSPARSE_OK;
+}
+
+rsparse_status rsparse_multiphase_bias(const void *W_host, int32_t dtype, int32_t d_in, int32_t d_out, const void *H_host,
+                                       int32_t n_tokens, const float *T, int32_t l, float *bias_out)
+{
+    if (!W_host || !H_host || !T || !bias_out) return fail(RSPARSE_EINVAL, "NULL argument");
+    if (d_in < 1 || d_out < 1 || n_tokens < 1 || l < 1) return fail(RSPARSE_EINVAL, "sizes must be positive");
+    if (dtype != RSPARSE_F16 && dtype != RSPARSE_BF16) return fail(RSPARSE_EINVAL, "dtype must be F16 or BF16");
+    for (int i = 0; i < l; ++i) {
+        if (!std::isfinite(T[i])) return fail(RSPARSE_EINVAL, "T[%d] is not finite", i);
+        if (i > 0 && !(T[i - 1] > T[i])) return fail(RSPARSE_EINVAL, "T must be strictly decreasing");
+    }
+    const uint16_t *W = (const uint16_t *)W_host, *H = (const uint16_t *)H_host;
+    // m[k] = mean over the tokens of the value the multi-phase activation puts in place of h_k when h_k < T[0]
+    std::vector<double> m((size_t)d_in, 0.0);
+    for (int n = 0; n < n_tokens; ++n)
+        for (int k = 0; k < d_in; ++k) {
+            const double h = (double)widen16(H[(size_t)n * d_in + k], dtype);
+            if (!(h < (double)T[0]) || l < 2) continue;          // sparse component, NaN, or nothing below T[0] is kept
+            int i = l - 2;                                       // below T[l-1]: the last interval
+            for (int j = 0; j + 1 < l; ++j)
+                if (h >= (double)T[j + 1]) { i = j; break; }
+            m[(size_t)k] += 0.5 * ((double)T[i] + (double)T[i + 1]);
+        }
+    for (int k = 0; k < d_in; ++k) m[(size_t)k] /= (double)n_tokens;
+    parallel_for((size_t)d_out, [&](size_t o) {
+        double acc = 0.0;
+        for (int k = 0; k < d_in; ++k) acc += (double)widen16(W[o * (size_t)d_in + k], dtype) * m[(size_t)k];
+        bias_out[o] = (float)acc;
+    });
     return RSPARSE_OK;
 }
 

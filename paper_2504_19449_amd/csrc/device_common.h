@@ -112,13 +112,38 @@ __device__ __forceinline__ u32x4 load_x8(const uint16_t *X, const uint16_t *G, s
     }
     return o;
 }
-// Keep-predicate of the sparsification function: |x| >= t (mode 0) or |x| > t (mode 1).
-// NaN compares false and is never kept.
-__device__ __forceinline__ bool keep(float x, float tau, int mode)
+// Exact widening of one stored 16-bit value.
+template <int DT>
+__device__ __forceinline__ float widen16(uint16_t h)
 {
-    float a = __builtin_fabsf(x);
-    return mode == 0 ? (a >= tau) : (a > tau);
+    return DT == F16 ? (float)__builtin_bit_cast(_Float16, h) : as_f((uint32_t)h << 16);
 }
+
+// Keep-predicate of the sparsification function (see KeepRule).  NaN compares false and is never kept.
+__device__ __forceinline__ bool keep(float x, int c, const KeepRule &r, bool sgn)
+{
+    const float v = sgn ? x : __builtin_fabsf(x);
+    return (v >= r.ge) | ((v == r.eq) & (c <= r.cut));
+}
+// The same for rules known to be a plain threshold on the magnitude (no `eq` part, not signed).
+__device__ __forceinline__ bool keep_threshold(float x, const KeepRule &r) { return __builtin_fabsf(x) >= r.ge; }
+// The rule of token b of the call: the layer's threshold, or the token's own fixed-count rule.
+__device__ __forceinline__ KeepRule rule_of(const LayerView &L, int b)
+{
+    KeepRule r;
+    if (L.rules) {
+        r.ge = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, L.rules[b].ge)));
+        r.eq = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, L.rules[b].eq)));
+        r.cut = __builtin_amdgcn_readfirstlane(L.rules[b].cut);
+    } else {
+        r.ge = L.tau_ge;
+        r.eq = __builtin_nanf("");
+        r.cut = -1;
+    }
+    r.pad = 0;
+    return r;
+}
+__device__ __forceinline__ float bias_at(const LayerView &L, int o) { return L.bias ? L.bias[o] : 0.f; }
 
 template <bool NT>
 __device__ __forceinline__ u32x4 ldg16(const uint16_t *p)

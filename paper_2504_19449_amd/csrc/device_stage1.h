@@ -63,33 +63,78 @@ __device__ __forceinline__ void load_raw8(const uint16_t *X, int b0, int nb, int
         raw[b] = b < nb ? *reinterpret_cast<const u32x4 *>(X + (size_t)(b0 + b) * d_in + c) : u32x4{0, 0, 0, 0};
 }
 
+// The rules of the tokens of one batch tile (wave-uniform).
+template <int BT>
+struct TileRules {
+    KeepRule r[BT];
+    bool sgn;
+    bool exact;          // false: plain thresholds on the magnitude (keep_threshold applies); true: the general form
+    bool per_token;      // the rules differ from token to token (fixed-count activation)
+};
+// EXT = false: the launch is known (on the host) to use nothing but a plain threshold on the magnitude; the
+// general forms then drop out at compile time.
+template <int BT, bool EXT = true>
+__device__ __forceinline__ void load_rules(const LayerView &L, int b0, int nb, TileRules<BT> &t)
+{
+    if (EXT) {
+        t.sgn = L.keep_signed != 0;
+        t.per_token = L.rules != nullptr;
+        t.exact = t.per_token || t.sgn;
+#pragma unroll
+        for (int b = 0; b < BT; ++b) t.r[b] = rule_of(L, b0 + (b < nb ? b : 0));
+    } else {
+        t.sgn = t.per_token = t.exact = false;
+#pragma unroll
+        for (int b = 0; b < BT; ++b) t.r[b] = KeepRule{L.tau_ge, __builtin_nanf(""), -1, 0};
+    }
+}
+
 // Per-token keep masks (bit e = channel c+e kept) of loaded channels.  With union_all
 // (batch_mask_mode 1) every token's mask becomes the union over the WHOLE batch.  Returns the union
 // over the tile's tokens.
 template <int DT, int BT>
-__device__ __forceinline__ uint32_t masks_of8(const uint16_t *X, int batch, int b0, int nb, int d_in, int c, float tau,
-                                              int mode, bool union_all, const u32x4 (&raw)[BT], uint32_t (&m)[BT])
+__device__ __forceinline__ uint32_t masks_of8(const LayerView &L, const uint16_t *X, int batch, int b0, int nb, int d_in, int c,
+                                              const TileRules<BT> &rules, bool union_all, const u32x4 (&raw)[BT],
+                                              uint32_t (&m)[BT])
 {
     uint32_t u = 0;
+    // the threshold form is the common one and sits on every workgroup's path to its first weight load (this code runs
+    // once per launch, from a cold instruction cache): it keeps its own short loop; the fixed-count form is out of line
+    if (__builtin_expect(!rules.exact, 1)) {
 #pragma unroll
-    for (int b = 0; b < BT; ++b) {
-        m[b] = 0;
-        if (b < nb) {
-            float xv[8];
-            unpack8<DT>(raw[b], xv);
+        for (int b = 0; b < BT; ++b) {
+            m[b] = 0;
+            if (b < nb) {
+                float xv[8];
+                unpack8<DT>(raw[b], xv);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) m[b] |= (uint32_t)keep(xv[e], tau, mode) << e;
+                for (int e = 0; e < 8; ++e) m[b] |= (uint32_t)keep_threshold(xv[e], rules.r[b]) << e;
+            }
+            u |= m[b];
         }
-        u |= m[b];
+    } else {
+#pragma unroll
+        for (int b = 0; b < BT; ++b) {
+            m[b] = 0;
+            if (b < nb) {
+                float xv[8];
+                unpack8<DT>(raw[b], xv);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) m[b] |= (uint32_t)keep(xv[e], c + e, rules.r[b], rules.sgn) << e;
+            }
+            u |= m[b];
+        }
     }
     if (union_all) {
         for (int bb = 0; bb < batch; ++bb) {
             if (bb >= b0 && bb < b0 + nb) continue;
+            const KeepRule rr = rules.per_token ? rule_of(L, bb) : rules.r[0];
             u32x4 r2 = *reinterpret_cast<const u32x4 *>(X + (size_t)bb * d_in + c);
             float f[8];
             unpack8<DT>(r2, f);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) u |= (uint32_t)keep(f[e], tau, mode) << e;
+            for (int e = 0; e < 8; ++e)
+                u |= (uint32_t)(rules.exact ? keep(f[e], c + e, rr, rules.sgn) : keep_threshold(f[e], rr)) << e;
         }
 #pragma unroll
         for (int b = 0; b < BT; ++b) m[b] = (b < nb) ? u : 0u;
@@ -196,7 +241,7 @@ __device__ __forceinline__ void close_generation(int *sync, int readers)
 // ---------------------------------------------------------------------------------------------
 constexpr int kRowsPerWave = 4;
 
-template <int DT, int BT, int PUB, typename Args>
+template <int DT, int BT, int PUB, typename Args, bool EXT = true>
 __device__ __forceinline__ void lowrank_rows(const Args &a, unsigned char *smem, int wg, int z)
 {
     constexpr int LU = 8;
@@ -206,6 +251,8 @@ __device__ __forceinline__ void lowrank_rows(const Args &a, unsigned char *smem,
     const int b0 = z * BT;
     const int nb = min(BT, a.batch - b0);
     const bool union_all = L.batch_mask_mode == 1;
+    TileRules<BT> rules;
+    load_rules<BT, EXT>(L, b0, nb, rules);
     uint16_t *s_xm = reinterpret_cast<uint16_t *>(smem);                           // [BT][chunk]
     const int row_lo = wg * a.lr_rows, row_hi = min(r, row_lo + a.lr_rows);
 
@@ -230,7 +277,7 @@ __device__ __forceinline__ void lowrank_rows(const Args &a, unsigned char *smem,
                 const int q = q0 + p * nthr;
                 if (q < nq) {
                     uint32_t m[BT];
-                    masks_of8<DT, BT>(a.X, a.batch, b0, nb, d_in, c0 + q * 8, L.tau, L.cmp_mode, union_all, raw[p], m);
+                    masks_of8<DT, BT>(L, a.X, a.batch, b0, nb, d_in, c0 + q * 8, rules, union_all, raw[p], m);
 #pragma unroll
                     for (int b = 0; b < BT; ++b) {
                         u32x4 o = raw[p][b];

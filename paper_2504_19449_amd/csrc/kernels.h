@@ -14,6 +14,16 @@ constexpr int kMaxBT = 8;        // tokens held in registers per workgroup (batc
 constexpr int kMfmaDefaultMinBatch = 5;
 constexpr int kMfmaDefaultMinBatchDense = 2;
 
+// Which channels of a token are kept (R-Sparse, Sec. 3.4: the sparsification function, and its fixed-count variant),
+// in one form:  v >= ge  ||  (v == eq && channel <= cut),  with v = |x| (v = x for the signed threshold).
+//   |x| >= t:   ge = t, eq = NaN (never equal).        |x| > t:  ge = the next fp32 above t.
+//   fixed count k:  eq = the k-th largest magnitude of the token, ge = the next fp32 above it, cut = the last channel
+//   among those equal to it that still belongs to the k (lower channels first).
+struct KeepRule {
+    float ge, eq;
+    int cut, pad;
+};
+
 // Device-side view of one prepared layer plus its per-call scratch.
 struct LayerView {
     const uint16_t *M;      // [d_in + rank][d_out]: W column-major (row c = W[:, c]), then U_r^T (row d_in + j = U_r[:, j])
@@ -47,7 +57,15 @@ struct LayerView {
     int d_in, d_out, rank;
     int dtype, out_dtype, cmp_mode, batch_mask_mode;
     float tau;
+    float tau_ge;           // the threshold as a KeepRule::ge (host-computed from tau and cmp_mode)
+    int keep_signed;        // cmp_mode 2: the rule applies to x itself, not to |x|
+    const KeepRule *rules;  // fixed-count activation: [batch] per-token rules written by launch_topk_rules; else nullptr
+    const float *bias;      // [d_out] fp32 added to every token's output before the rounding, or nullptr
 };
+
+// Fixed-count activation: per token of X [batch][d_in] the KeepRule that keeps exactly min(k, non-NaN channels)
+// channels of largest magnitude (ties: lower channel first).  One workgroup per token.
+hipError_t launch_topk_rules(const void *X, int dtype, int batch, int d_in, int k, KeepRule *rules, hipStream_t stream);
 
 // Per-call scratch of a layer: what the kernels write besides Y.  Normally owned by the handle (allocated when the
 // layer is prepared); rsparse_linear_static points it into a file-scope device array instead.
@@ -59,6 +77,7 @@ struct ScratchView {
     int *sync;
     uint32_t *t_pub;
     unsigned long long *t_tag;
+    KeepRule *rules;
     int t_slots;
     size_t n_t, n_y, sync_n;       // 32-bit words of t / t_pub (and 64-bit words of t_tag), of yacc, of sync
 };

@@ -387,7 +387,7 @@ __device__ __forceinline__ void q4_consume(Q4State<BT> &st, const LayerView &L, 
 // The two groups are independent, so they share one launch.
 // grid.x = lr_wgs + tiles * splits, grid.z = batch tiles of BT tokens, block = 64 * waves.
 // ---------------------------------------------------------------------------------------------
-template <int DT, int BT, bool NT, bool FUSED, bool Q4 = false>
+template <int DT, int BT, bool NT, bool FUSED, bool Q4 = false, bool EXT = true>
 __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *smem)
 {
     const int z = blockIdx.z;
@@ -398,11 +398,9 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
     const int lr_wgs = pin(a.lr_wgs), tile_map = pin(a.tile_map), n_tiles = pin(a.tiles), n_splits = pin(a.splits);
     const uint16_t *const X = pin(a.X);
     const int d_in = pin(L.d_in), d_out = pin(L.d_out), batch = pin(a.batch), cap = pin(a.cap);
-    const float tau = pin(L.tau);
-    const int cmp_mode = pin(L.cmp_mode);
     const bool union_all = pin(L.batch_mask_mode) == 1;
     if (__builtin_expect(wg < lr_wgs, 0)) {
-        lowrank_rows<DT, BT, FUSED ? kPubNotReady : kPubPlain>(a, smem, wg, z);
+        lowrank_rows<DT, BT, FUSED ? kPubNotReady : kPubPlain, GatherArgs, EXT>(a, smem, wg, z);
         return;
     }
     const int tid = threadIdx.x, nthr = blockDim.x, lane = tid & 63, w = tid >> 6, nw = nthr >> 6;
@@ -410,6 +408,8 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
     if (!map_tile(tile_map, n_tiles, n_splits, wg - lr_wgs, tile, split)) return;
     const int b0 = z * BT;
     const int nb = min(BT, batch - b0);
+    TileRules<BT> rules;
+    load_rules<BT, EXT>(L, b0, nb, rules);
     const GatherLds s = carve(smem, cap, BT, nw);
     const int col = tile * kTile + lane * 8;
     const bool colok = col < d_out;
@@ -440,7 +440,7 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
                 uint32_t kept = 0u;
                 if (q < nq) {
                     uint32_t m[BT];
-                    kept = masks_of8<DT, BT>(X, batch, b0, nb, d_in, q * 8, tau, cmp_mode, union_all, raw[p], m);
+                    kept = masks_of8<DT, BT>(L, X, batch, b0, nb, d_in, q * 8, rules, union_all, raw[p], m);
                     if (Q4 && a.dense) kept = 0xffu;
                 }
                 const int c = __popc(kept);
@@ -540,7 +540,8 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
             if (b < nb) {
                 const uint16_t h = X[(size_t)(b0 + b) * d_in + c];
                 xf = (DT == F16) ? (float)__builtin_bit_cast(_Float16, h) : as_f((uint32_t)h << 16);
-                kb = (union_all || (Q4 && a.dense)) ? true : keep(xf, tau, cmp_mode);
+                kb = (union_all || (Q4 && a.dense)) ? true
+                     : rules.exact ? keep(xf, c, rules.r[b], rules.sgn) : keep_threshold(xf, rules.r[b]);
             }
             s.coef[j * BT + b] = kb ? xf : 0.f;
             bits |= (uint32_t)kb << b;
@@ -686,11 +687,12 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
                 if (b >= nb) continue;
                 const size_t at = (size_t)(b0 + b) * d_out + o;
                 if (!pair) {
-                    store_out(a.Y, at, v[b], L.out_dtype);
+                    store_out(a.Y, at, EXT ? v[b] + bias_at(L, o) : v[b], L.out_dtype);
                 } else {
                     // g and u are rounded to the storage type first, as the two projections would store them
-                    const uint16_t g16 = DT == F16 ? to_f16(v[b]) : to_bf16(v[b]);
-                    const uint16_t u16 = DT == F16 ? to_f16(vu[b]) : to_bf16(vu[b]);
+                    const float gb = EXT ? v[b] + bias_at(ga.job[0].L, o) : v[b], ub = EXT ? vu[b] + bias_at(ga.job[1].L, o) : vu[b];
+                    const uint16_t g16 = DT == F16 ? to_f16(gb) : to_bf16(gb);
+                    const uint16_t u16 = DT == F16 ? to_f16(ub) : to_bf16(ub);
                     ((uint16_t *)ga.job[0].Y)[at] = gated1<DT>(g16, u16);
                 }
             }
@@ -739,11 +741,14 @@ __global__ __launch_bounds__(BT >= 8 ? 256 : 512) void k_sparse_and_t(const Grou
 }
 
 // The whole layer in one launch (see the file header).  Same grid as k_sparse_and_t.
-template <int DT, int BT, bool NT>
+// EXT = false: no layer of the launch has a fixed-count rule, a signed threshold or a bias (the host checks), and the
+// code for those is left out -- this kernel's once-per-launch code runs from a cold instruction cache, and the
+// general keep-predicate in its token scan measured +0.3 us per launch.
+template <int DT, int BT, bool NT, bool EXT>
 __global__ __launch_bounds__(BT >= 8 ? 256 : 512, BT >= 8 ? 3 : 4) void k_rsparse_fused(const GroupArgs ga)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    sparse_body<DT, BT, NT, true>(ga, smem);
+    sparse_body<DT, BT, NT, true, false, EXT>(ga, smem);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -929,7 +934,7 @@ __global__ __launch_bounds__(256) void k_finish(const FinishGroupArgs ga)
 #pragma unroll
         for (int b = 0; b < BT; ++b) {
             if (sub == 0 && o < d_out && b < nb) {
-                store_out(a.Y, (size_t)(b0 + b) * d_out + o, ya[g][b] + acc[g][b], L.out_dtype);
+                store_out(a.Y, (size_t)(b0 + b) * d_out + o, ya[g][b] + acc[g][b] + bias_at(L, o), L.out_dtype);
                 L.yacc[(size_t)(b0 + b) * d_out + o] = 0.f;
             }
         }
@@ -1202,10 +1207,14 @@ hipError_t launch_fused(const LayerView *L, const Launch *cfg, int n, const void
     ga.gate_up = gate_up ? 1 : 0;
     dim3 grid(total, 1, nz), block(kWave * cfg[0].waves);
     const bool nt = cfg[0].nontemporal != 0;
+    bool ext = false;
+    for (int i = 0; i < n; ++i) ext = ext || L[i].rules || L[i].bias || L[i].keep_signed;
 #define RS_U(DT)                                                                                        \
     RS_DISPATCH_BT(bt, {                                                                                \
-        if (nt) hipLaunchKernelGGL((k_rsparse_fused<DT, BT, true>), grid, block, lds, stream, ga);      \
-        else hipLaunchKernelGGL((k_rsparse_fused<DT, BT, false>), grid, block, lds, stream, ga);        \
+        if (nt && !ext) hipLaunchKernelGGL((k_rsparse_fused<DT, BT, true, false>), grid, block, lds, stream, ga);      \
+        else if (nt) hipLaunchKernelGGL((k_rsparse_fused<DT, BT, true, true>), grid, block, lds, stream, ga);          \
+        else if (!ext) hipLaunchKernelGGL((k_rsparse_fused<DT, BT, false, false>), grid, block, lds, stream, ga);      \
+        else hipLaunchKernelGGL((k_rsparse_fused<DT, BT, false, true>), grid, block, lds, stream, ga);                 \
     })
     if (L[0].dtype == F16) { RS_U(F16) } else { RS_U(BF16) }
 #undef RS_U

@@ -110,6 +110,8 @@ __global__ __launch_bounds__(256) void k_mfma_sparse_and_t(const MfmaArgs a)
     const int k0 = ksl * a.ks;
     const int klen = min(a.ks, d_in - k0);              // > 0 by construction of k_slices
     const uint32_t all_tokens = a.batch >= 32 ? 0xffffffffu : ((1u << a.batch) - 1u);
+    // the layer's threshold as a rule (the fixed-count activation never takes this path: its rules are per token)
+    const KeepRule thr = {L.tau_ge, __builtin_nanf(""), -1, 0};
 
     // ---- per-channel keep bits of every token: needed for the union mask and for read-back
     uint32_t *s_bits = reinterpret_cast<uint32_t *>(smem + (size_t)a.tok_pad * pitch);   // [ks]
@@ -123,7 +125,7 @@ __global__ __launch_bounds__(256) void k_mfma_sparse_and_t(const MfmaArgs a)
                 unpack8<DT>(*reinterpret_cast<const u32x4 *>(a.X + (size_t)tok * d_in + k0 + kq * 8), f);
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
-                    if (keep(f[e], L.tau, L.cmp_mode)) atomicOr(&s_bits[kq * 8 + e], 1u << tok);
+                    if (keep(f[e], k0 + kq * 8 + e, thr, L.keep_signed != 0)) atomicOr(&s_bits[kq * 8 + e], 1u << tok);
             }
         }
         __syncthreads();
@@ -155,7 +157,7 @@ __global__ __launch_bounds__(256) void k_mfma_sparse_and_t(const MfmaArgs a)
                     unpack8<DT>(o, f);
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
-                        const bool kept = union_all ? s_bits[kq * 8 + e] != 0u : keep(f[e], L.tau, L.cmp_mode);
+                        const bool kept = union_all ? s_bits[kq * 8 + e] != 0u : keep(f[e], k0 + kq * 8 + e, thr, L.keep_signed != 0);
                         if (kept == is_t) o[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;   // not this part's
                     }
                 }
@@ -340,7 +342,7 @@ __global__ __launch_bounds__(256) void k_mfma_finish(const MfmaFinishArgs a)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) o[j] = orow + j < d_out ? yp[(size_t)j * a.tok_pad] : 0.f;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) o[j] += acc[j];
+                for (int j = 0; j < 4; ++j) o[j] += acc[j] + (orow + j < d_out ? bias_at(L, orow + j) : 0.f);
                 const size_t oi = (size_t)tok * d_out + orow;
                 if (L.out_dtype == F32) {
                     *reinterpret_cast<float4 *>((float *)a.Y + oi) = float4{o[0], o[1], o[2], o[3]};

@@ -78,12 +78,6 @@ __device__ __forceinline__ int job_of(const int (&wg_end)[kMaxGroupLayers], int 
     return li;
 }
 
-template <int DT>
-__device__ __forceinline__ float widen16(uint16_t h)
-{
-    return DT == F16 ? (float)__builtin_bit_cast(_Float16, h) : as_f((uint32_t)h << 16);
-}
-
 // ---------------------------------------------------------------------------------------------
 // Stage 1 of the low-rank part inside the strip kernel's launch: t_i = sum_c (S_r V_r^T)[i, c] (x - sigma_t(x))_c.
 // The rows of S_r V_r^T do not depend on the token, so a wave requests its part of its row FIRST and stages the
@@ -102,6 +96,8 @@ __device__ __forceinline__ void stage1_tagged(const Args &a, unsigned char *smem
     const int b0 = z * BT;
     const int nb = min(BT, a.batch - b0);
     const bool union_all = L.batch_mask_mode == 1;
+    TileRules<BT> rules;
+    load_rules<BT>(L, b0, nb, rules);
     const int rpw = a.lr_rows, ws = nw / rpw;              // rows per workgroup, waves per row
     const int row = wg * rpw + w / ws, seg = w % ws;
     const bool have = row < r;
@@ -143,7 +139,7 @@ __device__ __forceinline__ void stage1_tagged(const Args &a, unsigned char *smem
                 const int q = p0 + p * nthr;
                 if (q < nq) {
                     uint32_t m[BT];
-                    masks_of8<DT, BT>(a.X, a.batch, b0, nb, d_in, c0 + q * 8, L.tau, L.cmp_mode, union_all, raw[p], m);
+                    masks_of8<DT, BT>(L, a.X, a.batch, b0, nb, d_in, c0 + q * 8, rules, union_all, raw[p], m);
 #pragma unroll
                     for (int b = 0; b < BT; ++b) {
                         u32x4 o = raw[p][b];
@@ -251,8 +247,6 @@ __device__ __forceinline__ void strip_body(const StripGroupArgs &ga, unsigned ch
     const int d_in = pin(L.d_in), d_out = pin(L.d_out), batch = pin(a.batch), cap = pin(a.cap);
     const bool dense = pin(a.dense) != 0;
     const int rank = dense ? 0 : pin(L.rank);
-    const float tau = pin(L.tau);
-    const int cmp_mode = pin(L.cmp_mode);
     const bool union_all = pin(L.batch_mask_mode) == 1;
     RS_STAMP(11);                                   // kernel arguments are here
     const int g = wg;
@@ -290,13 +284,8 @@ __device__ __forceinline__ void strip_body(const StripGroupArgs &ga, unsigned ch
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[b][e] = 0.f;
 
-    // |x| > tau (cmp_mode 1) is |x| >= the next fp32 above tau; nothing is above +inf: a NaN threshold keeps nothing
-    float tau_ge = tau;
-    if (cmp_mode == 1) {
-        const uint32_t tb = as_u(tau);
-        tau_ge = tau == __builtin_inff() ? __builtin_nanf("") : as_f(tau >= 0.f ? (tb & 0x7fffffffu) + 1u : tb - 1u);
-    }
-    tau_ge = uniform(tau_ge);
+    TileRules<BT> rules;
+    load_rules<BT>(L, b0, nb, rules);
     constexpr int SC = BT >= 8 ? 1 : 8 / BT;           // 64-channel pieces of the token held in registers per round
     const int c_lo = q_lo * 8, c_hi = q_hi * 8;
     int c = c_lo, pub = 0;
@@ -335,7 +324,7 @@ __device__ __forceinline__ void strip_body(const StripGroupArgs &ga, unsigned ch
 #pragma unroll
                 for (int b = 0; b < BT; ++b) {
                     xf[b] = widen16<DT>((uint16_t)xr[j][b]);
-                    kb[b] = valid && b < nb && (dense || __builtin_fabsf(xf[b]) >= tau_ge);
+                    kb[b] = valid && b < nb && (dense || keep(xf[b], cc, rules.r[b], rules.sgn));
                     any = any || kb[b];
                 }
                 if (union_all && !dense) {
@@ -343,7 +332,7 @@ __device__ __forceinline__ void strip_body(const StripGroupArgs &ga, unsigned ch
                     for (int bb = 0; bb < batch; ++bb) {
                         if (bb >= b0 && bb < b0 + nb) continue;
                         const float xo = valid ? widen16<DT>(X[(size_t)bb * d_in + cc]) : 0.f;
-                        any = any || (valid && __builtin_fabsf(xo) >= tau_ge);
+                        any = any || (valid && keep(xo, cc, rule_of(L, bb), rules.sgn));
                     }
 #pragma unroll
                     for (int b = 0; b < BT; ++b) kb[b] = any && b < nb;
@@ -538,7 +527,7 @@ __device__ __forceinline__ void strip_body(const StripGroupArgs &ga, unsigned ch
         if (b < nb && o < d_out) {
             const size_t at = (size_t)(b0 + b) * d_out + o;
             // one workgroup per strip: this IS Y_s + Y_r (Sec. 3.4); round once and store
-            if (!split_k) store_out(a.Y, at, s, L.out_dtype);
+            if (!split_k) store_out(a.Y, at, s + bias_at(L, o), L.out_dtype);
             else __hip_atomic_fetch_add(L.yacc + at, s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
@@ -570,7 +559,7 @@ __device__ __forceinline__ void strip_body(const StripGroupArgs &ga, unsigned ch
         if (b < nb && o < d_out) {
             const size_t at = (size_t)(b0 + b) * d_out + o;
             const float v = __hip_atomic_exchange(L.yacc + at, 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            store_out(a.Y, at, v, L.out_dtype);
+            store_out(a.Y, at, v + bias_at(L, o), L.out_dtype);
         }
     }
     RS_STAMP(10);

@@ -22,7 +22,8 @@ constexpr size_t kOffList = kOffTtag + up((size_t)kStaticMaxBatch * kStaticMaxRa
 constexpr size_t kOffBits = kOffList + up((size_t)kStaticMaxDim * 4);
 constexpr size_t kOffSeg = kOffBits + up((size_t)kStaticMaxDim * 4);
 constexpr size_t kOffCount = kOffSeg + up((size_t)kStaticMaxDim / 8 * 4);
-constexpr size_t kOffSync = kOffCount + up(16);
+constexpr size_t kOffRules = kOffCount + up(16);
+constexpr size_t kOffSync = kOffRules + up((size_t)kStaticMaxBatch * sizeof(KeepRule));
 constexpr size_t kSyncWords = kSyncTile + (size_t)kSyncMaxZ * (kStaticMaxDim / 32);     // strips of 32 columns at most
 constexpr size_t kStaticBytes = 2u << 20;
 static_assert(kOffSync + up(kSyncWords * 4) <= kStaticBytes, "the carve-up must fit the array");
@@ -86,6 +87,7 @@ hipError_t static_scratch_for_call(int device, int d_out, int rank, int batch, h
     sp.act_bits = reinterpret_cast<uint32_t *>(ptr + kOffBits);
     sp.act_seg = reinterpret_cast<int32_t *>(ptr + kOffSeg);
     sp.act_count = reinterpret_cast<int32_t *>(ptr + kOffCount);
+    sp.rules = reinterpret_cast<KeepRule *>(ptr + kOffRules);
     sp.sync = reinterpret_cast<int *>(ptr + kOffSync);
     sp.t_slots = kStaticMaxBatch;
     sp.n_t = (size_t)kStaticMaxBatch * (size_t)(rank > 0 ? rank : 1);

@@ -36,14 +36,15 @@ def test_product_never_imports_the_oracle():
 
 @pytest.mark.parametrize("bad", [
     dict(d_in=12), dict(d_out=0), dict(rank=-1), dict(rank=72), dict(rank=12), dict(max_batch=0), dict(max_batch=33),
-    dict(tau=float("nan")), dict(dtype=2), dict(out_dtype=0, dtype=1), dict(cmp_mode=2), dict(batch_mask_mode=-1),
+    dict(tau=float("nan")), dict(dtype=2), dict(out_dtype=0, dtype=1), dict(cmp_mode=3), dict(batch_mask_mode=-1),
+    dict(batch_mask_mode=3), dict(topk=-1), dict(topk=65), dict(topk=8, cmp_mode=1), dict(topk=8, cmp_mode=2),
 ])
 def test_config_validation(bad):
     kw = dict(d_in=64, d_out=64, rank=8, tau=0.5, dtype=rs.F16, max_batch=1)
     kw.update(bad)
     cfg = rs.make_config(kw["d_in"], kw["d_out"], kw["rank"], kw["tau"], kw["dtype"], max_batch=kw["max_batch"],
                          out_dtype=kw.get("out_dtype"), cmp_mode=kw.get("cmp_mode", 0),
-                         batch_mask_mode=kw.get("batch_mask_mode", 0))
+                         batch_mask_mode=kw.get("batch_mask_mode", 0), topk=kw.get("topk", 0))
     W = np.zeros((max(kw["d_out"], 1), max(kw["d_in"], 1)), dtype=np.uint16)
     lib = rs.load_library()
     import ctypes as C
@@ -270,3 +271,30 @@ def test_bf16_encodings_round_fp64_once():
     allv = np.concatenate([v, near, [0.0, -0.0, np.inf, -np.inf, 1e39, -1e39, 1e-45]])
     assert np.array_equal(synth.encode16(allv, synth.BF16), oracle.round16_from_double(allv, synth.BF16))
     assert np.array_equal(synth.encode16(allv, synth.F16), oracle.round16_from_double(allv, synth.F16))
+
+
+def test_multiphase_bias_is_the_mean_residual_of_sec_3_2():
+    """Host routine against the oracle's literal form (per token: interval sets, column sums, midpoints; then the mean)."""
+    import oracle
+    g = np.random.Generator(np.random.PCG64(77))
+    for dt in (synth.F16, synth.BF16):
+        d_in, d_out, N = 96, 40, 7
+        W16 = synth.encode16(g.standard_normal((d_out, d_in)) * 0.2, dt)
+        H16 = synth.encode16(g.standard_normal((N, d_in)), dt)
+        H16[0, :4] = synth.encode16(np.array([0.5, -0.25, -3.0, np.nan]), dt)        # ties at every threshold, a NaN
+        for T in ([0.5], [0.5, -0.25], [0.5, -0.25, -3.0], [1.0, 0.0, -1.0, -2.0]):
+            got = rs.rsparse_multiphase_bias(W16, dt, H16, T)
+            Hc = H16.copy()
+            nan = np.isnan(synth.decode16(Hc, dt))
+            want = oracle.static_bias(W16, dt, Hc, dt, np.array(T, dtype=np.float64))
+            assert not np.any(np.isnan(got))
+            assert np.allclose(got, want, rtol=2e-6, atol=1e-7), T                   # one rounding to fp32
+            assert nan.sum() == 1
+    lib = rs.load_library()
+    import ctypes as C
+    out = np.zeros(8, dtype=np.float32)
+    W = np.zeros((8, 8), dtype=np.uint16)
+    bad_T = np.array([0.0, 0.0], dtype=np.float32)
+    st = lib.rsparse_multiphase_bias(W.ctypes.data_as(C.c_void_p), 0, 8, 8, W.ctypes.data_as(C.c_void_p), 1,
+                                     bad_T.ctypes.data_as(C.c_void_p), 2, out.ctypes.data_as(C.c_void_p))
+    assert st == 1
