@@ -93,9 +93,12 @@ def shape_batch_sweep(args, torch, np, rs, synth):
             k_union = len(rs.rsparse_last_active(layers[-1], -1))
             us_dense = run(rs.rsparse_dense_ref)
             req = rs.rsparse_required_bytes(layers[0], B, k_union)
+            est_rs, est_dense, use = rs.rsparse_plan_layer(d_in, d_out, rank, 0.5, 1, B)
             out.append({"case": label, "batch": B, "ring_layers": n_ring, "k_union": k_union,
                         "us_rsparse": round(us_rs, 2), "us_dense": round(us_dense, 2),
-                        "speedup": round(us_dense / us_rs, 3), "required_MB": round(req / 1e6, 2),
+                        "speedup": round(us_dense / us_rs, 3),
+                        "plan": "rsparse" if use else "dense", "us_as_planned": round(us_rs if use else us_dense, 2),
+                        "plan_estimates_us": [round(est_rs, 1), round(est_dense, 1)], "required_MB": round(req / 1e6, 2),
                         "gbs_required": round(req / us_rs / 1e3, 1), "frac_of_8TBs": round(req / us_rs / 8e6, 3),
                         "dense_gbs": round(rs.rsparse_dense_bytes(layers[0], B) / us_dense / 1e3, 1)})
             log(str(out[-1]))
@@ -172,25 +175,24 @@ def decoder_layer_sweep(torch, np, rs, synth):
         set_all()
         row["us_dense"] = round(timed(B, rs.rsparse_dense_ref_group, rs.rsparse_dense_ref), 2)
         row["speedup"] = round(row["us_dense"] / min(row["us_rsparse_one_launch"], row["us_rsparse_two_launches"]), 3)
-        if B == 1:
-            # per call, what rsparse_plan_layer picks for single-token decode (byte model + fixed launch costs)
-            plan = {"qkv": rs.rsparse_plan_layer(4096, 4096, r, 0.5, 3)[2], "o": rs.rsparse_plan_layer(4096, 4096, r, 0.5, 1)[2],
-                    "gate_up": rs.rsparse_plan_layer(4096, 11008, r, 0.5, 2)[2], "down": rs.rsparse_plan_layer(11008, 4096, r, 0.5, 1)[2]}
+        # per call, what rsparse_plan_layer picks at this batch (byte model + fixed launch costs): R-Sparse or dense
+        plan = {"qkv": rs.rsparse_plan_layer(4096, 4096, r, 0.5, 3, B)[2], "o": rs.rsparse_plan_layer(4096, 4096, r, 0.5, 1, B)[2],
+                "gate_up": rs.rsparse_plan_layer(4096, 11008, r, 0.5, 2, B)[2], "down": rs.rsparse_plan_layer(11008, 4096, r, 0.5, 1, B)[2]}
 
-            def planned_layer(b, Bn, sptr, _g, _o):
-                grp = lambda use: rs.rsparse_linear_group if use else rs.rsparse_dense_ref_group
-                one = lambda use: rs.rsparse_linear if use else rs.rsparse_dense_ref
-                grp(plan["qkv"])([b[n][0] for n in "qkv"], b["q"][1].data_ptr(), Bn, [b[n][2].data_ptr() for n in "qkv"], sptr)
-                one(plan["o"])(b["o"][0], b["o"][1].data_ptr(), Bn, b["o"][2].data_ptr(), sptr)
-                grp(plan["gate_up"])([b["gate"][0], b["up"][0]], b["gate"][1].data_ptr(), Bn,
-                                     [b["gate"][2].data_ptr(), b["up"][2].data_ptr()], sptr)
-                one(plan["down"])(b["down"][0], b["down"][1].data_ptr(), Bn, b["down"][2].data_ptr(), sptr)
+        def planned_layer(b, Bn, sptr, _g, _o):
+            grp = lambda use: rs.rsparse_linear_group if use else rs.rsparse_dense_ref_group
+            one = lambda use: rs.rsparse_linear if use else rs.rsparse_dense_ref
+            grp(plan["qkv"])([b[n][0] for n in "qkv"], b["q"][1].data_ptr(), Bn, [b[n][2].data_ptr() for n in "qkv"], sptr)
+            one(plan["o"])(b["o"][0], b["o"][1].data_ptr(), Bn, b["o"][2].data_ptr(), sptr)
+            grp(plan["gate_up"])([b["gate"][0], b["up"][0]], b["gate"][1].data_ptr(), Bn,
+                                 [b["gate"][2].data_ptr(), b["up"][2].data_ptr()], sptr)
+            one(plan["down"])(b["down"][0], b["down"][1].data_ptr(), Bn, b["down"][2].data_ptr(), sptr)
 
-            set_all(launches=1)
-            row["plan"] = {k: ("rsparse" if v else "dense") for k, v in plan.items()}
-            row["us_planned"] = round(timed(B, None, None, layer_fn=planned_layer), 2)
-            row["speedup_planned"] = round(row["us_dense"] / row["us_planned"], 3)
-            set_all()
+        set_all(launches=1)
+        row["plan"] = {k: ("rsparse" if v else "dense") for k, v in plan.items()}
+        row["us_planned"] = round(timed(B, None, None, layer_fn=planned_layer), 2)
+        row["speedup_planned"] = round(row["us_dense"] / row["us_planned"], 3)
+        set_all()
         out.append(row)
         log(str(row))
     for b in ring:

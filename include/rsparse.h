@@ -333,19 +333,20 @@ rsparse_status rsparse_recipe(int32_t d_in, int32_t d_out, double budget_c, doub
                               double *keep_fraction_out, int32_t *rank_out, double *io_out);
 
 /*
- * Whether R-Sparse is expected to pay for one layer in single-token decode on this card: Sec. 3.4's I/O model
- * in bytes (kept columns of W + both factors, against all of W) plus the per-launch costs that do not scale
- * with bytes.  Sec. 3.5 lets the recipe differ per layer; this is the complementary per-layer decision to run
- * a layer dense, e.g. the small attention projections.  keep_fraction: share of channels the token keeps (s
- * of rsparse_recipe).  group: layers that share one launch (rsparse_linear_group), whose fixed cost they
- * split.  Constants (MI355X, measured with this library, 16-bit weights, one token): 6.5 TB/s marginal
- * streaming rate, 8.5 us fixed per R-Sparse launch, 3.6 us per dense launch; the estimates land within about
- * 15 % of the measured times on the benchmark shapes.  Larger batches are not modelled (the dense kernels
- * change regime there): measure instead.  Host code.  Any output pointer may be NULL.
+ * Whether R-Sparse is expected to pay for one layer on this card: Sec. 3.4's I/O model in bytes (kept columns of W +
+ * both factors, against all of W) plus the per-launch costs that do not scale with bytes.  Sec. 3.5 lets the recipe
+ * differ per layer; this is the complementary per-layer decision to run a layer dense, e.g. the small attention
+ * projections, or every layer once the batch is so large that the union of the tokens' kept channels is nearly all of
+ * them.  keep_fraction: share of channels ONE token keeps (s of rsparse_recipe); for `batch` tokens the loaded columns
+ * are their union, modelled as 1 - (1 - s)^batch.  group: layers that share one launch (rsparse_linear_group), whose
+ * fixed cost they split.  Constants (MI355X, measured with this library, 16-bit weights): one token -- 6.5 TB/s
+ * marginal rate, 8.5 us fixed per R-Sparse launch, 3.6 us per dense launch; 2-4 tokens (vector path) -- 6.7 TB/s,
+ * 8.5 + 3 log2(batch) us; 5-32 tokens (matrix cores, all of W read) -- 4.65 TB/s, 15 us; dense from 2 tokens --
+ * 5.26 TB/s, 7.3 us (4.86 TB/s, 9.2 us above 16 tokens).  The estimates land within about 20 % of the measured times
+ * on the benchmark shapes.  Host code.  Any output pointer may be NULL.  Errors: RSPARSE_EINVAL.
  */
-rsparse_status rsparse_plan_layer(int32_t d_in, int32_t d_out, int32_t rank, double keep_fraction,
-                                  int32_t group, double *us_rsparse_out, double *us_dense_out,
-                                  int32_t *use_rsparse_out);
+rsparse_status rsparse_plan_layer(int32_t d_in, int32_t d_out, int32_t rank, double keep_fraction, int32_t group,
+                                  int32_t batch, double *us_rsparse_out, double *us_dense_out, int32_t *use_rsparse_out);
 
 /*
  * Search for the per-layer shares rho_i of the sparse part (Sec. 3.5, the search algorithm for the

@@ -104,7 +104,7 @@ def load_library():
     lib.rsparse_recipe.argtypes = [i32, i32, C.c_double, C.c_double, C.POINTER(C.c_double), C.POINTER(i32),
                                    C.POINTER(C.c_double)]
     lib.rsparse_recipe.restype = C.c_int
-    lib.rsparse_plan_layer.argtypes = [i32, i32, i32, C.c_double, i32, C.POINTER(C.c_double), C.POINTER(C.c_double),
+    lib.rsparse_plan_layer.argtypes = [i32, i32, i32, C.c_double, i32, i32, C.POINTER(C.c_double), C.POINTER(C.c_double),
                                        C.POINTER(i32)]
     lib.rsparse_plan_layer.restype = C.c_int
     lib.rsparse_search_recipe.argtypes = [LOSS_FN, vp, i32, i32, i32, C.c_double, C.c_double, i32, C.c_uint64,
@@ -360,10 +360,10 @@ def rsparse_recipe(d_in: int, d_out: int, budget_c: float, rho: float):
     return s.value, r.value, io.value
 
 
-def rsparse_plan_layer(d_in: int, d_out: int, rank: int, keep_fraction: float, group: int = 1):
-    """(estimated us with R-Sparse, estimated us dense, use R-Sparse?) for one layer at one token; host code."""
+def rsparse_plan_layer(d_in: int, d_out: int, rank: int, keep_fraction: float, group: int = 1, batch: int = 1):
+    """(estimated us with R-Sparse, estimated us dense, use R-Sparse?) for one layer at `batch` tokens; host code."""
     a, b, use = C.c_double(), C.c_double(), C.c_int32()
-    _check(load_library().rsparse_plan_layer(d_in, d_out, rank, keep_fraction, group, C.byref(a), C.byref(b),
+    _check(load_library().rsparse_plan_layer(d_in, d_out, rank, keep_fraction, group, batch, C.byref(a), C.byref(b),
                                              C.byref(use)))
     return a.value, b.value, bool(use.value)
 

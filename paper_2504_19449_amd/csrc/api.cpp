@@ -138,6 +138,8 @@ struct rsparse_layer {
     bool last_strip = false;               // the last call went through the strip kernel ...
     int last_ranges = 0;                   // ... with this many channel ranges (splits x waves)
     float *t = nullptr, *yacc = nullptr;
+    float *t_acc = nullptr;                // [rank][32] accumulated t of the matrix-core path (zero between calls)
+    uint16_t *t16 = nullptr;               // [2][32][rank] its two 16-bit halves
     uint32_t *act_bits = nullptr, *chan_bits = nullptr;
     bool last_mfma = false;
     int32_t *act_list = nullptr, *act_count = nullptr;
@@ -176,7 +178,7 @@ struct rsparse_layer {
     {
         const ScratchView sp = ov ? *ov : own_scratch();
         LayerView v{};
-        v.M = M; v.SVt = SVt; v.U = U; v.Wrow = Wrow; v.t = sp.t; v.yacc = sp.yacc;
+        v.M = M; v.SVt = SVt; v.U = U; v.Wrow = Wrow; v.t = sp.t; v.yacc = sp.yacc; v.t_acc = ov ? nullptr : t_acc; v.t16 = ov ? nullptr : t16;
         v.act_list = sp.act_list; v.act_bits = sp.act_bits; v.act_count = sp.act_count; v.sync = sp.sync; v.t_pub = sp.t_pub;
         v.d_in = cfg.d_in; v.d_out = cfg.d_out; v.rank = cfg.rank;
         v.dtype = cfg.dtype; v.out_dtype = cfg.out_dtype; v.cmp_mode = cfg.cmp_mode;
@@ -335,7 +337,7 @@ void free_layer(rsparse_layer *L)
     (void)hipFree(L->M); (void)hipFree(L->SVt); (void)hipFree(L->U); (void)hipFree(L->Wrow); (void)hipFree(L->t);
     (void)hipFree(L->yacc); (void)hipFree(L->act_bits); (void)hipFree(L->chan_bits);
     (void)hipFree(L->act_list); (void)hipFree(L->act_count); (void)hipFree(L->sync); (void)hipFree(L->t_pub); (void)hipFree(L->xg); (void)hipFree(L->hy);
-    (void)hipFree(L->Ms); (void)hipFree(L->t_tag); (void)hipFree(L->act_seg); (void)hipFree(L->bias); (void)hipFree(L->rules);
+    (void)hipFree(L->Ms); (void)hipFree(L->t_tag); (void)hipFree(L->act_seg); (void)hipFree(L->bias); (void)hipFree(L->rules); (void)hipFree(L->t_acc); (void)hipFree(L->t16);
     (void)hipFree(L->Mq); (void)hipFree(L->qs); (void)hipFree(L->qz); (void)hipFree(L->Ut);
     delete L;
 }
@@ -447,6 +449,12 @@ rsparse_status build_layer(const rsparse_config *cfg, const uint16_t *W, const u
         if (cfg->dense_rowmajor && !q4) {
             RS_HIP(hipMalloc((void **)&L->Wrow, d_in * d_out * 2));
             RS_HIP(hipMemcpy(L->Wrow, W, d_in * d_out * 2, hipMemcpyHostToDevice));
+        }
+        if (cfg->dense_rowmajor && !q4 && r) {
+            RS_HIP(hipMalloc((void **)&L->t_acc, (size_t)32 * r * 4));
+            RS_HIP(hipMemset(L->t_acc, 0, (size_t)32 * r * 4));
+            RS_HIP(hipMalloc((void **)&L->t16, (size_t)2 * 32 * r * 2));
+            RS_HIP(hipMemset(L->t16, 0, (size_t)2 * 32 * r * 2));
         }
         RS_HIP(hipMalloc((void **)&L->xg, (size_t)cfg->max_batch * d_in * 2));
         RS_HIP(hipMalloc((void **)&L->hy, (size_t)cfg->max_batch * d_out * 2));
@@ -1218,19 +1226,34 @@ rsparse_status rsparse_recipe(int32_t d_in, int32_t d_out, double budget_c, doub
 }
 
 rsparse_status rsparse_plan_layer(int32_t d_in, int32_t d_out, int32_t rank, double keep_fraction, int32_t group,
-                                  double *us_rsparse_out, double *us_dense_out, int32_t *use_rsparse_out)
+                                  int32_t batch, double *us_rsparse_out, double *us_dense_out, int32_t *use_rsparse_out)
 {
     if (d_in < 1 || d_out < 1 || rank < 0 || rank > std::min(d_in, d_out)) return fail(RSPARSE_EINVAL, "bad layer shape");
     if (!(keep_fraction >= 0.0) || keep_fraction > 1.0) return fail(RSPARSE_EINVAL, "keep_fraction must be in [0, 1]");
     if (group < 1 || group > RSPARSE_MAX_GROUP) return fail(RSPARSE_EINVAL, "group %d outside [1, %d]", group, RSPARSE_MAX_GROUP);
-    // measured on MI355X with this library's kernels (16-bit weights, one token)
-    constexpr double kBytesPerUs = 6.5e6, kFixedRsparseUs = 8.5, kFixedDenseUs = 3.6;
-    const double m = d_out, n = d_in, r = rank, e = 2.0;
-    const double io = e * (n + m);
-    const double bytes_rs = e * (keep_fraction * n * m + r * (n + m)) + io;
-    const double bytes_dense = e * n * m + io;
-    const double us_rs = kFixedRsparseUs / group + bytes_rs / kBytesPerUs;
-    const double us_dense = kFixedDenseUs / group + bytes_dense / kBytesPerUs;
+    if (batch < 1 || batch > RSPARSE_MAX_BATCH) return fail(RSPARSE_EINVAL, "batch %d outside [1, %d]", batch, RSPARSE_MAX_BATCH);
+    // measured on MI355X with this library's kernels (16-bit weights): time = fixed cost of the launch(es) + bytes / rate
+    const double m = d_out, n = d_in, r = rank, e = 2.0, B = batch;
+    const double io = e * B * (n + m);
+    // the columns that are loaded are the union of the tokens' kept channels (independent tokens)
+    const double u = 1.0 - std::pow(1.0 - keep_fraction, B);
+    double us_rs, us_dense;
+    if (batch == 1) {
+        constexpr double kBytesPerUs = 6.5e6, kFixedRsparseUs = 8.5, kFixedDenseUs = 3.6;
+        us_rs = kFixedRsparseUs / group + (e * (keep_fraction * n * m + r * (n + m)) + io) / kBytesPerUs;
+        us_dense = kFixedDenseUs / group + (e * n * m + io) / kBytesPerUs;
+    } else {
+        if (batch <= 4) {
+            // vector path, one launch shared by the group; the fixed part grows with the batch tile (token loads,
+            // coefficient fetch, accumulators per token)
+            us_rs = (8.5 + 3.0 * std::log2(B)) / group + (e * (u * n * m + r * (n + m)) + io) / 6.7e6;
+        } else {
+            // matrix-core path: W is streamed whole whatever the masks are, three launches, no sharing in a group
+            us_rs = 15.0 + (e * (n * m + r * (n + m)) + io) / 4.65e6;
+        }
+        // dense product on the matrix cores
+        us_dense = (batch > 16 ? 9.2 : 7.3) + (e * n * m + io) / (batch > 16 ? 4.86e6 : 5.26e6);
+    }
     if (us_rsparse_out) *us_rsparse_out = us_rs;
     if (us_dense_out) *us_dense_out = us_dense;
     if (use_rsparse_out) *use_rsparse_out = us_rs < us_dense ? 1 : 0;

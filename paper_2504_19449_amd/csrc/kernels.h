@@ -31,6 +31,8 @@ struct LayerView {
     const uint16_t *U;      // [d_out][rank] = U_r, row-major
     const uint16_t *Wrow;   // [d_out][d_in] row-major copy of W, or nullptr
     float *t;               // [nz][BT][rank] stage-1 result, fp32
+    float *t_acc;           // [rank][16 or 32 tokens] matrix-core path: t summed over the K slices; zero between calls (or nullptr)
+    uint16_t *t16;          // [2][32][rank] matrix-core path: t split into two 16-bit halves, [token][rank] each (or nullptr)
     float *yacc;            // [max_batch][d_out] fp32 accumulators; zero between calls
     int32_t *act_list;      // [nz][d_in] ascending kept channels of batch tile z (union over its tokens)
     uint32_t *act_bits;     // [nz][d_in] per list entry: bit b = token b of the tile keeps it

@@ -208,7 +208,18 @@ def test_plan_layer_byte_model_and_decisions():
     assert rs.rsparse_plan_layer(4096, 11008, 256, 0.6)[0] > base
     assert rs.rsparse_plan_layer(4096, 11008, 512, 0.4)[0] > base
     assert rs.rsparse_plan_layer(4096, 11008, 256, 0.4, group=2)[0] < base
-    for bad in (dict(d_in=0), dict(rank=5000), dict(keep_fraction=1.5), dict(group=0), dict(group=5)):
+    # more than one token: the union of the kept channels grows as 1 - (1 - s)^B, the matrix-core path reads all of W:
+    # the 70B-shape MLP layers still pay at 2 tokens, nothing pays from 8 tokens on
+    assert rs.rsparse_plan_layer(8192, 28672, 1024, 0.5, 2, 2)[2]
+    for B in (8, 16, 32):
+        for shape in ((4096, 4096, 256), (8192, 28672, 1024), (28672, 8192, 1024)):
+            est_rs, est_d, use = rs.rsparse_plan_layer(*shape, 0.5, 1, B)
+            assert not use and est_rs > est_d
+    b2 = rs.rsparse_plan_layer(4096, 11008, 512, 0.5, 1, 2)
+    u2 = 1 - 0.5 ** 2
+    want2 = (8.5 + 3.0) + (2.0 * (u2 * 4096 * 11008 + 512 * (4096 + 11008)) + 2.0 * 2 * (4096 + 11008)) / 6.7e6
+    assert abs(b2[0] - want2) < 1e-9
+    for bad in (dict(d_in=0), dict(rank=5000), dict(keep_fraction=1.5), dict(group=0), dict(group=5), dict(batch=0), dict(batch=33)):
         kw = dict(d_in=4096, d_out=4096, rank=256, keep_fraction=0.5, group=1)
         kw.update(bad)
         with pytest.raises(rs.RSparseError):
