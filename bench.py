@@ -494,7 +494,8 @@ def leg_weights_4bit(col, args, mods, timers, base_us=None):
             Qc, Sc, Zc = synth.quantize_q4(synth.decode16(Lq.W16, dt), dt, 128)
             d_in, d_out = Lq.d_in, Lq.d_out
             for blk in range(blocks):
-                cfg = rs.make_config(d_in, d_out, q_rank, col.tau[name][args.sparsity], dt, max_batch=1)
+                cfg = rs.make_config(d_in, d_out, q_rank, col.tau[name][args.sparsity], dt, max_batch=1,
+                                     dense_rowmajor=1 if q_rank == 512 else 0)
                 q_ring.append((li, blk, rs.rsparse_prepare_q4(cfg, Qc, Sc, Zc, 128, Lq.U16[:, :q_rank], Lq.SV16[:q_rank])))
         q_ring.sort(key=lambda e: (e[1], e[0]))
 
@@ -514,8 +515,15 @@ def leg_weights_4bit(col, args, mods, timers, base_us=None):
                                        "gbs_required": round(rbq / (uq * 1e-6) / 1e9, 1)}
         if q_rank == 512:
             dbq = sum(rs.rsparse_dense_bytes(l, 1) for _, _, l in q_ring) / len(q_ring)
-            ud = us(pass_q4_dense)
-            q4["dense_4bit"] = {"us_per_linear": ud, "bytes_per_linear": int(dbq), "gbs": round(dbq / (ud * 1e-6) / 1e9, 1)}
+            ud = us(pass_q4_dense)                     # row-dot over row-major codes (the copy is kept at this rank)
+            q4["dense_4bit_rowdot"] = {"us_per_linear": ud, "bytes_per_linear": int(dbq), "gbs": round(dbq / (ud * 1e-6) / 1e9, 1)}
+            for _, _, layer in q_ring:
+                rs.rsparse_set_tuning(layer, dense_kernel=1)
+            uc = us(pass_q4_dense)                     # the channel-major kernel with every channel kept
+            q4["dense_4bit_channel_major"] = {"us_per_linear": uc, "bytes_per_linear": int(dbq), "gbs": round(dbq / (uc * 1e-6) / 1e9, 1)}
+            for _, _, layer in q_ring:
+                rs.rsparse_set_tuning(layer)
+            q4["speedup_rank512_vs_best_dense_4bit"] = round(min(ud, uc) / uq, 3)
         for _, _, layer in q_ring:
             layer.destroy()
     q4["note"] = ("configs[1]'s three linears with 4-bit weights (GPTQ format, groups of 128), batch 1, two launches per "

@@ -154,10 +154,13 @@ rsparse_status rsparse_prepare_factors(const rsparse_config *cfg, const void *W_
  * U16_host / SV16_host stay 16-bit and are the caller's (of the unquantised W, or of W~).  group_size: a power
  * of two in [32, 1024] that divides d_in.  The library packs the codes channel-major (one kept channel = one
  * contiguous run of d_out / 2 bytes) and dequantises in registers: per quantisation group it accumulates
- * sum x_c q_c and sum x_c and applies scale and zero point once.  Limits of this path: dense_rowmajor = 0
- * (no matrix-core path: batches above 4 tokens run as tiles of 4, the codes streamed once per tile); rsparse_linear and friends run it as two launches per layer by default (tuning
- * launches = 1 selects a one-launch form, measured no faster); grouped calls and rsparse_mlp_gate_up take
- * such layers one at a time; rsparse_dense_ref gives the dense product with W~.
+ * sum x_c q_c and sum x_c and applies scale and zero point once.  Limits of this path: no matrix-core path
+ * (batches above 4 tokens run as tiles of 4, the codes streamed once per tile); rsparse_linear and friends run it as
+ * two launches per layer by default (tuning launches = 1 selects a one-launch form, measured no faster); grouped
+ * calls and rsparse_mlp_gate_up take such layers one at a time.  rsparse_dense_ref gives the dense product with W~:
+ * with dense_rowmajor = 1 (a second, row-major copy of the codes, scales and zero points: + d_in * d_out / 2 bytes)
+ * as a row-dot GEMV over row-major codes, the form a dense 4-bit decoder would use (tuning dense_kernel = 1 forces the
+ * other form); without it through the channel-major kernel with every channel kept.
  */
 rsparse_status rsparse_prepare_q4(const rsparse_config *cfg, const uint8_t *Q_host, const void *S16_host,
                                   const uint8_t *Z_host, int32_t group_size, const void *U16_host,

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librsparse.so")
 LIB_STAMPS = os.path.join(HERE, "librsparse_stamps.so")     # measurement build, loaded only on request (RSPARSE_LIB)
-SOURCES = ["kernels.hip", "kernels_strip.hip", "kernels_mfma.hip", "kernels_topk.hip", "static_scratch.hip", "api.cpp", "svd_host.cpp", "recipe_search.cpp"]
+SOURCES = ["kernels.hip", "kernels_strip.hip", "kernels_mfma.hip", "kernels_topk.hip", "kernels_q4row.hip", "static_scratch.hip", "api.cpp", "svd_host.cpp", "recipe_search.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
          # keep the compiler from forming packed-fp32 instructions on its own

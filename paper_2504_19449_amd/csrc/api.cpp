@@ -154,6 +154,8 @@ struct rsparse_layer {
     bool last_fused = false;
     // 4-bit weights (rsparse_prepare_q4): codes, group scales, group zero points; M and Wrow stay null
     uint8_t *Mq = nullptr, *qz = nullptr;
+    uint8_t *Qrow = nullptr, *Zrow = nullptr;   // row-major codes and zero points (dense_rowmajor = 1): the row-dot dense baseline
+    uint16_t *Srow = nullptr;
     uint16_t *qs = nullptr, *Ut = nullptr;
     int qshift = 0, qtiles = 0;
     bool q4() const { return Mq != nullptr; }
@@ -339,6 +341,7 @@ void free_layer(rsparse_layer *L)
     (void)hipFree(L->act_list); (void)hipFree(L->act_count); (void)hipFree(L->sync); (void)hipFree(L->t_pub); (void)hipFree(L->xg); (void)hipFree(L->hy);
     (void)hipFree(L->Ms); (void)hipFree(L->t_tag); (void)hipFree(L->act_seg); (void)hipFree(L->bias); (void)hipFree(L->rules); (void)hipFree(L->t_acc); (void)hipFree(L->t16);
     (void)hipFree(L->Mq); (void)hipFree(L->qs); (void)hipFree(L->qz); (void)hipFree(L->Ut);
+    (void)hipFree(L->Qrow); (void)hipFree(L->Srow); (void)hipFree(L->Zrow);
     delete L;
 }
 
@@ -430,6 +433,21 @@ rsparse_status build_layer(const rsparse_config *cfg, const uint16_t *W, const u
             RS_HIP(hipMemcpy(L->qs, sq.data(), sq.size() * 2, hipMemcpyHostToDevice));
             RS_HIP(hipMalloc((void **)&L->qz, zq.size()));
             RS_HIP(hipMemcpy(L->qz, zq.data(), zq.size(), hipMemcpyHostToDevice));
+            if (cfg->dense_rowmajor && q4->group >= 32 && (d_in % 32) == 0) {
+                // row-major copy for the row-dot dense baseline: two codes per byte, channel 2j in the low nibble
+                std::vector<uint8_t> qr;
+                try { qr.assign(d_out * (d_in / 2), 0); } catch (const std::bad_alloc &) { return fail(RSPARSE_ENOMEM, "host allocation failed"); }
+                parallel_for(d_out, [&](size_t o) {
+                    for (size_t j = 0; j < d_in / 2; ++j)
+                        qr[o * (d_in / 2) + j] = (uint8_t)((q4->Q[o * d_in + 2 * j] & 15u) | ((q4->Q[o * d_in + 2 * j + 1] & 15u) << 4));
+                });
+                RS_HIP(hipMalloc((void **)&L->Qrow, qr.size()));
+                RS_HIP(hipMemcpy(L->Qrow, qr.data(), qr.size(), hipMemcpyHostToDevice));
+                RS_HIP(hipMalloc((void **)&L->Srow, d_out * G * 2));
+                RS_HIP(hipMemcpy(L->Srow, q4->S16, d_out * G * 2, hipMemcpyHostToDevice));
+                RS_HIP(hipMalloc((void **)&L->Zrow, d_out * G));
+                RS_HIP(hipMemcpy(L->Zrow, q4->Z, d_out * G, hipMemcpyHostToDevice));
+            }
             if (r) {
                 // U_r^T with rows padded to whole tiles, for the one-launch kernel
                 std::vector<uint16_t> ut;
@@ -586,7 +604,6 @@ rsparse_status rsparse_prepare_q4(const rsparse_config *cfg, const uint8_t *Q_ho
     if (cfg->rank > 0 && (!U16_host || !SV16_host)) return fail(RSPARSE_EINVAL, "factors are NULL but rank > 0");
     if (group_size < 32 || group_size > 1024 || (group_size & (group_size - 1)) || cfg->d_in % group_size)
         return fail(RSPARSE_EINVAL, "group_size must be a power of two in [32, 1024] that divides d_in (got %d)", group_size);
-    if (cfg->dense_rowmajor) return fail(RSPARSE_EINVAL, "dense_rowmajor is not available with 4-bit weights");
     if (cfg->strip_cols) return fail(RSPARSE_EINVAL, "strip_cols is not available with 4-bit weights");
     if (cfg->topk) return fail(RSPARSE_EINVAL, "the fixed-count activation (topk > 0) is not available with 4-bit weights");
     const size_t n = (size_t)cfg->d_in * cfg->d_out, ng = n / group_size;
@@ -892,6 +909,15 @@ rsparse_status rsparse_dense_ref_group(rsparse_layer *const *layers, int32_t n_l
     for (int i = 0; i < n_layers; ++i) any_q4 = any_q4 || layers[i]->q4();
     if (any_q4) {
         for (int i = 0; i < n_layers; ++i) {
+            rsparse_layer *Lq = layers[i];
+            // row-dot over row-major codes when the copy is kept (dense_rowmajor = 1) and asked for or left to the library
+            if (Lq->q4() && Lq->Qrow && Lq->tuning.dense_kernel != 1 && q4_rowdot_supported(Lq->cfg.d_in, batch)) {
+                RS_HIP(launch_q4_dense_rowdot(Lq->Qrow, Lq->Srow, Lq->Zrow, Lq->qshift, Lq->cfg.dtype, Lq->cfg.out_dtype, Lq->cfg.d_in,
+                                              Lq->cfg.d_out, X_dev, batch, Y_devs[i], s));
+                continue;
+            }
+            if (Lq->q4() && Lq->tuning.dense_kernel == 2)
+                return fail(RSPARSE_EINVAL, "row-dot dense kernel on 4-bit weights needs dense_rowmajor=1, groups >= 32 and batch_tile*d_in*2.125 <= 64 KiB");
             rsparse_status qs = layers[i]->q4() ? linear_q4(layers[i], X_dev, batch, Y_devs[i], true, s)
                                                 : rsparse_dense_ref_group(&layers[i], 1, X_dev, batch, &Y_devs[i], stream);
             if (qs != RSPARSE_OK) return qs;

@@ -65,6 +65,12 @@ struct LayerView {
     const float *bias;      // [d_out] fp32 added to every token's output before the rounding, or nullptr
 };
 
+// Dense 4-bit baseline over row-major codes (kernels_q4row.hip): Qrow [d_out][d_in/2] (channel 2j in the low nibble of byte
+// j), Srow / Zrow [d_out][d_in >> qshift].  Needs batch_tile * d_in * (2 + 1/8) bytes of LDS <= 64 KiB and groups >= 32.
+bool q4_rowdot_supported(int d_in, int batch);
+hipError_t launch_q4_dense_rowdot(const uint8_t *Qrow, const uint16_t *Srow, const uint8_t *Zrow, int qshift, int dtype, int out_dtype,
+                                  int d_in, int d_out, const void *X, int batch, void *Y, hipStream_t stream);
+
 // Fixed-count activation: per token of X [batch][d_in] the KeepRule that keeps exactly min(k, non-NaN channels)
 // channels of largest magnitude (ties: lower channel first).  One workgroup per token.
 hipError_t launch_topk_rules(const void *X, int dtype, int batch, int d_in, int k, KeepRule *rules, hipStream_t stream);

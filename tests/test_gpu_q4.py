@@ -313,3 +313,52 @@ def test_q4_random_shapes_and_settings(seed):
         print("case", dict(group=group, d_in=d_in, d_out=d_out, rank=rank, dt=dt, B=B, cmp=cmp_mode, mask=mask_mode,
                            s=s_level, **tuning), flush=True)
         _parity(q, X16, tau, out_dtype=rs.F32, tuning=tuning, cmp_mode=cmp_mode, batch_mask_mode=mask_mode)
+
+
+@pytest.mark.parametrize("dt", [synth.F16, synth.BF16])
+def test_q4_dense_rowdot_over_row_major_codes(ragged_q4, dt):
+    """The row-dot dense baseline (dense_rowmajor = 1): every batch tile, both output types, extreme codes, and the same
+    result as the channel-major dense form; R-Sparse on the same handle is untouched by the extra copy."""
+    q = ragged_q4[dt]
+    X16, src = gu.tokens_for(q.L, 9, kind="dmodel", config=91)
+    tau = gu.calibrated_tau(q.L, src, 0.5)
+    for out_dtype in (None, rs.F32):
+        layer = q.prepare(tau, max_batch=9, out_dtype=out_dtype, dense_rowmajor=1)
+        for B in (1, 2, 3, 4, 9):
+            want = q.dense(X16[:B])
+            gu.check_outputs(gu.run_dense(layer, X16[:B]), want, layer.cfg.out_dtype)          # row-dot (default with the copy)
+            rs.rsparse_set_tuning(layer, dense_kernel=1)
+            gu.check_outputs(gu.run_dense(layer, X16[:B]), want, layer.cfg.out_dtype)          # channel-major, every channel kept
+            rs.rsparse_set_tuning(layer)
+        got = gu.run_linear(layer, X16[:2])
+        want = q.oracle(X16[:2], tau)
+        gu.check_lists(got, want)
+        gu.check_outputs(got["Y"], want["Y"], layer.cfg.out_dtype)
+        layer.destroy()
+    # without the copy the row-dot form is refused, not silently replaced
+    layer = q.prepare(tau, max_batch=1)
+    rs.rsparse_set_tuning(layer, dense_kernel=2)
+    with pytest.raises(rs.RSparseError):
+        gu.run_dense(layer, X16[:1])
+    layer.destroy()
+
+
+def test_q4_dense_rowdot_extreme_codes_group_sizes_and_benchmark_shape():
+    dt = synth.BF16
+    for group, d_in in ((32, 256), (1024, 2048), (128, 4096)):
+        L = synth.make_layer(d_in, 264, 0, dt, config=93, linear=group % 7)
+        q = Q4Layer(L, group)
+        q.Q[:8, :] = 15
+        q.Z[:8, :] = 0
+        q.Q[8:16, :] = 0
+        q.Z[8:16, :] = 15
+        X16, _ = gu.tokens_for(L, 2, config=93)
+        layer = q.prepare(0.0, max_batch=2, out_dtype=rs.F32, dense_rowmajor=1)
+        gu.check_outputs(gu.run_dense(layer, X16), q.dense(X16), rs.F32)
+        layer.destroy()
+    L = synth.random_layer(11008, 4096, 64, dt, seed=17)
+    q = Q4Layer(L, 128)
+    X16, _ = gu.tokens_for(L, 1, kind="down", config=93)
+    layer = q.prepare(0.0, max_batch=1, dense_rowmajor=1)
+    gu.check_outputs(gu.run_dense(layer, X16), q.dense(X16), dt)
+    layer.destroy()

@@ -162,7 +162,7 @@ def test_recipe_search_matches_the_oracle_bit_for_bit():
 
 @pytest.mark.parametrize("bad", [
     dict(group=48), dict(group=16), dict(group=2048), dict(group=256, d_in=384), dict(max_batch=33),
-    dict(dense_rowmajor=1), dict(code=16), dict(zero=16), dict(null="Q"), dict(null="S"), dict(null="Z"),
+    dict(code=16), dict(zero=16), dict(null="Q"), dict(null="S"), dict(null="Z"),
 ])
 def test_q4_argument_validation(bad):
     """Every check of rsparse_prepare_q4 happens before the first device call, so it is testable here."""
