@@ -244,7 +244,9 @@ constexpr int kRowsPerWave = 4;
 template <int DT, int BT, int PUB, typename Args, bool EXT = true>
 __device__ __forceinline__ void lowrank_rows(const Args &a, unsigned char *smem, int wg, int z)
 {
-    constexpr int LU = 8;
+    // loads per batch and lane, batches in flight: two batches of six for one token; more tokens keep more of the
+    // register file for the token values, and a second batch then spills
+    constexpr int LU = BT == 1 ? 6 : 8, kRowBatches = BT == 1 ? 2 : 1;
     const int tid = threadIdx.x, nthr = blockDim.x, lane = tid & 63, w = tid >> 6, nw = nthr >> 6;
     const LayerView &L = a.L;
     const int d_in = L.d_in, r = L.rank;
@@ -295,28 +297,73 @@ __device__ __forceinline__ void lowrank_rows(const Args &a, unsigned char *smem,
             const int i = row_lo + w + sl * nw;
             if (i < row_hi) {
                 const uint16_t *row = L.SVt + (size_t)i * d_in + c0;
-                for (int q0 = lane; q0 < nq; q0 += 64 * LU) {
-                    u32x4 v[LU];
+                if constexpr (kRowBatches == 1) {
+                    for (int q0 = lane; q0 < nq; q0 += 64 * LU) {
+                        u32x4 v[LU];
 #pragma unroll
-                    for (int u = 0; u < LU; ++u) {
-                        const int q = q0 + u * 64;
-                        v[u] = (q < nq) ? ldg16<true>(row + q * 8) : u32x4{0, 0, 0, 0};       // streamed once
-                    }
+                        for (int u = 0; u < LU; ++u) {
+                            const int q = q0 + u * 64;
+                            v[u] = (q < nq) ? ldg16<true>(row + q * 8) : u32x4{0, 0, 0, 0};       // streamed once
+                        }
 #pragma unroll
-                    for (int u = 0; u < LU; ++u) {
-                        const int q = q0 + u * 64;
-                        if (q < nq) {
-                            float f[8];
-                            unpack8<DT>(v[u], f);
+                        for (int u = 0; u < LU; ++u) {
+                            const int q = q0 + u * 64;
+                            if (q < nq) {
+                                float f[8];
+                                unpack8<DT>(v[u], f);
 #pragma unroll
-                            for (int b = 0; b < BT; ++b) {
-                                float xf[8];
-                                unpack8<DT>(*reinterpret_cast<const u32x4 *>(s_xm + (size_t)b * a.lr_chunk + q * 8), xf);
+                                for (int b = 0; b < BT; ++b) {
+                                    float xf[8];
+                                    unpack8<DT>(*reinterpret_cast<const u32x4 *>(s_xm + (size_t)b * a.lr_chunk + q * 8), xf);
 #pragma unroll
-                                for (int e = 0; e < 8; ++e) part[sl][b] = __builtin_fmaf(f[e], xf[e], part[sl][b]);
+                                    for (int e = 0; e < 8; ++e) part[sl][b] = __builtin_fmaf(f[e], xf[e], part[sl][b]);
+                                }
                             }
                         }
                     }
+                } else {
+                // kRowBatches batches of LU loads in flight per lane; unconditional loads (positions past the row's
+                // end re-read its last piece and are dropped) so that the compiler counts the outstanding ones
+                // exactly -- with one batch at a time a wave needed one dependent round trip per 8 KiB of its row
+                // (seven for a 28672-channel down projection) through a saturated memory system
+                u32x4 v[kRowBatches][LU];
+                const int q_last = nq - 1;
+                constexpr int kStep = 64 * LU;
+                auto request = [&](u32x4 (&dst)[LU], int q0) {
+#pragma unroll
+                    for (int u = 0; u < LU; ++u) dst[u] = ldg16<true>(row + min(q0 + u * 64, q_last) * 8);      // streamed once
+                };
+                int q0 = lane;
+#pragma unroll
+                for (int j = 0; j < kRowBatches; ++j)
+                    if (j * kStep < nq) request(v[j], q0 + j * kStep);
+                bool more = nq > 0;                      // wave-uniform
+                while (more) {
+#pragma unroll
+                    for (int j = 0; j < kRowBatches; ++j) {
+                        if (more) {
+#pragma unroll
+                            for (int u = 0; u < LU; ++u) {
+                                const int q = q0 + u * 64;
+                                if (q < nq) {
+                                    float f[8];
+                                    unpack8<DT>(v[j][u], f);
+#pragma unroll
+                                    for (int b = 0; b < BT; ++b) {
+                                        float xf[8];
+                                        unpack8<DT>(*reinterpret_cast<const u32x4 *>(s_xm + (size_t)b * a.lr_chunk + q * 8), xf);
+#pragma unroll
+                                        for (int e = 0; e < 8; ++e) part[sl][b] = __builtin_fmaf(f[e], xf[e], part[sl][b]);
+                                    }
+                                }
+                            }
+                            const int qn = q0 + kRowBatches * kStep;
+                            if (qn - lane < nq) request(v[j], qn);
+                            q0 += kStep;
+                            more = q0 - lane < nq;
+                        }
+                    }
+                }
                 }
             }
         }

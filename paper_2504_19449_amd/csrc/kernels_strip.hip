@@ -86,6 +86,8 @@ __device__ __forceinline__ int job_of(const int (&wg_end)[kMaxGroupLayers], int 
 // workgroup (so that a wave's part of a row is one batch of loads for the usual row lengths); the parts meet in
 // LDS.  a.lr_rows = rows per workgroup = waves / ws.
 // ---------------------------------------------------------------------------------------------
+constexpr int kS1Batches = 2;      // batches of row loads a stage-1 wave keeps in flight
+
 template <int DT, int BT, typename Args>
 __device__ __forceinline__ void stage1_tagged(const Args &a, unsigned char *smem, int wg, int z)
 {
@@ -117,16 +119,22 @@ __device__ __forceinline__ void stage1_tagged(const Args &a, unsigned char *smem
         int s_lo, s_hi;                                     // my part of the chunk, in 16-byte pieces
         balanced_share(nq, ws, seg, s_lo, s_hi);
         const uint16_t *rowp = L.SVt + (size_t)(have ? row : 0) * d_in + c0;
-        u32x4 v[LU];
-        auto request = [&](int q0) {
+        // up to kS1Batches batches of LU loads in flight per lane.  The loads are unconditional (positions past the
+        // wave's part re-read its last piece and are dropped when consumed) so that the compiler counts the
+        // outstanding ones exactly and a wave really keeps the later batches in flight while it consumes the first;
+        // with one batch at a time a wave of the 28672-channel down projection needed four dependent round trips
+        // through a memory system that the strip waves keep saturated, and the strips waited 9 us for t
+        u32x4 v[kS1Batches][LU];
+        const int q_last = max(nq - 1, 0);
+        auto request = [&](u32x4 (&dst)[LU], int q0) {
 #pragma unroll
-            for (int u = 0; u < LU; ++u) {
-                const int q = q0 + u * 64;
-                v[u] = (have && q < s_hi) ? ldg16<true>(rowp + q * 8) : u32x4{0, 0, 0, 0};
-            }
+            for (int u = 0; u < LU; ++u) dst[u] = ldg16<true>(rowp + min(q0 + u * 64, q_last) * 8);
         };
+        constexpr int kStep = 64 * LU;
         int q0 = s_lo + lane;
-        request(q0);                                        // before the token: these loads need only the row
+#pragma unroll
+        for (int i = 0; i < kS1Batches; ++i)
+            if (s_lo + i * kStep < s_hi) request(v[i], q0 + i * kStep);     // before the token: these loads need only the row
         if (c0 > 0) __syncthreads();
         constexpr int PB = TokenBatch<BT>::kGroups;
         for (int p0 = tid; p0 < nq; p0 += nthr * PB) {
@@ -156,25 +164,32 @@ __device__ __forceinline__ void stage1_tagged(const Args &a, unsigned char *smem
             RS_STAMP(2);
             generation_was_read(L.sync, gen, (int)blockIdx.x * nw + w);
         }
-        while (true) {
+        bool more = s_lo < s_hi;                            // wave-uniform
+        while (more) {
 #pragma unroll
-            for (int u = 0; u < LU; ++u) {
-                const int q = q0 + u * 64;
-                if (have && q < s_hi) {
-                    float f[8];
-                    unpack8<DT>(v[u], f);
+            for (int i = 0; i < kS1Batches; ++i) {
+                if (more) {
 #pragma unroll
-                    for (int b = 0; b < BT; ++b) {
-                        float xf[8];
-                        unpack8<DT>(*reinterpret_cast<const u32x4 *>(s_xm + (size_t)b * a.lr_chunk + q * 8), xf);
+                    for (int u = 0; u < LU; ++u) {
+                        const int q = q0 + u * 64;
+                        if (have && q < s_hi) {
+                            float f[8];
+                            unpack8<DT>(v[i][u], f);
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) part[b] = __builtin_fmaf(f[e], xf[e], part[b]);
+                            for (int b = 0; b < BT; ++b) {
+                                float xf[8];
+                                unpack8<DT>(*reinterpret_cast<const u32x4 *>(s_xm + (size_t)b * a.lr_chunk + q * 8), xf);
+#pragma unroll
+                                for (int e = 0; e < 8; ++e) part[b] = __builtin_fmaf(f[e], xf[e], part[b]);
+                            }
+                        }
                     }
+                    const int qn = q0 + kS1Batches * kStep;
+                    if (qn - lane < s_hi) request(v[i], qn);
+                    q0 += kStep;
+                    more = q0 - lane < s_hi;
                 }
             }
-            q0 += 64 * LU;
-            if (q0 - lane >= s_hi) break;                   // wave-uniform
-            request(q0);
         }
     }
     RS_STAMP(3);
@@ -286,7 +301,7 @@ __device__ __forceinline__ void strip_body(const StripGroupArgs &ga, unsigned ch
 
     TileRules<BT> rules;
     load_rules<BT>(L, b0, nb, rules);
-    constexpr int SC = BT >= 8 ? 1 : 8 / BT;           // 64-channel pieces of the token held in registers per round
+    constexpr int SC = BT >= 8 ? 1 : (BT == 1 ? 6 : 8 / BT);           // 64-channel pieces of the token held in registers per round
     const int c_lo = q_lo * 8, c_hi = q_hi * 8;
     int c = c_lo, pub = 0;
     bool last;
