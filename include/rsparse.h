@@ -161,6 +161,10 @@ rsparse_status rsparse_prepare_factors(const rsparse_config *cfg, const void *W_
  * with dense_rowmajor = 1 (a second, row-major copy of the codes, scales and zero points: + d_in * d_out / 2 bytes)
  * as a row-dot GEMV over row-major codes, the form a dense 4-bit decoder would use (tuning dense_kernel = 1 forces the
  * other form); without it through the channel-major kernel with every channel kept.
+ * Non-finite inputs: NaN behaves as on 16-bit weights (never kept, reaches every output through the low-rank part; with
+ * rank 0 it is simply dropped).  A KEPT channel whose value is +-Inf makes the outputs of that token NaN here, where
+ * W~ x by the definition above would give +-Inf or NaN output by output: the group sums sum x_c q_c - z sum x_c meet
+ * Inf - Inf.  -0 is 0.
  */
 rsparse_status rsparse_prepare_q4(const rsparse_config *cfg, const uint8_t *Q_host, const void *S16_host,
                                   const uint8_t *Z_host, int32_t group_size, const void *U16_host,
@@ -246,6 +250,20 @@ rsparse_status rsparse_dense_ref_group(rsparse_layer *const *layers, int32_t n_l
                                        int32_t batch, void *const *Y_devs, void *stream);
 
 /*
+ * rsparse_linear_group with the per-layer decision of rsparse_plan_layer applied: if the byte model plus the fixed
+ * launch costs say that R-Sparse does not pay for these layers at this batch (small attention projections at any
+ * batch; every layer from about 8 tokens on), the call runs rsparse_dense_ref_group instead -- the exact dense product,
+ * which Sec. 3.5's per-layer recipe allows as the limit of zero sparsity.  keep_fraction: the share of channels one
+ * token keeps at the layers' threshold (1 - the sparsity the threshold was calibrated for).  The decision is taken for
+ * every layer with the group's size as `group`; if the layers disagree, each runs on its own as decided.  *used_rsparse_out (may be NULL): 1 if the R-Sparse path ran
+ * for all layers, 0 if the dense one did for at least one.  After a dense run rsparse_last_active reports the previous
+ * R-Sparse call.  Same arguments, asynchrony and errors as rsparse_linear_group.
+ */
+rsparse_status rsparse_linear_group_planned(rsparse_layer *const *layers, int32_t n_layers, const void *X_dev,
+                                            int32_t batch, void *const *Y_devs, void *stream, double keep_fraction,
+                                            int32_t *used_rsparse_out);
+
+/*
  * Kept-channel index set of the last rsparse_linear call on this handle (synchronises that
  * call's stream).  token in [0, batch): that token's ascending list; token == -1: the ascending
  * union over the batch.  idx_host: host, room for d_in int32; *count receives the length.
@@ -257,7 +275,10 @@ rsparse_status rsparse_last_active(rsparse_layer *layer, int32_t token, int32_t 
  * Wait for the last rsparse_linear call on this handle (synchronises that call's stream) and report
  * device-side trouble: RSPARSE_EHIP if a bounded cross-workgroup wait of the one-launch kernel ran
  * out (the result of that call is then invalid; the handle stays usable).  For callers that want a
- * checked result; the hot path itself never synchronises.
+ * checked result; the hot path itself never synchronises and keeps returning RSPARSE_OK: after a wait has run out,
+ * nothing computed on this handle may be trusted until rsparse_synchronize (or rsparse_last_active) has been called
+ * on it -- that call reports the error once and puts the handle's counters, accumulators and hand-off entries back to
+ * their idle state; calls enqueued before it may have read leftovers of the failed one.
  */
 rsparse_status rsparse_synchronize(rsparse_layer *layer);
 

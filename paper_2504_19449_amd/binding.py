@@ -13,7 +13,7 @@ _STATUS = {1: "EINVAL", 2: "ENOMEM", 3: "EHIP", 4: "EBATCH", 5: "EALIGN", 6: "ES
 
 EXPORTED_SYMBOLS = [
     "rsparse_prepare", "rsparse_compute_factors", "rsparse_prepare_factors", "rsparse_prepare_q4", "rsparse_linear", "rsparse_linear_static",
-    "rsparse_linear_gated", "rsparse_gated_input", "rsparse_mlp_gate_up", "rsparse_dense_ref", "rsparse_linear_group", "rsparse_dense_ref_group", "rsparse_last_active", "rsparse_synchronize",
+    "rsparse_linear_gated", "rsparse_gated_input", "rsparse_mlp_gate_up", "rsparse_dense_ref", "rsparse_linear_group", "rsparse_dense_ref_group", "rsparse_linear_group_planned", "rsparse_last_active", "rsparse_synchronize",
     "rsparse_get_factors", "rsparse_set_tau", "rsparse_set_bias", "rsparse_multiphase_bias", "rsparse_set_tuning",
     "rsparse_get_config", "rsparse_calibrate_tau", "rsparse_required_bytes", "rsparse_dense_bytes", "rsparse_io_model",
     "rsparse_recipe", "rsparse_plan_layer", "rsparse_search_recipe", "rsparse_debug_stamps", "rsparse_destroy", "rsparse_last_error",
@@ -83,6 +83,8 @@ def load_library():
     lib.rsparse_mlp_gate_up.argtypes = [vp, vp, vp, i32, vp, vp]
     lib.rsparse_linear_group.argtypes = [vp, i32, vp, i32, vp, vp]
     lib.rsparse_dense_ref_group.argtypes = [vp, i32, vp, i32, vp, vp]
+    lib.rsparse_linear_group_planned.argtypes = [vp, i32, vp, i32, vp, vp, C.c_double, C.POINTER(i32)]
+    lib.rsparse_linear_group_planned.restype = C.c_int
     lib.rsparse_last_active.argtypes = [vp, i32, vp, C.POINTER(i32)]
     lib.rsparse_synchronize.argtypes = [vp]
     lib.rsparse_get_factors.argtypes = [vp, vp, vp]
@@ -264,6 +266,14 @@ def rsparse_linear_group(layers, X_dev: int, batch: int, Y_devs, stream: int = 0
     """Layers sharing one input (q/k/v, gate/up): one pair of launches for all of them."""
     n, hs, ys = _group_arrays(layers, Y_devs)
     _check(load_library().rsparse_linear_group(hs, n, X_dev, batch, ys, stream))
+
+
+def rsparse_linear_group_planned(layers, X_dev: int, batch: int, Y_devs, keep_fraction: float, stream: int = 0) -> bool:
+    """R-Sparse or dense, as rsparse_plan_layer decides for these layers at this batch; returns True if R-Sparse ran."""
+    n, hs, ys = _group_arrays(layers, Y_devs)
+    used = C.c_int32()
+    _check(load_library().rsparse_linear_group_planned(hs, n, X_dev, batch, ys, stream, keep_fraction, C.byref(used)))
+    return bool(used.value)
 
 
 def rsparse_dense_ref_group(layers, X_dev: int, batch: int, Y_devs, stream: int = 0):

@@ -974,6 +974,32 @@ rsparse_status rsparse_dense_ref_group(rsparse_layer *const *layers, int32_t n_l
     return RSPARSE_OK;
 }
 
+rsparse_status rsparse_linear_group_planned(rsparse_layer *const *layers, int32_t n_layers, const void *X_dev,
+                                            int32_t batch, void *const *Y_devs, void *stream, double keep_fraction,
+                                            int32_t *used_rsparse_out)
+{
+    rsparse_status st = check_group(layers, n_layers, X_dev, batch, Y_devs);
+    if (st != RSPARSE_OK) return st;
+    int32_t use[RSPARSE_MAX_GROUP];
+    bool all = true, none = true;
+    for (int i = 0; i < n_layers; ++i) {
+        const rsparse_config &c = layers[i]->cfg;
+        st = rsparse_plan_layer(c.d_in, c.d_out, c.rank, keep_fraction, n_layers, batch, nullptr, nullptr, &use[i]);
+        if (st != RSPARSE_OK) return st;
+        all = all && use[i];
+        none = none && !use[i];
+    }
+    if (used_rsparse_out) *used_rsparse_out = all ? 1 : 0;
+    if (all) return rsparse_linear_group(layers, n_layers, X_dev, batch, Y_devs, stream);
+    if (none) return rsparse_dense_ref_group(layers, n_layers, X_dev, batch, Y_devs, stream);
+    for (int i = 0; i < n_layers; ++i) {
+        st = use[i] ? rsparse_linear_group(&layers[i], 1, X_dev, batch, &Y_devs[i], stream)
+                    : rsparse_dense_ref_group(&layers[i], 1, X_dev, batch, &Y_devs[i], stream);
+        if (st != RSPARSE_OK) return st;
+    }
+    return RSPARSE_OK;
+}
+
 rsparse_status rsparse_dense_ref(rsparse_layer *L, const void *X_dev, int32_t batch, void *Y_dev, void *stream)
 {
     return rsparse_dense_ref_group(&L, 1, X_dev, batch, &Y_dev, stream);

@@ -362,3 +362,32 @@ def test_q4_dense_rowdot_extreme_codes_group_sizes_and_benchmark_shape():
     layer = q.prepare(0.0, max_batch=1, dense_rowmajor=1)
     gu.check_outputs(gu.run_dense(layer, X16), q.dense(X16), dt)
     layer.destroy()
+
+
+@pytest.mark.parametrize("launches", [1, 2])
+def test_q4_nan_inf_and_negative_zero_inputs(ragged_q4, launches):
+    """NaN is never kept and reaches every output through the low-rank part; -0 is 0; a kept +-Inf channel makes that
+    token's outputs non-finite (NaN here, where the definition W~ x gives +-Inf or NaN output by output -- the
+    documented deviation of the factored group sums)."""
+    dt = synth.BF16
+    q = ragged_q4[dt]
+    X16, src = gu.tokens_for(q.L, 4, config=91)
+    tau = gu.calibrated_tau(q.L, src, 0.5)
+    x = synth.decode16(X16, dt)
+    x[0, 5] = np.nan
+    x[1, 7] = -0.0
+    x[1, 8] = 0.0
+    x[2, 9] = np.inf
+    x[3, 11] = -np.inf
+    X16 = synth.encode16(x, dt)
+    layer = q.prepare(tau, max_batch=4, out_dtype=rs.F32)
+    rs.rsparse_set_tuning(layer, launches=launches)
+    got = gu.run_linear(layer, X16)
+    want = q.oracle(X16, tau)
+    gu.check_lists(got, want)
+    assert np.all(np.isnan(got["Y"][0])) and np.all(np.isnan(want["Y"][0]))
+    gu.check_outputs(got["Y"][1:2], want["Y"][1:2], rs.F32)
+    for b in (2, 3):
+        assert not np.any(np.isfinite(want["Y"][b]))                  # the definition: +-Inf, or NaN where W~[o][c] = 0
+        assert np.all(~np.isfinite(got["Y"][b]))
+    layer.destroy()

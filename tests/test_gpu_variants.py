@@ -202,3 +202,25 @@ def test_topk_through_the_entry_point_that_allocates_nothing():
     for b in range(4):
         assert np.array_equal(rs.rsparse_last_active(layer, b), want["act"][b])
     layer.destroy()
+
+
+def test_planned_call_runs_dense_where_the_byte_model_says_so():
+    """rsparse_linear_group_planned: a small attention projection and any layer at 8 tokens run the dense kernel (exact
+    dense product), a large MLP layer at one token runs R-Sparse; results match the corresponding oracle either way."""
+    dt = synth.BF16
+    torch = gu.torch_mod()
+    small = synth.random_layer(4096, 4096, 256, dt, seed=21)
+    big = synth.random_layer(4096, 14336, 256, dt, seed=22)
+    for L, B, expect in ((small, 1, False), (big, 1, True), (big, 8, False)):
+        X16, src = gu.tokens_for(L, B)
+        tau = gu.calibrated_tau(L, src, 0.5)
+        layer = gu.prepare(L, tau, max_batch=8, dense_rowmajor=1)
+        Xd = gu.to_dev16(X16)
+        Y = torch.zeros((B, L.d_out), dtype=torch.int16, device="cuda")
+        used = rs.rsparse_linear_group_planned([layer], Xd.data_ptr(), B, [Y.data_ptr()], 0.5, gu.stream_ptr())
+        torch.cuda.synchronize()
+        assert used == expect == rs.rsparse_plan_layer(L.d_in, L.d_out, L.rank, 0.5, 1, B)[2]
+        got = synth.decode16(Y.cpu().numpy().view(np.uint16), dt)
+        want = gu.oracle_linear(L, X16, tau)["Y"] if used else oracle.dense_linear(L.W16, X16, dt, dt, nthreads=8)
+        gu.check_outputs(got, want, dt)
+        layer.destroy()
