@@ -5,6 +5,7 @@ W being an SVD product); every output of every token is compared with the fp64 o
 import numpy as np
 import pytest
 
+import oracle
 import paper_2504_19449_amd as rs
 from paper_2504_19449_amd import synth
 
@@ -94,3 +95,24 @@ def test_strip_layout_at_benchmark_shapes(shape):
     d_in, d_out, rank, kind, W = shape
     _case(d_in, d_out, rank, kind, 1, seed=770 + W, strip_cols=W)
     _case(d_in, d_out, rank, kind, 4, seed=771 + W, strip_cols=W, out_dtype=rs.F32)
+
+
+@pytest.mark.parametrize("strip_cols", [0, 128])
+def test_the_widest_input_the_library_accepts(strip_cols):
+    """d_in = 65536 is the documented maximum (the token scan's LDS): one and three tokens, threshold and fixed-count
+    activation, on both layouts; one more channel group is rejected on the host."""
+    dt = synth.BF16
+    L = synth.random_layer(65536, 264, 16, dt, seed=31)
+    X16, src = gu.tokens_for(L, 3)
+    tau = gu.calibrated_tau(L, src, 0.5)
+    for kw, okw in ((dict(), dict()), (dict(topk=30000), dict(topk=30000))):
+        layer = gu.prepare(L, tau, max_batch=4, strip_cols=strip_cols, **kw)
+        for B in (1, 3):
+            want = gu.oracle_linear(L, X16[:B], tau, **okw)
+            got = gu.run_linear(layer, X16[:B])
+            gu.check_lists(got, want)
+            gu.check_outputs(got["Y"], want["Y"], dt)
+        gu.check_outputs(gu.run_dense(layer, X16[:1]), oracle.dense_linear(L.W16, X16[:1], dt, dt, nthreads=8), dt)
+        layer.destroy()
+    with pytest.raises(rs.RSparseError):
+        rs.rsparse_prepare_factors(rs.make_config(65536 + 8, 264, 0, tau, dt), np.zeros((264, 65544), dtype=np.uint16), None, None)
