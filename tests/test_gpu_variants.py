@@ -224,3 +224,41 @@ def test_planned_call_runs_dense_where_the_byte_model_says_so():
         want = gu.oracle_linear(L, X16, tau)["Y"] if used else oracle.dense_linear(L.W16, X16, dt, dt, nthreads=8)
         gu.check_outputs(got, want, dt)
         layer.destroy()
+
+
+@pytest.mark.parametrize("strip_cols", [0, 64])
+def test_topk_with_bias_in_a_replayed_graph(strip_cols):
+    """The rule-writing kernel of the fixed-count activation is part of the captured call: every replay, with new token
+    values in the same buffer and an eager call between replays, selects afresh and matches the oracle."""
+    torch = gu.torch_mod()
+    dt = synth.BF16
+    L = _layer(1032, 520, 32, dt, seed=9)
+    X16, _ = gu.tokens_for(L, 8)
+    bias = np.random.Generator(np.random.PCG64(6)).standard_normal(520).astype(np.float32)
+    B, k = 2, 300
+    layer = gu.prepare(L, 0.0, max_batch=B, out_dtype=rs.F32, strip_cols=strip_cols, topk=k)
+    rs.rsparse_set_bias(layer, bias)
+    Xd = gu.to_dev16(X16[:B])
+    Y = gu._alloc_out(layer, B)
+    Ye = gu._alloc_out(layer, B)
+    rs.rsparse_linear(layer, Xd.data_ptr(), B, Y.data_ptr(), gu.stream_ptr())
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        rs.rsparse_linear(layer, Xd.data_ptr(), B, Y.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    for rep in range(4):
+        xb = X16[rep * B:(rep + 1) * B]
+        Xd.copy_(torch.from_numpy(np.ascontiguousarray(xb).view(np.int16)))
+        Y.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        got = Y.cpu().numpy().astype(np.float64)
+        rs.rsparse_linear(layer, Xd.data_ptr(), B, Ye.data_ptr(), gu.stream_ptr())
+        torch.cuda.synchronize()
+        want = gu.oracle_linear(L, xb, 0.0, topk=k, bias=bias.astype(np.float64))
+        gu.check_outputs(got, want["Y"], rs.F32)
+        eager = Ye.cpu().numpy().astype(np.float64)
+        assert np.linalg.norm(got - eager) <= 1e-5 * np.linalg.norm(eager)
+        for b in range(B):
+            assert np.array_equal(rs.rsparse_last_active(layer, b), want["act"][b])
+    layer.destroy()
