@@ -23,14 +23,15 @@ EXPORTED_SYMBOLS = [
 class Config(C.Structure):
     _fields_ = [("d_in", C.c_int32), ("d_out", C.c_int32), ("rank", C.c_int32), ("max_batch", C.c_int32),
                 ("tau", C.c_float), ("dtype", C.c_int32), ("out_dtype", C.c_int32), ("cmp_mode", C.c_int32),
-                ("batch_mask_mode", C.c_int32), ("dense_rowmajor", C.c_int32), ("strip_cols", C.c_int32), ("topk", C.c_int32)]
+                ("batch_mask_mode", C.c_int32), ("dense_rowmajor", C.c_int32), ("strip_cols", C.c_int32), ("topk", C.c_int32),
+                ("lowrank_channel_major", C.c_int32)]
 
 
 class Tuning(C.Structure):
     _fields_ = [("splits", C.c_int32), ("waves", C.c_int32), ("lowrank_rows", C.c_int32),
                 ("dense_kernel", C.c_int32), ("nontemporal", C.c_int32), ("stages", C.c_int32),
                 ("tile_map", C.c_int32), ("mfma_min_batch", C.c_int32), ("mfma_rows", C.c_int32),
-                ("launches", C.c_int32), ("debug_wait_polls", C.c_int32), ("debug_skip_stage1", C.c_int32)]
+                ("launches", C.c_int32), ("lowrank_wgs", C.c_int32), ("debug_wait_polls", C.c_int32), ("debug_skip_stage1", C.c_int32)]
 
 
 LOSS_FN = C.CFUNCTYPE(C.c_double, C.POINTER(C.c_double), C.c_int32, C.c_void_p)
@@ -164,9 +165,9 @@ class Layer:
 
 
 def _make_config(d_in, d_out, rank, tau, dtype, max_batch=1, out_dtype=None, cmp_mode=0,
-                 batch_mask_mode=0, dense_rowmajor=0, strip_cols=0, topk=0) -> Config:
+                 batch_mask_mode=0, dense_rowmajor=0, strip_cols=0, topk=0, lowrank_channel_major=0) -> Config:
     return Config(d_in, d_out, rank, max_batch, float(tau), dtype, dtype if out_dtype is None else out_dtype,
-                  cmp_mode, batch_mask_mode, dense_rowmajor, strip_cols, topk)
+                  cmp_mode, batch_mask_mode, dense_rowmajor, strip_cols, topk, lowrank_channel_major)
 
 
 def rsparse_prepare(cfg: Config, W16) -> Layer:

@@ -138,6 +138,8 @@ struct rsparse_layer {
     bool last_strip = false;               // the last call went through the strip kernel ...
     int last_ranges = 0;                   // ... with this many channel ranges (splits x waves)
     float *t = nullptr, *yacc = nullptr;
+    uint16_t *SVc = nullptr;               // [d_in][rank] channel-major copy of S_r V_r^T (cfg.lowrank_channel_major)
+    float *t_sum = nullptr;                // [rank] fp32 sums of the stage 1 that reads it (zero between calls)
     float *t_acc = nullptr;                // [rank][32] accumulated t of the matrix-core path (zero between calls)
     uint16_t *t16 = nullptr;               // [2][32][rank] its two 16-bit halves
     uint32_t *act_bits = nullptr, *chan_bits = nullptr;
@@ -180,7 +182,7 @@ struct rsparse_layer {
     {
         const ScratchView sp = ov ? *ov : own_scratch();
         LayerView v{};
-        v.M = M; v.SVt = SVt; v.U = U; v.Wrow = Wrow; v.t = sp.t; v.yacc = sp.yacc; v.t_acc = ov ? nullptr : t_acc; v.t16 = ov ? nullptr : t16;
+        v.M = M; v.SVt = SVt; v.U = U; v.Wrow = Wrow; v.t = sp.t; v.yacc = sp.yacc; v.t_acc = ov ? nullptr : t_acc; v.SVc = SVc; v.t_sum = ov ? nullptr : t_sum; v.t16 = ov ? nullptr : t16;
         v.act_list = sp.act_list; v.act_bits = sp.act_bits; v.act_count = sp.act_count; v.sync = sp.sync; v.t_pub = sp.t_pub;
         v.d_in = cfg.d_in; v.d_out = cfg.d_out; v.rank = cfg.rank;
         v.dtype = cfg.dtype; v.out_dtype = cfg.out_dtype; v.cmp_mode = cfg.cmp_mode;
@@ -223,6 +225,7 @@ rsparse_status check_config(const rsparse_config *c)
     if (c->topk < 0 || c->topk > c->d_in) return fail(RSPARSE_EINVAL, "topk %d outside [0, d_in]", c->topk);
     if (c->topk > 0 && c->cmp_mode != 0) return fail(RSPARSE_EINVAL, "the fixed-count activation (topk > 0) needs cmp_mode 0");
     if (c->dense_rowmajor != 0 && c->dense_rowmajor != 1) return fail(RSPARSE_EINVAL, "dense_rowmajor must be 0 or 1");
+    if (c->lowrank_channel_major != 0 && c->lowrank_channel_major != 1) return fail(RSPARSE_EINVAL, "lowrank_channel_major must be 0 or 1");
     if (c->strip_cols != 0 && !strip_width_ok(c->strip_cols)) return fail(RSPARSE_EINVAL, "strip_cols must be 0, 32, 64, 128, 256 or 512");
     return RSPARSE_OK;
 }
@@ -279,6 +282,15 @@ Launch resolve_launch(const rsparse_layer *L, int batch, bool dense, int group, 
         const int free_slots = 2 * L->cus / std::max(1, group) - L->tiles * splits;
         const int need = free_slots > 0 ? (L->cfg.rank + free_slots - 1) / free_slots : 4 * c.waves;
         c.lowrank_rows = std::max(std::max(1, c.waves / 2), std::min(4 * c.waves, need));
+    }
+    // one token over a channel-major copy of S_r V_r^T: stage 1 reads the dropped channels' rows only, each of its
+    // workgroups on a fixed channel range.  64 workgroups, 128 from 16 MB of expected rows (measured on 4096 x 4096
+    // up to 28672 -> 8192: fewer publish t too late for the gather workgroups' rows of U_r^T, more only add atomics),
+    // shared by the layers of a group
+    if (fused && !dense && bt == 1 && L->SVc && L->cfg.rank > 0) {
+        const double s1_bytes = 2.0 * L->cfg.rank * (L->cfg.d_in - rows);
+        c.lowrank_wgs = t.lowrank_wgs > 0 ? t.lowrank_wgs
+                                          : std::max(16, (s1_bytes >= 16.0 * 1024 * 1024 ? 128 : 64) / std::max(1, group));
     }
     return c;
 }
@@ -339,7 +351,7 @@ void free_layer(rsparse_layer *L)
     (void)hipFree(L->M); (void)hipFree(L->SVt); (void)hipFree(L->U); (void)hipFree(L->Wrow); (void)hipFree(L->t);
     (void)hipFree(L->yacc); (void)hipFree(L->act_bits); (void)hipFree(L->chan_bits);
     (void)hipFree(L->act_list); (void)hipFree(L->act_count); (void)hipFree(L->sync); (void)hipFree(L->t_pub); (void)hipFree(L->xg); (void)hipFree(L->hy);
-    (void)hipFree(L->Ms); (void)hipFree(L->t_tag); (void)hipFree(L->act_seg); (void)hipFree(L->bias); (void)hipFree(L->rules); (void)hipFree(L->t_acc); (void)hipFree(L->t16);
+    (void)hipFree(L->Ms); (void)hipFree(L->t_tag); (void)hipFree(L->act_seg); (void)hipFree(L->bias); (void)hipFree(L->rules); (void)hipFree(L->t_acc); (void)hipFree(L->SVc); (void)hipFree(L->t_sum); (void)hipFree(L->t16);
     (void)hipFree(L->Mq); (void)hipFree(L->qs); (void)hipFree(L->qz); (void)hipFree(L->Ut);
     (void)hipFree(L->Qrow); (void)hipFree(L->Srow); (void)hipFree(L->Zrow);
     delete L;
@@ -463,6 +475,14 @@ rsparse_status build_layer(const rsparse_config *cfg, const uint16_t *W, const u
             RS_HIP(hipMemcpy(L->SVt, SV16, r * d_in * 2, hipMemcpyHostToDevice));
             RS_HIP(hipMalloc((void **)&L->U, d_out * r * 2));
             RS_HIP(hipMemcpy(L->U, U16, d_out * r * 2, hipMemcpyHostToDevice));
+        }
+        if (cfg->lowrank_channel_major && !q4 && r) {
+            std::vector<uint16_t> svc(d_in * r);
+            transpose16(SV16, r, d_in, svc.data());
+            RS_HIP(hipMalloc((void **)&L->SVc, d_in * r * 2));
+            RS_HIP(hipMemcpy(L->SVc, svc.data(), d_in * r * 2, hipMemcpyHostToDevice));
+            RS_HIP(hipMalloc((void **)&L->t_sum, r * 4));
+            RS_HIP(hipMemset(L->t_sum, 0, r * 4));
         }
         if (cfg->dense_rowmajor && !q4) {
             RS_HIP(hipMalloc((void **)&L->Wrow, d_in * d_out * 2));
@@ -1173,7 +1193,7 @@ rsparse_status rsparse_set_tuning(rsparse_layer *L, const rsparse_tuning *t)
 {
     if (!L || !t) return fail(RSPARSE_EINVAL, "NULL argument");
     if (t->nontemporal < 0 || t->nontemporal > 2) return fail(RSPARSE_EINVAL, "nontemporal must be 0, 1 or 2");
-    if (t->splits < 0 || t->waves < 0 || t->lowrank_rows < 0 || t->dense_kernel < 0 || t->dense_kernel > 2)
+    if (t->splits < 0 || t->waves < 0 || t->lowrank_rows < 0 || t->lowrank_wgs < 0 || t->lowrank_wgs > 65536 || t->dense_kernel < 0 || t->dense_kernel > 2)
         return fail(RSPARSE_EINVAL, "negative or unknown tuning value");
     if (t->mfma_rows != 0 && t->mfma_rows != 64 && t->mfma_rows != 128 && t->mfma_rows != 256)
         return fail(RSPARSE_EINVAL, "mfma_rows must be 0, 64, 128 or 256");

@@ -156,6 +156,8 @@ struct GatherArgs {
     const uint16_t *X;
     int batch, splits, tiles, cap;
     int lr_wgs, lr_rows, lr_chunk;     // stage-1 workgroups at the front of the grid, rows each, LDS chunk
+    int lr_gather, lr_cap;             // one-launch kernel, one token: stage 1 over the channel-major copy of S_r V_r^T
+                                       // (lowrank_gather); lr_cap = list slots of a stage-1 workgroup
     int tile_map;
     void *Y;                           // one-launch path only: the output, [batch][d_out]
     int nz;                            // one-launch path only: batch tiles in the grid
@@ -192,6 +194,113 @@ __device__ __forceinline__ bool map_tile(int tile_map, int tiles, int splits, in
 __device__ __forceinline__ bool map_tile(const GatherArgs &a, int g, int &tile, int &split)
 {
     return map_tile(a.tile_map, a.tiles, a.splits, g, tile, split);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Stage 1 of the low-rank part over the channel-major copy SVc [d_in][rank] (row c = (S_r V_r^T)[:, c]), one
+// token: t = sum over the DROPPED channels c of x_c SVc[c, :] (Sec. 3.4: the low-rank part acts on x - sigma_t(x),
+// whose kept channels are zero), so only the rows of dropped channels are read -- rank * (d_in - k) elements
+// instead of rank * d_in.  Stage-1 workgroup wg of lr_wgs owns a fixed range of channels: it thresholds that range
+// only, compacts the dropped channels with wave scans, streams their rows (a wave covers 512 columns of a row per
+// load, the waves of a 512-column part share the list in batches of kUnroll rows), sums its waves in LDS and adds
+// the range's partial t to t_sum with fp32 atomics.  The last workgroup to arrive swaps the sums out (which
+// re-zeroes them) and publishes t.  No workgroup waits for another here.
+// ---------------------------------------------------------------------------------------------
+template <int DT, bool NT, bool EXT>
+__device__ __forceinline__ void lowrank_gather(const GatherArgs &a, unsigned char *smem, int wg)
+{
+    const int tid = threadIdx.x, nthr = blockDim.x, lane = tid & 63, w = uniform(tid >> 6), nw = nthr >> 6;
+    const LayerView &L = a.L;
+    const int d_in = L.d_in, r = L.rank, cap = a.lr_cap;
+    TileRules<1> rules;
+    load_rules<1, EXT>(L, 0, 1, rules);
+    float *s_red = reinterpret_cast<float *>(smem);                 // [nw][kTile]
+    float *s_coef = s_red + (size_t)nw * kTile;                     // [cap]
+    int *s_idx = reinterpret_cast<int *>(s_coef + cap);             // [cap]
+    int *s_wtot = s_idx + cap;                                      // [nw], then the arrival flag
+    int q_lo, q_hi;
+    balanced_share(d_in / 8, a.lr_wgs, wg, q_lo, q_hi);             // my chunks of 8 channels
+    // every list slot starts as a valid row with a zero coefficient
+    for (int i = tid; i < cap; i += nthr) { s_idx[i] = 0; s_coef[i] = 0.f; }
+    int n = 0;
+    for (int qb = q_lo; qb < q_hi; qb += nthr) {
+        const int q = qb + tid;
+        u32x4 raw[1] = {u32x4{0, 0, 0, 0}};
+        uint32_t drop = 0u;
+        if (q < q_hi) {
+            load_raw8<1>(a.X, 0, 1, d_in, q * 8, raw);
+            uint32_t m[1];
+            masks_of8<DT, 1>(L, a.X, 1, 0, 1, d_in, q * 8, rules, false, raw, m);
+            drop = ~m[0] & 0xffu;
+        }
+        const int c = __popc(drop);
+        const int inc = wave_inclusive_scan(c);
+        if (lane == 63) s_wtot[w] = inc;
+        __syncthreads();
+        int woff = 0, tot = 0;
+        for (int i = 0; i < nw; ++i) {
+            const int v = s_wtot[i];
+            woff += i < w ? v : 0;
+            tot += v;
+        }
+        if (drop != 0u) {
+            float f[8];
+            unpack8<DT>(raw[0], f);
+            int p = n + woff + inc - c;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (((drop >> e) & 1u) && p < cap) {
+                    s_idx[p] = q * 8 + e;
+                    s_coef[p] = f[e];
+                    ++p;
+                }
+        }
+        n += tot;
+        __syncthreads();
+    }
+    n = min(uniform(n), cap);
+
+    // ---- stream the dropped channels' rows: wave w -> 512-column part w % parts, row group w / parts
+    const int parts = (r + kTile - 1) / kTile;                      // host: parts <= nw
+    const int ng = nw / parts;
+    const int part = w % parts, g = w / parts;
+    const int col = part * kTile + lane * 8;
+    const bool colok = col < r;
+    float acc[1][8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[0][e] = 0.f;
+    if (g < ng) {
+        u32x4 va[kUnroll];
+        const int j_first = g * kUnroll, step = ng * kUnroll;
+        load_batch<NT>(L.SVc, (size_t)r, col, colok, s_idx, n, j_first, va);
+        stream_rest<DT, 1, NT>(L.SVc, (size_t)r, col, colok, s_idx, s_coef, n, j_first, step, va, acc, [](int) {});
+    }
+    float4 *dst = reinterpret_cast<float4 *>(s_red + w * kTile + lane * 8);
+    dst[0] = float4{acc[0][0], acc[0][1], acc[0][2], acc[0][3]};
+    dst[1] = float4{acc[0][4], acc[0][5], acc[0][6], acc[0][7]};
+    __syncthreads();
+    for (int i = tid; i < parts * kTile; i += nthr) {
+        const int pt = i / kTile, cl = i % kTile;
+        float sum = 0.f;
+        for (int gg = 0; gg < ng; ++gg) sum += s_red[(gg * parts + pt) * kTile + cl];
+        if (i < r) __hip_atomic_fetch_add(L.t_sum + i, sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+
+    // ---- arrive; the last stage-1 workgroup publishes t
+    wait_own_writes();
+    __syncthreads();
+    if (tid == 0) {
+        const int arrived = __hip_atomic_fetch_add(L.sync + kSyncStage1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_wtot[nw] = arrived == a.lr_wgs - 1;
+        if (arrived == a.lr_wgs - 1) __hip_atomic_store(L.sync + kSyncStage1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (!s_wtot[nw]) return;
+    for (int i = tid; i < r; i += nthr) {
+        uint32_t bits = as_u(__hip_atomic_exchange(L.t_sum + i, 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        if (bits == kNotReady) bits = 0x7fc00000u;
+        if (!a.skip_stage1) __hip_atomic_store(L.t_pub + i, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 }
 
 // Several layers that read the same input share one launch: job i owns workgroups
@@ -400,6 +509,12 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
     const int d_in = pin(L.d_in), d_out = pin(L.d_out), batch = pin(a.batch), cap = pin(a.cap);
     const bool union_all = pin(L.batch_mask_mode) == 1;
     if (__builtin_expect(wg < lr_wgs, 0)) {
+        if constexpr (FUSED && BT == 1 && !Q4) {
+            if (a.lr_gather) {
+                lowrank_gather<DT, NT, EXT>(a, smem, wg);
+                return;
+            }
+        }
         lowrank_rows<DT, BT, FUSED ? kPubNotReady : kPubPlain, GatherArgs, EXT>(a, smem, wg, z);
         return;
     }
@@ -1190,6 +1305,16 @@ hipError_t launch_fused(const LayerView *L, const Launch *cfg, int n, const void
         a.lr_rows = cfg[i].lowrank_rows;
         a.lr_wgs = L[i].rank > 0 ? (L[i].rank + cfg[i].lowrank_rows - 1) / cfg[i].lowrank_rows : 0;
         a.lr_chunk = lowrank_chunk(L[i].d_in, bt);
+        size_t lr_lds = a.lr_wgs > 0 ? lowrank_lds_bytes(L[i].d_in, bt) : 0;
+        // one token and a channel-major copy of S_r V_r^T: stage 1 reads only the dropped channels' rows
+        if (bt == 1 && cfg[i].lowrank_wgs > 0 && L[i].rank > 0 && L[i].SVc && L[i].t_sum &&
+            (L[i].rank + kTile - 1) / kTile <= cfg[0].waves) {
+            const int nq = L[i].d_in / 8;
+            a.lr_gather = 1;
+            a.lr_wgs = std::min(cfg[i].lowrank_wgs, nq);
+            a.lr_cap = ((nq + a.lr_wgs - 1) / a.lr_wgs) * 8;
+            lr_lds = (size_t)cfg[0].waves * kTile * 4 + (size_t)a.lr_cap * 8 + (size_t)(cfg[0].waves + 1) * 4;
+        }
         a.tile_map = cfg[i].tile_map;
         a.Y = Y[i];
         a.nz = nz;
@@ -1201,7 +1326,8 @@ hipError_t launch_fused(const LayerView *L, const Launch *cfg, int n, const void
         const size_t need = gather_lds_bytes(L[i].d_in, cfg[i].splits, cfg[0].waves, bt, L[i].rank);
         if (need > 64 * 1024) return hipErrorInvalidValue;
         lds = std::max(lds, need);
-        if (a.lr_wgs > 0) lds = std::max(lds, lowrank_lds_bytes(L[i].d_in, bt));
+        if (lr_lds > 64 * 1024) return hipErrorInvalidValue;
+        lds = std::max(lds, lr_lds);
     }
     for (int i = n; i < kMaxGroup; ++i) ga.wg_end[i] = total;
     ga.gate_up = gate_up ? 1 : 0;
