@@ -33,6 +33,7 @@ HBM_PEAK_GBS = 8000.0
 REPEATS = 10               # timed brackets of `steps` steps each; the median is reported
 K_TOKENS = 32              # tokens per linear for the statistics of k (kept channels)
 STRIP_COLS = 128           # strip width of the strip-layout variant
+CHANNEL_MAJOR_MIN_WEIGHTS = 1 << 26   # column layout: layers from this size on keep S_r V_r^T channel-major as well
 
 
 def log(msg):
@@ -234,7 +235,7 @@ class Ring:
         dt = wl["dtype"]
         rank = wl["rank"] if rank is None else rank
         self.base = base if base is not None else {}
-        self.src, self.tau, self.blocks = {}, {}, []
+        self.src, self.tau, self.blocks, self.channel_major = {}, {}, [], {}
         for li, (name, d_in, d_out, kind) in enumerate(wl["linears"]):
             if name not in self.base:
                 # i.i.d. operands of the workload's scales: kernel time, traffic and parity do not depend on W being an
@@ -253,8 +254,13 @@ class Ring:
                 for name in call:
                     _, d_in, d_out, _ = next(l for l in wl["linears"] if l[0] == name)
                     L = self.base[name]
+                    # column layout: layers of 2^26 weights or more also keep S_r V_r^T channel-major, so that stage 1
+                    # reads the dropped channels' rows only (measured to pay from that size on, to cost time below)
+                    cm = 1 if strip_cols == 0 and rank and d_in * d_out >= CHANNEL_MAJOR_MIN_WEIGHTS else 0
+                    self.channel_major[name] = cm
                     cfg = rs.make_config(d_in, d_out, rank, self.tau[name][sparsity], dt, max_batch=1,
-                                         dense_rowmajor=rowmajor if strip_cols == 0 else 0, strip_cols=strip_cols)
+                                         dense_rowmajor=rowmajor if strip_cols == 0 else 0, strip_cols=strip_cols,
+                                         lowrank_channel_major=cm)
                     layer = rs.rsparse_prepare_factors(cfg, L.W16, L.U16[:, :rank] if rank else None,
                                                        L.SV16[:rank] if rank else None)
                     b[name] = (layer, xd, torch.zeros((1, d_out), dtype=torch.int16, device="cuda"), x16)
@@ -401,11 +407,16 @@ def measure_workload(label, cfg_no, args, mods, timers, want_cpu):
     # exact k of the timed tokens: one pass, then read back every layer of the ring
     col.pass_fn()(stream.cuda_stream)
     torch.cuda.synchronize()
-    req_total = 0
+    req_total, req_less = 0, 0
     for b in col.blocks:
         for name, (layer, *_rest) in b.items():
-            req_total += rs.rsparse_required_bytes(layer, 1, len(rs.rsparse_last_active(layer, -1)))
+            k_b = len(rs.rsparse_last_active(layer, -1))
+            req_total += rs.rsparse_required_bytes(layer, 1, k_b)
+            # secondary denominator: a layer whose stage 1 reads only the dropped channels' rows of S_r V_r^T
+            # requests rank * k fewer elements than the required bytes count
+            req_less += 2 * wl["rank"] * k_b * col.channel_major[name]
     req_step = req_total / blocks                                   # algorithmic bytes of one step
+    requested_step = (req_total - req_less) / blocks
     dense_step = sum(dense_bytes.values())
     log(f"{label}: parity ok on both layouts; k per linear over {K_TOKENS} tokens: {k_stats}")
 
@@ -416,6 +427,14 @@ def measure_workload(label, cfg_no, args, mods, timers, want_cpu):
         res[lay] = {"us_per_linear": round(ms * 1000.0 / n_lin, 3), "launch_mode": mode, "kernel": kern,
                     "us_per_linear_by_launch_mode": {k: round(v * 1000.0 / n_lin, 3) for k, v in modes.items()},
                     "ms_per_step": ms}
+    if any(col.channel_major.values()) and not args.no_extras:
+        col.set_all(lowrank_wgs=-1)                                 # the same ring with stage 1 over the row-major copy
+        ms, mode, modes = best(col.pass_fn(), blocks)
+        col.set_all()
+        res["column_rowmajor_stage1"] = {"us_per_linear": round(ms * 1000.0 / n_lin, 3), "launch_mode": mode,
+                                         "kernel": "k_rsparse_fused",
+                                         "us_per_linear_by_launch_mode": {k: round(v * 1000.0 / n_lin, 3) for k, v in modes.items()},
+                                         "ms_per_step": ms}
     lay = min(res, key=lambda k: res[k]["ms_per_step"])
     ms_step = res[lay]["ms_per_step"]
     us_linear = ms_step * 1000.0 / n_lin
@@ -439,6 +458,9 @@ def measure_workload(label, cfg_no, args, mods, timers, want_cpu):
         "kept_channels": k_stats,
         "required_bytes_per_step": int(req_step), "dense_bytes_per_step": int(dense_step),
         "hbm_gbs_on_required_bytes": round(req_step / (ms_step * 1e-3) / 1e9, 1),
+        "requested_bytes_per_step": int(requested_step if lay == "column" else req_step),
+        "hbm_gbs_on_requested_bytes": round((requested_step if lay == "column" else req_step) / (ms_step * 1e-3) / 1e9, 1),
+        "channel_major_stage1": {k: bool(v) for k, v in col.channel_major.items()},
         "dense_gemv_us_per_linear": {k: round(v, 3) for k, v in dense_us.items()},
         "dense_gemv_gbs": round(dense_step / n_lin / (best_dense * 1e-6) / 1e9, 1),
         "speedup_vs_dense_gemv": round(best_dense / us_linear, 3),
@@ -760,7 +782,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--sparsity", type=float, default=0.5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-extras", action="store_true", help="skip the side measurements on configs[1]")
+    ap.add_argument("--no-extras", action="store_true", help="skip the side measurements (configs[1] extras, the row-major stage-1 variant of configs[4])")
     ap.add_argument("--only", default="", help="comma-separated workloads to run (default: all three)")
     ap.add_argument("--eager", action="store_true", help="time eager launches only (no graph replay)")
     ap.add_argument("--sweep", action="store_true",

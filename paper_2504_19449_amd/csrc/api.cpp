@@ -287,7 +287,7 @@ Launch resolve_launch(const rsparse_layer *L, int batch, bool dense, int group, 
     // workgroups on a fixed channel range.  64 workgroups, 128 from 16 MB of expected rows (measured on 4096 x 4096
     // up to 28672 -> 8192: fewer publish t too late for the gather workgroups' rows of U_r^T, more only add atomics),
     // shared by the layers of a group
-    if (fused && !dense && bt == 1 && L->SVc && L->cfg.rank > 0) {
+    if (fused && !dense && bt == 1 && L->SVc && L->cfg.rank > 0 && t.lowrank_wgs >= 0) {
         const double s1_bytes = 2.0 * L->cfg.rank * (L->cfg.d_in - rows);
         c.lowrank_wgs = t.lowrank_wgs > 0 ? t.lowrank_wgs
                                           : std::max(16, (s1_bytes >= 16.0 * 1024 * 1024 ? 128 : 64) / std::max(1, group));
@@ -1193,7 +1193,7 @@ rsparse_status rsparse_set_tuning(rsparse_layer *L, const rsparse_tuning *t)
 {
     if (!L || !t) return fail(RSPARSE_EINVAL, "NULL argument");
     if (t->nontemporal < 0 || t->nontemporal > 2) return fail(RSPARSE_EINVAL, "nontemporal must be 0, 1 or 2");
-    if (t->splits < 0 || t->waves < 0 || t->lowrank_rows < 0 || t->lowrank_wgs < 0 || t->lowrank_wgs > 65536 || t->dense_kernel < 0 || t->dense_kernel > 2)
+    if (t->splits < 0 || t->waves < 0 || t->lowrank_rows < 0 || t->lowrank_wgs < -1 || t->lowrank_wgs > 65536 || t->dense_kernel < 0 || t->dense_kernel > 2)
         return fail(RSPARSE_EINVAL, "negative or unknown tuning value");
     if (t->mfma_rows != 0 && t->mfma_rows != 64 && t->mfma_rows != 128 && t->mfma_rows != 256)
         return fail(RSPARSE_EINVAL, "mfma_rows must be 0, 64, 128 or 256");

@@ -9,6 +9,8 @@
 //                        for this layout so that a kept channel is one contiguous run), followed by
 //                        U_r^T (row d_in + j = U_r[:, j]) for the one-launch kernel
 //   SVt  [r][d_in]       S_r V_r^T, one singular component per row
+//   SVc  [d_in][r]       optional channel-major copy of S_r V_r^T (row c = its column c): at one token the stage 1 of
+//                        the one-launch kernel then reads the rows of the dropped channels only (lowrank_gather)
 //   U    [d_out][r]      U_r row-major
 //
 // One call is either two launches, ordered by the stream (no intra-kernel cross-workgroup waits):

@@ -37,14 +37,15 @@ def test_product_never_imports_the_oracle():
 @pytest.mark.parametrize("bad", [
     dict(d_in=12), dict(d_out=0), dict(rank=-1), dict(rank=72), dict(rank=12), dict(max_batch=0), dict(max_batch=33),
     dict(tau=float("nan")), dict(dtype=2), dict(out_dtype=0, dtype=1), dict(cmp_mode=3), dict(batch_mask_mode=-1),
-    dict(batch_mask_mode=3), dict(topk=-1), dict(topk=65), dict(topk=8, cmp_mode=1), dict(topk=8, cmp_mode=2),
+    dict(batch_mask_mode=3), dict(lowrank_channel_major=2), dict(lowrank_channel_major=-1), dict(topk=-1), dict(topk=65), dict(topk=8, cmp_mode=1), dict(topk=8, cmp_mode=2),
 ])
 def test_config_validation(bad):
     kw = dict(d_in=64, d_out=64, rank=8, tau=0.5, dtype=rs.F16, max_batch=1)
     kw.update(bad)
     cfg = rs.make_config(kw["d_in"], kw["d_out"], kw["rank"], kw["tau"], kw["dtype"], max_batch=kw["max_batch"],
                          out_dtype=kw.get("out_dtype"), cmp_mode=kw.get("cmp_mode", 0),
-                         batch_mask_mode=kw.get("batch_mask_mode", 0), topk=kw.get("topk", 0))
+                         batch_mask_mode=kw.get("batch_mask_mode", 0), topk=kw.get("topk", 0),
+                         lowrank_channel_major=kw.get("lowrank_channel_major", 0))
     W = np.zeros((max(kw["d_out"], 1), max(kw["d_in"], 1)), dtype=np.uint16)
     lib = rs.load_library()
     import ctypes as C
