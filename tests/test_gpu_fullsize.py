@@ -114,5 +114,17 @@ def test_the_widest_input_the_library_accepts(strip_cols):
             gu.check_outputs(got["Y"], want["Y"], dt)
         gu.check_outputs(gu.run_dense(layer, X16[:1]), oracle.dense_linear(L.W16, X16[:1], dt, dt, nthreads=8), dt)
         layer.destroy()
+    if strip_cols == 0:
+        # stage 1 over the channel-major copy of S_r V_r^T: default and extreme numbers of stage-1 workgroups (one would
+        # need a list of 65536 entries: the library raises the count until a workgroup's list fits its LDS)
+        layer = gu.prepare(L, tau, lowrank_channel_major=1)
+        want = gu.oracle_linear(L, X16[:1], tau)
+        for wgs in (0, 1, 8192):
+            rs.rsparse_set_tuning(layer, lowrank_wgs=wgs)
+            got = gu.run_linear(layer, X16[:1])
+            rs.rsparse_synchronize(layer)
+            gu.check_lists(got, want)
+            gu.check_outputs(got["Y"], want["Y"], dt)
+        layer.destroy()
     with pytest.raises(rs.RSparseError):
         rs.rsparse_prepare_factors(rs.make_config(65536 + 8, 264, 0, tau, dt), np.zeros((264, 65544), dtype=np.uint16), None, None)
