@@ -468,6 +468,9 @@ def measure_workload(label, cfg_no, args, mods, timers, want_cpu):
         "roofline": {"bound": "hbm", "kernel": kern, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic_from_profiles(kern, label),
                      "us_per_launch": round(us_launch, 3), "bytes_per_launch": int(bytes_launch),
+                     # what the launches ask memory for: the required bytes minus the kept channels' columns of
+                     # S_r V_r^T on the layers whose stage 1 reads the channel-major copy (traffic is compared with this)
+                     "requested_bytes_per_launch": int((requested_step if lay == "column" else req_step) / n_calls),
                      "launches_per_step": n_calls},
     }
     log(f"{label}: R-Sparse {us_linear:.2f} us/linear ({lay}, {res[lay]['launch_mode']}; "
