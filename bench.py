@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0
 REPEATS = 10               # timed brackets of `steps` steps each; the median is reported
 K_TOKENS = 32              # tokens per linear for the statistics of k (kept channels)
 STRIP_COLS = 128           # strip width of the strip-layout variant
-CHANNEL_MAJOR_MIN_WEIGHTS = 1 << 26   # column layout: layers from this size on keep S_r V_r^T channel-major as well
+CHANNEL_MAJOR_MIN_WEIGHTS = 1 << 26   # column layout: calls that read this many weights keep S_r V_r^T channel-major as well
 
 
 def log(msg):
@@ -254,9 +254,11 @@ class Ring:
                 for name in call:
                     _, d_in, d_out, _ = next(l for l in wl["linears"] if l[0] == name)
                     L = self.base[name]
-                    # column layout: layers of 2^26 weights or more also keep S_r V_r^T channel-major, so that stage 1
-                    # reads the dropped channels' rows only (measured to pay from that size on, to cost time below)
-                    cm = 1 if strip_cols == 0 and rank and d_in * d_out >= CHANNEL_MAJOR_MIN_WEIGHTS else 0
+                    # column layout: the layers of a call (one launch) that reads 2^26 weights or more also keep S_r V_r^T
+                    # channel-major, so that stage 1 reads the dropped channels' rows only (measured to pay from that
+                    # size on -- the launch is then long enough to hide that t is published later -- and to cost time below)
+                    call_weights = sum(di * do for n2, di, do, _ in wl["linears"] if n2 in call)
+                    cm = 1 if strip_cols == 0 and rank and call_weights >= CHANNEL_MAJOR_MIN_WEIGHTS else 0
                     self.channel_major[name] = cm
                     cfg = rs.make_config(d_in, d_out, rank, self.tau[name][sparsity], dt, max_batch=1,
                                          dense_rowmajor=rowmajor if strip_cols == 0 else 0, strip_cols=strip_cols,

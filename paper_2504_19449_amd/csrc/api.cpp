@@ -285,12 +285,20 @@ Launch resolve_launch(const rsparse_layer *L, int batch, bool dense, int group, 
     }
     // one token over a channel-major copy of S_r V_r^T: stage 1 reads the dropped channels' rows only, each of its
     // workgroups on a fixed channel range.  64 workgroups, 128 from 16 MB of expected rows (measured on 4096 x 4096
-    // up to 28672 -> 8192: fewer publish t too late for the gather workgroups' rows of U_r^T, more only add atomics),
-    // shared by the layers of a group
+    // up to 28672 -> 8192: fewer publish t too late for the gather workgroups' rows of U_r^T, more only add atomics) ...
     if (fused && !dense && bt == 1 && L->SVc && L->cfg.rank > 0 && t.lowrank_wgs >= 0) {
         const double s1_bytes = 2.0 * L->cfg.rank * (L->cfg.d_in - rows);
-        c.lowrank_wgs = t.lowrank_wgs > 0 ? t.lowrank_wgs
-                                          : std::max(16, (s1_bytes >= 16.0 * 1024 * 1024 ? 128 : 64) / std::max(1, group));
+        // ... as many as the resident slots (two per compute unit, shared by the layers of a group) that this layer's
+        // gather workgroups leave free, between 16 and that number (measured: gate/up grouped 32 each, q/k/v grouped
+        // 42 + 64 + 64, o 64, down 128 -- a launch that needs a second round of workgroups loses more)
+        const int base = s1_bytes >= 16.0 * 1024 * 1024 ? 128 : 64;
+        const int free_slots = 2 * L->cus / std::max(1, group) - L->tiles * splits;
+        c.lowrank_wgs = t.lowrank_wgs > 0 ? t.lowrank_wgs : std::max(16, std::min(base, free_slots));
+        // skinny layers (d_out of the order of the rank: the k / v projections of grouped-query attention), where stage 1
+        // is half or more of what the gather workgroups read: 128 whatever the slots (measured in the q/k/v group of
+        // 8192 -> 8192 / 1024 / 1024, r = 1024: 30.2 us against 32.0 us)
+        const double gather_bytes = 2.0 * ((double)rows + L->cfg.rank) * L->cfg.d_out;
+        if (t.lowrank_wgs == 0 && 2.0 * s1_bytes >= gather_bytes) c.lowrank_wgs = 128;
     }
     return c;
 }
