@@ -94,8 +94,9 @@ typedef struct {
                                 elements).  At one token the one-launch column-tile kernel then forms t from the rows of the
                                 DROPPED channels only (the low-rank part acts on x - sigma_t(x), whose kept channels are zero):
                                 rank * (d_in - k) elements read instead of rank * d_in, summed with fp32 atomics.  Same
-                                results within the stated tolerance.  Measured to pay from about 2^26 weights per layer (8192 x
-                                8192: 1 %, 28672 -> 8192: 6 %) and to cost time below (t is published later).  Ignored by the strip kernel, the larger batches, the
+                                results within the stated tolerance.  Measured to pay in launches (one layer, or the layers of a
+                                grouped call) of about 2^26 weights or more (28672 -> 8192: 7 %; q/k/v grouped at 8192: 17 %) and to
+                                cost time in smaller ones (t is published later).  Ignored by the strip kernel, the larger batches, the
                                 two-launch form, rsparse_linear_static and 4-bit weights (those read the row-major copy). */
 } rsparse_config;
 
@@ -119,7 +120,8 @@ typedef struct {
                                 (one launch; two on 4-bit weights), 1 one launch, 2 two launches (stage 2 and the
                                 rounding in a second kernel).  stages != 0 implies two launches */
     int32_t lowrank_wgs;     /* stage-1 workgroups of the channel-major form (cfg.lowrank_channel_major): 0 default (64, or 128
-                                from 16 MB of rows to read, shared by the layers of a group), -1: use the row-major copy */
+                                from 16 MB of rows to read, within the resident slots the layer's other workgroups leave free;
+                                128 on skinny layers), -1: use the row-major copy */
     int32_t debug_wait_polls;   /* one-launch kernel: bound on the re-reads of a low-rank intermediate that stage 1 has
                                    not published yet; 0 = default (2^20, or 0.5 s) */
     int32_t debug_skip_stage1;  /* test hook for the error path, needs debug_wait_polls in [1, 64]: stage 1 publishes
