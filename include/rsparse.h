@@ -91,13 +91,15 @@ typedef struct {
                                 each token's k-th magnitude.  Vector path only (batches above 8 run in tiles of 8); not with
                                 4-bit weights.  k <= d_in. */
     int32_t lowrank_channel_major; /* 1: also keep S_r V_r^T channel-major on the device ([d_in][rank]: rank * d_in more
-                                elements).  At one token the one-launch column-tile kernel then forms t from the rows of the
-                                DROPPED channels only (the low-rank part acts on x - sigma_t(x), whose kept channels are zero):
-                                rank * (d_in - k) elements read instead of rank * d_in, summed with fp32 atomics.  Same
-                                results within the stated tolerance.  Measured to pay in launches (one layer, or the layers of a
-                                grouped call) of about 2^26 weights or more (28672 -> 8192: 7 %; q/k/v grouped at 8192: 17 %) and to
-                                cost time in smaller ones (t is published later).  Ignored by the strip kernel, the larger batches, the
-                                two-launch form, rsparse_linear_static and 4-bit weights (those read the row-major copy). */
+                                elements).  Up to four tokens the one-launch column-tile kernel then forms t from the rows of
+                                the DROPPED channels only (the low-rank part acts on x - sigma_t(x), whose kept channels are
+                                zero): rank * (d_in - k) elements read instead of rank * d_in (k: channels that every token of
+                                the batch tile keeps), summed with fp32 atomics.  Same results within the stated tolerance.
+                                Measured to pay in launches (one layer, or the layers of a grouped call) of about 2^26 weights
+                                or more (28672 -> 8192: 7 %; q/k/v grouped at 8192: 17 %) and at four tokens with the union mask
+                                (few channels are dropped then: 1-7 %), and to cost time in smaller launches at one or two tokens
+                                (t is published later).  Ignored by the strip kernel, batches above four, the two-launch
+                                form, rsparse_linear_static and 4-bit weights (those read the row-major copy). */
 } rsparse_config;
 
 /* Launch-shape overrides for measurements; 0 = library default. */

@@ -286,7 +286,7 @@ Launch resolve_launch(const rsparse_layer *L, int batch, bool dense, int group, 
     // one token over a channel-major copy of S_r V_r^T: stage 1 reads the dropped channels' rows only, each of its
     // workgroups on a fixed channel range.  64 workgroups, 128 from 16 MB of expected rows (measured on 4096 x 4096
     // up to 28672 -> 8192: fewer publish t too late for the gather workgroups' rows of U_r^T, more only add atomics) ...
-    if (fused && !dense && bt == 1 && L->SVc && L->cfg.rank > 0 && t.lowrank_wgs >= 0) {
+    if (fused && !dense && bt <= 4 && L->SVc && L->cfg.rank > 0 && t.lowrank_wgs >= 0) {
         const double s1_bytes = 2.0 * L->cfg.rank * (L->cfg.d_in - rows);
         // ... as many as the resident slots (two per compute unit, shared by the layers of a group) that this layer's
         // gather workgroups leave free, between 16 and that number (measured: gate/up grouped 32 each, q/k/v grouped
@@ -489,8 +489,9 @@ rsparse_status build_layer(const rsparse_config *cfg, const uint16_t *W, const u
             transpose16(SV16, r, d_in, svc.data());
             RS_HIP(hipMalloc((void **)&L->SVc, d_in * r * 2));
             RS_HIP(hipMemcpy(L->SVc, svc.data(), d_in * r * 2, hipMemcpyHostToDevice));
-            RS_HIP(hipMalloc((void **)&L->t_sum, r * 4));
-            RS_HIP(hipMemset(L->t_sum, 0, r * 4));
+            const size_t n_sum = r * (size_t)L->nz_max * kMaxBT;
+            RS_HIP(hipMalloc((void **)&L->t_sum, n_sum * 4));
+            RS_HIP(hipMemset(L->t_sum, 0, n_sum * 4));
         }
         if (cfg->dense_rowmajor && !q4) {
             RS_HIP(hipMalloc((void **)&L->Wrow, d_in * d_out * 2));

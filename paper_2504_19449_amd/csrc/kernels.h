@@ -30,7 +30,7 @@ struct LayerView {
     const uint16_t *SVt;    // [rank][d_in]  = S_r V_r^T
     const uint16_t *U;      // [d_out][rank] = U_r, row-major
     const uint16_t *SVc;    // [d_in][rank] channel-major copy of S_r V_r^T (row c = its column c), or nullptr
-    float *t_sum;           // [rank] fp32 sums of the stage 1 that reads SVc; zero between calls (or nullptr)
+    float *t_sum;           // [nz][BT][rank] fp32 sums of the stage 1 that reads SVc; zero between calls (or nullptr)
     const uint16_t *Wrow;   // [d_out][d_in] row-major copy of W, or nullptr
     float *t;               // [nz][BT][rank] stage-1 result, fp32
     float *t_acc;           // [rank][16 or 32 tokens] matrix-core path: t summed over the K slices; zero between calls (or nullptr)
@@ -115,7 +115,7 @@ struct Launch {
 // Arrival counters of the one-launch path, as offsets into LayerView::sync (32-bit words).
 constexpr int kSyncTilesDone = 0;   // column tiles (over all batch tiles) whose outputs have been stored
 constexpr int kSyncError = 1;       // set when a bounded wait ran out (results of that call are invalid)
-constexpr int kSyncStage1 = 3;      // one-launch kernel: stage-1 workgroups (channel-major form) that have added their partial t
+constexpr int kSyncStage1 = 3;      // [kSyncMaxZ] one-launch kernel, per batch tile: stage-1 workgroups (channel-major form) that have added their partial t
 constexpr int kSyncGen = 2;         // strip kernel: generation number of the next launch (bumped once per launch)
 constexpr int kSyncStarted = 8;     // strip kernel: [kSyncStartedN] how many waves of the launch have read the generation
 constexpr int kSyncStartedN = 256;

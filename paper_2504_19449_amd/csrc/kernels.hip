@@ -200,7 +200,7 @@ __device__ __forceinline__ bool map_tile(const GatherArgs &a, int g, int &tile, 
 
 // ---------------------------------------------------------------------------------------------
 // Stage 1 of the low-rank part over the channel-major copy SVc [d_in][rank] (row c = (S_r V_r^T)[:, c]), one
-// token: t = sum over the DROPPED channels c of x_c SVc[c, :] (Sec. 3.4: the low-rank part acts on x - sigma_t(x),
+// token (or a batch tile of up to 4, every token with its own coefficients): t = sum over the DROPPED channels c of x_c SVc[c, :] (Sec. 3.4: the low-rank part acts on x - sigma_t(x),
 // whose kept channels are zero), so only the rows of dropped channels are read -- rank * (d_in - k) elements
 // instead of rank * d_in.  Stage-1 workgroup wg of lr_wgs owns a fixed range of channels: it thresholds that range
 // only, compacts the dropped channels with wave scans, streams their rows (a wave covers 512 columns of a row per
@@ -208,32 +208,43 @@ __device__ __forceinline__ bool map_tile(const GatherArgs &a, int g, int &tile, 
 // the range's partial t to t_sum with fp32 atomics.  The last workgroup to arrive swaps the sums out (which
 // re-zeroes them) and publishes t.  No workgroup waits for another here.
 // ---------------------------------------------------------------------------------------------
-template <int DT, bool NT, bool EXT>
-__device__ __forceinline__ void lowrank_gather(const GatherArgs &a, unsigned char *smem, int wg)
+template <int DT, int BT, bool NT, bool EXT>
+__device__ __forceinline__ void lowrank_gather(const GatherArgs &a, unsigned char *smem, int wg, int z)
 {
     const int tid = threadIdx.x, nthr = blockDim.x, lane = tid & 63, w = uniform(tid >> 6), nw = nthr >> 6;
     const LayerView &L = a.L;
     const int d_in = L.d_in, r = L.rank, cap = a.lr_cap;
-    TileRules<1> rules;
-    load_rules<1, EXT>(L, 0, 1, rules);
+    const int b0 = z * BT;
+    const int nb = min(BT, a.batch - b0);
+    const bool union_all = L.batch_mask_mode == 1;
+    TileRules<BT> rules;
+    load_rules<BT, EXT>(L, b0, nb, rules);
     float *s_red = reinterpret_cast<float *>(smem);                 // [nw][kTile]
-    float *s_coef = s_red + (size_t)nw * kTile;                     // [cap]
-    int *s_idx = reinterpret_cast<int *>(s_coef + cap);             // [cap]
+    float *s_coef = s_red + (size_t)nw * kTile;                     // [cap][BT]
+    int *s_idx = reinterpret_cast<int *>(s_coef + (size_t)cap * BT);// [cap]
     int *s_wtot = s_idx + cap;                                      // [nw], then the arrival flag
     int q_lo, q_hi;
     balanced_share(d_in / 8, a.lr_wgs, wg, q_lo, q_hi);             // my chunks of 8 channels
-    // every list slot starts as a valid row with a zero coefficient
-    for (int i = tid; i < cap; i += nthr) { s_idx[i] = 0; s_coef[i] = 0.f; }
+    // every list slot starts as a valid row with zero coefficients
+    for (int i = tid; i < cap; i += nthr) s_idx[i] = 0;
+    for (int i = tid; i < cap * BT; i += nthr) s_coef[i] = 0.f;
     int n = 0;
     for (int qb = q_lo; qb < q_hi; qb += nthr) {
         const int q = qb + tid;
-        u32x4 raw[1] = {u32x4{0, 0, 0, 0}};
-        uint32_t drop = 0u;
+        u32x4 raw[BT];
+        uint32_t dm[BT];                                            // per token: the channels of the chunk it drops
+        uint32_t drop = 0u;                                         // dropped by at least one token of the tile
+#pragma unroll
+        for (int b = 0; b < BT; ++b) { raw[b] = u32x4{0, 0, 0, 0}; dm[b] = 0u; }
         if (q < q_hi) {
-            load_raw8<1>(a.X, 0, 1, d_in, q * 8, raw);
-            uint32_t m[1];
-            masks_of8<DT, 1>(L, a.X, 1, 0, 1, d_in, q * 8, rules, false, raw, m);
-            drop = ~m[0] & 0xffu;
+            load_raw8<BT>(a.X, b0, nb, d_in, q * 8, raw);
+            uint32_t m[BT];
+            masks_of8<DT, BT>(L, a.X, a.batch, b0, nb, d_in, q * 8, rules, union_all, raw, m);
+#pragma unroll
+            for (int b = 0; b < BT; ++b) {
+                dm[b] = b < nb ? (~m[b] & 0xffu) : 0u;
+                drop |= dm[b];
+            }
         }
         const int c = __popc(drop);
         const int inc = wave_inclusive_scan(c);
@@ -246,14 +257,16 @@ __device__ __forceinline__ void lowrank_gather(const GatherArgs &a, unsigned cha
             tot += v;
         }
         if (drop != 0u) {
-            float f[8];
-            unpack8<DT>(raw[0], f);
+            float f[BT][8];
+#pragma unroll
+            for (int b = 0; b < BT; ++b) unpack8<DT>(raw[b], f[b]);
             int p = n + woff + inc - c;
 #pragma unroll
             for (int e = 0; e < 8; ++e)
                 if (((drop >> e) & 1u) && p < cap) {
                     s_idx[p] = q * 8 + e;
-                    s_coef[p] = f[e];
+#pragma unroll
+                    for (int b = 0; b < BT; ++b) s_coef[p * BT + b] = ((dm[b] >> e) & 1u) ? f[b][e] : 0.f;
                     ++p;
                 }
         }
@@ -268,40 +281,51 @@ __device__ __forceinline__ void lowrank_gather(const GatherArgs &a, unsigned cha
     const int part = w % parts, g = w / parts;
     const int col = part * kTile + lane * 8;
     const bool colok = col < r;
-    float acc[1][8];
+    float acc[BT][8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[0][e] = 0.f;
+    for (int b = 0; b < BT; ++b)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[b][e] = 0.f;
     if (g < ng) {
         u32x4 va[kUnroll];
         const int j_first = g * kUnroll, step = ng * kUnroll;
         load_batch<NT>(L.SVc, (size_t)r, col, colok, s_idx, n, j_first, va);
-        stream_rest<DT, 1, NT>(L.SVc, (size_t)r, col, colok, s_idx, s_coef, n, j_first, step, va, acc, [](int) {});
+        stream_rest<DT, BT, NT>(L.SVc, (size_t)r, col, colok, s_idx, s_coef, n, j_first, step, va, acc, [](int) {});
     }
-    float4 *dst = reinterpret_cast<float4 *>(s_red + w * kTile + lane * 8);
-    dst[0] = float4{acc[0][0], acc[0][1], acc[0][2], acc[0][3]};
-    dst[1] = float4{acc[0][4], acc[0][5], acc[0][6], acc[0][7]};
-    __syncthreads();
-    for (int i = tid; i < parts * kTile; i += nthr) {
-        const int pt = i / kTile, cl = i % kTile;
-        float sum = 0.f;
-        for (int gg = 0; gg < ng; ++gg) sum += s_red[(gg * parts + pt) * kTile + cl];
-        if (i < r) __hip_atomic_fetch_add(L.t_sum + i, sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // b must stay a compile-time index (a run-time subscript would push acc[][] into scratch memory)
+    float *const t_sum = L.t_sum + (size_t)z * BT * r;
+#pragma unroll
+    for (int b = 0; b < BT; ++b) {
+        if (b >= nb) break;
+        if (b > 0) __syncthreads();
+        float4 *dst = reinterpret_cast<float4 *>(s_red + w * kTile + lane * 8);
+        dst[0] = float4{acc[b][0], acc[b][1], acc[b][2], acc[b][3]};
+        dst[1] = float4{acc[b][4], acc[b][5], acc[b][6], acc[b][7]};
+        __syncthreads();
+        for (int i = tid; i < parts * kTile; i += nthr) {
+            const int pt = i / kTile, cl = i % kTile;
+            float sum = 0.f;
+            for (int gg = 0; gg < ng; ++gg) sum += s_red[(gg * parts + pt) * kTile + cl];
+            if (i < r) __hip_atomic_fetch_add(t_sum + (size_t)b * r + i, sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
 
-    // ---- arrive; the last stage-1 workgroup publishes t
+    // ---- arrive; the last stage-1 workgroup of the batch tile publishes its t
     wait_own_writes();
     __syncthreads();
     if (tid == 0) {
-        const int arrived = __hip_atomic_fetch_add(L.sync + kSyncStage1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int *ctr = L.sync + kSyncStage1 + z;
+        const int arrived = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         s_wtot[nw] = arrived == a.lr_wgs - 1;
-        if (arrived == a.lr_wgs - 1) __hip_atomic_store(L.sync + kSyncStage1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (arrived == a.lr_wgs - 1) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
     if (!s_wtot[nw]) return;
-    for (int i = tid; i < r; i += nthr) {
-        uint32_t bits = as_u(__hip_atomic_exchange(L.t_sum + i, 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    uint32_t *const t_pub = L.t_pub + (size_t)z * BT * r;
+    for (int i = tid; i < nb * r; i += nthr) {
+        uint32_t bits = as_u(__hip_atomic_exchange(t_sum + i, 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
         if (bits == kNotReady) bits = 0x7fc00000u;
-        if (!a.skip_stage1) __hip_atomic_store(L.t_pub + i, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (!a.skip_stage1) __hip_atomic_store(t_pub + i, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -514,9 +538,9 @@ __device__ __forceinline__ void sparse_body(const GroupArgs &ga, unsigned char *
         // every gather workgroup ends with rows that need t: the stage-1 waves issue ahead of the gather waves they
         // share a compute unit with (measured: q/k/v grouped at 8192 wide 37.0 -> 35.6 us, the other launches unchanged)
         if constexpr (FUSED) __builtin_amdgcn_s_setprio(3);
-        if constexpr (FUSED && BT == 1 && !Q4) {
+        if constexpr (FUSED && BT <= 4 && !Q4) {
             if (a.lr_gather) {
-                lowrank_gather<DT, NT, EXT>(a, smem, wg);
+                lowrank_gather<DT, BT, NT, EXT>(a, smem, wg, z);
                 return;
             }
         }
@@ -1312,16 +1336,17 @@ hipError_t launch_fused(const LayerView *L, const Launch *cfg, int n, const void
         a.lr_chunk = lowrank_chunk(L[i].d_in, bt);
         size_t lr_lds = a.lr_wgs > 0 ? lowrank_lds_bytes(L[i].d_in, bt) : 0;
         // one token and a channel-major copy of S_r V_r^T: stage 1 reads only the dropped channels' rows
-        if (bt == 1 && cfg[i].lowrank_wgs > 0 && L[i].rank > 0 && L[i].SVc && L[i].t_sum &&
+        if (bt <= 4 && cfg[i].lowrank_wgs > 0 && L[i].rank > 0 && L[i].SVc && L[i].t_sum &&
             (L[i].rank + kTile - 1) / kTile <= cfg[0].waves) {
             const int nq = L[i].d_in / 8;
+            const int entry = 4 + 4 * bt;                            // bytes of a list entry: index + a coefficient per token
             a.lr_gather = 1;
             a.lr_wgs = std::min(cfg[i].lowrank_wgs, nq);
-            // a workgroup's list of dropped channels (index + coefficient, all of its range at worst) has to fit LDS
-            // next to the reduction buffer: at least as many workgroups as keep it under 32 KiB
-            a.lr_wgs = std::max(a.lr_wgs, (nq * 8 * 8 + 32 * 1024 - 1) / (32 * 1024));
+            // a workgroup's list of dropped channels (all of its range at worst) has to fit LDS next to the reduction
+            // buffer: at least as many workgroups as keep it under 32 KiB
+            a.lr_wgs = std::max(a.lr_wgs, (nq * 8 * entry + 32 * 1024 - 1) / (32 * 1024));
             a.lr_cap = ((nq + a.lr_wgs - 1) / a.lr_wgs) * 8;
-            lr_lds = (size_t)cfg[0].waves * kTile * 4 + (size_t)a.lr_cap * 8 + (size_t)(cfg[0].waves + 1) * 4;
+            lr_lds = (size_t)cfg[0].waves * kTile * 4 + (size_t)a.lr_cap * entry + (size_t)(cfg[0].waves + 1) * 4;
         }
         a.tile_map = cfg[i].tile_map;
         a.Y = Y[i];

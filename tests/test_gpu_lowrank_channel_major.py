@@ -1,6 +1,6 @@
-"""GPU parity for the stage 1 that reads a channel-major copy of S_r V_r^T (config lowrank_channel_major = 1): at one
-token the one-launch column-tile kernel forms t from the rows of the dropped channels only (Sec. 3.4: the low-rank
-part acts on x - sigma_t(x)).  Same oracle, same tolerances, kept lists bit-exact; every other path of a layer
+"""GPU parity for the stage 1 that reads a channel-major copy of S_r V_r^T (config lowrank_channel_major = 1): up to
+four tokens the one-launch column-tile kernel forms t from the rows of the dropped channels only (Sec. 3.4: the
+low-rank part acts on x - sigma_t(x)).  Same oracle, same tolerances, kept lists bit-exact; every other path of a layer
 prepared this way (more tokens, two launches, the dense reference) reads the row-major copy and must be unchanged."""
 import numpy as np
 import pytest
@@ -66,15 +66,40 @@ def test_special_values_and_ties_at_the_threshold():
     layer.destroy()
 
 
+@pytest.mark.parametrize("dt", [synth.F16, synth.BF16])
+@pytest.mark.parametrize("mask_mode", [0, 1, 2])
+def test_two_to_four_tokens(dt, mask_mode):
+    """Batch tiles of 2 and 4 tokens: a channel's row is read if any token of the tile drops it, every token with its
+    own coefficient (zero where it keeps the channel); with the union mask the dropped channels are the few that no
+    token of the batch keeps.  Ragged tiles (3 tokens), a token of all zeros, repeated calls."""
+    L = _layer(1032, 1096, 520, dt, seed=10)
+    X16, src = gu.tokens_for(L, 8, linear=5)
+    X16[2, :] = 0                                                      # a token that keeps nothing at tau > 0
+    tau = gu.calibrated_tau(L, src, 0.5)
+    for out in (None, rs.F32):
+        layer = gu.prepare(L, tau, max_batch=4, out_dtype=out, batch_mask_mode=mask_mode, lowrank_channel_major=1)
+        for wgs in (0, 5, 129):
+            rs.rsparse_set_tuning(layer, lowrank_wgs=wgs)
+            for B in (2, 3, 4, 1):
+                _check(L, layer, X16[:B], tau, batch_mask_mode=1 if (mask_mode == 1 or (mask_mode == 2 and B >= 4)) else 0)
+        layer.destroy()
+    # fixed-count activation with a bias at three tokens
+    bias = np.random.Generator(np.random.PCG64(9)).standard_normal(1096).astype(np.float32)
+    layer = gu.prepare(L, 0.0, max_batch=4, out_dtype=rs.F32, topk=400, lowrank_channel_major=1)
+    rs.rsparse_set_bias(layer, bias)
+    _check(L, layer, X16[3:6], 0.0, topk=400, bias=bias.astype(np.float64))
+    layer.destroy()
+
+
 def test_other_paths_of_such_a_layer_are_unchanged():
-    """More than one token, the two-launch form, a workgroup too narrow for the rank's parts, the entry point that
+    """More than four tokens, the two-launch form, a workgroup too narrow for the rank's parts, the entry point that
     allocates nothing and the dense reference read the row-major copy."""
     dt = synth.BF16
     L = _layer(1032, 1096, 520, dt, seed=2)
     X16, src = gu.tokens_for(L, 8)
     tau = gu.calibrated_tau(L, src, 0.5)
     layer = gu.prepare(L, tau, max_batch=8, out_dtype=rs.F32, lowrank_channel_major=1)
-    for B in (1, 2, 3, 8):
+    for B in (1, 2, 5, 8):
         _check(L, layer, X16[:B], tau)
     for tuning in (dict(launches=2), dict(waves=1), dict(splits=3, waves=2)):
         rs.rsparse_set_tuning(layer, **tuning)
