@@ -98,7 +98,8 @@ typedef struct {
                                 Measured to pay in launches (one layer, or the layers of a grouped call) of about 2^26 weights
                                 or more (28672 -> 8192: 7 %; q/k/v grouped at 8192: 17 %) and at four tokens with the union mask
                                 (few channels are dropped then: 1-7 %), and to cost time in smaller launches at one or two tokens
-                                (t is published later).  Ignored by the strip kernel, batches above four, the two-launch
+                                (t is published later): the library uses the copy in exactly those two cases unless
+                                rsparse_tuning.lowrank_wgs says otherwise.  Ignored by the strip kernel, batches above four, the two-launch
                                 form, rsparse_linear_static and 4-bit weights (those read the row-major copy). */
 } rsparse_config;
 
@@ -123,7 +124,8 @@ typedef struct {
                                 rounding in a second kernel).  stages != 0 implies two launches */
     int32_t lowrank_wgs;     /* stage-1 workgroups of the channel-major form (cfg.lowrank_channel_major): 0 default (64, or 128
                                 from 16 MB of rows to read, within the resident slots the layer's other workgroups leave free;
-                                128 on skinny layers), -1: use the row-major copy */
+                                128 on skinny layers; the copy is used only where it was measured to pay), > 0: that many,
+                                always, -1: always the row-major copy */
     int32_t debug_wait_polls;   /* one-launch kernel: bound on the re-reads of a low-rank intermediate that stage 1 has
                                    not published yet; 0 = default (2^20, or 0.5 s) */
     int32_t debug_skip_stage1;  /* test hook for the error path, needs debug_wait_polls in [1, 64]: stage 1 publishes

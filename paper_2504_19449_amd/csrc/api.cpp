@@ -234,7 +234,7 @@ rsparse_status check_config(const rsparse_config *c)
 // enough rows to amortise its scan, and the staged share small enough for 64 KiB of LDS.
 // Stage-1 workgroups get about as many bytes of S_r V_r^T as a gather workgroup gets of W.
 Launch resolve_launch(const rsparse_layer *L, int batch, bool dense, int group, int waves_of_group = 0,
-                      bool fused = false)
+                      bool fused = false, size_t launch_weights = 0)
 {
     Launch c{};
     const rsparse_tuning &t = L->tuning;
@@ -286,7 +286,13 @@ Launch resolve_launch(const rsparse_layer *L, int batch, bool dense, int group, 
     // one token over a channel-major copy of S_r V_r^T: stage 1 reads the dropped channels' rows only, each of its
     // workgroups on a fixed channel range.  64 workgroups, 128 from 16 MB of expected rows (measured on 4096 x 4096
     // up to 28672 -> 8192: fewer publish t too late for the gather workgroups' rows of U_r^T, more only add atomics) ...
-    if (fused && !dense && bt <= 4 && L->SVc && L->cfg.rank > 0 && t.lowrank_wgs >= 0) {
+    // By default only where it was measured to pay: in launches that read 2^26 weights or more (t is published one
+    // dependent phase later than by the row dots, which a shorter launch does not hide), and at four tokens under the
+    // union mask (hardly any channel is dropped then, so stage 1 reads almost nothing).  lowrank_wgs > 0 forces it.
+    const size_t lw = launch_weights ? launch_weights : (size_t)L->cfg.d_in * L->cfg.d_out;
+    const bool union_now = L->cfg.batch_mask_mode == 1 || (L->cfg.batch_mask_mode == 2 && batch >= 4);
+    const bool pays = lw >= ((size_t)1 << 26) || (bt == 4 && union_now);
+    if (fused && !dense && bt <= 4 && L->SVc && L->cfg.rank > 0 && (t.lowrank_wgs > 0 || (t.lowrank_wgs == 0 && pays))) {
         const double s1_bytes = 2.0 * L->cfg.rank * (L->cfg.d_in - rows);
         // ... as many as the resident slots (two per compute unit, shared by the layers of a group) that this layer's
         // gather workgroups leave free, between 16 and that number (measured: gate/up grouped 32 each, q/k/v grouped
@@ -787,9 +793,11 @@ rsparse_status linear_group_impl(rsparse_layer *const *layers, int32_t n_layers,
     const int stages = layers[0]->tuning.stages;
     // one launch unless asked otherwise (timing a stage alone needs the two-launch form)
     const bool fused = layers[0]->tuning.launches != 2 && stages == 0;
+    size_t launch_weights = 0;
+    for (int i = 0; i < n_layers; ++i) launch_weights += (size_t)layers[i]->cfg.d_in * layers[i]->cfg.d_out;
     for (int i = 0; i < n_layers; ++i) {
         v[i] = layers[i]->view(ov, batch);
-        lc[i] = resolve_launch(layers[i], batch, false, n_layers, i ? lc[0].waves : 0, fused);
+        lc[i] = resolve_launch(layers[i], batch, false, n_layers, i ? lc[0].waves : 0, fused, launch_weights);
         layers[i]->last_scratch = ov ? *ov : layers[i]->own_scratch();
     }
     bool mfma = !ov && batch >= (layers[0]->tuning.mfma_min_batch > 0 ? layers[0]->tuning.mfma_min_batch : kMfmaDefaultMinBatch);
@@ -877,7 +885,8 @@ rsparse_status rsparse_mlp_gate_up(rsparse_layer *gate, rsparse_layer *up, const
     Launch lc[2];
     for (int i = 0; i < 2; ++i) {
         v[i] = pair[i]->view(nullptr, batch);
-        lc[i] = resolve_launch(pair[i], batch, false, 2, i ? lc[0].waves : 0, fused);
+        lc[i] = resolve_launch(pair[i], batch, false, 2, i ? lc[0].waves : 0, fused,
+                               (size_t)pair[0]->cfg.d_in * pair[0]->cfg.d_out + (size_t)pair[1]->cfg.d_in * pair[1]->cfg.d_out);
     }
     bool mfma = batch >= (gate->tuning.mfma_min_batch > 0 ? gate->tuning.mfma_min_batch : kMfmaDefaultMinBatch);
     for (int i = 0; i < 2; ++i) mfma = mfma && mfma_path_supported(v[i], batch) && pair[i]->cfg.topk == 0;

@@ -1,7 +1,9 @@
 """GPU parity for the stage 1 that reads a channel-major copy of S_r V_r^T (config lowrank_channel_major = 1): up to
 four tokens the one-launch column-tile kernel forms t from the rows of the dropped channels only (Sec. 3.4: the
 low-rank part acts on x - sigma_t(x)).  Same oracle, same tolerances, kept lists bit-exact; every other path of a layer
-prepared this way (more tokens, two launches, the dense reference) reads the row-major copy and must be unchanged."""
+prepared this way (more tokens, two launches, the dense reference) reads the row-major copy and must be unchanged.
+Left to itself the library uses the copy only in launches of 2^26 weights or more and at four tokens under the union mask;
+the small layers here force it with an explicit number of stage-1 workgroups."""
 import numpy as np
 import pytest
 
@@ -56,6 +58,7 @@ def test_special_values_and_ties_at_the_threshold():
     X[5], X[77], X[8] = 0x7C00, 0xFC00, 0x8000                        # +inf and -inf are kept, -0 is dropped
     X[100:110] = synth.encode16(np.full(10, tau), dt)                 # ties at the threshold
     layer = gu.prepare(L, tau, out_dtype=rs.F32, lowrank_channel_major=1)
+    rs.rsparse_set_tuning(layer, lowrank_wgs=16)          # (a launch this small uses the row-major copy unless told to)
     got = _check(L, layer, X, tau)
     assert 5 in got["act"][0] and 77 in got["act"][0] and 8 not in got["act"][0]
     X[9] = 0x7E00                                                      # a NaN is dropped and poisons t
@@ -86,6 +89,7 @@ def test_two_to_four_tokens(dt, mask_mode):
     # fixed-count activation with a bias at three tokens
     bias = np.random.Generator(np.random.PCG64(9)).standard_normal(1096).astype(np.float32)
     layer = gu.prepare(L, 0.0, max_batch=4, out_dtype=rs.F32, topk=400, lowrank_channel_major=1)
+    rs.rsparse_set_tuning(layer, lowrank_wgs=20)
     rs.rsparse_set_bias(layer, bias)
     _check(L, layer, X16[3:6], 0.0, topk=400, bias=bias.astype(np.float64))
     layer.destroy()
@@ -123,6 +127,7 @@ def test_fixed_count_activation_bias_and_grouped_calls():
     bias = np.random.Generator(np.random.PCG64(8)).standard_normal(520).astype(np.float32)
     # fixed-count activation with a bias
     layer = gu.prepare(Ls[0], 0.0, out_dtype=rs.F32, topk=300, lowrank_channel_major=1)
+    rs.rsparse_set_tuning(layer, lowrank_wgs=12)
     rs.rsparse_set_bias(layer, bias)
     for b in range(2):
         got = _check(Ls[0], layer, X16[b], 0.0, topk=300, bias=bias.astype(np.float64))
@@ -131,6 +136,8 @@ def test_fixed_count_activation_bias_and_grouped_calls():
     # a group whose layers differ in rank and in the flag
     torch = gu.torch_mod()
     layers = [gu.prepare(L, tau, out_dtype=rs.F32, lowrank_channel_major=flag) for L, flag in zip(Ls, (1, 1, 0))]
+    for l in layers:
+        rs.rsparse_set_tuning(l, lowrank_wgs=10)
     Xd = gu.to_dev16(X16[:1])
     Ys = [gu._alloc_out(l, 1) for l in layers]
     for _ in range(2):
@@ -146,6 +153,8 @@ def test_fixed_count_activation_bias_and_grouped_calls():
     Lg, Lu = _layer(1032, 520, 64, dt, seed=7), _layer(1032, 520, 32, dt, seed=8)
     g = gu.prepare(Lg, tau, lowrank_channel_major=1)
     u = gu.prepare(Lu, tau, lowrank_channel_major=1)
+    rs.rsparse_set_tuning(g, lowrank_wgs=8)
+    rs.rsparse_set_tuning(u, lowrank_wgs=24)
     H = torch.zeros((1, 520), dtype=torch.int16, device="cuda")
     rs.rsparse_mlp_gate_up(g, u, Xd.data_ptr(), 1, H.data_ptr(), gu.stream_ptr())
     torch.cuda.synchronize()
@@ -165,6 +174,7 @@ def test_replayed_graph_and_the_bounded_wait():
     X16, src = gu.tokens_for(L, 4)
     tau = gu.calibrated_tau(L, src, 0.5)
     layer = gu.prepare(L, tau, out_dtype=rs.F32, lowrank_channel_major=1)
+    rs.rsparse_set_tuning(layer, lowrank_wgs=16)
     Xd = gu.to_dev16(X16[:1])
     Y, Ye = gu._alloc_out(layer, 1), gu._alloc_out(layer, 1)
     rs.rsparse_linear(layer, Xd.data_ptr(), 1, Y.data_ptr(), gu.stream_ptr())
@@ -188,12 +198,12 @@ def test_replayed_graph_and_the_bounded_wait():
         assert np.array_equal(rs.rsparse_last_active(layer, 0), want["act"][0])
     # stage 1 publishes nothing: every bounded wait runs out, the kernel ends, the call is reported invalid, the sums
     # it left are gone (the last stage-1 workgroup swaps them out either way) and the next call is right
-    rs.rsparse_set_tuning(layer, debug_skip_stage1=1, debug_wait_polls=4)
+    rs.rsparse_set_tuning(layer, lowrank_wgs=16, debug_skip_stage1=1, debug_wait_polls=4)
     rs.rsparse_linear(layer, Xd.data_ptr(), 1, Y.data_ptr(), gu.stream_ptr())
     with pytest.raises(rs.RSparseError) as e:
         rs.rsparse_synchronize(layer)
     assert e.value.status == rs.binding.EHIP
-    rs.rsparse_set_tuning(layer)
+    rs.rsparse_set_tuning(layer, lowrank_wgs=16)
     for b in range(2):
         _check(L, layer, X16[b], tau)
     layer.destroy()
