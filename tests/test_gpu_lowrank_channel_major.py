@@ -221,3 +221,37 @@ def test_full_size_down_projection():
         got = _check(L, layer, X16[b], tau)
         assert abs(len(got["act"][0]) - 14336) < 1500
     layer.destroy()
+
+
+@pytest.mark.parametrize("seed", list(range(4)))
+def test_random_shapes_and_settings(seed):
+    """Seeded sweep over small random layers with the channel-major stage 1 forced: every dimension a multiple of 8
+    from 8 up, ranks from 8 to full (one to three 512-column parts, ragged), 1-4 tokens, both dtypes, all compare and
+    mask modes, random launch shapes and numbers of stage-1 workgroups.  Lists equal, outputs within the fp32 bound."""
+    rng = np.random.default_rng(4321 + seed)
+    for case in range(8):
+        d_in = 8 * int(rng.integers(1, 150))
+        d_out = 8 * int(rng.integers(1, 200))
+        rank = 8 * int(rng.integers(1, min(d_in, d_out) // 8 + 1))
+        dt = int(rng.integers(0, 2))
+        B = int(rng.choice([1, 1, 2, 3, 4]))
+        cmp_mode, mask_mode = int(rng.integers(0, 3)), int(rng.integers(0, 3))
+        L = synth.random_layer(d_in, d_out, rank, dt, seed=7000 + 100 * seed + case)
+        src = synth.DModelInput(d_in, config=91, linear=10 * seed + case)
+        X16 = synth.encode16(src.tokens(B), dt)
+        s_level = float(rng.choice([0.0, 0.3, 0.5, 0.5, 0.8, 1.0]))
+        tau = gu.calibrated_tau(L, src, s_level) if 0.0 < s_level < 1.0 else (-INF if s_level == 0.0 else INF)
+        if cmp_mode == 2 and not np.isfinite(tau):
+            tau = 0.0
+        tuning = {"lowrank_wgs": int(rng.integers(1, 200))}
+        if rng.random() < 0.5:
+            tuning.update(splits=int(rng.integers(1, 40)), waves=int(rng.choice([2, 4, 8])))
+        label = dict(d_in=d_in, d_out=d_out, rank=rank, dt=dt, B=B, cmp=cmp_mode, mask=mask_mode, s=s_level, **tuning)
+        print("case", label, flush=True)
+        layer = gu.prepare(L, tau, max_batch=4, out_dtype=rs.F32, cmp_mode=cmp_mode, batch_mask_mode=mask_mode,
+                           lowrank_channel_major=1)
+        rs.rsparse_set_tuning(layer, **tuning)
+        union = mask_mode == 1 or (mask_mode == 2 and B >= 4)
+        for _ in range(2):
+            _check(L, layer, X16, tau, cmp_mode=cmp_mode, batch_mask_mode=1 if union else 0)
+        layer.destroy()
