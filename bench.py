@@ -62,7 +62,7 @@ def shape_batch_sweep(args, torch, np, rs, synth):
         maxb = max(batches)
         layers = []
         for i in range(n_ring):
-            cfg = rs.make_config(d_in, d_out, rank, tau, dt, max_batch=maxb, dense_rowmajor=1)
+            cfg = rs.make_config(d_in, d_out, rank, tau, dt, max_batch=maxb, dense_rowmajor=1, lowrank_channel_major=1)
             layers.append(rs.rsparse_prepare_factors(cfg, L.W16, L.U16, L.SV16))
         for B in batches:
             xs = [torch.from_numpy(synth.encode16(src.tokens(B, offset=10 + i), dt).view(np.int16)).cuda()
@@ -126,7 +126,7 @@ def decoder_layer_sweep(torch, np, rs, synth):
             L = synth.random_layer(d_in, d_out, r, dt, seed=7000 + li)
             src = (synth.DModelInput if kind == "dmodel" else synth.DownInput)(d_in, config=2, linear=li)
             tau = rs.rsparse_calibrate_tau(synth.encode16(src.tokens(64, stream=synth.STREAM_CALIB), dt), dt, 0.5)
-            cfg = rs.make_config(d_in, d_out, r, tau, dt, max_batch=maxb, dense_rowmajor=1)
+            cfg = rs.make_config(d_in, d_out, r, tau, dt, max_batch=maxb, dense_rowmajor=1, lowrank_channel_major=1)
             x = torch.from_numpy(synth.encode16(src.tokens(maxb, offset=20 + blk), dt).view(np.int16)).cuda()
             y = torch.zeros((maxb, d_out), dtype=torch.int16, device="cuda")
             blkl[name] = (rs.rsparse_prepare_factors(cfg, L.W16, L.U16, L.SV16), x, y)
